@@ -1,0 +1,181 @@
+"""Pins for the W4A4 half of the CPU oracle (signed 4-bit weights per output
+channel, unsigned 4-bit activations per tensor, exact integer conv-as-GEMM,
+requantisation): invariants, closed forms, textbook special cases, brute force."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import qail_oracle as O
+from paper_2412_01034_amd import synth
+
+
+def _tiny(B=1, H=4, W=4, Cin=8, Cout=3, KH=3, KW=3, stride=1, pad=1, name="t"):
+    return synth.ConvShape(name, B, H, W, Cin, Cout, KH, KW, stride, pad)
+
+
+def _codes(shape, seed):
+    a = synth.random_codes((shape.B, shape.H, shape.W, shape.Cin), 0, 15, seed).astype(np.uint8)
+    w = synth.random_codes((shape.Cout, shape.KH, shape.KW, shape.Cin), -8, 7, seed + 1)
+    return a, w
+
+
+def _acc(shape, a, w, **kw):
+    return O.w4a4_conv_acc(O.pack_nibbles(a), O.pack_nibbles(w.reshape(shape.Cout, -1)),
+                           shape.B, shape.H, shape.W, shape.Cin, shape.Cout, shape.KH, shape.KW,
+                           shape.stride, shape.pad, **kw)
+
+
+# ---- quantisers -------------------------------------------------------------
+
+def test_weight_codes_range_error_bound_and_extremes():
+    sh = _tiny(Cin=16, Cout=12)
+    w = synth.conv_weight(sh, 3)
+    q, s = O.quantize_w4_sym_channel(w)
+    assert q.dtype == np.int8 and q.min() >= -7 and q.max() <= 7      # absmax/7 never emits -8
+    flat = w.reshape(12, -1).astype(np.float64)
+    err = np.abs(flat - q.reshape(12, -1) * s.astype(np.float64)[:, None])
+    assert np.all(err <= s.astype(np.float64)[:, None] * (0.5 + 2.0 ** -20))
+    assert np.all(np.abs(q.reshape(12, -1)).max(axis=1) == 7)          # the absmax element maps to +-7
+    # per-tensor quantisation = every channel sharing one absmax
+    w2 = w.copy()
+    w2[:, 0, 0, 0] = np.abs(w).max()
+    _, s2 = O.quantize_w4_sym_channel(w2)
+    assert np.all(s2 == s2[0])
+    # exact cases, ties to even, sign symmetry
+    wq = np.array([[7, -7, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5]], np.float32)
+    q3, s3 = O.quantize_w4_sym_channel(wq)
+    assert float(s3[0]) == 1.0 and q3[0].tolist() == [7, -7, 0, 2, 2, 0, -2, -2]
+    q4, s4 = O.quantize_w4_sym_channel(np.zeros((2, 8), np.float32))
+    assert np.all(q4 == 0) and s4.tolist() == [1.0, 1.0]
+
+
+def test_activation_codes_range_bound_and_skew():
+    sh = _tiny(B=2, H=16, W=16, Cin=64)
+    a = synth.conv_activation(sh, 5)
+    s_a = O.act_scale_u4(a)
+    q = O.quantize_act_u4(a, s_a)
+    assert q.dtype == np.uint8 and q.max() == 15 and q.min() == 0
+    err = np.abs(a.astype(np.float64) - q * float(s_a))
+    assert np.all(err <= float(s_a) * (0.5 + 2.0 ** -20))
+    assert (q == 0).mean() > 0.5                       # ReLU input: at least half the codes are 0
+    # exact cases with s_a = 1: range, clamp below 0 and above 15, ties to even
+    v = np.array([0, 15, 0.5, 1.5, 2.5, -3.0, 14.5, 99.0], np.float32)
+    assert O.quantize_act_u4(v, 1.0).tolist() == [0, 15, 0, 2, 2, 0, 14, 15]
+    assert float(O.act_scale_u4(np.array([0, 30, 7.5], np.float32))) == 2.0
+    assert float(O.act_scale_u4(np.zeros(4, np.float32))) == 1.0
+
+
+# ---- integer conv-as-GEMM ---------------------------------------------------
+
+def _brute(shape, a, w):
+    OH, OW = shape.OH, shape.OW
+    out = np.zeros((shape.B * OH * OW, shape.Cout), dtype=np.int64)
+    for b in range(shape.B):
+        for oh in range(OH):
+            for ow in range(OW):
+                for n in range(shape.Cout):
+                    t = 0
+                    for kh in range(shape.KH):
+                        for kw in range(shape.KW):
+                            ih = oh * shape.stride + kh - shape.pad
+                            iw = ow * shape.stride + kw - shape.pad
+                            if 0 <= ih < shape.H and 0 <= iw < shape.W:
+                                for c in range(shape.Cin):
+                                    t += int(a[b, ih, iw, c]) * int(w[n, kh, kw, c])
+                    out[(b * OH + oh) * OW + ow, n] = t
+    return out
+
+
+@pytest.mark.parametrize("shape", [
+    _tiny(),
+    _tiny(B=2, H=5, W=6, Cin=8, Cout=4, stride=2, pad=1),
+    _tiny(B=1, H=6, W=6, Cin=16, Cout=2, KH=1, KW=1, stride=2, pad=0),
+    _tiny(B=1, H=7, W=5, Cin=8, Cout=2, KH=3, KW=3, stride=2, pad=1),
+])
+def test_conv_matches_nested_loop_definition(shape):
+    a, w = _codes(shape, 7)
+    ref = _brute(shape, a, w)
+    assert np.array_equal(_acc(shape, a, w), ref)
+    assert np.array_equal(_acc(shape, a, w, use_blas=True), ref)
+
+
+def test_1x1_conv_is_plain_gemm():
+    sh = _tiny(B=2, H=3, W=5, Cin=24, Cout=7, KH=1, KW=1, stride=1, pad=0)
+    a, w = _codes(sh, 9)
+    ref = a.reshape(-1, 24).astype(np.int64) @ w.reshape(7, 24).astype(np.int64).T
+    assert np.array_equal(_acc(sh, a, w), ref)
+
+
+def test_centre_tap_identity_and_shifted_tap():
+    sh = _tiny(B=1, H=5, W=6, Cin=8, Cout=8)
+    a, _ = _codes(sh, 13)
+    w = np.zeros((8, 3, 3, 8), np.int8)
+    for c in range(8):
+        w[c, 1, 1, c] = 1
+    assert np.array_equal(_acc(sh, a, w).reshape(1, 5, 6, 8), a.astype(np.int32))
+    # tap (kh=0, kw=2): out[oh, ow] = in[oh-1, ow+1], zero outside the image
+    w = np.zeros((8, 3, 3, 8), np.int8)
+    for c in range(8):
+        w[c, 0, 2, c] = -3
+    exp = np.zeros((1, 5, 6, 8), np.int64)
+    exp[:, 1:, :-1, :] = a[:, :-1, 1:, :]
+    assert np.array_equal(_acc(sh, a, w).reshape(1, 5, 6, 8), -3 * exp)
+
+
+def test_extreme_codes_closed_form_and_bound():
+    for K_ch in (8, 64, 512):
+        sh = _tiny(B=1, H=3, W=3, Cin=K_ch, Cout=2, KH=3, KW=3, stride=1, pad=1)
+        a = np.full((1, 3, 3, K_ch), 15, np.uint8)
+        w = np.empty((2, 3, 3, K_ch), np.int8)
+        w[0], w[1] = -8, 7
+        acc = _acc(sh, a, w).reshape(3, 3, 2)
+        # the centre pixel sees all 9 taps; a corner sees 4
+        assert acc[1, 1].tolist() == [-120 * 9 * K_ch, 105 * 9 * K_ch]
+        assert acc[0, 0].tolist() == [-120 * 4 * K_ch, 105 * 4 * K_ch]
+    assert 8 * 15 * 4608 == 552960 < 2 ** 31
+
+
+def test_im2col_column_order_is_kh_kw_c():
+    sh = _tiny(B=1, H=3, W=3, Cin=8, Cout=1)
+    a = np.arange(72, dtype=np.int64).reshape(1, 3, 3, 8)
+    cols = O.im2col_nhwc(a, 3, 3, 1, 1)
+    assert cols.shape == (9, 72)
+    centre = cols[4].reshape(3, 3, 8)
+    assert np.array_equal(centre, a[0])
+    corner = cols[0].reshape(3, 3, 8)
+    assert np.all(corner[0] == 0) and np.all(corner[:, 0] == 0) and np.array_equal(corner[1:, 1:], a[0, :2, :2])
+
+
+# ---- requantisation ---------------------------------------------------------
+
+def test_requant_closed_form():
+    acc = np.array([[3, -4], [0, 100]], np.int32)
+    scale = np.array([0.5, 0.25], np.float32)
+    bias = np.array([1.0, -2.0], np.float32)
+    assert O.requant(acc, scale, bias).tolist() == [[2.5, -3.0], [1.0, 23.0]]
+    s = O.requant_scale(np.float32(0.1), np.array([0.3, 2.0], np.float32))
+    assert s.dtype == np.float32
+    for i, sw in enumerate((0.3, 2.0)):
+        exact = Fraction(float(np.float32(0.1))) * Fraction(float(np.float32(sw)))
+        assert abs(Fraction(float(s[i])) - exact) <= abs(exact) * Fraction(1, 2 ** 24)
+
+
+def test_end_to_end_quantised_conv_tracks_real_conv():
+    # the integer path reproduces the real-valued convolution up to the
+    # quantisation step sizes (a dropped scale or transposed operand would not)
+    sh = _tiny(B=1, H=8, W=8, Cin=32, Cout=16)
+    w = synth.conv_weight(sh, 17)
+    a = synth.conv_activation(sh, 18)
+    bias = synth.conv_bias(sh, 19)
+    qw, s_w = O.quantize_w4_sym_channel(w)
+    s_a = O.act_scale_u4(a)
+    qa = O.quantize_act_u4(a, s_a)
+    acc = _acc(sh, qa, qw)
+    y = O.requant(acc, O.requant_scale(s_a, s_w), bias)
+    real = O.im2col_nhwc(a.astype(np.float64), 3, 3, 1, 1) @ w.reshape(16, -1).astype(np.float64).T + bias
+    rel = np.linalg.norm(y - real) / np.linalg.norm(real)
+    assert rel < 0.2
+    deq = (O.im2col_nhwc(qa.astype(np.float64) * float(s_a), 3, 3, 1, 1)
+           @ (qw.reshape(16, -1) * s_w.astype(np.float64)[:, None]).T + bias)
+    assert np.allclose(y, deq, rtol=1e-6, atol=1e-6)
