@@ -1,0 +1,309 @@
+#!/usr/bin/env python3
+"""Benchmark of the 4-bit linear-layer hot path on one MI355X.
+
+Primary workload (the one `value` is quoted on): the four W4A16 linears of a
+Llama-2-7B decoder layer at M = 1 (fused QKV 4096->12288, out 4096->4096, fused
+gate+up 4096->22016, down 11008->4096; group 128, asymmetric uint4).  One step
+= one decoder layer's four GEMVs through qail_w4a16_linear_batch.  The steps
+rotate through `--layers` independently seeded layers (default 8, 841 MB of
+packed weights) so that neither L2 nor the 256 MB last-level cache can serve the
+reads.  Throughput = algorithmic bytes (packed weights + scales + zero-points +
+x + y) per second, with everything resident in HBM before the timed region.
+
+Secondary workloads (reported under "extra", never in `value`): prefill GEMM
+at M = 288 / 1024, the 35 W4A4 convolutions of a ResNet-34 body at batch 32,
+and a decode stack walk at M in {1, 4, 16}.
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
+BF16_PEAK_TFLOPS = 2500.0     # dense bf16 MFMA, published
+INT8_PEAK_TOPS = 5000.0       # dense int8 MFMA, published
+GROUP = 128
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=2000)
+    p.add_argument("--warmup", type=int, default=100)
+    p.add_argument("--layers", type=int, default=8, help="independently seeded layers to rotate through")
+    p.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
+    p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return p.parse_args()
+
+
+def linear_bytes(N, K, M, g=GROUP):
+    G = K // g
+    return N * K // 2 + N * G * 2 + N * ((G + 7) // 8) * 4 + M * K * 2 + M * N * 2
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2412_01034_amd import binding as B
+    from paper_2412_01034_amd import synth
+
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2412_01034_amd import build
+        build.build_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint32:
+            a = a.view(np.int32)
+        elif a.dtype == np.uint16:
+            a = a.view(np.int16)
+        return torch.from_numpy(a).cuda()
+
+    # ---------------------------------------------------------------- weights
+    t0 = time.time()
+    shapes = synth.LLAMA7B_LINEARS
+    L = args.layers
+
+    def gen(job):
+        layer, i = job
+        _, N, K = shapes[i]
+        return job, synth.llm_weight(N, K, synth.seed_for(4, layer * 4 + i, 0), outlier_frac=0.01)
+
+    layers = [[None] * 4 for _ in range(L)]
+    jobs = [(l, i) for l in range(L) for i in range(4)]
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        for (l, i), w in ex.map(gen, jobs):
+            _, N, K = shapes[i]
+            qb, sb, zb = B.qail_packed_sizes(N, K, GROUP, B.QAIL_W4_ASYM_GROUP)
+            qw = torch.empty(qb // 4, dtype=torch.int32, device="cuda")
+            sc = torch.empty(sb // 2, dtype=torch.int16, device="cuda")
+            zr = torch.empty(zb // 4, dtype=torch.int32, device="cuda")
+            wd = torch.from_numpy(w).cuda()
+            B.qail_quantize_weights(wd, GROUP, B.QAIL_W4_ASYM_GROUP, qw, sc, zr)
+            torch.cuda.synchronize()
+            del wd, w
+            layers[l][i] = dict(N=N, K=K, group_size=GROUP, qweight=qw, scales=sc, zeros=zr)
+    log(f"[bench] {L} layers generated and quantised in {time.time() - t0:.1f} s")
+
+    def with_io(M):
+        """Attach x / y buffers for batch M to every layer; returns per-layer item arrays."""
+        xs = [dev(synth.llm_activation_bf16(M, K, synth.seed_for(1, i, 1))) for i, (_, N, K) in enumerate(shapes)]
+        out = []
+        for l in range(L):
+            ents = []
+            for i, (_, N, K) in enumerate(shapes):
+                e = dict(layers[l][i])
+                e["x"] = xs[i]
+                e["y"] = torch.empty(M * N, dtype=torch.int16, device="cuda")
+                ents.append(e)
+            out.append((B.make_w4a16_items(ents, M), ents))
+        return out
+
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    # ------------------------------------------------- primary: decode GEMVs
+    dec = with_io(1)
+    bytes_per_step = sum(linear_bytes(N, K, 1) for _, N, K in shapes)
+
+    def step(i):
+        items, _ = dec[i % L]
+        B.qail_w4a16_linear_batch(items, 4, 1, None, sh)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_begin = time.perf_counter()
+    ev0.record(stream)
+    for i in range(args.steps):
+        step(i)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / args.steps
+    value = bytes_per_step / (wall / args.steps) / 1e9
+    # one launch per step: the batched call serves the four linears in one kernel
+    launches = args.steps
+    kern_us = gpu_ms * 1e3 / launches
+    achieved = bytes_per_step / (kern_us * 1e-6) / 1e9
+    log(f"[bench] decode: {ms_per_step * 1e3:.2f} us/step wall, {kern_us:.2f} us/launch by events, "
+        f"{value:.0f} GB/s ({100 * value / HBM_PEAK_GBS:.1f}% of HBM peak)")
+
+    result = {
+        "metric": "W4A16 decode GEMV GB/s at Llama-2-7B shapes (M=1)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "configs[1]: four Llama-2-7B decode linears (12288x4096, 4096x4096, 22016x4096, "
+                        "4096x11008), W4A16 group 128 asymmetric uint4, M=1, one decoder layer per step",
+            "layers_rotated": L,
+            "bytes_per_step": bytes_per_step,
+            "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "w4a16_gemv_kernel (one launch = one decoder layer, 4 linears)",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "avg_launch_us": round(kern_us, 3),
+        },
+    }
+
+    # --------------------------------------------------------------- extras
+    extra = {}
+    if not args.no_extra:
+        def timed(fn, iters, warm=5):
+            for _ in range(warm):
+                fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(iters):
+                fn()
+            b.record(stream)
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) * 1e-3 / iters
+
+        # single-linear decode launches (cold weights: rotate layers)
+        per = {}
+        for i, (name, N, K) in enumerate(shapes):
+            singles = [B.make_w4a16_items([dec[l][1][i]], 1) for l in range(L)]
+            cnt = [0]
+
+            def one():
+                B.qail_w4a16_linear_batch(singles[cnt[0] % L], 1, 1, None, sh)
+                cnt[0] += 1
+            t = timed(one, 400)
+            per[name] = {"us": round(t * 1e6, 2), "GBps": round(linear_bytes(N, K, 1) / t / 1e9, 1)}
+        extra["decode_single_linear"] = per
+
+        # decode stack walk: 32 layer-steps per token (the loaded layers cycled), 7 tokens
+        stack = {}
+        for M in (1, 4, 16):
+            io = dec if M == 1 else with_io(M)
+
+            def walk():
+                for l in range(32):
+                    B.qail_w4a16_linear_batch(io[l % L][0], 4, M, None, sh)
+            t = timed(walk, 7, warm=1)
+            stack[f"M={M}"] = {"ms_per_token_step": round(t * 1e3, 4), "tokens_per_s": round(M / t, 1),
+                               "GBps": round(32 * sum(linear_bytes(N, K, M) for _, N, K in shapes) / t / 1e9, 1)}
+            if M != 1:
+                del io
+        stack["note"] = f"32 layer-steps per token over {L} distinct layers cycled"
+        extra["decode_stack"] = stack
+
+        # prefill GEMM
+        pre = {}
+        for M in (288, 1024):
+            io = with_io(M)
+            for i, (name, N, K) in enumerate(shapes):
+                it = B.make_w4a16_items([io[0][1][i]], M)
+                t = timed(lambda: B.qail_w4a16_linear_batch(it, 1, M, None, sh), 20)
+                tf = 2.0 * M * N * K / t / 1e12
+                pre[f"{name}_M{M}"] = {"us": round(t * 1e6, 1), "TFLOPs": round(tf, 1),
+                                       "frac_bf16_peak": round(tf / BF16_PEAK_TFLOPS, 4)}
+            del io
+        extra["prefill_gemm"] = pre
+
+        # W4A4 ResNet-34 body, batch 32
+        convs = synth.resnet34_convs(32)
+        rng = np.random.default_rng(synth.seed_for(3, 0, 0))
+        calls, tot_ops = [], 0
+        cache = {}
+        for li, s in enumerate(convs):
+            key = (s.H, s.Cin)
+            if key not in cache:   # one code tensor per input shape (values do not affect timing)
+                cache[key] = dev(rng.integers(0, 2 ** 32, size=s.B * s.H * s.W * s.Cin // 8,
+                                              dtype=np.uint64).astype(np.uint32))
+            ww = dev(rng.integers(0, 2 ** 32, size=s.Cout * s.K // 8, dtype=np.uint64).astype(np.uint32))
+            scale = torch.full((s.Cout,), 1e-3, dtype=torch.float32, device="cuda")
+            bias = torch.zeros(s.Cout, dtype=torch.float32, device="cuda")
+            y = torch.empty(s.M * s.Cout, dtype=torch.float32, device="cuda")
+            calls.append((s, cache[key], ww, scale, bias, y))
+            tot_ops += s.ops
+
+        def body():
+            for s, a, ww, scale, bias, y in calls:
+                B.qail_w4a4_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww,
+                                 scale=scale, bias=bias, y_out=y, stream=sh)
+        t = timed(body, 20)
+        per_shape = {}
+        for s, a, ww, scale, bias, y in calls:
+            key = f"{s.KH}x{s.KW}_{s.Cin}to{s.Cout}_s{s.stride}"
+            if key in per_shape:
+                continue
+            tt = timed(lambda: B.qail_w4a4_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad,
+                                                a, ww, scale=scale, bias=bias, y_out=y, stream=sh), 50)
+            per_shape[key] = {"us": round(tt * 1e6, 2), "TOPs": round(s.ops / tt / 1e12, 1)}
+        extra["w4a4_resnet34_b32"] = {"ms_per_pass": round(t * 1e3, 4), "TOPs": round(tot_ops / t / 1e12, 1),
+                                      "frac_int8_peak": round(tot_ops / t / 1e12 / INT8_PEAK_TOPS, 4),
+                                      "calls": len(calls), "per_shape": per_shape}
+        result["extra"] = extra
+        log("[bench] extra:", json.dumps(extra))
+
+    # ---------------------------------------------------------- CPU baseline
+    if not args.no_cpu:
+        from oracle import qail_oracle as O
+        host = []
+        for i, (_, N, K) in enumerate(shapes):
+            e = dec[0][1][i]
+            host.append((e["qweight"].cpu().numpy().view(np.uint32).reshape(N, K // 8),
+                         e["scales"].cpu().numpy().view(np.float16).reshape(N, K // GROUP),
+                         e["zeros"].cpu().numpy().view(np.uint32).reshape(N, -1),
+                         e["x"].cpu().numpy().view(np.uint16).reshape(1, K)))
+        c0, w0 = time.process_time(), time.perf_counter()
+        for qw, sc, zr, xb in host:
+            O.w4a16_linear(xb, qw, sc, zr, GROUP)
+        cpu_s, wall_s = time.process_time() - c0, time.perf_counter() - w0
+        result["cpu_baseline"] = {
+            "value": round(bytes_per_step / wall_s / 1e9, 4),
+            "unit": "GB/s",
+            "cores": max(1, int(round(cpu_s / wall_s))),
+            "kind": "oracle",
+            "sample": f"one decoder layer (the same four linears, M=1) through the numpy oracle: "
+                      f"unpack + dequantise + fp64 matmul, {wall_s:.1f} s wall; host has {os.cpu_count()} logical CPUs",
+        }
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

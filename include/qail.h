@@ -1,0 +1,184 @@
+/*
+ * qail.h - C ABI of libqail: 4-bit quantised linear layers on AMD MI355X (gfx950).
+ *
+ * The operations are the deployed low-bit layers behind the efficiency results
+ * of "Quantization-Aware Imitation-Learning for Resource-Efficient Robotic
+ * Control" (Sec. 5.4 "Implementation" and the appendix "Analysis"):
+ *
+ *   W4A16  weight-only 4-bit linears of the Llama-2-7B backbone of the VLA
+ *          policy.  Sec. 2.1: LLM linears are limited by weight loading, so only
+ *          the weight operand of the GEMM is quantised; Sec. 5.1: 4-bit AWQ
+ *          format (unsigned codes, scale, integer zero-point).  The appendix
+ *          "Analysis" finds the decode stage memory-bound; that is the M = 1 case.
+ *   W4A4   4-bit weights and 4-bit activations of the ResNet encoder of the
+ *          driving policy.  Sec. 2.1: convolutional models are compute-bound, so
+ *          both GEMM operands are quantised; Sec. 5.1: RTN / LSQ integer format.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers into memory owned by the caller,
+ *     16-byte aligned.  Descriptors and size outputs are HOST pointers.  The
+ *     library allocates nothing, frees nothing and keeps no state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     A call validates its arguments, enqueues its kernels and returns; it never
+ *     synchronises.  Outputs are fully overwritten.
+ *   - Argument errors (null pointer, bad shape, misalignment, short workspace)
+ *     are detected before anything is launched and leave device memory untouched;
+ *     they can be exercised on a host without a GPU.  A failed launch maps to
+ *     QAIL_ERR_HIP.
+ *   - Packed 4-bit data: 8 codes per uint32, code j of the packed axis in bits
+ *     [4*(j%8), 4*(j%8)+3] of word j/8.  Signed codes are two's-complement nibbles.
+ *   - bf16 and fp16 values cross the boundary as their 16-bit patterns (uint16_t).
+ *   - Inputs are finite.  NaN or infinity in a tensor to be quantised gives
+ *     unspecified codes (no fault).
+ */
+#ifndef QAIL_H
+#define QAIL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QAIL_OK = 0,
+    QAIL_ERR_NULL = -1,        /* a required pointer is NULL */
+    QAIL_ERR_SHAPE = -2,       /* a dimension is non-positive or violates a divisibility rule */
+    QAIL_ERR_ALIGN = -3,       /* a device pointer is not 16-byte aligned */
+    QAIL_ERR_WORKSPACE = -4,   /* workspace missing or smaller than the matching *_workspace query */
+    QAIL_ERR_UNSUPPORTED = -5, /* valid request outside what the kernels cover */
+    QAIL_ERR_HIP = -6          /* the HIP runtime refused a launch */
+} qail_status;
+
+typedef enum {
+    /* Unsigned codes 0..15, one fp16 scale and one integer zero-point 0..15 per
+     * group of `group_size` consecutive k of a row (Sec. 5.1, VLA policy;
+     * group_size == K is the channel-wise case of the appendix). */
+    QAIL_W4_ASYM_GROUP = 0,
+    /* Signed codes -8..7, one fp32 scale per row (output channel); group_size is
+     * ignored (Sec. 5.1, driving policy). */
+    QAIL_W4_SYM_CHANNEL = 1
+} qail_scheme;
+
+/* A quantised weight matrix W[N][K] (row n = output channel, K contiguous). */
+typedef struct {
+    int32_t N;          /* rows / output channels, >= 1 */
+    int32_t K;          /* columns / input channels, multiple of 8 */
+    int32_t group_size; /* ASYM_GROUP: multiple of 8 that divides K */
+    int32_t scheme;     /* qail_scheme */
+} qail_wdesc;
+
+/* A 2-D convolution read as a GEMM with M = B*OH*OW, N = Cout, K = KH*KW*Cin,
+ * OH = (H + 2*pad - KH)/stride + 1 (same for OW).  KH = KW = 1, stride = 1,
+ * pad = 0 makes it a plain [B*H*W, Cin] x [Cout, Cin]^T GEMM. */
+typedef struct {
+    int32_t B, H, W;    /* batch, input height, input width */
+    int32_t Cin, Cout;  /* Cin multiple of 8; Cout >= 1 */
+    int32_t KH, KW;     /* filter taps */
+    int32_t stride, pad;
+} qail_conv_desc;
+
+int qail_version(void);
+const char* qail_status_string(int status);
+
+/* ---------------------------------------------------------------- quantise --
+ * Sec. 2.1 (round-to-nearest) and Sec. 5.1 (the two 4-bit formats). */
+
+/* Byte sizes of the packed form of `d` (host computation only):
+ *   qweight  N * K/8 uint32
+ *   scales   ASYM_GROUP: N * K/group_size fp16     SYM_CHANNEL: N fp32
+ *   zeros    ASYM_GROUP: N * ceil(K/group_size/8) uint32 (unused nibbles 0)
+ *            SYM_CHANNEL: 0
+ * Any output pointer may be NULL. */
+int qail_packed_sizes(const qail_wdesc* d, size_t* qweight_bytes, size_t* scales_bytes,
+                      size_t* zeros_bytes);
+
+/* Round-to-nearest quantisation of w (fp32, [N][K] row-major) into the packed form.
+ *
+ * ASYM_GROUP, per row and group, in IEEE fp32 with correctly rounded division:
+ *   lo = min(min w, 0); hi = max(max w, 0)
+ *   s  = (hi - lo)/15 rounded UP to fp16, at least 2^-14; an all-zero group has s = 1
+ *   z  = clamp(rint(-lo/s), 0, 15);  q = clamp(rint(w/s) + z, 0, 15)   (ties to even)
+ * SYM_CHANNEL, per row:
+ *   s  = max|w|/7 (fp32; 1 for an all-zero row);  q = clamp(rint(w/s), -8, 7)
+ *   `zeros` is ignored and may be NULL.
+ *
+ * range_errors (device, one uint32, may be NULL): if given it is NOT cleared; it is
+ * incremented once per ASYM group whose (hi-lo)/15 exceeds the largest fp16
+ * (65504).  Such a group is stored with s = 65504 and clamped codes. */
+int qail_quantize_weights(const qail_wdesc* d, const float* w, uint32_t* qweight, void* scales,
+                          uint32_t* zeros, uint32_t* range_errors, void* stream);
+
+/* Packed words -> one code per byte, [N][K]: uint8 0..15 (ASYM_GROUP) or int8 -8..7
+ * (SYM_CHANNEL, sign-extended). */
+int qail_unpack_weights(const qail_wdesc* d, const uint32_t* qweight, uint8_t* codes, void* stream);
+
+/* One activation step size for a whole tensor (appendix: tensor-wise activation
+ * quantisation): *s_a = max(a)/15 in fp32, or 1 if no element is positive.
+ * a: fp32 [n]; s_a: device, one float. */
+int qail_act_scale_u4(const float* a, size_t n, float* s_a, void* stream);
+
+/* q = clamp(rint(a / *s_a), 0, 15), packed 8 per word along the flat index
+ * (for an NHWC tensor that is along C).  n multiple of 8; s_a: device, one float. */
+int qail_quantize_act_u4(const float* a, size_t n, const float* s_a, uint32_t* a_u4, void* stream);
+
+/* ------------------------------------------------------------------ W4A16 --
+ * y[m][n] = sum_k x[m][k] * (q[n][k] - z[n][k/g]) * s[n][k/g]
+ * Sec. 2.1 (weight-only quantised GEMM operand); appendix "Analysis" (decode is
+ * the memory-bound stage, prefill the compute-heavy one). */
+
+/* Bytes of scratch the call below needs for this (d, M); may be 0. */
+int qail_w4a16_workspace(const qail_wdesc* d, int32_t M, size_t* bytes);
+
+/* d must be ASYM_GROUP.  x: bf16 [M][K]; y: bf16 [M][N].  Products are accumulated
+ * in fp32 and rounded once to bf16 (nearest even).  M = 1 (decode) is served by a
+ * bandwidth-bound streaming kernel, 2 <= M <= 16 by a weight-streaming MFMA kernel,
+ * larger M (prefill) by an LDS-tiled bf16 MFMA kernel that dequantises weights to
+ * bf16 first.  workspace may be NULL when the query returns 0. */
+int qail_w4a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales,
+                      const uint32_t* zeros, const uint16_t* x, uint16_t* y, int32_t M,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* One linear of a batch for qail_w4a16_linear_batch. */
+typedef struct {
+    qail_wdesc d;
+    const uint32_t* qweight;
+    const uint16_t* scales;
+    const uint32_t* zeros;
+    const uint16_t* x;   /* bf16 [M][K] */
+    uint16_t* y;         /* bf16 [M][N] */
+} qail_w4a16_item;
+
+/* `count` linears with the same M, given as a HOST array, enqueued on one stream
+ * (appendix "Analysis": a decode step is a fixed sequence of such linears, 4 per
+ * layer).  The items must be independent: no item may read what another writes.
+ * Result is the same as `count` calls of qail_w4a16_linear; the library may run
+ * them in fewer launches.  count >= 0 (0 is a no-op). */
+int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t M,
+                            void* workspace, size_t workspace_bytes, void* stream);
+int qail_w4a16_batch_workspace(const qail_w4a16_item* items, int32_t count, int32_t M,
+                               size_t* bytes);
+
+/* ------------------------------------------------------------------- W4A4 --
+ * acc[(b,oh,ow)][n] = sum_{kh,kw,c} a[b][oh*stride+kh-pad][ow*stride+kw-pad][c] * w[n][kh][kw][c]
+ * with zero outside the image, exact in int32; then optionally
+ * y = float(acc) * scale[n] + bias[n]   (one fp32 fused multiply-add).
+ * Sec. 2.1 (both GEMM operands quantised for compute-bound convolutions);
+ * Sec. 5.4 (W4A4 GPU kernels of the driving policy). */
+
+int qail_w4a4_workspace(const qail_conv_desc* d, size_t* bytes);
+
+/* a_u4: packed unsigned codes, NHWC [B][H][W][Cin/8] words.
+ * w_s4: packed signed codes [Cout][KH][KW][Cin/8] words.
+ * acc_out: int32 [M][Cout] or NULL.  y_out: fp32 [M][Cout] or NULL (then scale and
+ * bias, fp32 [Cout], are required).  At least one output must be given.
+ * |acc| <= 8*15*K must stay below 2^27 (K <= 1118480). */
+int qail_w4a4_gemm(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t* w_s4,
+                   int32_t* acc_out, const float* scale, const float* bias, float* y_out,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QAIL_H */

@@ -1,0 +1,230 @@
+// C entry points of libqail: argument validation and dispatch.  Every check is
+// done on the host before the first HIP call, so that the error paths can be
+// exercised on a machine without a GPU.
+#include "qail_internal.h"
+
+using namespace qail;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_wdesc(const qail_wdesc* d) {
+    if (!d) return QAIL_ERR_NULL;
+    if (d->scheme != QAIL_W4_ASYM_GROUP && d->scheme != QAIL_W4_SYM_CHANNEL) return QAIL_ERR_UNSUPPORTED;
+    if (d->N < 1 || d->K < 8 || d->K % 8 != 0) return QAIL_ERR_SHAPE;
+    if (d->scheme == QAIL_W4_ASYM_GROUP) {
+        if (d->group_size < 8 || d->group_size % 8 != 0 || d->K % d->group_size != 0) return QAIL_ERR_SHAPE;
+        if (d->K / d->group_size > 32768) return QAIL_ERR_UNSUPPORTED;  // zero-points of a row are staged in LDS
+    }
+    return QAIL_OK;
+}
+
+int check_conv(const qail_conv_desc* d) {
+    if (!d) return QAIL_ERR_NULL;
+    if (d->B < 1 || d->H < 1 || d->W < 1 || d->Cin < 8 || d->Cin % 8 != 0 || d->Cout < 1 || d->KH < 1 ||
+        d->KW < 1 || d->stride < 1 || d->pad < 0)
+        return QAIL_ERR_SHAPE;
+    if (d->H + 2 * d->pad < d->KH || d->W + 2 * d->pad < d->KW) return QAIL_ERR_SHAPE;
+    const long long K = (long long)d->KH * d->KW * d->Cin;
+    if (K > 1118480) return QAIL_ERR_UNSUPPORTED;  // 16 * 8 * 15 * K must fit int32
+    const long long OH = (d->H + 2 * d->pad - d->KH) / d->stride + 1;
+    const long long OW = (d->W + 2 * d->pad - d->KW) / d->stride + 1;
+    const long long M = (long long)d->B * OH * OW;
+    if (M > 0x7FFFFFFFll / 2 || M / 128 + 1 > 65535) return QAIL_ERR_UNSUPPORTED;
+    if ((long long)d->B * d->H * d->W > 0x7FFFFFFFll) return QAIL_ERR_UNSUPPORTED;
+    return QAIL_OK;
+}
+
+int check_item(const qail_w4a16_item& it, int M) {
+    int e = check_wdesc(&it.d);
+    if (e != QAIL_OK) return e;
+    if (it.d.scheme != QAIL_W4_ASYM_GROUP) return QAIL_ERR_UNSUPPORTED;
+    if (!it.qweight || !it.scales || !it.zeros || !it.x || !it.y) return QAIL_ERR_NULL;
+    if (!aligned16(it.qweight) || !aligned16(it.scales) || !aligned16(it.zeros) || !aligned16(it.x) ||
+        !aligned16(it.y))
+        return QAIL_ERR_ALIGN;
+    if ((long long)M * it.d.N > 0x7FFFFFFFll || (long long)M * it.d.K > 0x7FFFFFFFll) return QAIL_ERR_UNSUPPORTED;
+    return QAIL_OK;
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? QAIL_OK : QAIL_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int qail_version(void) { return 100; }
+
+const char* qail_status_string(int status) {
+    switch (status) {
+        case QAIL_OK: return "ok";
+        case QAIL_ERR_NULL: return "required pointer is NULL";
+        case QAIL_ERR_SHAPE: return "bad shape";
+        case QAIL_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case QAIL_ERR_WORKSPACE: return "workspace missing or too small";
+        case QAIL_ERR_UNSUPPORTED: return "unsupported request";
+        case QAIL_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int qail_packed_sizes(const qail_wdesc* d, size_t* qweight_bytes, size_t* scales_bytes, size_t* zeros_bytes) {
+    const int e = check_wdesc(d);
+    if (e != QAIL_OK) return e;
+    const size_t N = (size_t)d->N, K = (size_t)d->K;
+    if (qweight_bytes) *qweight_bytes = N * (K / 8) * 4;
+    if (d->scheme == QAIL_W4_ASYM_GROUP) {
+        const size_t G = K / (size_t)d->group_size;
+        if (scales_bytes) *scales_bytes = N * G * 2;
+        if (zeros_bytes) *zeros_bytes = N * ((G + 7) / 8) * 4;
+    } else {
+        if (scales_bytes) *scales_bytes = N * 4;
+        if (zeros_bytes) *zeros_bytes = 0;
+    }
+    return QAIL_OK;
+}
+
+int qail_quantize_weights(const qail_wdesc* d, const float* w, uint32_t* qweight, void* scales,
+                          uint32_t* zeros, uint32_t* range_errors, void* stream) {
+    const int e = check_wdesc(d);
+    if (e != QAIL_OK) return e;
+    const bool asym = d->scheme == QAIL_W4_ASYM_GROUP;
+    if (!w || !qweight || !scales || (asym && !zeros)) return QAIL_ERR_NULL;
+    if (!aligned16(w) || !aligned16(qweight) || !aligned16(scales) || (asym && !aligned16(zeros)))
+        return QAIL_ERR_ALIGN;
+    if (range_errors && (reinterpret_cast<uintptr_t>(range_errors) & 3u)) return QAIL_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (asym)
+        return hip_status(launch_quantize_asym(*d, w, qweight, static_cast<uint16_t*>(scales), zeros,
+                                               range_errors, st));
+    return hip_status(launch_quantize_sym(*d, w, qweight, static_cast<float*>(scales), st));
+}
+
+int qail_unpack_weights(const qail_wdesc* d, const uint32_t* qweight, uint8_t* codes, void* stream) {
+    const int e = check_wdesc(d);
+    if (e != QAIL_OK) return e;
+    if (!qweight || !codes) return QAIL_ERR_NULL;
+    if (!aligned16(qweight) || !aligned16(codes)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_unpack(*d, qweight, codes, static_cast<hipStream_t>(stream)));
+}
+
+int qail_act_scale_u4(const float* a, size_t n, float* s_a, void* stream) {
+    if (!s_a || (n > 0 && !a)) return QAIL_ERR_NULL;
+    if ((n > 0 && !aligned16(a)) || (reinterpret_cast<uintptr_t>(s_a) & 3u)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_act_scale(a, n, s_a, static_cast<hipStream_t>(stream)));
+}
+
+int qail_quantize_act_u4(const float* a, size_t n, const float* s_a, uint32_t* a_u4, void* stream) {
+    if (n % 8 != 0) return QAIL_ERR_SHAPE;
+    if (n / 8 > 0xFFFFFFFFull * 64) return QAIL_ERR_UNSUPPORTED;
+    if (n == 0) return QAIL_OK;
+    if (!a || !s_a || !a_u4) return QAIL_ERR_NULL;
+    if (!aligned16(a) || !aligned16(a_u4) || (reinterpret_cast<uintptr_t>(s_a) & 3u)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_act_quant(a, n, s_a, a_u4, static_cast<hipStream_t>(stream)));
+}
+
+int qail_w4a16_workspace(const qail_wdesc* d, int32_t M, size_t* bytes) {
+    const int e = check_wdesc(d);
+    if (e != QAIL_OK) return e;
+    if (d->scheme != QAIL_W4_ASYM_GROUP) return QAIL_ERR_UNSUPPORTED;
+    if (M < 1) return QAIL_ERR_SHAPE;
+    if (!bytes) return QAIL_ERR_NULL;
+    *bytes = 0;
+    return QAIL_OK;
+}
+
+int qail_w4a16_batch_workspace(const qail_w4a16_item* items, int32_t count, int32_t M, size_t* bytes) {
+    if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
+    if (!bytes || (count > 0 && !items)) return QAIL_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const int e = check_wdesc(&items[i].d);
+        if (e != QAIL_OK) return e;
+        if (items[i].d.scheme != QAIL_W4_ASYM_GROUP) return QAIL_ERR_UNSUPPORTED;
+    }
+    *bytes = 0;
+    return QAIL_OK;
+}
+
+int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t M, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
+    if (count == 0) return QAIL_OK;
+    if (!items) return QAIL_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const int e = check_item(items[i], M);
+        if (e != QAIL_OK) return e;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (M == 1) {
+        // runs of items the streaming kernel takes go out together
+        int i = 0;
+        while (i < count) {
+            int j = i;
+            while (j < count && gemv_supports(items[j].d)) ++j;
+            if (j > i) {
+                const hipError_t e = launch_w4a16_gemv(items + i, j - i, st);
+                if (e != hipSuccess) return QAIL_ERR_HIP;
+                i = j;
+            } else {
+                const hipError_t e = launch_w4a16_generic(items[i], 1, st);
+                if (e != hipSuccess) return QAIL_ERR_HIP;
+                ++i;
+            }
+        }
+        return QAIL_OK;
+    }
+    for (int i = 0; i < count; ++i) {
+        const qail_wdesc& d = items[i].d;
+        hipError_t e;
+        if (d.K % 64 == 0 && d.group_size % 64 == 0)
+            e = launch_w4a16_gemm(items[i], M, st);
+        else
+            e = launch_w4a16_generic(items[i], M, st);
+        if (e != hipSuccess) return QAIL_ERR_HIP;
+    }
+    return QAIL_OK;
+}
+
+int qail_w4a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales,
+                      const uint32_t* zeros, const uint16_t* x, uint16_t* y, int32_t M, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    if (!d) return QAIL_ERR_NULL;
+    qail_w4a16_item it;
+    it.d = *d;
+    it.qweight = qweight;
+    it.scales = scales;
+    it.zeros = zeros;
+    it.x = x;
+    it.y = y;
+    return qail_w4a16_linear_batch(&it, 1, M, workspace, workspace_bytes, stream);
+}
+
+int qail_w4a4_workspace(const qail_conv_desc* d, size_t* bytes) {
+    const int e = check_conv(d);
+    if (e != QAIL_OK) return e;
+    if (!bytes) return QAIL_ERR_NULL;
+    *bytes = 0;
+    return QAIL_OK;
+}
+
+int qail_w4a4_gemm(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t* w_s4, int32_t* acc_out,
+                   const float* scale, const float* bias, float* y_out, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    const int e = check_conv(d);
+    if (e != QAIL_OK) return e;
+    if (!a_u4 || !w_s4) return QAIL_ERR_NULL;
+    if (!acc_out && !y_out) return QAIL_ERR_NULL;
+    if (y_out && (!scale || !bias)) return QAIL_ERR_NULL;
+    if (!aligned16(a_u4) || !aligned16(w_s4) || (acc_out && !aligned16(acc_out)) ||
+        (y_out && !aligned16(y_out)) || (scale && !aligned16(scale)) || (bias && !aligned16(bias)))
+        return QAIL_ERR_ALIGN;
+    return hip_status(launch_w4a4_conv(*d, a_u4, w_s4, acc_out, scale, bias, y_out,
+                                       static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,57 @@
+// Internal declarations shared by the translation units of libqail.
+// Nothing here crosses the C ABI; see include/qail.h for the public surface.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "qail.h"
+
+namespace qail {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+typedef __attribute__((ext_vector_type(16))) int i32x16_t;
+
+constexpr int kWave = 64;
+
+// fp32 -> bf16 bit pattern, round to nearest even (finite inputs).
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+    return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) {
+    return (float)__builtin_bit_cast(_Float16, b);
+}
+
+// Launchers (host side).  Each validates nothing: the C entry points do.
+hipError_t launch_quantize_asym(const qail_wdesc& d, const float* w, uint32_t* qw, uint16_t* scales,
+                                uint32_t* zeros, uint32_t* range_errors, hipStream_t st);
+hipError_t launch_quantize_sym(const qail_wdesc& d, const float* w, uint32_t* qw, float* scales,
+                               hipStream_t st);
+hipError_t launch_unpack(const qail_wdesc& d, const uint32_t* qw, uint8_t* codes, hipStream_t st);
+hipError_t launch_act_scale(const float* a, size_t n, float* s_a, hipStream_t st);
+hipError_t launch_act_quant(const float* a, size_t n, const float* s_a, uint32_t* out, hipStream_t st);
+
+// W4A16.  `items` lives in host memory; the launcher copies what it needs into
+// kernel arguments.
+bool gemv_supports(const qail_wdesc& d);
+hipError_t launch_w4a16_gemv(const qail_w4a16_item* items, int count, hipStream_t st);
+hipError_t launch_w4a16_gemm(const qail_w4a16_item& it, int M, hipStream_t st);
+hipError_t launch_w4a16_generic(const qail_w4a16_item& it, int M, hipStream_t st);
+
+// W4A4.
+hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
+                            const float* scale, const float* bias, float* y, hipStream_t st);
+
+}  // namespace qail

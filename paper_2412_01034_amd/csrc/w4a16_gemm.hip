@@ -1,0 +1,169 @@
+// W4A16 linear for M > 1: y[m][n] = sum_k x[m][k] * (q[n][k] - z[n][k/g]) * s[n][k/g].
+//
+// Appendix "Analysis": prefill is the compute-heavy stage of the backbone.  The
+// weights are dequantised to bf16 on their way into LDS and the contraction runs
+// on the bf16 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulate).
+//
+// MFMA operand layout used here (16x16x32, wave64): lane l supplies, for the A
+// operand, row l%16 and the 8 consecutive k starting at 8*(l/16); for the B
+// operand, column l%16 and the same k; it receives D[4*(l/16)+r][l%16], r=0..3.
+// A = activations (rows m), B = weights (columns n), so that a lane's results
+// are contiguous along n in y.
+#include "qail_internal.h"
+
+namespace qail {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+
+constexpr int kBM = 128, kBN = 128, kBK = 64;
+constexpr int kPitch = kBK + 8;  // bf16 elements per LDS row (144 B: 16-byte aligned)
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    f32x2_t v = {a, b};
+    bf16x2_t r = __builtin_convertvector(v, bf16x2_t);  // nearest even
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// 8 codes of one word -> 8 bf16 (q - z) * s, in k order.
+__device__ __forceinline__ uint4 dequant8(uint32_t w, float s, float zc) {
+    float d[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t t = ((w >> (4 * i)) & 0x000F000Fu) | 0x43004300u;  // bf16 (128+c_i, 128+c_{i+4})
+        d[i] = (__builtin_bit_cast(float, t << 16) - zc) * s;
+        d[i + 4] = (__builtin_bit_cast(float, t & 0xFFFF0000u) - zc) * s;
+    }
+    return make_uint4(pack_bf16(d[0], d[1]), pack_bf16(d[2], d[3]), pack_bf16(d[4], d[5]),
+                      pack_bf16(d[6], d[7]));
+}
+
+__global__ __launch_bounds__(256) void w4a16_gemm_kernel(
+    const uint32_t* __restrict__ qw, const uint16_t* __restrict__ sc, const uint32_t* __restrict__ zr,
+    const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int M, int N, int K, int g) {
+    __shared__ __attribute__((aligned(16))) uint16_t As[kBM * kPitch];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[kBN * kPitch];
+
+    const int t = threadIdx.x;
+    const int lane = t % kWave, wave = t / kWave;
+    const int wm = wave / 2, wn = wave % 2;
+    const int bm = blockIdx.y * kBM, bn = blockIdx.x * kBN;
+    const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
+
+    f32x4_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    const int brow = t >> 1, bhalf = t & 1;
+    const int bnrow = min(bn + brow, N - 1);
+
+    for (int k0 = 0; k0 < K; k0 += kBK) {
+        uint4 av[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = t + 256 * i;
+            const int row = idx >> 3, seg = idx & 7;
+            const int m = bm + row;
+            av[i] = (m < M) ? *reinterpret_cast<const uint4*>(x + (size_t)m * K + k0 + seg * 8)
+                            : make_uint4(0, 0, 0, 0);
+        }
+        const int kb = k0 + bhalf * 32;
+        const int grp = kb / g;
+        const uint4 qv = *reinterpret_cast<const uint4*>(qw + (size_t)bnrow * kw + kb / 8);
+        const float s = f16_bits_to_f32(sc[(size_t)bnrow * G + grp]);
+        const float zc = (float)(128u + ((zr[(size_t)bnrow * zwords + grp / 8] >> (4 * (grp & 7))) & 0xFu));
+
+        __syncthreads();  // previous step's MFMAs have read LDS
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = t + 256 * i;
+            const int row = idx >> 3, seg = idx & 7;
+            *reinterpret_cast<uint4*>(&As[row * kPitch + seg * 8]) = av[i];
+        }
+        {
+            uint4* dst = reinterpret_cast<uint4*>(&Bs[brow * kPitch + bhalf * 32]);
+            dst[0] = dequant8(qv.x, s, zc);
+            dst[1] = dequant8(qv.y, s, zc);
+            dst[2] = dequant8(qv.z, s, zc);
+            dst[3] = dequant8(qv.w, s, zc);
+        }
+        __syncthreads();
+
+#pragma unroll
+        for (int kk = 0; kk < kBK; kk += 32) {
+            bf16x8_t a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                a[i] = *reinterpret_cast<const bf16x8_t*>(
+                    &As[(wm * 64 + i * 16 + (lane & 15)) * kPitch + kk + (lane >> 4) * 8]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                b[j] = *reinterpret_cast<const bf16x8_t*>(
+                    &Bs[(wn * 64 + j * 16 + (lane & 15)) * kPitch + kk + (lane >> 4) * 8]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = bn + wn * 64 + j * 16 + (lane & 15);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = bm + wm * 64 + i * 16 + (lane >> 4) * 4 + r;
+                if (m < M && n < N) y[(size_t)m * N + n] = f32_to_bf16_rne(acc[i][j][r]);
+            }
+        }
+}
+
+// Any valid shape (K % 8 == 0, g % 8 == 0): one thread per output, fp32
+// accumulation in k order.  Slow; only for shapes the tiled kernels do not take.
+__global__ __launch_bounds__(256) void w4a16_generic_kernel(
+    const uint32_t* __restrict__ qw, const uint16_t* __restrict__ sc, const uint32_t* __restrict__ zr,
+    const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int M, int N, int K, int g) {
+    const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= (size_t)M * N) return;
+    const int m = (int)(o / N), n = (int)(o % N);
+    const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
+    float acc = 0.f;
+    for (int wi = 0; wi < kw; ++wi) {
+        const int grp = (wi * 8) / g;
+        const uint32_t w = qw[(size_t)n * kw + wi];
+        const float s = f16_bits_to_f32(sc[(size_t)n * G + grp]);
+        const int z = (zr[(size_t)n * zwords + grp / 8] >> (4 * (grp & 7))) & 0xF;
+        float part = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int q = (w >> (4 * j)) & 0xF;
+            part = fmaf(bf16_bits_to_f32(x[(size_t)m * K + wi * 8 + j]), (float)(q - z), part);
+        }
+        acc = fmaf(part, s, acc);
+    }
+    y[o] = f32_to_bf16_rne(acc);
+}
+
+}  // namespace
+
+hipError_t launch_w4a16_gemm(const qail_w4a16_item& it, int M, hipStream_t st) {
+    dim3 grid((it.d.N + kBN - 1) / kBN, (M + kBM - 1) / kBM);
+    hipLaunchKernelGGL(w4a16_gemm_kernel, grid, dim3(256), 0, st, it.qweight, it.scales, it.zeros, it.x,
+                       it.y, M, it.d.N, it.d.K, it.d.group_size);
+    return hipGetLastError();
+}
+
+hipError_t launch_w4a16_generic(const qail_w4a16_item& it, int M, hipStream_t st) {
+    const size_t outs = (size_t)M * it.d.N;
+    hipLaunchKernelGGL(w4a16_generic_kernel, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st,
+                       it.qweight, it.scales, it.zeros, it.x, it.y, M, it.d.N, it.d.K, it.d.group_size);
+    return hipGetLastError();
+}
+
+}  // namespace qail

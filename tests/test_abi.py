@@ -1,0 +1,85 @@
+"""CPU-side checks of the C ABI: the library loads, exports every function the
+header declares, and reports argument errors before touching the GPU."""
+import ctypes
+
+import pytest
+
+from tests.helpers import ensure_built, header_functions
+
+
+@pytest.fixture(scope="module")
+def B():
+    return ensure_built()
+
+
+def test_exports_match_header(B):
+    L = B.lib()
+    names = header_functions()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+    assert B.qail_version() >= 100
+    assert B.status_string(0) == "ok"
+    for s in range(-6, 0):
+        assert B.status_string(s) not in ("ok", "unknown status")
+
+
+def test_packed_sizes(B):
+    # K=11008, g=128: 86 groups -> 11 zero-point words per row
+    assert B.qail_packed_sizes(4096, 11008, 128, B.QAIL_W4_ASYM_GROUP) == (4096 * 1376 * 4, 4096 * 86 * 2, 4096 * 11 * 4)
+    assert B.qail_packed_sizes(512, 512, 64, B.QAIL_W4_ASYM_GROUP) == (512 * 64 * 4, 512 * 8 * 2, 512 * 4)
+    assert B.qail_packed_sizes(64, 576, 0, B.QAIL_W4_SYM_CHANNEL) == (64 * 72 * 4, 64 * 4, 0)
+    total = 0
+    for n, k in ((12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008)):
+        total += sum(B.qail_packed_sizes(n, k, 128, B.QAIL_W4_ASYM_GROUP))
+    assert abs(total - 105.14e6) < 0.2e6          # one decoder layer
+    for bad in ((0, 64, 64), (4, 60, 8), (4, 64, 12), (4, 64, 48), (4, 0, 8)):
+        with pytest.raises(B.QailError) as e:
+            B.qail_packed_sizes(*bad, B.QAIL_W4_ASYM_GROUP)
+        assert e.value.status == B.QAIL_ERR_SHAPE
+    with pytest.raises(B.QailError) as e:
+        B.qail_packed_sizes(4, 64, 8, 7)
+    assert e.value.status == B.QAIL_ERR_UNSUPPORTED
+
+
+def test_argument_errors_are_reported_without_a_gpu(B):
+    L = B.lib()
+    d = B.qail_wdesc(16, 64, 32, B.QAIL_W4_ASYM_GROUP)
+    ok, odd = 0x10000, 0x10008
+    st = L.qail_quantize_weights(ctypes.byref(d), None, ok, ok, ok, None, None)
+    assert st == B.QAIL_ERR_NULL
+    assert L.qail_quantize_weights(ctypes.byref(d), ok, ok, ok, None, None, None) == B.QAIL_ERR_NULL
+    assert L.qail_quantize_weights(ctypes.byref(d), odd, ok, ok, ok, None, None) == B.QAIL_ERR_ALIGN
+    assert L.qail_quantize_weights(None, ok, ok, ok, ok, None, None) == B.QAIL_ERR_NULL
+    assert L.qail_unpack_weights(ctypes.byref(d), ok, None, None) == B.QAIL_ERR_NULL
+    assert L.qail_w4a16_linear(ctypes.byref(d), ok, ok, ok, ok, ok, 0, None, 0, None) == B.QAIL_ERR_SHAPE
+    assert L.qail_w4a16_linear(ctypes.byref(d), ok, ok, ok, None, ok, 1, None, 0, None) == B.QAIL_ERR_NULL
+    assert L.qail_w4a16_linear(ctypes.byref(d), ok, ok, odd, ok, ok, 1, None, 0, None) == B.QAIL_ERR_ALIGN
+    ds = B.qail_wdesc(16, 64, 32, B.QAIL_W4_SYM_CHANNEL)
+    assert L.qail_w4a16_linear(ctypes.byref(ds), ok, ok, ok, ok, ok, 1, None, 0, None) == B.QAIL_ERR_UNSUPPORTED
+    assert L.qail_w4a16_linear_batch(None, 0, 1, None, 0, None) == B.QAIL_OK
+    assert L.qail_w4a16_linear_batch(None, 2, 1, None, 0, None) == B.QAIL_ERR_NULL
+    assert L.qail_w4a16_linear_batch(None, -1, 1, None, 0, None) == B.QAIL_ERR_SHAPE
+    assert L.qail_quantize_act_u4(ok, 12, ok, ok, None) == B.QAIL_ERR_SHAPE
+    assert L.qail_quantize_act_u4(None, 0, None, None, None) == B.QAIL_OK
+    assert L.qail_act_scale_u4(ok, 8, None, None) == B.QAIL_ERR_NULL
+    c = B.qail_conv_desc(1, 4, 4, 8, 4, 3, 3, 1, 1)
+    assert L.qail_w4a4_gemm(ctypes.byref(c), ok, ok, None, None, None, None, None, 0, None) == B.QAIL_ERR_NULL
+    assert L.qail_w4a4_gemm(ctypes.byref(c), ok, ok, None, None, ok, ok, None, 0, None) == B.QAIL_ERR_NULL
+    assert L.qail_w4a4_gemm(ctypes.byref(c), ok, odd, ok, None, None, None, None, 0, None) == B.QAIL_ERR_ALIGN
+    bad = B.qail_conv_desc(1, 4, 4, 12, 4, 3, 3, 1, 1)
+    assert L.qail_w4a4_gemm(ctypes.byref(bad), ok, ok, ok, None, None, None, None, 0, None) == B.QAIL_ERR_SHAPE
+    bad = B.qail_conv_desc(1, 2, 2, 8, 4, 5, 5, 1, 0)
+    assert L.qail_w4a4_gemm(ctypes.byref(bad), ok, ok, ok, None, None, None, None, 0, None) == B.QAIL_ERR_SHAPE
+    sz = ctypes.c_size_t(99)
+    assert L.qail_w4a4_workspace(ctypes.byref(c), ctypes.byref(sz)) == B.QAIL_OK
+    assert L.qail_w4a16_workspace(ctypes.byref(d), 1, ctypes.byref(sz)) == B.QAIL_OK
+    assert L.qail_w4a16_workspace(ctypes.byref(d), 0, ctypes.byref(sz)) == B.QAIL_ERR_SHAPE
+
+
+def test_binding_refuses_host_tensors(B):
+    import torch
+    t = torch.zeros(16, 64)
+    with pytest.raises(ValueError):
+        B.qail_quantize_weights(t, 32, B.QAIL_W4_ASYM_GROUP, torch.zeros(128, dtype=torch.int32),
+                                torch.zeros(32, dtype=torch.float16), torch.zeros(16, dtype=torch.int32))

@@ -1,0 +1,197 @@
+"""GPU parity of the W4A16 linear (decode GEMV, small batch, prefill GEMM)
+against the CPU oracle.  Bar: max |y - y_ref| / (||x_m|| ||w_hat_n||) <= 2e-3,
+and bit-exact wherever the exact result is representable in bf16."""
+import numpy as np
+import pytest
+
+from oracle import qail_oracle as O
+from paper_2412_01034_amd import synth
+from tests.helpers import dev, ensure_built, host, w4a16_norm_err
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+# One bf16 rounding of the result is up to 2^-8 of |y|.  At the sizes of the
+# paper's workloads |y| is a small fraction of ||x|| ||w||, and TOL holds with
+# a wide margin; with a handful of k and a shared outlier column a dot product
+# can be almost fully aligned, and then the output rounding alone exceeds TOL.
+TOL_TINY_K = 2.0 ** -8 * 1.01
+
+
+@pytest.fixture(scope="module")
+def B():
+    return ensure_built()
+
+
+def oracle_pack(w, g):
+    q, s, z = O.quantize_w4_asym_group(w, g)
+    qw, zw = O.pack_w4a16(q, z)
+    return qw, s, zw
+
+
+def gpu_linear(B, qw, s, zw, xb, g, N, K, M):
+    import torch
+    y = torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")    # NaN pattern: must be overwritten
+    B.qail_w4a16_linear(N, K, g, dev(qw), dev(s.view(np.uint16)), dev(zw), dev(xb), y, M)
+    torch.cuda.synchronize()
+    return host(y, np.uint16).reshape(M, N)
+
+
+def check(B, N, K, g, M, seed, w_kw=None, x_kw=None, tol=TOL):
+    w = synth.llm_weight(N, K, seed, **(w_kw or {}))
+    xb = synth.llm_activation_bf16(M, K, seed + 1, **(x_kw or {}))
+    qw, s, zw = oracle_pack(w, g)
+    y = gpu_linear(B, qw, s, zw, xb, g, N, K, M)
+    ref = O.w4a16_linear(xb, qw, s, zw, g)
+    nx, nw = O.w4a16_row_norms(xb, qw, s, zw, g)
+    err = w4a16_norm_err(y, ref, nx, nw)
+    assert err <= tol, err
+    return err
+
+
+def test_config0_tiny_gemv(B):
+    # M=1, K=512, N=512, group 64, seed 0
+    w = synth.llm_weight(512, 512, synth.seed_for(0, 0, 0))
+    xb = synth.llm_activation_bf16(1, 512, synth.seed_for(0, 0, 1))
+    qw, s, zw = oracle_pack(w, 64)
+    y = gpu_linear(B, qw, s, zw, xb, 64, 512, 512, 1)
+    ref = O.w4a16_linear(xb, qw, s, zw, 64)
+    nx, nw = O.w4a16_row_norms(xb, qw, s, zw, 64)
+    # fp32 accumulation then one bf16 rounding: far inside the bar
+    assert w4a16_norm_err(y, ref, nx, nw) <= 2.0 ** -9
+    # determinism: a second run gives the same bits
+    assert np.array_equal(y, gpu_linear(B, qw, s, zw, xb, 64, 512, 512, 1))
+
+
+@pytest.mark.parametrize("N,K,g", [
+    (1000, 4096, 128),       # ragged N, two full wave-wide loads per row
+    (37, 11008, 128),        # 86 groups: wave-wide load with a partial tail
+    (130, 2048, 32),
+    (64, 32, 32),            # a single 32-k chunk
+    (16, 16384, 128),        # largest K of the streaming kernel
+    (5, 40, 8),              # shape only the generic kernel takes
+    (24, 32768, 256),        # K beyond the streaming kernel
+])
+def test_gemv_shapes(B, N, K, g):
+    check(B, N, K, g, 1, 7 * N + K, w_kw=dict(outlier_frac=0.01), tol=TOL if K >= 512 else TOL_TINY_K)
+
+
+@pytest.mark.parametrize("M", [2, 4, 16, 100, 288])
+@pytest.mark.parametrize("N,K,g", [(200, 1024, 128), (384, 4096, 128), (72, 11008, 128), (16, 64, 64), (9, 48, 16)])
+def test_batched_shapes(B, M, N, K, g):
+    check(B, N, K, g, M, 3 * M + N, w_kw=dict(outlier_frac=0.01), x_kw=dict(outlier_frac=0.005),
+          tol=TOL if K >= 512 else TOL_TINY_K)
+
+
+@pytest.mark.parametrize("M", [1, 4, 16, 130])
+def test_closed_forms_bit_exact(B, M):
+    N, K, g = 96, 1024, 128
+    G = K // g
+    for c in (1, 15):
+        # all codes c, z = 0, s = 1, x = 1  ->  y = K * c, exact in bf16
+        qw = O.pack_nibbles(np.full((N, K), c))
+        s = np.ones((N, G), np.float16)
+        zw = O.pack_nibbles(np.zeros((N, G), np.uint8))
+        xb = synth.f32_to_bf16_bits(np.ones((M, K), np.float32))
+        y = gpu_linear(B, qw, s, zw, xb, g, N, K, M)
+        assert np.all(y == synth.f32_to_bf16_bits(np.float32([K * c]))[0])
+    # one-hot x reads single dequantised weights, each exactly representable after one rounding
+    w = synth.llm_weight(N, K, 5)
+    qw, s, zw = oracle_pack(w, g)
+    w_hat = O.dequantize_w4_asym_group(O.unpack_nibbles_u4(qw, K), s, O.unpack_nibbles_u4(zw, G), g)
+    for k in (0, 5, 127, 128, 1023):
+        x = np.zeros((M, K), np.float32)
+        x[:, k] = 1.0
+        x[M - 1, k] = -2.0
+        y = gpu_linear(B, qw, s, zw, synth.f32_to_bf16_bits(x), g, N, K, M)
+        exp = np.repeat(w_hat[None, :, k], M, axis=0)
+        exp[M - 1] *= -2.0
+        # compared as values: an exact zero may come out as +0 or -0
+        assert np.array_equal(synth.bf16_bits_to_f32(y),
+                              synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(exp.astype(np.float32))))
+
+
+def test_homogeneity_and_determinism(B):
+    N, K, g = 256, 4096, 128
+    w = synth.llm_weight(N, K, 9, outlier_frac=0.01)
+    qw, s, zw = oracle_pack(w, g)
+    for M in (1, 16, 64):
+        xb = synth.llm_activation_bf16(M, K, 10)
+        x8 = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(xb) * np.float32(8))
+        y1 = gpu_linear(B, qw, s, zw, xb, g, N, K, M)
+        y8 = gpu_linear(B, qw, s, zw, x8, g, N, K, M)
+        f1 = synth.bf16_bits_to_f32(y1) * np.float32(8)
+        assert np.array_equal(synth.f32_to_bf16_bits(f1), y8)
+        assert np.array_equal(y1, gpu_linear(B, qw, s, zw, xb, g, N, K, M))
+
+
+def test_batch_equals_single_calls(B):
+    import torch
+    shapes = [(160, 4096, 128), (48, 4096, 128), (70, 11008, 128), (33, 1024, 64), (9, 40, 8)]
+    for M in (1, 4):
+        ents, singles = [], []
+        for i, (N, K, g) in enumerate(shapes):
+            w = synth.llm_weight(N, K, 40 + i)
+            xb = synth.llm_activation_bf16(M, K, 50 + i)
+            qw, s, zw = oracle_pack(w, g)
+            e = dict(N=N, K=K, group_size=g, qweight=dev(qw), scales=dev(s.view(np.uint16)), zeros=dev(zw),
+                     x=dev(xb), y=torch.zeros(M * N, dtype=torch.int16, device="cuda"))
+            ents.append(e)
+            singles.append(gpu_linear(B, qw, s, zw, xb, g, N, K, M))
+        items = B.make_w4a16_items(ents, M)
+        B.qail_w4a16_linear_batch(items, len(ents), M)
+        torch.cuda.synchronize()
+        for e, ref in zip(ents, singles):
+            assert np.array_equal(host(e["y"], np.uint16).reshape(ref.shape), ref)
+
+
+def _sampled_full_size(B, M, x_kw, rows_per_linear=96, m_rows=8):
+    """The four Llama-2-7B linears at full size through the batched call (the
+    launch configuration the benchmark times); the GPU quantises the full
+    matrices, the oracle re-derives sampled rows only (rows are independent)."""
+    import torch
+    rng = np.random.default_rng(77)
+    ents, keep = [], []
+    for i, (name, N, K) in enumerate(synth.LLAMA7B_LINEARS):
+        w = synth.llm_weight(N, K, synth.seed_for(1, i, 0), outlier_frac=0.01)
+        xb = synth.llm_activation_bf16(M, K, synth.seed_for(1, i, 1), **x_kw)
+        qb, sb, zb = B.qail_packed_sizes(N, K, 128, B.QAIL_W4_ASYM_GROUP)
+        qw = torch.zeros(qb // 4, dtype=torch.int32, device="cuda")
+        sc = torch.zeros(sb // 2, dtype=torch.int16, device="cuda")
+        zr = torch.zeros(zb // 4, dtype=torch.int32, device="cuda")
+        wd = dev(w)
+        B.qail_quantize_weights(wd, 128, B.QAIL_W4_ASYM_GROUP, qw, sc, zr)
+        torch.cuda.synchronize()
+        del wd
+        rows = np.sort(rng.choice(N, rows_per_linear, replace=False))
+        rows[0], rows[-1] = 0, N - 1
+        ents.append(dict(N=N, K=K, group_size=128, qweight=qw, scales=sc, zeros=zr, x=dev(xb),
+                         y=torch.zeros(M * N, dtype=torch.int16, device="cuda")))
+        keep.append((w[rows], xb, rows))
+        del w
+    items = B.make_w4a16_items(ents, M)
+    B.qail_w4a16_linear_batch(items, len(ents), M)
+    torch.cuda.synchronize()
+    ms = np.unique(np.linspace(0, M - 1, m_rows).astype(int))
+    worst = 0.0
+    for e, (w_rows, xb, rows) in zip(ents, keep):
+        N, K = e["N"], e["K"]
+        q, s, z = O.quantize_w4_asym_group(w_rows, 128)
+        qw_ref, zw_ref = O.pack_w4a16(q, z)
+        G = K // 128
+        assert np.array_equal(host(e["qweight"], np.uint32).reshape(N, K // 8)[rows], qw_ref)
+        assert np.array_equal(host(e["scales"], np.uint16).reshape(N, G)[rows], s.view(np.uint16))
+        assert np.array_equal(host(e["zeros"], np.uint32).reshape(N, (G + 7) // 8)[rows], zw_ref)
+        y = host(e["y"], np.uint16).reshape(M, N)[np.ix_(ms, rows)]
+        ref = O.w4a16_linear(xb[ms], qw_ref, s, zw_ref, 128)
+        nx, nw = O.w4a16_row_norms(xb[ms], qw_ref, s, zw_ref, 128)
+        worst = max(worst, w4a16_norm_err(y, ref, nx, nw))
+    assert worst <= TOL, worst
+
+
+def test_full_size_decode_linears_sampled(B):
+    _sampled_full_size(B, 1, {})
+
+
+@pytest.mark.parametrize("M", [288, 1024])
+def test_full_size_prefill_linears_sampled(B, M):
+    _sampled_full_size(B, M, dict(outlier_frac=0.005))

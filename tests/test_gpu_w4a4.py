@@ -1,0 +1,118 @@
+"""GPU parity of the W4A4 conv-as-GEMM against the CPU oracle: int32
+accumulators bit-exact, requantised output within one fp32 rounding."""
+import numpy as np
+import pytest
+
+from oracle import qail_oracle as O
+from paper_2412_01034_amd import synth
+from tests.helpers import dev, ensure_built, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    return ensure_built()
+
+
+def geom(s):
+    return (s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad)
+
+
+def gpu_conv(B, s, a_words, w_words, scale=None, bias=None, want_acc=True):
+    import torch
+    acc = torch.full((s.M * s.Cout,), 0x55555555, dtype=torch.int32, device="cuda") if want_acc else None
+    y = torch.full((s.M * s.Cout,), float("nan"), dtype=torch.float32, device="cuda") if scale is not None else None
+    B.qail_w4a4_gemm(*geom(s), dev(a_words), dev(w_words), acc_out=acc,
+                     scale=dev(scale) if scale is not None else None,
+                     bias=dev(bias) if bias is not None else None, y_out=y)
+    torch.cuda.synchronize()
+    return (host(acc, np.int32).reshape(s.M, s.Cout) if want_acc else None,
+            host(y, np.float32).reshape(s.M, s.Cout) if y is not None else None)
+
+
+def quantised_inputs(s, seed):
+    w = synth.conv_weight(s, seed)
+    a = synth.conv_activation(s, seed + 1)
+    bias = synth.conv_bias(s, seed + 2)
+    qw, s_w = O.quantize_w4_sym_channel(w)
+    s_a = O.act_scale_u4(a)
+    qa = O.quantize_act_u4(a, s_a)
+    return O.pack_nibbles(qa), O.pack_nibbles(qw.reshape(s.Cout, -1)), O.requant_scale(s_a, s_w), bias
+
+
+def check_requant(y, acc_ref, scale, bias):
+    ref = O.requant(acc_ref, scale, bias)
+    bound = 2.0 ** -22 * (np.abs(acc_ref.astype(np.float64) * scale.astype(np.float64)[None, :])
+                          + np.abs(bias.astype(np.float64))[None, :])
+    assert np.all(np.abs(y.astype(np.float64) - ref) <= bound)
+
+
+TINY = [
+    synth.ConvShape("t0", 1, 4, 4, 64, 3, 3, 3, 1, 1),
+    synth.ConvShape("t1", 2, 9, 7, 64, 70, 3, 3, 2, 1),       # odd sizes, ragged M and N tiles
+    synth.ConvShape("t2", 3, 6, 6, 128, 64, 1, 1, 2, 0),
+    synth.ConvShape("t3", 1, 12, 12, 192, 40, 3, 3, 1, 1),
+    synth.ConvShape("t4", 2, 5, 5, 8, 6, 3, 3, 1, 1),         # Cin not a multiple of 64: generic kernel
+    synth.ConvShape("t5", 1, 7, 7, 24, 9, 1, 1, 1, 0),
+    synth.ConvShape("t6", 1, 1, 1, 64, 1, 1, 1, 1, 0),        # a single dot product
+    synth.ConvShape("t7", 1, 16, 16, 64, 16, 5, 5, 1, 2),
+]
+
+
+@pytest.mark.parametrize("s", TINY, ids=[s.name for s in TINY])
+def test_random_codes_full_range_bit_exact(B, s):
+    a = synth.random_codes((s.B, s.H, s.W, s.Cin), 0, 15, 3).astype(np.uint8)
+    w = synth.random_codes((s.Cout, s.K), -8, 7, 4)
+    aw, ww = O.pack_nibbles(a), O.pack_nibbles(w)
+    ref = O.w4a4_conv_acc(aw, ww, *geom(s))
+    acc, _ = gpu_conv(B, s, aw, ww)
+    assert np.array_equal(acc, ref)
+    acc2, _ = gpu_conv(B, s, aw, ww)
+    assert np.array_equal(acc, acc2)
+
+
+def test_extreme_codes(B):
+    s = synth.ConvShape("x", 1, 6, 6, 512, 32, 3, 3, 1, 1)        # K = 4608, the deepest layer
+    a = np.full((1, 6, 6, 512), 15, np.uint8)
+    w = np.empty((32, s.K), np.int8)
+    w[0::2], w[1::2] = -8, 7
+    acc, _ = gpu_conv(B, s, O.pack_nibbles(a), O.pack_nibbles(w))
+    acc = acc.reshape(6, 6, 32)
+    assert acc[2, 3, 0] == -120 * 4608 and acc[2, 3, 1] == 105 * 4608
+    assert acc[0, 0, 0] == -120 * 4 * 512 and acc[5, 0, 1] == 105 * 4 * 512
+    assert np.array_equal(acc.reshape(36, 32), O.w4a4_conv_acc(O.pack_nibbles(a), O.pack_nibbles(w), *geom(s)))
+
+
+def distinct_resnet_shapes(batch):
+    seen, out = set(), []
+    for s in synth.resnet34_convs(batch):
+        key = (s.H, s.Cin, s.Cout, s.KH, s.stride)
+        if key not in seen:
+            seen.add(key)
+            out.append(s)
+    return out
+
+
+@pytest.mark.parametrize("s", distinct_resnet_shapes(2), ids=lambda s: s.name)
+def test_resnet34_shapes_small_batch(B, s):
+    aw, ww, scale, bias = quantised_inputs(s, 20)
+    ref = O.w4a4_conv_acc(aw, ww, *geom(s), use_blas=True)
+    acc, y = gpu_conv(B, s, aw, ww, scale, bias)
+    assert np.array_equal(acc, ref)
+    check_requant(y, ref, scale, bias)
+    _, y_only = gpu_conv(B, s, aw, ww, scale, bias, want_acc=False)
+    assert np.array_equal(y_only, y)
+
+
+@pytest.mark.parametrize("s", distinct_resnet_shapes(32), ids=lambda s: s.name)
+def test_resnet34_shapes_full_batch_sampled_images(B, s):
+    # batch 32 as benchmarked; the oracle recomputes images 0, 13 and 31 (images are independent)
+    aw, ww, scale, bias = quantised_inputs(s, synth.seed_for(3, 1, 0))
+    acc, y = gpu_conv(B, s, aw, ww, scale, bias)
+    per = s.OH * s.OW
+    for b in (0, 13, 31):
+        one = (1,) + geom(s)[1:]
+        ref = O.w4a4_conv_acc(aw[b:b + 1], ww, *one, use_blas=True)
+        assert np.array_equal(acc[b * per:(b + 1) * per], ref)
+        check_requant(y[b * per:(b + 1) * per], ref, scale, bias)
