@@ -1,22 +1,28 @@
 // W4A16 linear for M = 1 (decode): y[n] = sum_k x[k] * (q[n,k] - z[n,k/g]) * s[n,k/g].
 //
 // Appendix "Analysis": the decode stage is memory-bound, its time is the time to
-// stream the packed weights.  The kernel is therefore organised around the HBM
-// stream: each lane fetches 16 bytes (32 codes) of a row per load, a wave covers
-// 2048 consecutive k of one row, and the arithmetic per weight is kept to about
-// 1.5 vector-ALU operations so that it hides under the loads:
+// stream the packed weights.  The kernel is organised around that stream:
 //
-//   sum_k x_k (q_k - z) s  =  s * ( sum_k x_k (q_k + 128)  -  (128 + z) * sum_k x_k )
+//   * a lane fetches 16 bytes (32 codes) of a row per load, a wave covers 2048
+//     consecutive k of one row per load instruction, rows are contiguous, so every
+//     wave-wide load is one 1 KB burst;
+//   * every wave keeps several rows of loads in flight (a register pipeline), and a
+//     block works on rows of ONE linear only, so the activations are staged in LDS
+//     once per block and there is no barrier inside the stream;
+//   * the multiply-adds run on the matrix cores (see stream_rows), so the vector ALU only
+//     expands nibbles.  With
 //
-//   * (q_k + 128) as bf16 is the bit pattern 0x4300 | q_k, so one AND-OR turns two
-//     nibbles of a packed word into a bf16 pair; nibbles j and j+4 come out
-//     together, and x is staged in LDS in that pair order once per block.
-//   * the pair products go through v_dot2c_f32_bf16 (fp32 accumulate).
-//   * sum_k x_k per 32-k chunk is computed once per block; a chunk never straddles
-//     a group because group_size is a multiple of 32.
+//       sum_k x_k (q_k - z) s  =  s * ( sum_k x_k (q_k + 1024)  -  1024 sum_k x_k  -  z sum_k x_k )
 //
-// One launch serves a list of independent linears (a work list in the kernel
-// arguments), so that a decode layer's four GEMVs ramp up once.
+//     (q_k + 1024) as fp16 is the bit pattern 0x6400 | q_k, and 0x6400 | (q_k << 4) is
+//     16 q_k + 1024, so one AND-OR turns two nibbles of a packed word into an fp16 pair at
+//     either of two bit positions; the activations that meet the shifted codes are staged
+//     divided by 16.  The sums of x over a lane's 32-k chunk are computed once per wave; a
+//     chunk never straddles a group because group_size is a multiple of 32.
+//
+// One launch serves a list of independent linears: the blocks of the grid are
+// divided among the linears in proportion to their bytes, so a decoder layer's
+// four GEMVs ramp up once and finish together.
 #include "qail_internal.h"
 
 namespace qail {
@@ -28,7 +34,8 @@ constexpr int kGemvWaves = 16;                    // waves per block
 constexpr int kGemvThreads = kGemvWaves * kWave;  // 1024
 constexpr int kChunkK = 32;                       // k per lane per load (16 bytes of codes)
 constexpr int kWaveK = kWave * kChunkK;           // 2048 k per wave-wide load
-constexpr int kGemvMaxK = 16384;                  // x (32 KB) + chunk sums (2 KB) in LDS
+constexpr int kGemvMaxChunks = 6;                 // K <= 12288 (more chunks would spill registers)
+constexpr int kGemvMaxK = kGemvMaxChunks * kWaveK;
 
 struct GemvItem {
     const uint32_t* qw;
@@ -37,134 +44,316 @@ struct GemvItem {
     const uint16_t* x;
     uint16_t* y;
     int N, K, g;
-    int pass_begin;  // first pass (of rows_per_pass rows) of this item in the launch
+    int block_begin;  // first block of the grid that works on this item
+    int blocks;       // number of blocks that share its rows
 };
 
 struct GemvArgs {
     GemvItem it[kGemvMaxItems];
     int count;
-    int total_passes;
 };
 
-__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
-                                           __builtin_bit_cast(bf16x2_t, b), c, false);
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+
+template <int kCtrl>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xF, 0xF, true);
+    return v + __builtin_bit_cast(float, moved);
 }
 
+template <int kCtrl>
+__device__ __forceinline__ float dpp_max(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xF, 0xF, true);
+    return fmaxf(v, __builtin_bit_cast(float, moved));
+}
+
+// Sum over the 64 lanes; the result is wave-uniform.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+    v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);  // row_half_mirror
+    v = dpp_add<0x140>(v);  // row_mirror: every lane of a 16-lane row holds the row sum
+    const int vi = __builtin_bit_cast(int, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 0)) +
+           __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 16)) +
+           (__builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 32)) +
+            __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 48)));
 }
 
-// 32 codes (one uint4) against the matching 32 staged activations.
-__device__ __forceinline__ float dot32(const uint4& q, const uint4* __restrict__ xl) {
-    float acc = 0.f;
-    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+// LDS map of a block (uint4 units unless noted), nch = ceil(K / 2048):
+//   [0, nch*256)       staged activations: word j of lane L in chunk c at (c*4 + j)*64 + L
+//   then nch*64 float  the power of two 2^e of lane L's chunk c, at c*64 + L
+//   then nch*64 float4 (nch > 4 only) per-chunk constants of lane L, see stream_rows
+// Lane L of a wave owns, in chunk c, the 32 k starting at c*2048 + 32*L.  Its staged word j
+// holds those k's 8j..8j+7 as fp16 in the order x0,x4 | x1/16,x5/16 | x2,x6 | x3/16,x7/16
+// (all times 2^-e), matching the four registers the weight nibbles are expanded into.
+// Everything past K is zero.
+
+// Stages the activations of one item (whole block; one barrier).
+//
+// x is bf16; the matrix cores take fp16 here because fp16 has room for a 4-bit code at two
+// mantissa positions (see stream_rows).  Every bf16 significand fits fp16, the range does
+// not, so each 32-k chunk is scaled by the power of two that brings its largest magnitude
+// into [2^14, 2^15); the dot product of the chunk is multiplied back by 2^e in fp32.
+// Elements more than 2^-28 below the chunk's maximum lose bits or vanish, which is far
+// below the fp32 accumulation noise of the products.
+template <int kMaxRuns>
+__device__ __forceinline__ void stage_x(const GemvItem& it, int nch, uint4* __restrict__ lds,
+                                        const uint4 (&xr)[kMaxRuns]) {
+    const int K = it.K;
+    float* post = reinterpret_cast<float*>(lds + nch * 4 * kWave);
+    const int runs = nch * (kWaveK / 8);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint4 xv = xl[j];
-        const uint32_t t0 = (w[j] & 0x000F000Fu) | 0x43004300u;          // codes 0,4
-        const uint32_t t1 = ((w[j] >> 4) & 0x000F000Fu) | 0x43004300u;   // codes 1,5
-        const uint32_t t2 = ((w[j] >> 8) & 0x000F000Fu) | 0x43004300u;   // codes 2,6
-        const uint32_t t3 = ((w[j] >> 12) & 0x000F000Fu) | 0x43004300u;  // codes 3,7
-        acc = dot2_bf16(t0, xv.x, acc);
-        acc = dot2_bf16(t1, xv.y, acc);
-        acc = dot2_bf16(t2, xv.z, acc);
-        acc = dot2_bf16(t3, xv.w, acc);
+    for (int u = 0; u < kMaxRuns; ++u) {
+        // run i = 8 consecutive k; the 4 threads of a quad hold the 4 runs of one chunk
+        const int i = threadIdx.x + u * kGemvThreads;
+        const uint32_t w[4] = {xr[u].x, xr[u].y, xr[u].z, xr[u].w};
+        float f[8];
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f[2 * e] = __builtin_bit_cast(float, w[e] << 16);
+            f[2 * e + 1] = __builtin_bit_cast(float, w[e] & 0xFFFF0000u);
+            amax = fmaxf(amax, fmaxf(fabsf(f[2 * e]), fabsf(f[2 * e + 1])));
+        }
+        amax = dpp_max<0xB1>(amax);  // quad_perm [1,0,3,2]
+        amax = dpp_max<0x4E>(amax);  // quad_perm [2,3,0,1]
+        // 2^-e with amax * 2^-e in [2^14, 2^15): exponent arithmetic on the bit pattern
+        const int ex = (int)((__builtin_bit_cast(uint32_t, amax) >> 23) & 0xFF);  // biased exponent
+        int down = (amax > 0.f) ? (ex - 141) : 0;                                 // 141 = 127 + 14
+        down = max(-126, min(113, down));  // keeps both exponent fields valid
+        const float pre = __builtin_bit_cast(float, (uint32_t)(127 - down) << 23);
+        if (i < runs) {
+            auto pk = [](float lo, float hi) {
+                typedef __attribute__((ext_vector_type(2))) _Float16 h2;
+                const h2 v = {(_Float16)lo, (_Float16)hi};
+                return __builtin_bit_cast(uint32_t, v);
+            };
+            const float pre16 = pre * 0.0625f;
+            uint4 o;
+            o.x = pk(f[0] * pre, f[4] * pre);
+            o.y = pk(f[1] * pre16, f[5] * pre16);
+            o.z = pk(f[2] * pre, f[6] * pre);
+            o.w = pk(f[3] * pre16, f[7] * pre16);
+            if (i >= K / 8) o = make_uint4(0, 0, 0, 0);
+            const int c = i / (kWaveK / 8), r = i % (kWaveK / 8);
+            lds[(c * 4 + (r & 3)) * kWave + (r >> 2)] = o;
+            if ((r & 3) == 0) post[c * kWave + (r >> 2)] = __builtin_bit_cast(float, (uint32_t)(127 + down) << 23);
+        }
     }
-    return acc;
+    __syncthreads();
 }
 
-// R rows per wave per pass; a pass is kGemvWaves * R consecutive rows of one item.
-template <int R>
+// Rows [r0, r1) of one item, streamed by one wave.  The wave keeps NCH * kPR wave-wide
+// loads (1 KB each) in flight: a register slot is refilled with the same chunk of a later
+// row as soon as its codes have been consumed.  The first loads go out before the
+// activations are staged, so the two latencies overlap.
+//
+// The multiply-adds run on the matrix cores.  v_mfma_f32_4x4x4_16b_f16 computes 16
+// independent 4x4x4 products; lane l = 4b + j supplies row j of A and column j of B of
+// block b (4 values each) and receives column j of D.  D[j][j], register j of lane l, is
+// therefore the dot product of the lane's own four A values with its own four B values:
+// eight such instructions, chained through the accumulator, give every lane the dot
+// product of its 32 codes with the 32 activations at the same k.  The other entries of D
+// are ignored.  The vector ALU only expands nibbles: 5 operations per 8 codes.
+template <int NCH, int kPR>
+__device__ __forceinline__ void stream_rows(const GemvItem& it, int rbase, int nrows, int lane,
+                                            uint4* __restrict__ xlds) {
+    typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+    const int K = it.K, g = it.g;
+    const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
+
+    // x first: it is needed first and loads return in order
+    constexpr int kMaxRuns = (NCH * (kWaveK / 8) + kGemvThreads - 1) / kGemvThreads;
+    uint4 xr[kMaxRuns];
+#pragma unroll
+    for (int u = 0; u < kMaxRuns; ++u) {
+        const int i = threadIdx.x + u * kGemvThreads;
+        xr[u] = (i < K / 8) ? reinterpret_cast<const uint4*>(it.x)[i] : make_uint4(0, 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // the scheduler must not move the x load behind the weights
+
+    // Per-chunk constants of this lane.  Only the last chunk of a row can run past K;
+    // there the lane reads the start of the row instead (valid data) and meets zeros in x.
+    const bool tail_out = (NCH - 1) * kWaveK + lane * kChunkK >= K;
+    int goff[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int kc = c * kWaveK + lane * kChunkK;
+        goff[c] = ((c == NCH - 1 && tail_out) ? 0 : kc) / g;
+    }
+    const int lane_w = lane * (kChunkK / 8);  // word offset within chunk 0
+    const int last_w = tail_out ? 0 : (NCH - 1) * (kWaveK / 8) + lane_w;
+
+    uint4 q[kPR][NCH];
+    _Float16 sh[kPR][NCH];  // kept in its loaded type: a widening at the load would force a wait there
+    uint32_t zw[kPR][NCH];
+
+    auto issue = [&](int p, int c, int row) {
+        const uint32_t* qrow = it.qw + (size_t)row * kw;
+        const _Float16* srow = reinterpret_cast<const _Float16*>(it.sc) + (size_t)row * G;
+        const uint32_t* zrow = it.zr + (size_t)row * zwords;
+        const int wo = (c == NCH - 1) ? last_w : c * (kWaveK / 8) + lane_w;
+        q[p][c] = *reinterpret_cast<const uint4*>(qrow + wo);
+        sh[p][c] = srow[goff[c]];
+        zw[p][c] = zrow[goff[c] >> 3];
+    };
+
+    // Every load below is issued unconditionally (rows past the end are clamped to the last
+    // row and their results dropped), so that the number of loads in flight at each point is
+    // known at compile time and the waits can be exact.
+    const int ilast = max(nrows - 1, 0);
+#pragma unroll
+    for (int p = 0; p < kPR; ++p)
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            issue(p, c, min(rbase + min(p, ilast) * kGemvWaves, it.N - 1));
+            __builtin_amdgcn_sched_barrier(0);  // program order = consumption order, see above
+        }
+
+    stage_x<kMaxRuns>(it, NCH, xlds, xr);
+
+    // Per chunk, from the lane's own staged activations:
+    //   xoff = 1024 * (sum of the staged values): what the fp16 offsets add to the MFMA result
+    //   xsum = sum of x * 2^-e
+    //   post = 2^e
+    // kept in registers for short rows; for long ones parked in an LDS table behind the 2^e
+    // table (every wave writes the same values to the same slots, and reads only its own
+    // lanes' slots after its own writes, so no barrier is needed)
+    constexpr bool kParked = NCH > 4;
+    float* postl = reinterpret_cast<float*>(xlds + NCH * 4 * kWave);
+    float4* parked = reinterpret_cast<float4*>(postl + NCH * kWave);
+    float xoff[NCH], xsum[NCH], post[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) post[c] = postl[c * kWave + lane];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        typedef __attribute__((ext_vector_type(2))) _Float16 h2;
+        float se = 0.f, so = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint4 v = xlds[(c * 4 + j) * kWave + lane];
+            const h2 a = __builtin_bit_cast(h2, v.x), b = __builtin_bit_cast(h2, v.y);
+            const h2 c2 = __builtin_bit_cast(h2, v.z), d = __builtin_bit_cast(h2, v.w);
+            se += ((float)a[0] + (float)a[1]) + ((float)c2[0] + (float)c2[1]);
+            so += ((float)b[0] + (float)b[1]) + ((float)d[0] + (float)d[1]);
+        }
+        xoff[c] = 1024.f * (se + so);
+        xsum[c] = se + 16.f * so;
+        if (kParked) parked[c * kWave + lane] = make_float4(xoff[c], xsum[c], post[c], 0.f);
+    }
+    if (nrows <= 0) return;
+    uint32_t magic = 0x64006400u;   // fp16 pair (1024, 1024); held in a vector register so that
+    asm volatile("" : "+v"(magic)); // the AND-OR needs only one scalar operand
+
+    // Results stay in registers (the wave's i-th row in lane i; the launcher gives a wave at most 64
+    // rows) and are stored once at the end: a store between the loads would break the
+    // in-order completion that exact load waits rely on.
+    float ykeep = 0.f;
+
+    const bool odd = lane & 1, hi = lane & 2;
+
+    // The arithmetic of the wave's i-th row, whose codes sit in slot p.
+    auto consume = [&](int p, int i) {
+        float acc = 0.f;
+        // x is the same for every row, but holding all of it in registers costs 16 per
+        // chunk.  It is re-read from LDS per row, one chunk ahead of the arithmetic; the
+        // empty asm ties each chunk's reads to the previous chunk's result so that the
+        // compiler can neither hoist the reads out of the row loop nor bunch them up.
+        int xo = lane;
+        asm volatile("" : "+v"(xo));
+        uint4 xv[2][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xv[0][j] = xlds[j * kWave + xo];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if (c + 1 < NCH) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xv[(c + 1) & 1][j] = xlds[((c + 1) * 4 + j) * kWave + xo];
+            }
+            const uint32_t w[4] = {q[p][c].x, q[p][c].y, q[p][c].z, q[p][c].w};
+            f32x4_t d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // codes 0,4 | 16*codes 1,5 | codes 2,6 | 16*codes 3,7, each plus 1024, as fp16
+                const uint32_t w8 = w[j] >> 8;
+                const uint2 a01 = make_uint2((w[j] & 0x000F000Fu) | magic, (w[j] & 0x00F000F0u) | magic);
+                const uint2 a23 = make_uint2((w8 & 0x000F000Fu) | magic, (w8 & 0x00F000F0u) | magic);
+                const uint4 xj = xv[c & 1][j];
+                d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a01),
+                                                        __builtin_bit_cast(f16x4_t, make_uint2(xj.x, xj.y)), d0, 0, 0, 0);
+                d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a23),
+                                                        __builtin_bit_cast(f16x4_t, make_uint2(xj.z, xj.w)), d1, 0, 0, 0);
+            }
+            // D[j][j] is register j = lane % 4
+            const float e0 = odd ? d0[1] : d0[0], e1 = odd ? d0[3] : d0[2];
+            const float f0 = odd ? d1[1] : d1[0], f1 = odd ? d1[3] : d1[2];
+            const float dsel = (hi ? e1 : e0) + (hi ? f1 : f0);
+            float cxoff = xoff[c], cxsum = xsum[c], cpost = post[c];
+            if (kParked) {
+                const float4 t = parked[c * kWave + xo];
+                cxoff = t.x; cxsum = t.y; cpost = t.z;
+            }
+            const float s = (float)sh[p][c] * cpost;
+            const float z = (float)((zw[p][c] >> (4 * (goff[c] & 7))) & 0xFu);
+            // sum_k x_k (q_k - z) = (D - xoff) - z * xsum
+            acc = fmaf(s, dsel - fmaf(z, cxsum, cxoff), acc);
+            asm volatile("" : "+v"(acc), "+v"(xo));
+        }
+        const float v = wave_sum(acc);
+        ykeep = (lane == i) ? v : ykeep;
+    };
+
+    // main part: every consumed slot is refilled with the row kPR further on (clamped in
+    // the last trip); then the last kPR rows are drained without further loads
+    int r = 0;
+    for (; r + kPR < nrows; r += kPR) {
+#pragma unroll
+        for (int p = 0; p < kPR; ++p) {
+            consume(p, r + p);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                issue(p, c, min(rbase + min(r + p + kPR, ilast) * kGemvWaves, it.N - 1));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < kPR; ++p)
+        if (r + p < nrows) consume(p, r + p);
+    if (lane < nrows) it.y[rbase + lane * kGemvWaves] = f32_to_bf16_rne(ykeep);
+}
+
+template <int kUnits>
 __global__ __launch_bounds__(kGemvThreads) void w4a16_gemv_kernel(const GemvArgs args) {
     extern __shared__ uint4 lds[];
-    // layout: x pairs, K/8 uint4 (8 bf16 each, order x0,x4,x1,x5,x2,x6,x3,x7), then K/32 floats
-    const int wave = threadIdx.x / kWave;
-    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform: row
+    const int lane = threadIdx.x % kWave;                                  // addresses stay scalar
 
-    const int nb = gridDim.x;
-    const int p_begin = (int)(((long long)args.total_passes * blockIdx.x) / nb);
-    const int p_end = (int)(((long long)args.total_passes * (blockIdx.x + 1)) / nb);
+    int idx = 0;
+    while (idx + 1 < args.count && args.it[idx + 1].block_begin <= (int)blockIdx.x) ++idx;
+    idx = __builtin_amdgcn_readfirstlane(idx);
+    const GemvItem& it = args.it[idx];
+    const int K = it.K, N = it.N;
+    const int nch = (K + kWaveK - 1) / kWaveK;
 
-    int cur = -1;
-    for (int p = p_begin; p < p_end; ++p) {
-        int idx = 0;
-        while (idx + 1 < args.count && args.it[idx + 1].pass_begin <= p) ++idx;
-        idx = __builtin_amdgcn_readfirstlane(idx);
-        const GemvItem& it = args.it[idx];
-        const int K = it.K, N = it.N, g = it.g;
-        float* xs = reinterpret_cast<float*>(lds + K / 8);
+    // this block's slab of rows, then this wave's share of the slab
+    const int b = (int)blockIdx.x - it.block_begin;
+    const int s0 = (int)(((long long)N * b) / it.blocks);
+    const int s1 = (int)(((long long)N * (b + 1)) / it.blocks);
+    // Rows are dealt to the waves of the block in turn, so that at any moment the block's
+    // 16 waves read 16 adjacent rows: one contiguous stretch of memory per block.
+    const int r0 = s0 + wave;
+    const int r1 = max(0, (s1 - s0 - wave + kGemvWaves - 1) / kGemvWaves);  // number of rows
 
-        if (idx != cur) {
-            if (cur >= 0) __syncthreads();  // everyone is done with the previous x
-            const uint4* xg = reinterpret_cast<const uint4*>(it.x);
-            for (int i = threadIdx.x; i < K / 8; i += kGemvThreads) {
-                const uint4 v = xg[i];  // (x0,x1) (x2,x3) (x4,x5) (x6,x7)
-                uint4 o;
-                o.x = (v.x & 0xFFFFu) | (v.z << 16);          // x0,x4
-                o.y = (v.x >> 16) | (v.z & 0xFFFF0000u);      // x1,x5
-                o.z = (v.y & 0xFFFFu) | (v.w << 16);          // x2,x6
-                o.w = (v.y >> 16) | (v.w & 0xFFFF0000u);      // x3,x7
-                lds[i] = o;
-            }
-            __syncthreads();
-            for (int c = threadIdx.x; c < K / kChunkK; c += kGemvThreads) {
-                float s = 0.f;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint4 v = lds[c * 4 + j];
-                    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        s += __builtin_bit_cast(float, u[e] << 16) +
-                             __builtin_bit_cast(float, u[e] & 0xFFFF0000u);
-                }
-                xs[c] = s;
-            }
-            __syncthreads();
-            cur = idx;
-        }
-
-        const int G = K / g;
-        const int zwords = (G + 7) / 8;
-        const int kw = K / 8;
-        const int row0 = (p - it.pass_begin) * (kGemvWaves * R) + wave * R;
-
-        float acc[R];
-        int rown[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            acc[r] = 0.f;
-            rown[r] = min(row0 + r, N - 1);  // clamp: tail rows are read, not stored
-        }
-
-        for (int k0 = lane * kChunkK; k0 < K; k0 += kWaveK) {
-            const int grp = k0 / g;
-            uint4 q[R];
-            uint32_t sb[R], zw[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                q[r] = *reinterpret_cast<const uint4*>(it.qw + (size_t)rown[r] * kw + k0 / 8);
-                sb[r] = it.sc[(size_t)rown[r] * G + grp];
-                zw[r] = it.zr[(size_t)rown[r] * zwords + grp / 8];
-            }
-            const float xsum = xs[k0 / kChunkK];
-            const uint4* xl = lds + k0 / 8;
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const float d = dot32(q[r], xl);
-                const float s = f16_bits_to_f32((uint16_t)sb[r]);
-                const float zc = (float)(128u + ((zw[r] >> (4 * (grp & 7))) & 0xFu));
-                acc[r] = fmaf(s, fmaf(-zc, xsum, d), acc[r]);
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const float v = wave_sum(acc[r]);
-            if (lane == 0 && row0 + r < N) it.y[row0 + r] = f32_to_bf16_rne(v);
-        }
+    switch (nch) {
+        // about kUnits wave-wide loads (1 KB each) in flight per wave
+        case 1: stream_rows<1, kUnits>(it, r0, r1, lane, lds); break;
+        case 2: stream_rows<2, kUnits / 2>(it, r0, r1, lane, lds); break;
+        case 3: stream_rows<3, kUnits / 3>(it, r0, r1, lane, lds); break;
+        case 4: stream_rows<4, kUnits / 4>(it, r0, r1, lane, lds); break;
+        case 5: stream_rows<5, 1>(it, r0, r1, lane, lds); break;
+        default: stream_rows<6, 1>(it, r0, r1, lane, lds); break;
     }
 }
 
@@ -180,27 +369,61 @@ int device_cus() {
     return cus;
 }
 
-template <int R>
+size_t item_bytes(const qail_wdesc& d) {
+    const size_t G = (size_t)d.K / d.group_size;
+    return (size_t)d.N * (d.K / 2 + G * 2 + ((G + 7) / 8) * 4);
+}
+
 hipError_t launch_chunk(const qail_w4a16_item* items, int count, hipStream_t st) {
     GemvArgs a;
-    int passes = 0;
-    int maxK = 0;
+    int grid = device_cus();
+    if (grid < count) grid = count;
+    // blocks per item in proportion to its bytes (largest remainder), at least one each
+    double total = 0;
+    for (int i = 0; i < count; ++i) total += (double)item_bytes(items[i].d);
+    int nb[kGemvMaxItems];
+    double frac[kGemvMaxItems];
+    int used = 0;
+    for (int i = 0; i < count; ++i) {
+        const double share = (double)item_bytes(items[i].d) / total * grid;
+        nb[i] = (int)share;
+        if (nb[i] < 1) nb[i] = 1;
+        // a wave keeps its results in one register: at most 64 rows per wave
+        const int need = (items[i].d.N + kGemvWaves * kWave - 1) / (kGemvWaves * kWave);
+        if (nb[i] < need) nb[i] = need;
+        // no more blocks than 16-row slabs
+        const int cap = (items[i].d.N + kGemvWaves - 1) / kGemvWaves;
+        if (nb[i] > cap) nb[i] = cap;
+        frac[i] = share - (int)share;
+        used += nb[i];
+    }
+    while (used < grid) {
+        int best = -1;
+        for (int i = 0; i < count; ++i) {
+            const int cap = (items[i].d.N + kGemvWaves - 1) / kGemvWaves;
+            if (nb[i] < cap && (best < 0 || frac[i] > frac[best])) best = i;
+        }
+        if (best < 0) break;
+        ++nb[best];
+        frac[best] = -1.0;
+        ++used;
+    }
+    int maxK = 0, bb = 0;
     for (int i = 0; i < count; ++i) {
         const qail_w4a16_item& s = items[i];
         GemvItem& t = a.it[i];
         t.qw = s.qweight; t.sc = s.scales; t.zr = s.zeros; t.x = s.x; t.y = s.y;
         t.N = s.d.N; t.K = s.d.K; t.g = s.d.group_size;
-        t.pass_begin = passes;
-        passes += (s.d.N + kGemvWaves * R - 1) / (kGemvWaves * R);
+        t.block_begin = bb;
+        t.blocks = nb[i];
+        bb += nb[i];
         if (s.d.K > maxK) maxK = s.d.K;
     }
     for (int i = count; i < kGemvMaxItems; ++i) a.it[i] = a.it[count - 1];
     a.count = count;
-    a.total_passes = passes;
-    const size_t lds = (size_t)maxK * 2 + (size_t)(maxK / kChunkK) * 4;
-    int grid = device_cus();
-    if (grid > passes) grid = passes;
-    hipLaunchKernelGGL(w4a16_gemv_kernel<R>, dim3(grid), dim3(kGemvThreads), lds, st, a);
+    const int nch = (maxK + kWaveK - 1) / kWaveK;
+    const size_t lds = (size_t)nch * kWave * (4 * 16 + 4 + (nch > 4 ? 16 : 0));
+    hipLaunchKernelGGL(w4a16_gemv_kernel<8>, dim3(bb), dim3(kGemvThreads), lds, st, a);
     return hipGetLastError();
 }
 
@@ -213,14 +436,7 @@ bool gemv_supports(const qail_wdesc& d) {
 hipError_t launch_w4a16_gemv(const qail_w4a16_item* items, int count, hipStream_t st) {
     for (int i0 = 0; i0 < count; i0 += kGemvMaxItems) {
         const int c = (count - i0 < kGemvMaxItems) ? count - i0 : kGemvMaxItems;
-        long long rows = 0;
-        for (int i = 0; i < c; ++i) rows += items[i0 + i].d.N;
-        // more rows per wave once every CU has several passes to chew on
-        const long long per_cu = rows / device_cus();
-        hipError_t e;
-        if (per_cu >= 4 * kGemvWaves * 4) e = launch_chunk<4>(items + i0, c, st);
-        else if (per_cu >= 2 * kGemvWaves * 2) e = launch_chunk<2>(items + i0, c, st);
-        else e = launch_chunk<1>(items + i0, c, st);
+        const hipError_t e = launch_chunk(items + i0, c, st);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

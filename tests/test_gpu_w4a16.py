@@ -67,7 +67,8 @@ def test_config0_tiny_gemv(B):
     (37, 11008, 128),        # 86 groups: wave-wide load with a partial tail
     (130, 2048, 32),
     (64, 32, 32),            # a single 32-k chunk
-    (16, 16384, 128),        # largest K of the streaming kernel
+    (16, 12288, 128),        # largest K of the streaming kernel
+    (3, 14336, 128),         # just beyond it
     (5, 40, 8),              # shape only the generic kernel takes
     (24, 32768, 256),        # K beyond the streaming kernel
 ])
