@@ -262,14 +262,21 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, int rbase, int n
         // compiler can neither hoist the reads out of the row loop nor bunch them up.
         int xo = lane;
         asm volatile("" : "+v"(xo));
-        uint4 xv[2][4];
+        constexpr int kXB = kParked ? 1 : 2;  // long rows: no read-ahead, to stay within the registers
+        uint4 xv[kXB][4];
+        if (kXB == 2) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) xv[0][j] = xlds[j * kWave + xo];
+            for (int j = 0; j < 4; ++j) xv[0][j] = xlds[j * kWave + xo];
+        }
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            if (c + 1 < NCH) {
+            if (kXB == 2 && c + 1 < NCH) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) xv[(c + 1) & 1][j] = xlds[((c + 1) * 4 + j) * kWave + xo];
+            }
+            if (kXB == 1) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xv[0][j] = xlds[(c * 4 + j) * kWave + xo];
             }
             const uint32_t w[4] = {q[p][c].x, q[p][c].y, q[p][c].z, q[p][c].w};
             f32x4_t d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
@@ -279,7 +286,7 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, int rbase, int n
                 const uint32_t w8 = w[j] >> 8;
                 const uint2 a01 = make_uint2((w[j] & 0x000F000Fu) | magic, (w[j] & 0x00F000F0u) | magic);
                 const uint2 a23 = make_uint2((w8 & 0x000F000Fu) | magic, (w8 & 0x00F000F0u) | magic);
-                const uint4 xj = xv[c & 1][j];
+                const uint4 xj = xv[c & (kXB - 1)][j];
                 d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a01),
                                                         __builtin_bit_cast(f16x4_t, make_uint2(xj.x, xj.y)), d0, 0, 0, 0);
                 d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a23),
