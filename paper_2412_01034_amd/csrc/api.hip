@@ -31,7 +31,7 @@ int check_conv(const qail_conv_desc* d) {
     const long long OH = (d->H + 2 * d->pad - d->KH) / d->stride + 1;
     const long long OW = (d->W + 2 * d->pad - d->KW) / d->stride + 1;
     const long long M = (long long)d->B * OH * OW;
-    if (M > 0x7FFFFFFFll / 2 || M / 128 + 1 > 65535) return QAIL_ERR_UNSUPPORTED;
+    if (M > 0x7FFFFFFFll / 2 || M / 64 + 1 > 65535) return QAIL_ERR_UNSUPPORTED;
     if ((long long)d->B * d->H * d->W > 0x7FFFFFFFll) return QAIL_ERR_UNSUPPORTED;
     return QAIL_OK;
 }

@@ -19,6 +19,11 @@
 // (B) l%16 and the 16 consecutive k starting at 16*(l/16); it receives
 // D[4*(l/16)+r][l%16], r = 0..3.  A = activations (rows m), B = weights (columns n).
 //
+// Tiling: a block of 4 waves (2 x 2) owns a BM x BN output tile and walks K in
+// steps of 128 codes (16 packed words per row; K is ordered (kh, kw, c), so a step
+// is a run of channels of one or two filter taps).  Nibbles stay packed in LDS
+// (half the LDS traffic of int8); global loads run several steps ahead in a register
+// ring and are moved to one of two LDS buffers when they are due, one barrier per step.
 // Zero padding costs nothing: code 0 of the unsigned activations is the value 0.
 #include "qail_internal.h"
 
@@ -26,111 +31,198 @@ namespace qail {
 
 namespace {
 
-constexpr int kCBM = 128, kCBN = 64, kCBK = 64;  // block tile; kCBK codes = 8 words of one filter tap
-constexpr int kCPitch = 8 + 4;                   // words per LDS row (48 B)
+constexpr int kStepWords = 16;  // packed words per row per K step (128 codes)
+constexpr int kPitchW = 18;     // words per LDS row: 8-byte aligned, conflict-free for the fragment reads
 
 struct ConvGeom {
     int B, H, W, Cin, Cout, KH, KW, stride, pad, OH, OW, M;
 };
 
-__global__ __launch_bounds__(256) void w4a4_conv_kernel(
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+
+// Raw buffer descriptor over [p, p + bytes): loads past the end return 0 and stores past the
+// end are dropped by the hardware, which turns every image-border, K-tail and tile-edge test
+// into the choice of an offset.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+constexpr uint32_t kOut = 0xFFFFFFF0u;  // an offset no buffer here reaches
+
+template <int BM, int BN, int kDepth>
+__global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv_kernel(
     const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w,
     int32_t* __restrict__ acc_out, const float* __restrict__ scale, const float* __restrict__ bias,
     float* __restrict__ y_out) {
-    __shared__ __attribute__((aligned(16))) uint32_t As[kCBM * kCPitch];
-    __shared__ __attribute__((aligned(16))) uint32_t Bs[kCBN * kCPitch];
+    constexpr int kAR = BM / 64;   // A rows per thread
+    constexpr int kBR = BN / 64;   // B rows per thread
+    constexpr int kTM = BM / 32;   // MFMA tiles per wave along m
+    constexpr int kTN = BN / 32;   // ... along n
+    __shared__ __attribute__((aligned(16))) uint32_t As[2][BM * kPitchW];
+    __shared__ __attribute__((aligned(16))) uint32_t Bs[2][BN * kPitchW];
 
     const int t = threadIdx.x;
-    const int lane = t % kWave, wave = t / kWave;
-    const int wm = wave / 2, wn = wave % 2;  // 2 x 2 waves, each 64 (m) x 32 (n)
-    const int bm = blockIdx.y * kCBM, bn = blockIdx.x * kCBN;
+    const int lane = t % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(t / kWave);
+    const int wm = wave / 2, wn = wave % 2;
+    const int bm = blockIdx.y * BM, bn = blockIdx.x * BN;
     const int cw = gm.Cin / 8;                 // words per pixel
     const int kwords = gm.KH * gm.KW * cw;     // words per filter
+    const int steps = (kwords + kStepWords - 1) / kStepWords;
+    const int ntaps = gm.KH * gm.KW;
 
-    // this thread's share of the A tile: row t/2, 4 words at (t%2)*4
-    const int arow = t >> 1, ahalf = t & 1;
-    const int am = bm + arow;
-    const bool am_ok = am < gm.M;
-    int ab = 0, ih0 = 0, iw0 = 0;
-    if (am_ok) {
-        ab = am / (gm.OH * gm.OW);
-        const int rem = am - ab * (gm.OH * gm.OW);
-        const int oh = rem / gm.OW, ow = rem - oh * gm.OW;
-        ih0 = oh * gm.stride - gm.pad;
-        iw0 = ow * gm.stride - gm.pad;
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(a, (uint32_t)((size_t)gm.B * gm.H * gm.W * cw * 4));
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)((size_t)gm.Cout * kwords * 4));
+
+    // Loader geometry: thread t loads words [4q, 4q+4) of a step for rows t/4 + 64*i: the four
+    // lanes of a row fetch 64 contiguous bytes.
+    const int q = t & 3, lrow = t >> 2;
+    int abase[kAR];       // byte offset of (b, ih0, iw0, 0); may be negative at the border
+    uint32_t amask[kAR];  // bit tap = the tap's pixel is inside the image
+#pragma unroll
+    for (int i = 0; i < kAR; ++i) {
+        const int m = bm + lrow + 64 * i;
+        abase[i] = 0;
+        amask[i] = 0;
+        if (m < gm.M) {
+            const int b = m / (gm.OH * gm.OW);
+            const int rem = m - b * (gm.OH * gm.OW);
+            const int oh = rem / gm.OW, ow = rem - oh * gm.OW;
+            const int ih0 = oh * gm.stride - gm.pad, iw0 = ow * gm.stride - gm.pad;
+            abase[i] = ((b * gm.H + ih0) * gm.W + iw0) * cw * 4;
+            for (int kh = 0; kh < gm.KH; ++kh)
+                for (int kwi = 0; kwi < gm.KW; ++kwi)
+                    if (ih0 + kh >= 0 && ih0 + kh < gm.H && iw0 + kwi >= 0 && iw0 + kwi < gm.W)
+                        amask[i] |= 1u << (kh * gm.KW + kwi);
+        }
     }
-    // B tile: 64 rows x 8 words; threads 0..127: row t/2, 4 words at (t%2)*4
-    const int brow = (t >> 1) & 63;
-    const int bnrow = min(bn + brow, gm.Cout - 1);
-
-    i32x4_t acc[4][2];
+    uint32_t bbase[kBR];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = i32x4_t{0, 0, 0, 0};
+    for (int i = 0; i < kBR; ++i) {
+        const int n = bn + lrow + 64 * i;
+        bbase[i] = n < gm.Cout ? (uint32_t)n * kwords * 4 : kOut;
+    }
 
-    for (int kh = 0; kh < gm.KH; ++kh) {
-        for (int kwi = 0; kwi < gm.KW; ++kwi) {
-            const int ih = ih0 + kh, iw = iw0 + kwi;
-            const bool in = am_ok && ih >= 0 && ih < gm.H && iw >= 0 && iw < gm.W;
-            const uint32_t* ap = a + ((size_t)(ab * gm.H + (in ? ih : 0)) * gm.W + (in ? iw : 0)) * cw;
-            const uint32_t* wp = w + (size_t)bnrow * kwords + (size_t)(kh * gm.KW + kwi) * cw;
-            for (int c0 = 0; c0 < cw; c0 += 8) {
-                uint4 av = make_uint4(0, 0, 0, 0);
-                if (in) av = *reinterpret_cast<const uint4*>(ap + c0 + ahalf * 4);
-                uint4 bv = make_uint4(0, 0, 0, 0);
-                if (t < 128) bv = *reinterpret_cast<const uint4*>(wp + c0 + ahalf * 4);
-                __syncthreads();
-                *reinterpret_cast<uint4*>(&As[arow * kCPitch + ahalf * 4]) = av;
-                if (t < 128) *reinterpret_cast<uint4*>(&Bs[brow * kCPitch + ahalf * 4]) = bv;
-                __syncthreads();
-
-                i32x4_t af[4], bf[2];
+    // Register ring of kDepth K-steps of loads: a step's loads are issued kDepth steps before
+    // they are needed (a step is only a few hundred MFMA cycles, far less than a cache
+    // latency).  Nothing about a load is conditional, so the loads in flight at every wait are
+    // known at compile time.
+    u32x4_t ar[kDepth][kAR], br[kDepth][kBR];
+    // position of the next step to issue (per thread: it depends on q), advanced without divisions
+    int nkw0 = 4 * q, ncword = 4 * q, ntap = 0, ntapoff = 0, nkwi = 0;
+    auto advance = [&](int words) {
+        nkw0 += words;
+        ncword += words;
+        while (ncword >= cw) {
+            ncword -= cw;
+            ++ntap;
+            ntapoff += cw * 4;
+            if (++nkwi == gm.KW) { nkwi = 0; ntapoff += (gm.W - gm.KW) * cw * 4; }
+        }
+    };
+    advance(0);
+    auto issue = [&](int d) {
+        const bool kin = ntap < ntaps;
+        const int koff = ntapoff + ncword * 4;  // bytes from (ih0, iw0, 0) to this tap's words
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < kAR; ++i) {
+            const bool in = kin && ((amask[i] >> ntap) & 1u);
+            ar[d][i] = __builtin_amdgcn_raw_buffer_load_b128(ra, in ? (uint32_t)(abase[i] + koff) : kOut, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < kBR; ++i)
+            br[d][i] = __builtin_amdgcn_raw_buffer_load_b128(rw, kin ? bbase[i] + (uint32_t)nkw0 * 4 : kOut, 0, 0);
+        advance(kStepWords);
+    };
+    auto store_lds = [&](int d, int buf) {
+#pragma unroll
+        for (int i = 0; i < kAR; ++i) {
+            uint2* dst = reinterpret_cast<uint2*>(&As[buf][(lrow + 64 * i) * kPitchW + 4 * q]);
+            dst[0] = make_uint2(ar[d][i].x, ar[d][i].y);
+            dst[1] = make_uint2(ar[d][i].z, ar[d][i].w);
+        }
+#pragma unroll
+        for (int i = 0; i < kBR; ++i) {
+            uint2* dst = reinterpret_cast<uint2*>(&Bs[buf][(lrow + 64 * i) * kPitchW + 4 * q]);
+            dst[0] = make_uint2(br[d][i].x, br[d][i].y);
+            dst[1] = make_uint2(br[d][i].z, br[d][i].w);
+        }
+    };
+
+    i32x4_t acc[kTM][kTN];
+#pragma unroll
+    for (int i = 0; i < kTM; ++i)
+#pragma unroll
+        for (int j = 0; j < kTN; ++j) acc[i][j] = i32x4_t{0, 0, 0, 0};
+
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+        issue(d);  // steps past the end of K read nothing
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    for (int s0 = 0; s0 < steps; s0 += kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            if (s0 + d >= steps) break;
+            const int buf = d & 1;  // kDepth is even
+            store_lds(d, buf);
+            issue(d);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {  // two MFMA k-steps of 64 codes (8 words)
+                i32x4_t af[kTM], bf[kTN];
+#pragma unroll
+                for (int i = 0; i < kTM; ++i) {
                     const uint2 p = *reinterpret_cast<const uint2*>(
-                        &As[(wm * 64 + i * 16 + (lane & 15)) * kCPitch + (lane >> 4) * 2]);
+                        &As[buf][(wm * (BM / 2) + i * 16 + (lane & 15)) * kPitchW + sub * 8 + (lane >> 4) * 2]);
                     af[i] = i32x4_t{(int)(p.x & 0x0F0F0F0Fu), (int)((p.x >> 4) & 0x0F0F0F0Fu),
                                     (int)(p.y & 0x0F0F0F0Fu), (int)((p.y >> 4) & 0x0F0F0F0Fu)};
                 }
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
+                for (int j = 0; j < kTN; ++j) {
                     const uint2 p = *reinterpret_cast<const uint2*>(
-                        &Bs[(wn * 32 + j * 16 + (lane & 15)) * kCPitch + (lane >> 4) * 2]);
+                        &Bs[buf][(wn * (BN / 2) + j * 16 + (lane & 15)) * kPitchW + sub * 8 + (lane >> 4) * 2]);
                     bf[j] = i32x4_t{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
                                     (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < kTM; ++i)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+                    for (int j = 0; j < kTN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
             }
         }
     }
 
+    // Epilogue through buffer stores: rows past M and columns past Cout get an offset past the
+    // end and are dropped.
+    const uint32_t out_bytes = (uint32_t)((size_t)gm.M * gm.Cout * 4);
+    const __amdgpu_buffer_rsrc_t racc = make_rsrc(acc_out, acc_out ? out_bytes : 0);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(y_out, y_out ? out_bytes : 0);
+    const int m0 = bm + wm * (BM / 2) + (lane >> 4) * 4;
+    const int n0 = bn + wn * (BN / 2) + (lane & 15);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < kTN; ++j) {
+        const int n = n0 + j * 16;
+        const bool nin = n < gm.Cout;
+        const float sc = (y_out && nin) ? scale[n] : 0.f;
+        const float bi = (y_out && nin) ? bias[n] : 0.f;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = bn + wn * 32 + j * 16 + (lane & 15);
-            if (n >= gm.Cout) continue;
-            const float sc = y_out ? scale[n] : 0.f;
-            const float bi = y_out ? bias[n] : 0.f;
+        for (int i = 0; i < kTM; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int m = bm + wm * 64 + i * 16 + (lane >> 4) * 4 + r;
-                if (m >= gm.M) continue;
+                const int m = m0 + i * 16 + r;
+                const uint32_t off = (nin && m < gm.M) ? (uint32_t)(m * gm.Cout + n) * 4 : kOut;
                 const int v = acc[i][j][r] >> 4;  // exact: the accumulator is 16 * result
-                const size_t o = (size_t)m * gm.Cout + n;
-                if (acc_out) acc_out[o] = v;
-                if (y_out) y_out[o] = fmaf((float)v, sc, bi);
+                if (acc_out) __builtin_amdgcn_raw_buffer_store_b32((uint32_t)v, racc, off, 0, 0);
+                if (y_out) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, fmaf((float)v, sc, bi)), ry, off, 0, 0);
             }
-        }
+    }
 }
 
 // Any Cin % 8 == 0: one thread per output.  Slow; for shapes whose Cin is not a
-// multiple of 64.
+// multiple of 32, more than 32 filter taps, or tensors of 4 GB and more.
 __global__ __launch_bounds__(256) void w4a4_generic_kernel(
     const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w,
     int32_t* __restrict__ acc_out, const float* __restrict__ scale, const float* __restrict__ bias,
@@ -163,6 +255,25 @@ __global__ __launch_bounds__(256) void w4a4_generic_kernel(
     if (y_out) y_out[o] = fmaf((float)acc, scale[n], bias[n]);
 }
 
+int conv_cus() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+template <int BM, int BN, int kDepth>
+void launch_tiled(const ConvGeom& gm, const uint32_t* a, const uint32_t* w, int32_t* acc, const float* scale,
+                  const float* bias, float* y, hipStream_t st) {
+    dim3 grid((gm.Cout + BN - 1) / BN, (gm.M + BM - 1) / BM);
+    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN, kDepth>), grid, dim3(256), 0, st, gm, a, w, acc, scale, bias, y);
+}
+
 }  // namespace
 
 hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
@@ -173,9 +284,20 @@ hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const ui
     gm.OH = (d.H + 2 * d.pad - d.KH) / d.stride + 1;
     gm.OW = (d.W + 2 * d.pad - d.KW) / d.stride + 1;
     gm.M = d.B * gm.OH * gm.OW;
-    if (d.Cin % kCBK == 0) {
-        dim3 grid((d.Cout + kCBN - 1) / kCBN, (gm.M + kCBM - 1) / kCBM);
-        hipLaunchKernelGGL(w4a4_conv_kernel, grid, dim3(256), 0, st, gm, a, w, acc, scale, bias, y);
+    const bool fits32 = (size_t)gm.B * gm.H * gm.W * (gm.Cin / 2) < 0xFFFFFFF0ull &&
+                        (size_t)gm.Cout * gm.KH * gm.KW * (gm.Cin / 2) < 0xFFFFFFF0ull &&
+                        (size_t)gm.M * gm.Cout * 4 < 0xFFFFFFF0ull;
+    if (d.Cin % 32 == 0 && d.KH * d.KW <= 32 && fits32) {
+        // the largest tile that still gives every CU about two blocks
+        const long long want = 2LL * conv_cus();
+        auto blocks = [&](int bm, int bn) {
+            return (long long)((gm.M + bm - 1) / bm) * ((gm.Cout + bn - 1) / bn);
+        };
+        const bool wide = gm.Cout > 64;
+        if (wide && blocks(128, 128) >= want) launch_tiled<128, 128, 2>(gm, a, w, acc, scale, bias, y, st);
+        else if (blocks(128, 64) >= want) launch_tiled<128, 64, 2>(gm, a, w, acc, scale, bias, y, st);
+        else if (wide && blocks(64, 128) >= want / 2) launch_tiled<64, 128, 2>(gm, a, w, acc, scale, bias, y, st);
+        else launch_tiled<64, 64, 2>(gm, a, w, acc, scale, bias, y, st);
     } else {
         const size_t outs = (size_t)gm.M * d.Cout;
         hipLaunchKernelGGL(w4a4_generic_kernel, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st, gm,
