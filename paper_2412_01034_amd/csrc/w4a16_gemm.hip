@@ -17,7 +17,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 
-constexpr int kBM = 128, kBN = 128, kBK = 64;
+constexpr int kBN = 128, kBK = 64;
 constexpr int kPitch = kBK + 8;  // bf16 elements per LDS row (144 B: 16-byte aligned)
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -26,22 +26,33 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
-// 8 codes of one word -> 8 bf16 (q - z) * s, in k order.
-__device__ __forceinline__ uint4 dequant8(uint32_t w, float s, float zc) {
+// 8 codes of one word -> 8 bf16 (q - z) * s, in k order.  The even and the odd codes are
+// masked into bytes, converted with the byte-to-float instruction, and q * s - z * s is one
+// fused multiply-add (both products are exact, so the result is the exact (q - z) * s).
+__device__ __forceinline__ uint4 dequant8(uint32_t w, float s, float nzs) {
+    const uint32_t e = w & 0x0F0F0F0Fu, o = (w >> 4) & 0x0F0F0F0Fu;
     float d[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const uint32_t t = ((w >> (4 * i)) & 0x000F000Fu) | 0x43004300u;  // bf16 (128+c_i, 128+c_{i+4})
-        d[i] = (__builtin_bit_cast(float, t << 16) - zc) * s;
-        d[i + 4] = (__builtin_bit_cast(float, t & 0xFFFF0000u) - zc) * s;
+        d[2 * i] = fmaf((float)((e >> (8 * i)) & 0xFFu), s, nzs);
+        d[2 * i + 1] = fmaf((float)((o >> (8 * i)) & 0xFFu), s, nzs);
     }
     return make_uint4(pack_bf16(d[0], d[1]), pack_bf16(d[2], d[3]), pack_bf16(d[4], d[5]),
                       pack_bf16(d[6], d[7]));
 }
 
-__global__ __launch_bounds__(256) void w4a16_gemm_kernel(
+// Block tile (64 * kWM) x 128 with kWM x 2 waves of 64 x 64, K step 64, one LDS buffer.
+// The weight tile is dequantised once per block and step, so a taller tile spreads that
+// vector-ALU work over more matrix work; the next step's global loads are in flight while
+// the current step's MFMAs run.
+template <int kWM>
+__global__ __launch_bounds__(128 * kWM) void w4a16_gemm_kernel(
     const uint32_t* __restrict__ qw, const uint16_t* __restrict__ sc, const uint32_t* __restrict__ zr,
     const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int M, int N, int K, int g) {
+    constexpr int kBM = 64 * kWM;
+    constexpr int kThreads = 128 * kWM;
+    constexpr int kBT = kThreads < 512 ? kThreads : 512;  // threads that load weights
+    constexpr int kBW = 1024 / kBT;                       // packed words per such thread: 8, 4 or 2
     __shared__ __attribute__((aligned(16))) uint16_t As[kBM * kPitch];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[kBN * kPitch];
 
@@ -57,40 +68,65 @@ __global__ __launch_bounds__(256) void w4a16_gemm_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    const int brow = t >> 1, bhalf = t & 1;
+    // weight loader: row t / (8 / kBW), words [kBW * part, kBW * (part + 1)) of the step's 8
+    constexpr int kParts = 8 / kBW;
+    const bool bact = t < kBT;
+    const int brow = (t / kParts) & 127, bpart = t % kParts;
     const int bnrow = min(bn + brow, N - 1);
+    const uint32_t* qrow = qw + (size_t)bnrow * kw + bpart * kBW;
+    const _Float16* srow = reinterpret_cast<const _Float16*>(sc) + (size_t)bnrow * G;
+    const uint32_t* zrow = zr + (size_t)bnrow * zwords;
 
-    for (int k0 = 0; k0 < K; k0 += kBK) {
-        uint4 av[4];
+    // this thread's share of one K step, fetched one step ahead of its use
+    uint4 av[4];
+    uint32_t qv[kBW];
+    _Float16 sh = (_Float16)0.f;  // kept in its loaded type: a widening at the load would wait there
+    uint32_t zword = 0;
+    auto gload = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int idx = t + 256 * i;
+            const int idx = t + kThreads * i;
             const int row = idx >> 3, seg = idx & 7;
             const int m = bm + row;
             av[i] = (m < M) ? *reinterpret_cast<const uint4*>(x + (size_t)m * K + k0 + seg * 8)
                             : make_uint4(0, 0, 0, 0);
         }
-        const int kb = k0 + bhalf * 32;
-        const int grp = kb / g;
-        const uint4 qv = *reinterpret_cast<const uint4*>(qw + (size_t)bnrow * kw + kb / 8);
-        const float s = f16_bits_to_f32(sc[(size_t)bnrow * G + grp]);
-        const float zc = (float)(128u + ((zr[(size_t)bnrow * zwords + grp / 8] >> (4 * (grp & 7))) & 0xFu));
+        if (bact) {
+            const int grp = (k0 + bpart * kBW * 8) / g;
+            if (kBW == 2) {
+                const uint2 v = *reinterpret_cast<const uint2*>(qrow + k0 / 8);
+                qv[0] = v.x; qv[1] = v.y;
+            } else {
+#pragma unroll
+                for (int u = 0; u < kBW; u += 4) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(qrow + k0 / 8 + u);
+                    qv[u] = v.x; qv[u + 1] = v.y; qv[u + 2] = v.z; qv[u + 3] = v.w;
+                }
+            }
+            sh = srow[grp];
+            zword = zrow[grp / 8];
+        }
+    };
+    gload(0);
 
+    for (int k0 = 0; k0 < K; k0 += kBK) {
         __syncthreads();  // previous step's MFMAs have read LDS
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int idx = t + 256 * i;
+            const int idx = t + kThreads * i;
             const int row = idx >> 3, seg = idx & 7;
             *reinterpret_cast<uint4*>(&As[row * kPitch + seg * 8]) = av[i];
         }
-        {
-            uint4* dst = reinterpret_cast<uint4*>(&Bs[brow * kPitch + bhalf * 32]);
-            dst[0] = dequant8(qv.x, s, zc);
-            dst[1] = dequant8(qv.y, s, zc);
-            dst[2] = dequant8(qv.z, s, zc);
-            dst[3] = dequant8(qv.w, s, zc);
+        if (bact) {
+            const int grp = (k0 + bpart * kBW * 8) / g;
+            const float s = (float)sh;
+            const float nzs = -(float)((zword >> (4 * (grp & 7))) & 0xFu) * s;
+            uint4* dst = reinterpret_cast<uint4*>(&Bs[brow * kPitch + bpart * kBW * 8]);
+#pragma unroll
+            for (int u = 0; u < kBW; ++u) dst[u] = dequant8(qv[u], s, nzs);
         }
         __syncthreads();
+        if (k0 + kBK < K) gload(k0 + kBK);  // lands while the MFMAs below run
 
 #pragma unroll
         for (int kk = 0; kk < kBK; kk += 32) {
@@ -152,11 +188,23 @@ __global__ __launch_bounds__(256) void w4a16_generic_kernel(
 
 }  // namespace
 
-hipError_t launch_w4a16_gemm(const qail_w4a16_item& it, int M, hipStream_t st) {
+namespace {
+template <int kWM>
+hipError_t launch_gemm_tile(const qail_w4a16_item& it, int M, hipStream_t st) {
+    constexpr int kBM = 64 * kWM;
     dim3 grid((it.d.N + kBN - 1) / kBN, (M + kBM - 1) / kBM);
-    hipLaunchKernelGGL(w4a16_gemm_kernel, grid, dim3(256), 0, st, it.qweight, it.scales, it.zeros, it.x,
-                       it.y, M, it.d.N, it.d.K, it.d.group_size);
+    hipLaunchKernelGGL(w4a16_gemm_kernel<kWM>, grid, dim3(128 * kWM), 0, st, it.qweight, it.scales, it.zeros,
+                       it.x, it.y, M, it.d.N, it.d.K, it.d.group_size);
     return hipGetLastError();
+}
+}  // namespace
+
+// 64-row tiles for small batches, 128-row tiles otherwise.  (Taller tiles with more waves
+// spread the dequantisation further but leave too few blocks for 256 CUs at these shapes:
+// measured slower.)
+hipError_t launch_w4a16_gemm(const qail_w4a16_item& it, int M, hipStream_t st) {
+    if (M <= 64) return launch_gemm_tile<1>(it, M, st);
+    return launch_gemm_tile<2>(it, M, st);
 }
 
 hipError_t launch_w4a16_generic(const qail_w4a16_item& it, int M, hipStream_t st) {
