@@ -176,7 +176,16 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
         }
         return QAIL_OK;
     }
-    for (int i = 0; i < count; ++i) {
+    int i = 0;
+    while (i < count) {
+        // runs of items the small-batch streaming kernel takes go out together
+        int j = i;
+        while (j < count && smallm_supports(items[j].d, M)) ++j;
+        if (j > i) {
+            if (launch_w4a16_smallm(items + i, j - i, M, st) != hipSuccess) return QAIL_ERR_HIP;
+            i = j;
+            continue;
+        }
         const qail_wdesc& d = items[i].d;
         hipError_t e;
         if (d.K % 64 == 0 && d.group_size % 64 == 0)
@@ -184,6 +193,7 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
         else
             e = launch_w4a16_generic(items[i], M, st);
         if (e != hipSuccess) return QAIL_ERR_HIP;
+        ++i;
     }
     return QAIL_OK;
 }

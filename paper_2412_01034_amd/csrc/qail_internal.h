@@ -47,6 +47,8 @@ hipError_t launch_act_quant(const float* a, size_t n, const float* s_a, uint32_t
 // kernel arguments.
 bool gemv_supports(const qail_wdesc& d);
 hipError_t launch_w4a16_gemv(const qail_w4a16_item* items, int count, hipStream_t st);
+bool smallm_supports(const qail_wdesc& d, int M);
+hipError_t launch_w4a16_smallm(const qail_w4a16_item* items, int count, int M, hipStream_t st);
 hipError_t launch_w4a16_gemm(const qail_w4a16_item& it, int M, hipStream_t st);
 hipError_t launch_w4a16_generic(const qail_w4a16_item& it, int M, hipStream_t st);
 

@@ -77,10 +77,20 @@ def test_gemv_shapes(B, N, K, g):
 
 
 @pytest.mark.parametrize("M", [2, 4, 16, 100, 288])
-@pytest.mark.parametrize("N,K,g", [(200, 1024, 128), (384, 4096, 128), (72, 11008, 128), (16, 64, 64), (9, 48, 16)])
+@pytest.mark.parametrize("N,K,g", [(200, 1024, 128), (384, 4096, 128), (72, 11008, 128), (16, 64, 64), (9, 48, 16),
+                                   (1000, 4096, 128),     # ragged last 16-row tile
+                                   (37, 6144, 128),       # odd N, largest K of the small-batch stream
+                                   (5, 128, 128),         # one 128-k step: 15 of the 16 K-slices are empty
+                                   (2100, 2048, 256)])    # several blocks, group of two steps
 def test_batched_shapes(B, M, N, K, g):
     check(B, N, K, g, M, 3 * M + N, w_kw=dict(outlier_frac=0.01), x_kw=dict(outlier_frac=0.005),
           tol=TOL if K >= 512 else TOL_TINY_K)
+
+
+@pytest.mark.parametrize("M", [3, 7, 15])
+def test_small_batch_odd_row_counts(B, M):
+    check(B, 333, 4096, 128, M, 900 + M, w_kw=dict(outlier_frac=0.01), x_kw=dict(outlier_frac=0.005))
+    check(B, 64, 1536, 128, M, 950 + M)
 
 
 @pytest.mark.parametrize("M", [1, 4, 16, 130])
