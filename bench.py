@@ -263,7 +263,9 @@ def main():
             io = with_io(M)
             for i, (name, N, K) in enumerate(shapes):
                 it = B.make_w4a16_items([io[0][1][i]], M)
-                t = timed(lambda: B.qail_w4a16_linear_batch(it, 1, M, None, sh), 20)
+                nws = B.qail_w4a16_batch_workspace(it, 1, M)
+                ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+                t = timed(lambda: B.qail_w4a16_linear_batch(it, 1, M, ws, sh), 20)
                 tf = 2.0 * M * N * K / t / 1e12
                 pre[f"{name}_M{M}"] = {"us": round(t * 1e6, 1), "TFLOPs": round(tf, 1),
                                        "frac_bf16_peak": round(tf / BF16_PEAK_TFLOPS, 4)}

@@ -128,14 +128,21 @@ int qail_quantize_act_u4(const float* a, size_t n, const float* s_a, uint32_t* a
  * Sec. 2.1 (weight-only quantised GEMM operand); appendix "Analysis" (decode is
  * the memory-bound stage, prefill the compute-heavy one). */
 
-/* Bytes of scratch the call below needs for this (d, M); may be 0. */
+/* Bytes of device scratch the call below needs for this (d, M).  0 for the streaming
+ * kernels (M <= 16 on shapes they take); for the matrix-core GEMM it holds an fp16 copy
+ * of x (rows padded to a multiple of 128, K to a multiple of 128) plus one float per
+ * padded row and per output column.  The workspace must be 256-byte aligned, is
+ * overwritten by every call and carries nothing between calls; calls that share one
+ * must be ordered on one stream. */
 int qail_w4a16_workspace(const qail_wdesc* d, int32_t M, size_t* bytes);
 
 /* d must be ASYM_GROUP.  x: bf16 [M][K]; y: bf16 [M][N].  Products are accumulated
  * in fp32 and rounded once to bf16 (nearest even).  M = 1 (decode) is served by a
  * bandwidth-bound streaming kernel, 2 <= M <= 16 by a weight-streaming MFMA kernel,
- * larger M (prefill) by an LDS-tiled bf16 MFMA kernel that dequantises weights to
- * bf16 first.  workspace may be NULL when the query returns 0. */
+ * larger M (prefill) by an fp16 MFMA kernel that expands the codes in registers
+ * ((q - z) * s rounded once to fp16, x rescaled per row by a power of two).
+ * workspace may be NULL when the query returns 0; otherwise a missing or short one
+ * is QAIL_ERR_WORKSPACE and a misaligned one QAIL_ERR_ALIGN. */
 int qail_w4a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales,
                       const uint32_t* zeros, const uint16_t* x, uint16_t* y, int32_t M,
                       void* workspace, size_t workspace_bytes, void* stream);
@@ -157,6 +164,8 @@ typedef struct {
  * them in fewer launches.  count >= 0 (0 is a no-op). */
 int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t M,
                             void* workspace, size_t workspace_bytes, void* stream);
+/* Workspace for the batch call: the largest need of any item (the items run one after
+ * the other on the stream and share it). */
 int qail_w4a16_batch_workspace(const qail_w4a16_item* items, int32_t count, int32_t M,
                                size_t* bytes);
 

@@ -1,6 +1,8 @@
 // C entry points of libqail: argument validation and dispatch.  Every check is
 // done on the host before the first HIP call, so that the error paths can be
 // exercised on a machine without a GPU.
+#include <algorithm>
+
 #include "qail_internal.h"
 
 using namespace qail;
@@ -124,13 +126,19 @@ int qail_quantize_act_u4(const float* a, size_t n, const float* s_a, uint32_t* a
     return hip_status(launch_act_quant(a, n, s_a, a_u4, static_cast<hipStream_t>(stream)));
 }
 
+// Workspace one linear needs at batch M: only the matrix-core GEMM (M > 16) uses any.
+static size_t item_workspace(const qail_wdesc& d, int M) {
+    if (M == 1 || smallm_supports(d, M) || !gemm_f16_supports(d, M)) return 0;
+    return gemm_f16_workspace(d, M);
+}
+
 int qail_w4a16_workspace(const qail_wdesc* d, int32_t M, size_t* bytes) {
     const int e = check_wdesc(d);
     if (e != QAIL_OK) return e;
     if (d->scheme != QAIL_W4_ASYM_GROUP) return QAIL_ERR_UNSUPPORTED;
     if (M < 1) return QAIL_ERR_SHAPE;
     if (!bytes) return QAIL_ERR_NULL;
-    *bytes = 0;
+    *bytes = item_workspace(*d, M);
     return QAIL_OK;
 }
 
@@ -142,20 +150,27 @@ int qail_w4a16_batch_workspace(const qail_w4a16_item* items, int32_t count, int3
         if (e != QAIL_OK) return e;
         if (items[i].d.scheme != QAIL_W4_ASYM_GROUP) return QAIL_ERR_UNSUPPORTED;
     }
-    *bytes = 0;
+    // the linears of a batch run one after the other on the stream and share the workspace
+    size_t need = 0;
+    for (int i = 0; i < count; ++i) need = std::max(need, item_workspace(items[i].d, M));
+    *bytes = need;
     return QAIL_OK;
 }
 
 int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t M, void* workspace,
                             size_t workspace_bytes, void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
     if (count == 0) return QAIL_OK;
     if (!items) return QAIL_ERR_NULL;
+    size_t need = 0;
     for (int i = 0; i < count; ++i) {
         const int e = check_item(items[i], M);
         if (e != QAIL_OK) return e;
+        need = std::max(need, item_workspace(items[i].d, M));
+    }
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return QAIL_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QAIL_ERR_ALIGN;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (M == 1) {
@@ -188,8 +203,8 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
         }
         const qail_wdesc& d = items[i].d;
         hipError_t e;
-        if (d.K % 64 == 0 && d.group_size % 64 == 0)
-            e = launch_w4a16_gemm(items[i], M, st);
+        if (gemm_f16_supports(d, M))
+            e = launch_w4a16_gemm_f16(items[i], M, workspace, st);
         else
             e = launch_w4a16_generic(items[i], M, st);
         if (e != hipSuccess) return QAIL_ERR_HIP;

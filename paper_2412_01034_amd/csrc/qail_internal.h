@@ -49,7 +49,10 @@ bool gemv_supports(const qail_wdesc& d);
 hipError_t launch_w4a16_gemv(const qail_w4a16_item* items, int count, hipStream_t st);
 bool smallm_supports(const qail_wdesc& d, int M);
 hipError_t launch_w4a16_smallm(const qail_w4a16_item* items, int count, int M, hipStream_t st);
-hipError_t launch_w4a16_gemm(const qail_w4a16_item& it, int M, hipStream_t st);
+// fp16-MFMA GEMM for M > 16; needs gemm_f16_workspace() bytes of 256-byte aligned device memory.
+bool gemm_f16_supports(const qail_wdesc& d, int M);
+size_t gemm_f16_workspace(const qail_wdesc& d, int M);
+hipError_t launch_w4a16_gemm_f16(const qail_w4a16_item& it, int M, void* ws, hipStream_t st);
 hipError_t launch_w4a16_generic(const qail_w4a16_item& it, int M, hipStream_t st);
 
 // W4A4.

@@ -1,217 +1,508 @@
-// W4A16 linear for M > 1: y[m][n] = sum_k x[m][k] * (q[n][k] - z[n][k/g]) * s[n][k/g].
+// W4A16 linear for M > 16 on the fp16 matrix cores:
+//   y[m][n] = sum_k x[m][k] * (q[n][k] - z[n][k/g]) * s[n][k/g].
 //
-// Appendix "Analysis": prefill is the compute-heavy stage of the backbone.  The
-// weights are dequantised to bf16 on their way into LDS and the contraction runs
-// on the bf16 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulate).
+// Appendix "Analysis": prefill is the compute-heavy stage of the backbone, so this is
+// the one W4A16 kernel bound by the matrix pipe rather than by HBM.  The design goal is
+// to keep vector-ALU and LDS work per MFMA low:
 //
-// MFMA operand layout used here (16x16x32, wave64): lane l supplies, for the A
-// operand, row l%16 and the 8 consecutive k starting at 8*(l/16); for the B
-// operand, column l%16 and the same k; it receives D[4*(l/16)+r][l%16], r=0..3.
-// A = activations (rows m), B = weights (columns n), so that a lane's results
-// are contiguous along n in y.
+//   * The weights never pass through LDS.  A wave owns 64 columns n; lane (c, kb) loads
+//     the 8 packed words (64 consecutive k) of row n = c of a 128-k step straight from
+//     global memory and expands one word into the 8 fp16 values one
+//     v_mfma_f32_32x32x16_f16 needs from it as B operand:  0x6400 | q is the fp16 number
+//     1024 + q and 0x6400 | (q << 4) is 1024 + 16 q, so a v_and_or_b32 yields two codes,
+//     one packed add (or fma with 1/16) removes the offset together with the zero-point
+//     exactly, and one packed multiply applies the scale: 13 vector operations per word,
+//     used by BM / 32 MFMAs.
+//   * Only the activations are staged in LDS, once per block, and every wave reads the
+//     whole tile: one 16-byte LDS read per two MFMAs.
+//   * fp16 holds every bf16 significand but not its range, so a small kernel first
+//     rewrites x per row as fp16 scaled by a power of two (largest magnitude in
+//     [2^14, 2^15)), with the k order inside each group of 8 that the expansion above
+//     produces (0,4,1,5,2,6,3,7).  Group scales are divided by the power of two of the
+//     row's largest scale, which keeps (q - z) * s below 32 in fp16; both powers of two
+//     are multiplied back in fp32 at the end.  A weight is therefore rounded once to 11
+//     significant bits (the bf16 alternative keeps 8).
+//
+// MFMA operand layout (32x32x16, wave64): lane l supplies row (A) / column (B) l%32 and
+// the 8 consecutive k starting at 8*(l/32); it receives D[8*(r/4) + 4*(l/32) + r%4][l%32]
+// for r = 0..15.  A = activations (rows m), B = weights (columns n).
 #include "qail_internal.h"
 
 namespace qail {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kBN = 128, kBK = 64;
-constexpr int kPitch = kBK + 8;  // bf16 elements per LDS row (144 B: 16-byte aligned)
+constexpr int kBK = 128;                // k per step
+constexpr int kRowPad = 128;            // workspace rows are padded to this
 
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-    f32x2_t v = {a, b};
-    bf16x2_t r = __builtin_convertvector(v, bf16x2_t);  // nearest even
-    return __builtin_bit_cast(uint32_t, r);
-}
+__host__ __device__ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-// 8 codes of one word -> 8 bf16 (q - z) * s, in k order.  The even and the odd codes are
-// masked into bytes, converted with the byte-to-float instruction, and q * s - z * s is one
-// fused multiply-add (both products are exact, so the result is the exact (q - z) * s).
-__device__ __forceinline__ uint4 dequant8(uint32_t w, float s, float nzs) {
-    const uint32_t e = w & 0x0F0F0F0Fu, o = (w >> 4) & 0x0F0F0F0Fu;
-    float d[8];
+// ---------------------------------------------------------------------------------------
+// Preparation: blocks [0, Mpad) rewrite one row of x each, the rest find the power of two
+// of each weight row's largest scale.
+__global__ __launch_bounds__(256) void gemm_prep_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ sc, uint16_t* __restrict__ xh,
+    float* __restrict__ rscale, float* __restrict__ wmul, int M, int Mpad, int N, int K, int Kpad, int G) {
+    __shared__ uint32_t red[4];
+    const int t = threadIdx.x;
+    if ((int)blockIdx.x < Mpad) {
+        const int m = blockIdx.x;
+        uint4* dst = reinterpret_cast<uint4*>(xh + (size_t)m * Kpad);
+        if (m >= M) {
+            for (int i = t; i < Kpad / 8; i += 256) dst[i] = make_uint4(0, 0, 0, 0);
+            if (t == 0) rscale[m] = 0.f;
+            return;
+        }
+        const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)m * K);
+        uint32_t mx = 0;  // largest magnitude bit pattern (order-preserving for bf16 magnitudes)
+        for (int i = t; i < K / 8; i += 256) {
+            const uint4 v = src[i];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        d[2 * i] = fmaf((float)((e >> (8 * i)) & 0xFFu), s, nzs);
-        d[2 * i + 1] = fmaf((float)((o >> (8 * i)) & 0xFFu), s, nzs);
+            for (int j = 0; j < 4; ++j) {
+                mx = max(mx, w[j] & 0x7FFFu);
+                mx = max(mx, (w[j] >> 16) & 0x7FFFu);
+            }
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o));
+        if (t % kWave == 0) red[t / kWave] = mx;
+        __syncthreads();
+        mx = max(max(red[0], red[1]), max(red[2], red[3]));
+        // x * 2^p has its largest magnitude in [2^14, 2^15); p is kept in the normal fp32 range
+        const int e = (int)(mx >> 7);  // biased exponent of the largest magnitude
+        int p = mx == 0 ? 0 : 141 - e;
+        p = p > 126 ? 126 : (p < -126 ? -126 : p);
+        const float up = __builtin_bit_cast(float, (uint32_t)(127 + p) << 23);
+        if (t == 0) rscale[m] = __builtin_bit_cast(float, (uint32_t)(127 - p) << 23);
+        for (int i = t; i < Kpad / 8; i += 256) {
+            uint4 o = make_uint4(0, 0, 0, 0);
+            if (i < K / 8) {
+                const uint4 v = src[i];
+                const uint16_t b[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
+                                       (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
+                uint32_t h[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    h[j] = __builtin_bit_cast(uint16_t, (_Float16)(bf16_bits_to_f32(b[j]) * up));
+                // stored order inside the 8: 0,4,1,5,2,6,3,7
+                o = make_uint4(h[0] | (h[4] << 16), h[1] | (h[5] << 16), h[2] | (h[6] << 16), h[3] | (h[7] << 16));
+            }
+            dst[i] = o;
+        }
+        return;
     }
-    return make_uint4(pack_bf16(d[0], d[1]), pack_bf16(d[2], d[3]), pack_bf16(d[4], d[5]),
-                      pack_bf16(d[6], d[7]));
+    // 8 lanes per weight row, 32 rows per block
+    const int n = ((int)blockIdx.x - Mpad) * 32 + t / 8;
+    const int part = t % 8;
+    uint32_t mx = 0;
+    if (n < N)
+        for (int gi = part; gi < G; gi += 8) mx = max(mx, (uint32_t)sc[(size_t)n * G + gi]);
+#pragma unroll
+    for (int o = 4; o >= 1; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o));
+    if (n < N && part == 0) {
+        // scales are positive fp16, at least 2^-14 (a stored subnormal is treated as 2^-14)
+        int e = (int)(mx >> 10) & 31;
+        e = e < 1 ? 1 : e;
+        wmul[n] = __builtin_bit_cast(float, (uint32_t)(127 + e - 15) << 23);
+    }
 }
 
-// Block tile (64 * kWM) x 128 with kWM x 2 waves of 64 x 64, K step 64, one LDS buffer.
-// The weight tile is dequantised once per block and step, so a taller tile spreads that
-// vector-ALU work over more matrix work; the next step's global loads are in flight while
-// the current step's MFMAs run.
-template <int kWM>
-__global__ __launch_bounds__(128 * kWM) void w4a16_gemm_kernel(
-    const uint32_t* __restrict__ qw, const uint16_t* __restrict__ sc, const uint32_t* __restrict__ zr,
-    const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int M, int N, int K, int g) {
-    constexpr int kBM = 64 * kWM;
-    constexpr int kThreads = 128 * kWM;
-    constexpr int kBT = kThreads < 512 ? kThreads : 512;  // threads that load weights
-    constexpr int kBW = 1024 / kBT;                       // packed words per such thread: 8, 4 or 2
-    __shared__ __attribute__((aligned(16))) uint16_t As[kBM * kPitch];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[kBN * kPitch];
+// ---------------------------------------------------------------------------------------
+// 8 codes of a word -> 8 fp16 (q - z) * s in the order 0,4,1,5,2,6,3,7.
+//   nz  = -(1024 + z) in both halves, nz6 = -(64 + z), s2 = scale in both halves.
+__device__ __forceinline__ f16x8_t expand_word(uint32_t w, uint32_t magic, f16x2_t nz, f16x2_t nz6, f16x2_t s2) {
+    const f16x2_t sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const uint32_t w8 = w >> 8;
+    const f16x2_t p0 = __builtin_bit_cast(f16x2_t, (w & 0x000F000Fu) | magic);
+    const f16x2_t p1 = __builtin_bit_cast(f16x2_t, (w & 0x00F000F0u) | magic);
+    const f16x2_t p2 = __builtin_bit_cast(f16x2_t, (w8 & 0x000F000Fu) | magic);
+    const f16x2_t p3 = __builtin_bit_cast(f16x2_t, (w8 & 0x00F000F0u) | magic);
+    const f16x2_t h0 = (p0 + nz) * s2;
+    const f16x2_t h1 = (p1 * sixteenth + nz6) * s2;
+    const f16x2_t h2 = (p2 + nz) * s2;
+    const f16x2_t h3 = (p3 * sixteenth + nz6) * s2;
+    return f16x8_t{h0[0], h0[1], h1[0], h1[1], h2[0], h2[1], h3[0], h3[1]};
+}
+
+// Global -> LDS copies by the load unit: lane l's 16 (or 4) bytes at base + off land at LDS
+// address lds + 16 l (4 l).  Written as assembly on purpose: the compiler would otherwise
+// make every later LDS read wait for all such copies in flight (it cannot see that the ring
+// slots are distinct), which would drain the prefetch ring at every step.  The waits are
+// explicit s_waitcnt vmcnt(n) at the points where a slot is handed over.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+__device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds), "v"(off), "s"(base) : "memory", "m0");
+}
+__device__ __forceinline__ void dma4(const void* base, uint32_t off, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :: "s"(lds), "v"(off), "s"(base) : "memory", "m0");
+}
+
+struct GemmArgs {
+    const uint32_t* qw;
+    const uint16_t* sc;
+    const uint32_t* zr;
+    const uint16_t* xh;     // [Mpad][Kpad] fp16, scaled and permuted
+    const float* rscale;    // [Mpad]
+    const float* wmul;      // [N]
+    uint16_t* y;
+    int M, N, K, Kpad, g;
+};
+
+// Block tile (32 * MB) x (128 * WN): 4 waves side by side along n, each (32 * MB) x (32 * WN).
+//
+// The x tile of a step (32 * MB rows x 128 k, 256 B per row) is written into LDS by the
+// load unit itself (global_load_lds_dwordx4: lane l's 16 bytes land at base + 16 l, so a
+// wave fills four rows per instruction) and costs no registers.  Rows are not padded;
+// instead the 16-byte chunk s of row r is kept at position s ^ (r % 16), which the
+// loading lane arranges by choosing its global address, and which makes the 16 lanes of a
+// fragment read (16 consecutive rows, same s) hit 16 different positions: conflict-free.
+//
+// Latency.  A step is only about a microsecond of matrix work, less than a trip to L2 or
+// HBM under load, so the loads of step s + 2 are issued during step s: a ring of three x
+// tiles (and three sets of packed weights) in LDS.  Every load is unconditional (steps past the end of K
+// reload the last tile, which nothing reads), so the number of loads in flight at each
+// wait is a compile-time constant and the wait is an exact vmcnt, not a drain.
+//
+// The K loop is one continuous pipeline of sub-steps (16 k of every lane pair = one MFMA per
+// 32 x 32 output block): the LDS reads and the expansion for sub-step u + 1 are issued
+// among the MFMAs of sub-step u.  The tile of step s + 1 must be complete one sub-step
+// before step s ends, so the wait + barrier sits between sub-steps 6 and 7.
+constexpr int kStages = 3;
+
+// s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt untouched.
+__host__ __device__ constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
+
+template <int MB, int WN>
+__global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) {
+    constexpr int kBM = 32 * MB;
+    constexpr int kBN = 128 * WN;
+    constexpr int kALoads = kBM / 16;             // wave-wide 1 KB loads per wave per step
+    constexpr int kStepLoads = kALoads + 4 * WN;  // all loads a lane issues per step
+    constexpr int kBufBytes = kBM * 256;          // one x tile
+    constexpr int kCPitch = kBN * 2 + 16;         // bytes per row of the output staging tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char As[];  // [kStages][kBM][256 B]
 
     const int t = threadIdx.x;
-    const int lane = t % kWave, wave = t / kWave;
-    const int wm = wave / 2, wn = wave % 2;
-    const int bm = blockIdx.y * kBM, bn = blockIdx.x * kBN;
-    const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
+    const int lane = t % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(t / kWave);
+    const int c = lane & 31, kb = lane >> 5;
+    const int bm = blockIdx.x * kBM, bn = blockIdx.y * kBN;
+    const int G = ga.K / ga.g, zwords = (G + 7) / 8, kw = ga.K / 8;
+    const int steps = ga.Kpad / kBK;
 
-    f32x4_t acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    uint32_t magic = 0x64006400u;
+    asm volatile("" : "+v"(magic));  // in a VGPR: v_and_or_b32 takes one scalar operand only
 
-    // weight loader: row t / (8 / kBW), words [kBW * part, kBW * (part + 1)) of the step's 8
-    constexpr int kParts = 8 / kBW;
-    const bool bact = t < kBT;
-    const int brow = (t / kParts) & 127, bpart = t % kParts;
-    const int bnrow = min(bn + brow, N - 1);
-    const uint32_t* qrow = qw + (size_t)bnrow * kw + bpart * kBW;
-    const _Float16* srow = reinterpret_cast<const _Float16*>(sc) + (size_t)bnrow * G;
-    const uint32_t* zrow = zr + (size_t)bnrow * zwords;
-
-    // this thread's share of one K step, fetched one step ahead of its use
-    uint4 av[4];
-    uint32_t qv[kBW];
-    _Float16 sh = (_Float16)0.f;  // kept in its loaded type: a widening at the load would wait there
-    uint32_t zword = 0;
-    auto gload = [&](int k0) {
+    // Byte offsets of this lane's weight rows (WN 32-column blocks).  All tensors here are
+    // below 4 GB (checked by the host), so addresses are a uniform base plus a 32-bit offset.
+    uint32_t qoff[WN], soff[WN], zoff[WN];
+    float winv[WN];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = t + kThreads * i;
-            const int row = idx >> 3, seg = idx & 7;
-            const int m = bm + row;
-            av[i] = (m < M) ? *reinterpret_cast<const uint4*>(x + (size_t)m * K + k0 + seg * 8)
-                            : make_uint4(0, 0, 0, 0);
+    for (int j = 0; j < WN; ++j) {
+        const int n = min(bn + (wave * WN + j) * 32 + c, ga.N - 1);
+        qoff[j] = (uint32_t)n * (uint32_t)kw * 4u;
+        soff[j] = (uint32_t)n * (uint32_t)G * 2u;
+        zoff[j] = (uint32_t)n * (uint32_t)zwords * 4u;
+        winv[j] = __builtin_bit_cast(float, 0x7F000000u - __builtin_bit_cast(uint32_t, ga.wmul[n]));
+    }
+    const char* qbase = reinterpret_cast<const char*>(ga.qw);
+    const char* sbase = reinterpret_cast<const char*>(ga.sc);
+    const char* zbase = reinterpret_cast<const char*>(ga.zr);
+    const char* xbase = reinterpret_cast<const char*>(ga.xh);
+
+    // x tile loader: load i of this thread fills LDS slot (row 16 i + t / 16, position t % 16)
+    // with chunk (t % 16) ^ (row % 16) of that row.
+    uint32_t xoff0;
+    {
+        const int row0 = t >> 4, pos = t & 15;
+        xoff0 = ((uint32_t)(bm + row0) * (uint32_t)ga.Kpad + (uint32_t)((pos ^ (row0 & 15)) * 8)) * 2u;
+    }
+    const uint32_t xstride = 16u * (uint32_t)ga.Kpad * 2u;  // 16 rows further per load
+    const uint32_t as_lds = __builtin_amdgcn_readfirstlane(lds_addr(As));
+    // One step's loads are issued a few at a time between the sub-steps of an earlier step
+    // (all at once they would queue up behind each other in the load unit while the matrix
+    // pipe idles).  plan() fixes the offsets of a step, issue(i, slot) sends its i-th load.
+    uint32_t pk0b = 0;                    // x: byte offset of the step inside a row
+    uint32_t pq[WN], ps[WN], pz[WN];      // weights: byte offsets of codes, scale word, zero word
+    // fragment read offsets of this lane for the 8 sub-steps (row c of a 32-row block)
+    int aoff[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) aoff[jj] = c * 256 + (((8 * kb + jj) ^ (c & 15)) << 4);
+
+    // Weight loader: the lane's 64 k of a step (two 16-byte pieces per column block) plus the
+    // 4-byte words holding its group's scale and zero-point, again through the load unit into
+    // LDS: each lane only ever reads back its own slots, so LDS is a per-lane FIFO here and
+    // no registers (and no compiler-inserted load waits) are tied up while the loads fly.
+    // The group of a lane's 64 k is tracked without divisions (the group size is a multiple
+    // of 64, so they never straddle two groups).
+    unsigned char* const Bs = As + kStages * kBufBytes;  // [kStages][4 waves][WN][2560 B]
+    constexpr int kBLane = 2560;                          // 2 x 1024 (codes) + 256 (scale) + 256 (zero)
+    constexpr int kBStage = 4 * WN * kBLane;
+    int lk = 64 * kb, lgrp = lk / ga.g, lkin = lk - lgrp * ga.g;  // position of the next planned step
+    int pstep = 0;
+    auto plan = [&]() {
+        pk0b = (uint32_t)(min(pstep, steps - 1) * kBK) * 2u;
+        ++pstep;
+        const bool v = lk < ga.K;
+        const uint32_t kc = v ? (uint32_t)lk : 0u;  // past the end: any valid address, the scale becomes 0
+        const uint32_t grp = v ? (uint32_t)lgrp : 0u;
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            pq[j] = qoff[j] + kc / 2;
+            ps[j] = (soff[j] + grp * 2u) & ~3u;
+            pz[j] = zoff[j] + (grp / 8u) * 4u;
         }
-        if (bact) {
-            const int grp = (k0 + bpart * kBW * 8) / g;
-            if (kBW == 2) {
-                const uint2 v = *reinterpret_cast<const uint2*>(qrow + k0 / 8);
-                qv[0] = v.x; qv[1] = v.y;
-            } else {
+        lk += kBK;
+        lkin += kBK;
 #pragma unroll
-                for (int u = 0; u < kBW; u += 4) {
-                    const uint4 v = *reinterpret_cast<const uint4*>(qrow + k0 / 8 + u);
-                    qv[u] = v.x; qv[u + 1] = v.y; qv[u + 2] = v.z; qv[u + 3] = v.w;
-                }
-            }
-            sh = srow[grp];
-            zword = zrow[grp / 8];
+        for (int r = 0; r < 2; ++r) {  // the step is at most two groups long
+            const int over = lkin >= ga.g;
+            lkin -= over * ga.g;
+            lgrp += over;
         }
     };
-    gload(0);
+    auto issue = [&](int i, int slot) {
+        if (i < kALoads) {
+            dma16(xbase, xoff0 + i * xstride + pk0b, as_lds + slot * kBufBytes + (i * 256 + wave * 64) * 16);
+        } else {
+            const int j = (i - kALoads) / 4, part = (i - kALoads) % 4;
+            const uint32_t dst = as_lds + kStages * kBufBytes + slot * kBStage + (wave * WN + j) * kBLane;
+            if (part == 0) dma16(qbase, pq[j], dst);
+            if (part == 1) dma16(qbase, pq[j] + 16, dst + 1024);
+            if (part == 2) dma4(sbase, ps[j], dst + 2048);
+            if (part == 3) dma4(zbase, pz[j], dst + 2304);
+        }
+    };
 
-    for (int k0 = 0; k0 < K; k0 += kBK) {
-        __syncthreads();  // previous step's MFMAs have read LDS
+    // operands of the step being multiplied; ck / cgrp follow the consumed steps like lk / lgrp
+    uint32_t wq[WN][8];
+    f16x2_t nz[WN], nz6[WN], s2[WN];
+    int ck = 64 * kb, cgrp = ck / ga.g, ckin = ck - cgrp * ga.g;
+    auto take = [&](int stage) {
+        const bool v = ck < ga.K;
+        const uint32_t grp = v ? (uint32_t)cgrp : 0u;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = t + kThreads * i;
-            const int row = idx >> 3, seg = idx & 7;
-            *reinterpret_cast<uint4*>(&As[row * kPitch + seg * 8]) = av[i];
+        for (int j = 0; j < WN; ++j) {
+            const unsigned char* src = Bs + stage * kBStage + (wave * WN + j) * kBLane;
+            const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(src + lane * 16);
+            const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(src + 1024 + lane * 16);
+            const uint32_t sword = *reinterpret_cast<const uint32_t*>(src + 2048 + lane * 4);
+            const uint32_t zword = *reinterpret_cast<const uint32_t*>(src + 2304 + lane * 4);
+            wq[j][0] = lo.x; wq[j][1] = lo.y; wq[j][2] = lo.z; wq[j][3] = lo.w;
+            wq[j][4] = hi.x; wq[j][5] = hi.y; wq[j][6] = hi.z; wq[j][7] = hi.w;
+            // the scale's 2 bytes inside the aligned word that was fetched
+            const uint32_t sbits = (sword >> (8u * ((soff[j] + grp * 2u) & 2u))) & 0xFFFFu;
+            const float sf = (float)__builtin_bit_cast(_Float16, (uint16_t)sbits);
+            const float z = (float)((zword >> (4u * (grp & 7u))) & 0xFu);
+            const _Float16 srel = v ? (_Float16)(sf * winv[j]) : (_Float16)0.f;
+            const _Float16 a = (_Float16)(-1024.f - z), b = (_Float16)(-64.f - z);
+            nz[j] = f16x2_t{a, a};
+            nz6[j] = f16x2_t{b, b};
+            s2[j] = f16x2_t{srel, srel};
         }
-        if (bact) {
-            const int grp = (k0 + bpart * kBW * 8) / g;
-            const float s = (float)sh;
-            const float nzs = -(float)((zword >> (4 * (grp & 7))) & 0xFu) * s;
-            uint4* dst = reinterpret_cast<uint4*>(&Bs[brow * kPitch + bpart * kBW * 8]);
+        ck += kBK;
+        ckin += kBK;
 #pragma unroll
-            for (int u = 0; u < kBW; ++u) dst[u] = dequant8(qv[u], s, nzs);
+        for (int r = 0; r < 2; ++r) {
+            const int over = ckin >= ga.g;
+            ckin -= over * ga.g;
+            cgrp += over;
         }
-        __syncthreads();
-        if (k0 + kBK < K) gload(k0 + kBK);  // lands while the MFMAs below run
+    };
 
+    f32x16_t acc[MB][WN];
 #pragma unroll
-        for (int kk = 0; kk < kBK; kk += 32) {
-            bf16x8_t a[4], b[4];
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                a[i] = *reinterpret_cast<const bf16x8_t*>(
-                    &As[(wm * 64 + i * 16 + (lane & 15)) * kPitch + kk + (lane >> 4) * 8]);
+        for (int j = 0; j < WN; ++j)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                b[j] = *reinterpret_cast<const bf16x8_t*>(
-                    &Bs[(wn * 64 + j * 16 + (lane & 15)) * kPitch + kk + (lane >> 4) * 8]);
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    f16x8_t af[2][MB], bf[2][WN];
+    auto fetch = [&](int stage, int jj, int slot) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MB; ++i)
+            af[slot][i] = *reinterpret_cast<const f16x8_t*>(As + stage * kBufBytes + i * (32 * 256) + aoff[jj]);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < WN; ++j) bf[slot][j] = expand_word(wq[j][jj], magic, nz[j], nz6[j], s2[j]);
+    };
+    auto multiply = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[slot][i], bf[slot][j], acc[i][j], 0, 0, 0);
+        // issue order: each MFMA is followed by one LDS read and a share of the vector
+        // operations that prepare the next sub-step
+#pragma unroll
+        for (int u = 0; u < MB * WN; ++u) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+            __builtin_amdgcn_sched_group_barrier(0x002, (13 * WN + MB * WN - 1) / (MB * WN), 0);  // VALU
         }
+    };
+
+    // steps 0 and 1 are loaded up front; from then on step s + 2 is loaded during step s
+#pragma unroll
+    for (int p = 0; p < kStages - 1; ++p) {
+        plan();
+#pragma unroll
+        for (int i = 0; i < kStepLoads; ++i) issue(i, p);
+        __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kStepLoads));
+    __syncthreads();
+    take(0);
+    fetch(0, 0, 0);
 
+    for (int s0 = 0; s0 < steps; s0 += kStages) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int u = 0; u < kStages; ++u) {
+            if (s0 + u >= steps) break;
+            const int cur = u, nxt = (u + 1) % kStages, fill = (u + 2) % kStages;
+            // slot `fill` held step s - 1 and is free since the previous barrier
+            plan();
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = bn + wn * 64 + j * 16 + (lane & 15);
+            for (int jj = 0; jj < 7; ++jj) {
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(cur, jj + 1, (jj + 1) & 1);
+                multiply(jj & 1);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int m = bm + wm * 64 + i * 16 + (lane >> 4) * 4 + r;
-                if (m < M && n < N) y[(size_t)m * N + n] = f32_to_bf16_rne(acc[i][j][r]);
+                for (int i = 0; i < kStepLoads; ++i)
+                    if (i * 7 / kStepLoads == jj) issue(i, fill);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            // In flight: step s+1 (issued during step s-1) and step s+2 (just issued).  Step
+            // s+1 has to be complete; the wait also covers this wave's LDS reads (lgkmcnt 0),
+            // so after the barrier slot `cur` is dead for everyone once sub-step 7 is done
+            // (its operands are already in registers).
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(kStepLoads));
+            __syncthreads();
+            take(nxt);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(nxt, 0, 0);
+            multiply(1);
         }
-}
-
-// Any valid shape (K % 8 == 0, g % 8 == 0): one thread per output, fp32
-// accumulation in k order.  Slow; only for shapes the tiled kernels do not take.
-__global__ __launch_bounds__(256) void w4a16_generic_kernel(
-    const uint32_t* __restrict__ qw, const uint16_t* __restrict__ sc, const uint32_t* __restrict__ zr,
-    const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int M, int N, int K, int g) {
-    const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (o >= (size_t)M * N) return;
-    const int m = (int)(o / N), n = (int)(o % N);
-    const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
-    float acc = 0.f;
-    for (int wi = 0; wi < kw; ++wi) {
-        const int grp = (wi * 8) / g;
-        const uint32_t w = qw[(size_t)n * kw + wi];
-        const float s = f16_bits_to_f32(sc[(size_t)n * G + grp]);
-        const int z = (zr[(size_t)n * zwords + grp / 8] >> (4 * (grp & 7))) & 0xF;
-        float part = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int q = (w >> (4 * j)) & 0xF;
-            part = fmaf(bf16_bits_to_f32(x[(size_t)m * K + wi * 8 + j]), (float)(q - z), part);
-        }
-        acc = fmaf(part, s, acc);
     }
-    y[o] = f32_to_bf16_rne(acc);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // nothing may still be writing LDS
+    __syncthreads();
+
+    // y = acc * 2^-p(m) * 2^E(n), rounded once to bf16, staged in LDS so that rows leave as
+    // 16-byte pieces of full lines.
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+        const int col = (wave * WN + j) * 32 + c;
+        const float wm = ga.wmul[min(bn + col, ga.N - 1)];
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
+                const float v = acc[i][j][r] * ga.rscale[bm + row] * wm;
+                *reinterpret_cast<uint16_t*>(As + row * kCPitch + col * 2) = f32_to_bf16_rne(v);
+            }
+    }
+    __syncthreads();
+    constexpr int kChunks = kBN / 8;  // 16-byte pieces per row
+    const bool vec_ok = (ga.N % 8) == 0;
+    for (int idx = t; idx < kBM * kChunks; idx += 256) {
+        const int row = idx / kChunks, ch = idx % kChunks;
+        const int m = bm + row, n = bn + ch * 8;
+        if (m >= ga.M || n >= ga.N) continue;
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(As + row * kCPitch + ch * 16);
+        uint16_t* dst = ga.y + (size_t)m * ga.N + n;
+        if (vec_ok && n + 8 <= ga.N) {
+            *reinterpret_cast<u32x4_t*>(dst) = v;
+        } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            for (int e = 0; e < 8 && n + e < ga.N; ++e) dst[e] = (uint16_t)(w[e / 2] >> (16 * (e & 1)));
+        }
+    }
+}
+
+int gemm_cus() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+template <int MB, int WN>
+hipError_t launch_tile(const GemmArgs& ga, hipStream_t st) {
+    constexpr int kBM = 32 * MB, kBN = 128 * WN;
+    const size_t lds = (size_t)kStages * (kBM * 256 + 4 * WN * 2560);
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_gemm_f16_kernel<MB, WN>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((ga.M + kBM - 1) / kBM, (ga.N + kBN - 1) / kBN);
+    hipLaunchKernelGGL((w4a16_gemm_f16_kernel<MB, WN>), grid, dim3(256), lds, st, ga);
+    return hipGetLastError();
+}
+
+// 64-column waves spread the expansion of a weight word over more MFMAs; 32-column waves
+// double the number of blocks.  The narrow tile is taken when the wide one would leave CUs idle.
+template <int MB>
+hipError_t launch_rows(const GemmArgs& ga, hipStream_t st) {
+    const long long wide = (long long)((ga.M + 32 * MB - 1) / (32 * MB)) * ((ga.N + 255) / 256);
+    if (wide >= 3LL * gemm_cus() / 2) return launch_tile<MB, 2>(ga, st);
+    return launch_tile<MB, 1>(ga, st);
 }
 
 }  // namespace
 
-namespace {
-template <int kWM>
-hipError_t launch_gemm_tile(const qail_w4a16_item& it, int M, hipStream_t st) {
-    constexpr int kBM = 64 * kWM;
-    dim3 grid((it.d.N + kBN - 1) / kBN, (M + kBM - 1) / kBM);
-    hipLaunchKernelGGL(w4a16_gemm_kernel<kWM>, grid, dim3(128 * kWM), 0, st, it.qweight, it.scales, it.zeros,
-                       it.x, it.y, M, it.d.N, it.d.K, it.d.group_size);
-    return hipGetLastError();
-}
-}  // namespace
-
-// 64-row tiles for small batches, 128-row tiles otherwise.  (Taller tiles with more waves
-// spread the dequantisation further but leave too few blocks for 256 CUs at these shapes:
-// measured slower.)
-hipError_t launch_w4a16_gemm(const qail_w4a16_item& it, int M, hipStream_t st) {
-    if (M <= 64) return launch_gemm_tile<1>(it, M, st);
-    return launch_gemm_tile<2>(it, M, st);
+bool gemm_f16_supports(const qail_wdesc& d, int M) {
+    if (d.K % 64 != 0 || d.group_size % 64 != 0) return false;
+    // 32-bit byte offsets inside the kernel
+    const unsigned long long lim = 0xFFFFFFFFull;
+    const unsigned long long Mpad = (unsigned long long)round_up(M, kRowPad), Kpad = (unsigned long long)round_up(d.K, kBK);
+    return (unsigned long long)d.N * d.K / 2 <= lim && Mpad * Kpad * 2 <= lim && (unsigned long long)M * d.N * 2 <= lim;
 }
 
-hipError_t launch_w4a16_generic(const qail_w4a16_item& it, int M, hipStream_t st) {
-    const size_t outs = (size_t)M * it.d.N;
-    hipLaunchKernelGGL(w4a16_generic_kernel, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st,
-                       it.qweight, it.scales, it.zeros, it.x, it.y, M, it.d.N, it.d.K, it.d.group_size);
-    return hipGetLastError();
+size_t gemm_f16_workspace(const qail_wdesc& d, int M) {
+    const size_t Mpad = (size_t)round_up(M, kRowPad), Kpad = (size_t)round_up(d.K, kBK);
+    size_t b = Mpad * Kpad * 2;                       // xh
+    b += Mpad * 4;                                    // rscale
+    b += (size_t)round_up(d.N, 64) * 4;               // wmul
+    return (b + 255) / 256 * 256;
+}
+
+hipError_t launch_w4a16_gemm_f16(const qail_w4a16_item& it, int M, void* ws, hipStream_t st) {
+    const qail_wdesc& d = it.d;
+    const int Mpad = round_up(M, kRowPad), Kpad = round_up(d.K, kBK), G = d.K / d.group_size;
+    uint16_t* xh = static_cast<uint16_t*>(ws);
+    float* rscale = reinterpret_cast<float*>(xh + (size_t)Mpad * Kpad);
+    float* wmul = rscale + Mpad;
+    hipLaunchKernelGGL(gemm_prep_kernel, dim3(Mpad + (d.N + 31) / 32), dim3(256), 0, st, it.x, it.scales, xh,
+                       rscale, wmul, M, Mpad, d.N, d.K, Kpad, G);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    GemmArgs ga{it.qweight, it.scales, it.zeros, xh, rscale, wmul, it.y, M, d.N, d.K, Kpad, d.group_size};
+    // tile height: the multiple of 32 rows (at most 128) that pads M least
+    if (M <= 32) return launch_rows<1>(ga, st);
+    if (M <= 64) return launch_rows<2>(ga, st);
+    if (M <= 96) return launch_rows<3>(ga, st);
+    const int pad3 = round_up(M, 96), pad4 = round_up(M, 128);
+    return pad3 < pad4 ? launch_rows<3>(ga, st) : launch_rows<4>(ga, st);
 }
 
 }  // namespace qail

@@ -47,3 +47,11 @@ def w4a16_norm_err(y_bits: np.ndarray, y_ref: np.ndarray, nx: np.ndarray, nw: np
     denom = nx[:, None] * nw[None, :]
     denom = np.where(denom == 0, 1.0, denom)
     return float((np.abs(y - y_ref) / denom).max())
+
+
+def ws_for(B, nbytes):
+    """Device workspace of at least nbytes (None when none is needed)."""
+    import torch
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device="cuda")

@@ -6,7 +6,7 @@ import pytest
 
 from oracle import qail_oracle as O
 from paper_2412_01034_amd import synth
-from tests.helpers import dev, ensure_built, host, w4a16_norm_err
+from tests.helpers import dev, ensure_built, host, w4a16_norm_err, ws_for
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
@@ -31,7 +31,8 @@ def oracle_pack(w, g):
 def gpu_linear(B, qw, s, zw, xb, g, N, K, M):
     import torch
     y = torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")    # NaN pattern: must be overwritten
-    B.qail_w4a16_linear(N, K, g, dev(qw), dev(s.view(np.uint16)), dev(zw), dev(xb), y, M)
+    ws = ws_for(B, B.qail_w4a16_workspace(N, K, g, M))
+    B.qail_w4a16_linear(N, K, g, dev(qw), dev(s.view(np.uint16)), dev(zw), dev(xb), y, M, ws)
     torch.cuda.synchronize()
     return host(y, np.uint16).reshape(M, N)
 
@@ -87,6 +88,40 @@ def test_batched_shapes(B, M, N, K, g):
           tol=TOL if K >= 512 else TOL_TINY_K)
 
 
+@pytest.mark.parametrize("M", [17, 33, 96, 129, 200])
+@pytest.mark.parametrize("N,K,g", [(300, 192, 64),        # K = 128 + 64: the last step is half empty
+                                   (257, 384, 192),       # group of one and a half steps
+                                   (64, 1152, 64),        # two groups per step
+                                   (520, 4096, 128)])     # three column blocks, the last ragged
+def test_matrix_core_gemm_edges(B, M, N, K, g):
+    check(B, N, K, g, M, 11 * M + N, w_kw=dict(outlier_frac=0.01), x_kw=dict(outlier_frac=0.005),
+          tol=TOL if K >= 512 else TOL_TINY_K)
+
+
+def test_matrix_core_gemm_value_ranges(B):
+    # rows of x and rows of W spanning 60 binades each: the per-row powers of two that keep the
+    # fp16 operands in range must come back out exactly
+    N, K, g, M = 96, 1024, 128, 40
+    rng = np.random.default_rng(123)
+    w = synth.llm_weight(N, K, 31) * (2.0 ** rng.integers(-8, 18, size=(N, 1))).astype(np.float32)
+    x = rng.standard_normal((M, K)).astype(np.float32) * (2.0 ** rng.integers(-30, 30, size=(M, 1))).astype(np.float32)
+    xb = synth.f32_to_bf16_bits(x)
+    qw, s, zw = oracle_pack(w, g)
+    y = gpu_linear(B, qw, s, zw, xb, g, N, K, M)
+    ref = O.w4a16_linear(xb, qw, s, zw, g)
+    nx, nw = O.w4a16_row_norms(xb, qw, s, zw, g)
+    assert w4a16_norm_err(y, ref, nx, nw) <= TOL
+    # groups of one row whose scales differ by 2^20: the small ones may lose bits, the result
+    # is still within the bar relative to the row's norm
+    w2 = synth.llm_weight(N, K, 32)
+    w2[:, :g] *= np.float32(2.0 ** 20)
+    qw, s, zw = oracle_pack(w2, g)
+    y = gpu_linear(B, qw, s, zw, xb, g, N, K, M)
+    ref = O.w4a16_linear(xb, qw, s, zw, g)
+    nx, nw = O.w4a16_row_norms(xb, qw, s, zw, g)
+    assert w4a16_norm_err(y, ref, nx, nw) <= TOL
+
+
 @pytest.mark.parametrize("M", [3, 7, 15])
 def test_small_batch_odd_row_counts(B, M):
     check(B, 333, 4096, 128, M, 900 + M, w_kw=dict(outlier_frac=0.01), x_kw=dict(outlier_frac=0.005))
@@ -116,9 +151,15 @@ def test_closed_forms_bit_exact(B, M):
         y = gpu_linear(B, qw, s, zw, synth.f32_to_bf16_bits(x), g, N, K, M)
         exp = np.repeat(w_hat[None, :, k], M, axis=0)
         exp[M - 1] *= -2.0
-        # compared as values: an exact zero may come out as +0 or -0
-        assert np.array_equal(synth.bf16_bits_to_f32(y),
-                              synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(exp.astype(np.float32))))
+        got = synth.bf16_bits_to_f32(y)
+        if M <= 16:
+            # compared as values: an exact zero may come out as +0 or -0
+            assert np.array_equal(got, synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(exp.astype(np.float32))))
+        else:
+            # the matrix-core GEMM rounds (q - z) * s to fp16 (2^-11 relative) before the bf16
+            # rounding of the output (2^-8): still one weight per output, so any layout or
+            # permutation mistake shows, but the two roundings need not equal a single one
+            assert np.all(np.abs(got.astype(np.float64) - exp) <= (2.0 ** -8 + 2.0 ** -11) * np.abs(exp))
 
 
 def test_homogeneity_and_determinism(B):
@@ -149,7 +190,8 @@ def test_batch_equals_single_calls(B):
             ents.append(e)
             singles.append(gpu_linear(B, qw, s, zw, xb, g, N, K, M))
         items = B.make_w4a16_items(ents, M)
-        B.qail_w4a16_linear_batch(items, len(ents), M)
+        ws = ws_for(B, B.qail_w4a16_batch_workspace(items, len(ents), M))
+        B.qail_w4a16_linear_batch(items, len(ents), M, ws)
         torch.cuda.synchronize()
         for e, ref in zip(ents, singles):
             assert np.array_equal(host(e["y"], np.uint16).reshape(ref.shape), ref)
@@ -180,7 +222,8 @@ def _sampled_full_size(B, M, x_kw, rows_per_linear=96, m_rows=8):
         keep.append((w[rows], xb, rows))
         del w
     items = B.make_w4a16_items(ents, M)
-    B.qail_w4a16_linear_batch(items, len(ents), M)
+    ws = ws_for(B, B.qail_w4a16_batch_workspace(items, len(ents), M))
+    B.qail_w4a16_linear_batch(items, len(ents), M, ws)
     torch.cuda.synchronize()
     ms = np.unique(np.linspace(0, M - 1, m_rows).astype(int))
     worst = 0.0
