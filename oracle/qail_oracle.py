@@ -275,3 +275,34 @@ def requant(acc: np.ndarray, scale: np.ndarray, bias: np.ndarray) -> np.ndarray:
 def requant_scale(s_a, s_w: np.ndarray) -> np.ndarray:
     """scale[n] = float32(s_a * s_w[n])."""
     return (F32(s_a) * np.asarray(s_w, dtype=F32)).astype(F32)
+
+
+def fused_requant_u4(acc: np.ndarray, scale: np.ndarray, bias: np.ndarray, s_out,
+                     res_codes: np.ndarray = None, res_scale=None, res_f32: np.ndarray = None) -> np.ndarray:
+    """Output of a W4A4 layer written directly as the next layer's unsigned 4-bit
+    codes (Sec. 5.1 and the appendix's implementation details for autonomous
+    driving: every activation tensor is 4-bit with one learned step per tensor, so
+    the step s_out of the consumer is a constant known when the producer runs).
+    The shortcut of a residual block is added before the ReLU, either as the 4-bit
+    codes of the block input with their step, or as a float32 tensor (projection
+    shortcut).  Per element, every line one IEEE float32 operation, no fused
+    multiply-add:
+
+        t = float32(acc) * scale[n]
+        t = t + bias[n]
+        t = t + r              r = res_scale * float32(q_r)  or  r = res_f32, if given
+        t = max(t, 0)
+        q = clamp(rint(t / s_out), 0, 15)          rint: ties to even
+
+    acc int [M, N]; scale, bias float32 [N]; returns uint8 codes [M, N]."""
+    t = acc.astype(F32) * np.asarray(scale, dtype=F32)[None, :]
+    t = t + np.asarray(bias, dtype=F32)[None, :]
+    if res_codes is not None:
+        assert res_f32 is None
+        t = t + F32(res_scale) * np.asarray(res_codes).astype(F32)
+    elif res_f32 is not None:
+        t = t + np.asarray(res_f32, dtype=F32)
+    t = np.maximum(t, F32(0))
+    assert t.dtype == F32
+    q = np.rint(t / F32(s_out))
+    return np.clip(q, 0, 15).astype(np.uint8)

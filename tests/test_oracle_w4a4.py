@@ -1,6 +1,7 @@
 """Pins for the W4A4 half of the CPU oracle (signed 4-bit weights per output
 channel, unsigned 4-bit activations per tensor, exact integer conv-as-GEMM,
 requantisation): invariants, closed forms, textbook special cases, brute force."""
+import os
 from fractions import Fraction
 
 import numpy as np
@@ -179,3 +180,105 @@ def test_end_to_end_quantised_conv_tracks_real_conv():
     deq = (O.im2col_nhwc(qa.astype(np.float64) * float(s_a), 3, 3, 1, 1)
            @ (qw.reshape(16, -1) * s_w.astype(np.float64)[:, None]).T + bias)
     assert np.allclose(y, deq, rtol=1e-6, atol=1e-6)
+
+
+# ------------------------------------------------------------------ fused output epilogue
+
+def _golden_fused():
+    rows = []
+    path = os.path.join(os.path.dirname(__file__), "golden", "w4a4_fused_epilogue.txt")
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if line:
+            v = line.split()
+            rows.append((int(v[0]), float(v[1]), float(v[2]), int(v[3]), float(v[4]), float(v[5]), int(v[6])))
+    return rows
+
+
+def test_fused_epilogue_hand_worked_cases():
+    rows = _golden_fused()
+    assert len(rows) >= 10
+    for acc, sc, bi, rc, rs, so, want in rows:
+        a = np.array([[acc]], np.int32)
+        if rc < 0:
+            got = O.fused_requant_u4(a, [sc], [bi], so)
+        else:
+            got = O.fused_requant_u4(a, [sc], [bi], so, res_codes=np.array([[rc]], np.uint8), res_scale=rs)
+        assert int(got[0, 0]) == want, (acc, sc, bi, rc, rs, so, int(got[0, 0]), want)
+
+
+def _fl32(x64):
+    return np.asarray(x64, np.float64).astype(np.float32)
+
+
+def test_fused_epilogue_is_a_chain_of_single_float32_operations():
+    # +, * and / of float32 operands carried out in float64 (53 >= 2*24+2 bits) and then
+    # rounded to float32 equal the correctly rounded float32 operation, so this re-derivation,
+    # which never lets numpy do float32 arithmetic, pins every step: a fused multiply-add,
+    # a float64 accumulation or a reciprocal multiply would differ on some element.
+    rng = np.random.default_rng(5)
+    M, N = 257, 64
+    acc = rng.integers(-40000, 40000, size=(M, N)).astype(np.int32)
+    scale = (rng.random(N).astype(np.float32) * 1e-3 + 1e-4).astype(np.float32)
+    bias = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    rc = rng.integers(0, 16, size=(M, N)).astype(np.uint8)
+    rs, so = np.float32(0.2371), np.float32(0.3113)
+    rf = rng.standard_normal((M, N)).astype(np.float32)
+    for kind in ("none", "codes", "f32"):
+        t = _fl32(acc.astype(np.float64) * scale.astype(np.float64)[None, :])
+        t = _fl32(t.astype(np.float64) + bias.astype(np.float64)[None, :])
+        if kind == "codes":
+            r = _fl32(np.float64(rs) * rc.astype(np.float64))
+            t = _fl32(t.astype(np.float64) + r.astype(np.float64))
+            got = O.fused_requant_u4(acc, scale, bias, so, res_codes=rc, res_scale=rs)
+        elif kind == "f32":
+            t = _fl32(t.astype(np.float64) + rf.astype(np.float64))
+            got = O.fused_requant_u4(acc, scale, bias, so, res_f32=rf)
+        else:
+            got = O.fused_requant_u4(acc, scale, bias, so)
+        t = np.maximum(t, np.float32(0))
+        q = np.clip(np.rint(_fl32(t.astype(np.float64) / np.float64(so)).astype(np.float64)), 0, 15).astype(np.uint8)
+        assert np.array_equal(got, q), kind
+        assert got.min() == 0 and got.max() == 15          # the data exercises both clamps
+
+
+def test_fused_epilogue_agrees_with_the_unfused_chain_away_from_ties():
+    # requant (float64, pinned above) -> + shortcut -> ReLU -> quantize_act_u4 (pinned above)
+    rng = np.random.default_rng(6)
+    M, N = 300, 32
+    acc = rng.integers(-3000, 3000, size=(M, N)).astype(np.int32)
+    scale = (rng.random(N) * 2e-3 + 5e-4).astype(np.float32)
+    bias = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    rc = rng.integers(0, 16, size=(M, N)).astype(np.uint8)
+    rs, so = np.float32(0.11), np.float32(0.27)
+    y64 = O.requant(acc, scale, bias) + np.float64(rs) * rc
+    y64 = np.maximum(y64, 0.0)
+    frac = y64 / np.float64(so)
+    away = np.abs(frac - np.floor(frac) - 0.5) > 1e-4
+    ref = O.quantize_act_u4(y64.astype(np.float32), so)
+    got = O.fused_requant_u4(acc, scale, bias, so, res_codes=rc, res_scale=rs)
+    assert away.mean() > 0.99
+    assert np.array_equal(got[away], ref[away])
+
+
+def test_fused_epilogue_invariants_and_identity_case():
+    rng = np.random.default_rng(7)
+    N = 16
+    scale = (rng.random(N) * 1e-2 + 1e-3).astype(np.float32)
+    bias = (rng.standard_normal(N) * 0.05).astype(np.float32)
+    accs = np.arange(-500, 2500, dtype=np.int32)[:, None].repeat(N, 1)
+    q = O.fused_requant_u4(accs, scale, bias, np.float32(0.4))
+    assert q.min() >= 0 and q.max() <= 15
+    assert np.all(np.diff(q.astype(int), axis=0) >= 0)              # monotone in acc for scale > 0
+    y = O.requant(accs, scale, bias)
+    assert np.all(q[y <= 0] == 0)                                   # ReLU
+    # scale == s_out, no bias: the code is the accumulator itself, clamped
+    a = np.arange(-3, 20, dtype=np.int32)[:, None]
+    q = O.fused_requant_u4(a, [0.37], [0.0], 0.37)
+    assert np.array_equal(q[:, 0], np.clip(a[:, 0], 0, 15))
+    # a shortcut given as codes or as the float32 tensor they stand for is the same thing
+    rc = rng.integers(0, 16, size=accs.shape).astype(np.uint8)
+    rs = np.float32(0.3)
+    qa = O.fused_requant_u4(accs, scale, bias, 0.4, res_codes=rc, res_scale=rs)
+    qb = O.fused_requant_u4(accs, scale, bias, 0.4, res_f32=(rs * rc.astype(np.float32)))
+    assert np.array_equal(qa, qb)
