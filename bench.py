@@ -305,6 +305,32 @@ def main():
         extra["w4a4_resnet34_b32"] = {"ms_per_pass": round(t * 1e3, 4), "TOPs": round(tot_ops / t / 1e12, 1),
                                       "frac_int8_peak": round(tot_ops / t / 1e12 / INT8_PEAK_TOPS, 4),
                                       "calls": len(calls), "per_shape": per_shape}
+
+        # the same 35 calls with the fused 4-bit output (ReLU + shortcut + quantise for the next
+        # layer): every call writes 0.5 B per output instead of 4 B
+        fcalls = []
+        for s, a, ww, scale, bias, y in calls:
+            out = torch.empty(s.M * s.Cout // 8, dtype=torch.int32, device="cuda")
+            res = a if (s.Cin == s.Cout and s.stride == 1) else None   # identity shortcut: same shape as the output
+            fcalls.append((s, a, ww, scale, bias, out, res))
+
+        def fused_body():
+            for s, a, ww, scale, bias, out, res in fcalls:
+                B.qail_w4a4_conv_u4(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww, scale, bias,
+                                    0.37, out, res_u4=res, res_scale=0.11, stream=sh)
+        tf_ = timed(fused_body, 20)
+        fper = {}
+        for s, a, ww, scale, bias, out, res in fcalls:
+            key = f"{s.KH}x{s.KW}_{s.Cin}to{s.Cout}_s{s.stride}"
+            if key in fper:
+                continue
+            tt = timed(lambda: B.qail_w4a4_conv_u4(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww,
+                                                   scale, bias, 0.37, out, res_u4=res, res_scale=0.11, stream=sh), 50)
+            fper[key] = {"us": round(tt * 1e6, 2), "TOPs": round(s.ops / tt / 1e12, 1)}
+        extra["w4a4_resnet34_b32_fused_u4"] = {"ms_per_pass": round(tf_ * 1e3, 4),
+                                               "TOPs": round(tot_ops / tf_ / 1e12, 1),
+                                               "frac_int8_peak": round(tot_ops / tf_ / 1e12 / INT8_PEAK_TOPS, 4),
+                                               "calls": len(fcalls), "per_shape": fper}
         result["extra"] = extra
         log("[bench] extra:", json.dumps(extra))
 

@@ -187,6 +187,29 @@ int qail_w4a4_gemm(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t
                    int32_t* acc_out, const float* scale, const float* bias, float* y_out,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same convolution with the output written directly as the NEXT layer's packed
+ * unsigned 4-bit activations (Sec. 5.1 and the appendix's implementation details for
+ * autonomous driving: every activation tensor of the driving encoder is 4-bit with one
+ * step per tensor, so the consumer's step s_out is a constant of the network).  Per
+ * output element, each line one correctly rounded fp32 operation (no fused multiply-add):
+ *     t = float(acc) * scale[n]
+ *     t = t + bias[n]
+ *     t = t + r                  only with a shortcut, see below
+ *     t = max(t, 0)              ReLU
+ *     q = clamp(rint(t / s_out), 0, 15)        rint: ties to even
+ * out_u4: [M][Cout/8] words, i.e. NHWC [B][OH][OW][Cout/8], the a_u4 layout; Cout % 8 == 0.
+ * Shortcut of a residual block, at most one of
+ *     res_u4:  packed unsigned codes [M][Cout/8] (the block input), r = res_scale * code;
+ *     res_f32: fp32 [M][Cout] (a projection shortcut's y_out), r = res_f32[m][n].
+ * scale, bias: fp32 [Cout], required.  s_out > 0 and res_scale >= 0 are host values.
+ * All buffers are device memory owned by the caller; nothing is allocated, the call is
+ * enqueued on `stream` and returns.  Errors as for qail_w4a4_gemm, plus QAIL_ERR_SHAPE for
+ * Cout % 8 != 0, s_out not positive and finite, or two shortcuts at once. */
+int qail_w4a4_conv_u4(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t* w_s4,
+                      const float* scale, const float* bias, float s_out,
+                      const uint32_t* res_u4, float res_scale, const float* res_f32,
+                      uint32_t* out_u4, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

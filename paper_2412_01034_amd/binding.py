@@ -32,7 +32,7 @@ EXPORTS = (
     "qail_version", "qail_status_string", "qail_packed_sizes", "qail_quantize_weights",
     "qail_unpack_weights", "qail_act_scale_u4", "qail_quantize_act_u4", "qail_w4a16_workspace",
     "qail_w4a16_linear", "qail_w4a16_linear_batch", "qail_w4a16_batch_workspace",
-    "qail_w4a4_workspace", "qail_w4a4_gemm",
+    "qail_w4a4_workspace", "qail_w4a4_gemm", "qail_w4a4_conv_u4",
 )
 
 
@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.qail_w4a16_batch_workspace.argtypes = [ctypes.POINTER(qail_w4a16_item), i32, i32, psz]
         L.qail_w4a4_workspace.argtypes = [ctypes.POINTER(qail_conv_desc), psz]
         L.qail_w4a4_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.qail_w4a4_conv_u4.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, ctypes.c_float, vp,
+                                        ctypes.c_float, vp, vp, vp, sz, vp]
         for name in EXPORTS:
             if name not in ("qail_status_string",):
                 getattr(L, name).restype = ctypes.c_int
@@ -263,3 +265,29 @@ def qail_w4a4_gemm(B, H, W, Cin, Cout, KH, KW, stride, pad, a_u4: torch.Tensor, 
     _check(lib().qail_w4a4_gemm(ctypes.byref(d), _ptr(a_u4), _ptr(w_s4), _ptr(acc_out), _ptr(scale),
                                 _ptr(bias), _ptr(y_out), _ptr(workspace), wsb,
                                 _stream() if stream is None else stream), "qail_w4a4_gemm")
+
+
+def qail_w4a4_conv_u4(B, H, W, Cin, Cout, KH, KW, stride, pad, a_u4: torch.Tensor, w_s4: torch.Tensor,
+                      scale: torch.Tensor, bias: torch.Tensor, s_out: float, out_u4: torch.Tensor,
+                      res_u4: Optional[torch.Tensor] = None, res_scale: float = 0.0,
+                      res_f32: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                      stream: Optional[int] = None) -> None:
+    """Convolution with the fused 4-bit output epilogue; out_u4: [M, Cout/8] packed words."""
+    OH = (H + 2 * pad - KH) // stride + 1
+    OW = (W + 2 * pad - KW) // stride + 1
+    M = B * OH * OW
+    _need(a_u4, B * H * W * Cin // 2, "a_u4")
+    _need(w_s4, Cout * KH * KW * Cin // 2, "w_s4")
+    _need(scale, Cout * 4, "scale")
+    _need(bias, Cout * 4, "bias")
+    _need(out_u4, M * Cout // 2, "out_u4")
+    if res_u4 is not None:
+        _need(res_u4, M * Cout // 2, "res_u4")
+    if res_f32 is not None:
+        _need(res_f32, M * Cout * 4, "res_f32")
+    d = qail_conv_desc(B, H, W, Cin, Cout, KH, KW, stride, pad)
+    wsb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().qail_w4a4_conv_u4(ctypes.byref(d), _ptr(a_u4), _ptr(w_s4), _ptr(scale), _ptr(bias),
+                                   float(s_out), _ptr(res_u4), float(res_scale), _ptr(res_f32), _ptr(out_u4),
+                                   _ptr(workspace), wsb, _stream() if stream is None else stream),
+           "qail_w4a4_conv_u4")

@@ -252,4 +252,24 @@ int qail_w4a4_gemm(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t
                                        static_cast<hipStream_t>(stream)));
 }
 
+int qail_w4a4_conv_u4(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t* w_s4, const float* scale,
+                      const float* bias, float s_out, const uint32_t* res_u4, float res_scale,
+                      const float* res_f32, uint32_t* out_u4, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    const int e = check_conv(d);
+    if (e != QAIL_OK) return e;
+    if (d->Cout % 8 != 0) return QAIL_ERR_SHAPE;           // codes are packed 8 per word along Cout
+    if (!(s_out > 0.f) || !(s_out <= 3.0e38f)) return QAIL_ERR_SHAPE;
+    if (res_u4 && res_f32) return QAIL_ERR_SHAPE;          // at most one shortcut
+    if (res_u4 && !(res_scale >= 0.f && res_scale <= 3.0e38f)) return QAIL_ERR_SHAPE;
+    if (!a_u4 || !w_s4 || !scale || !bias || !out_u4) return QAIL_ERR_NULL;
+    if (!aligned16(a_u4) || !aligned16(w_s4) || !aligned16(scale) || !aligned16(bias) || !aligned16(out_u4) ||
+        (res_u4 && !aligned16(res_u4)) || (res_f32 && !aligned16(res_f32)))
+        return QAIL_ERR_ALIGN;
+    return hip_status(launch_w4a4_conv_u4(*d, a_u4, w_s4, scale, bias, s_out, res_u4, res_scale, res_f32, out_u4,
+                                          static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

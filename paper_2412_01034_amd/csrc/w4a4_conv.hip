@@ -48,17 +48,80 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 }
 constexpr uint32_t kOut = 0xFFFFFFF0u;  // an offset no buffer here reaches
 
+// Where the results go.  Plain outputs: acc and / or y = fma(float(acc), scale, bias).
+// Fused output (out_u4 != nullptr): the next layer's packed unsigned codes, see fused_code().
+struct ConvOut {
+    int32_t* acc;
+    const float* scale;
+    const float* bias;
+    float* y;
+    uint32_t* out_u4;
+    const uint32_t* res_u4;
+    const float* res_f32;
+    float s_out, res_scale;
+};
+
+// One output element of the fused epilogue (Sec. 5.1: every activation tensor of the driving
+// encoder is 4-bit with one step per tensor, so the consumer's step is known here).  Each
+// line is one correctly rounded fp32 operation; contraction to fma is switched off because
+// the code is decided by these roundings and must equal the reference bit for bit.
+__device__ __forceinline__ uint32_t fused_code(int acc, float scale, float bias, float r, float s_out) {
+#pragma clang fp contract(off)
+    float t = (float)acc * scale;
+    t = t + bias;
+    t = t + r;
+    t = fmaxf(t, 0.f);
+    const float q = __builtin_rintf(t / s_out);
+    return (uint32_t)fminf(q, 15.f);
+}
+
+// 8 consecutive channels of one output pixel -> one packed word.
+__device__ __forceinline__ uint32_t fused_word(const int (&acc)[8], const ConvOut& o, size_t m, int n0, int cout) {
+    const float4 s0 = *reinterpret_cast<const float4*>(o.scale + n0), s1 = *reinterpret_cast<const float4*>(o.scale + n0 + 4);
+    const float4 b0 = *reinterpret_cast<const float4*>(o.bias + n0), b1 = *reinterpret_cast<const float4*>(o.bias + n0 + 4);
+    const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+    const float bi[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+    float r[8];
+    if (o.res_u4) {
+        const uint32_t rw = o.res_u4[m * (size_t)(cout / 8) + n0 / 8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+#pragma clang fp contract(off)
+            r[e] = o.res_scale * (float)((rw >> (4 * e)) & 0xFu);
+        }
+    } else if (o.res_f32) {
+        const float4 r0 = *reinterpret_cast<const float4*>(o.res_f32 + m * (size_t)cout + n0);
+        const float4 r1 = *reinterpret_cast<const float4*>(o.res_f32 + m * (size_t)cout + n0 + 4);
+        r[0] = r0.x; r[1] = r0.y; r[2] = r0.z; r[3] = r0.w; r[4] = r1.x; r[5] = r1.y; r[6] = r1.z; r[7] = r1.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = 0.f;
+    }
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        // without a shortcut r is 0 and t + 0 == t (a -0 becomes +0; both end as code 0)
+        word |= fused_code(acc[e], sc[e], bi[e], r[e], o.s_out) << (4 * e);
+    }
+    return word;
+}
+
 template <int BM, int BN, int kDepth>
 __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv_kernel(
-    const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w,
-    int32_t* __restrict__ acc_out, const float* __restrict__ scale, const float* __restrict__ bias,
-    float* __restrict__ y_out) {
+    const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, const ConvOut out) {
+    int32_t* const acc_out = out.acc;
+    const float* const scale = out.scale;
+    const float* const bias = out.bias;
+    float* const y_out = out.y;
     constexpr int kAR = BM / 64;   // A rows per thread
     constexpr int kBR = BN / 64;   // B rows per thread
     constexpr int kTM = BM / 32;   // MFMA tiles per wave along m
     constexpr int kTN = BN / 32;   // ... along n
-    __shared__ __attribute__((aligned(16))) uint32_t As[2][BM * kPitchW];
-    __shared__ __attribute__((aligned(16))) uint32_t Bs[2][BN * kPitchW];
+    // [2][BM] activation rows, then [2][BN] weight rows, kPitchW words each; the fused epilogue
+    // reuses the space as an int32 staging tile
+    __shared__ __attribute__((aligned(16))) uint32_t smem[2 * (BM + BN) * kPitchW];
+    uint32_t* const As0 = smem;
+    uint32_t* const Bs0 = smem + 2 * BM * kPitchW;
 
     const int t = threadIdx.x;
     const int lane = t % kWave;
@@ -136,13 +199,13 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
     auto store_lds = [&](int d, int buf) {
 #pragma unroll
         for (int i = 0; i < kAR; ++i) {
-            uint2* dst = reinterpret_cast<uint2*>(&As[buf][(lrow + 64 * i) * kPitchW + 4 * q]);
+            uint2* dst = reinterpret_cast<uint2*>(&As0[buf * BM * kPitchW + (lrow + 64 * i) * kPitchW + 4 * q]);
             dst[0] = make_uint2(ar[d][i].x, ar[d][i].y);
             dst[1] = make_uint2(ar[d][i].z, ar[d][i].w);
         }
 #pragma unroll
         for (int i = 0; i < kBR; ++i) {
-            uint2* dst = reinterpret_cast<uint2*>(&Bs[buf][(lrow + 64 * i) * kPitchW + 4 * q]);
+            uint2* dst = reinterpret_cast<uint2*>(&Bs0[buf * BN * kPitchW + (lrow + 64 * i) * kPitchW + 4 * q]);
             dst[0] = make_uint2(br[d][i].x, br[d][i].y);
             dst[1] = make_uint2(br[d][i].z, br[d][i].w);
         }
@@ -175,14 +238,14 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
 #pragma unroll
                 for (int i = 0; i < kTM; ++i) {
                     const uint2 p = *reinterpret_cast<const uint2*>(
-                        &As[buf][(wm * (BM / 2) + i * 16 + (lane & 15)) * kPitchW + sub * 8 + (lane >> 4) * 2]);
+                        &As0[buf * BM * kPitchW + (wm * (BM / 2) + i * 16 + (lane & 15)) * kPitchW + sub * 8 + (lane >> 4) * 2]);
                     af[i] = i32x4_t{(int)(p.x & 0x0F0F0F0Fu), (int)((p.x >> 4) & 0x0F0F0F0Fu),
                                     (int)(p.y & 0x0F0F0F0Fu), (int)((p.y >> 4) & 0x0F0F0F0Fu)};
                 }
 #pragma unroll
                 for (int j = 0; j < kTN; ++j) {
                     const uint2 p = *reinterpret_cast<const uint2*>(
-                        &Bs[buf][(wn * (BN / 2) + j * 16 + (lane & 15)) * kPitchW + sub * 8 + (lane >> 4) * 2]);
+                        &Bs0[buf * BN * kPitchW + (wn * (BN / 2) + j * 16 + (lane & 15)) * kPitchW + sub * 8 + (lane >> 4) * 2]);
                     bf[j] = i32x4_t{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
                                     (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
                 }
@@ -193,6 +256,41 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
                         acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
             }
         }
+    }
+
+    if (out.out_u4) {
+        // Fused output: the accumulators of half the tile's rows at a time are staged in LDS
+        // (pitch BN + 4 words: conflict-free for the writes below), then every thread turns 8
+        // consecutive channels of a pixel into one packed word.
+        constexpr int kSPitch = BN + 4;
+        static_assert((BM / 2) * kSPitch <= 2 * (BM + BN) * kPitchW, "staging tile must fit");
+        int32_t* const stage = reinterpret_cast<int32_t*>(smem);
+        constexpr int kWordsPerRow = BN / 8;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            __syncthreads();  // the operand tiles (or the previous pass) are no longer read
+            if (wm == pass) {
+#pragma unroll
+                for (int i = 0; i < kTM; ++i)
+#pragma unroll
+                    for (int j = 0; j < kTN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            stage[(i * 16 + (lane >> 4) * 4 + r) * kSPitch + wn * (BN / 2) + j * 16 + (lane & 15)] =
+                                acc[i][j][r] >> 4;  // exact: the accumulator is 16 * result
+            }
+            __syncthreads();
+            for (int idx = t; idx < (BM / 2) * kWordsPerRow; idx += 256) {
+                const int row = idx / kWordsPerRow, wd = idx % kWordsPerRow;
+                const int m = bm + pass * (BM / 2) + row, n0 = bn + wd * 8;
+                if (m >= gm.M || n0 >= gm.Cout) continue;
+                const i32x4_t v0 = *reinterpret_cast<const i32x4_t*>(&stage[row * kSPitch + wd * 8]);
+                const i32x4_t v1 = *reinterpret_cast<const i32x4_t*>(&stage[row * kSPitch + wd * 8 + 4]);
+                const int av[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+                out.out_u4[(size_t)m * (gm.Cout / 8) + n0 / 8] = fused_word(av, out, (size_t)m, n0, gm.Cout);
+            }
+        }
+        return;
     }
 
     // Epilogue through buffer stores: rows past M and columns past Cout get an offset past the
@@ -224,9 +322,11 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
 // Any Cin % 8 == 0: one thread per output.  Slow; for shapes whose Cin is not a
 // multiple of 32, more than 32 filter taps, or tensors of 4 GB and more.
 __global__ __launch_bounds__(256) void w4a4_generic_kernel(
-    const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w,
-    int32_t* __restrict__ acc_out, const float* __restrict__ scale, const float* __restrict__ bias,
-    float* __restrict__ y_out) {
+    const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, const ConvOut out) {
+    int32_t* const acc_out = out.acc;
+    const float* const scale = out.scale;
+    const float* const bias = out.bias;
+    float* const y_out = out.y;
     const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (o >= (size_t)gm.M * gm.Cout) return;
     const int m = (int)(o / gm.Cout), n = (int)(o % gm.Cout);
@@ -255,6 +355,37 @@ __global__ __launch_bounds__(256) void w4a4_generic_kernel(
     if (y_out) y_out[o] = fmaf((float)acc, scale[n], bias[n]);
 }
 
+// Fused output for the shapes above: one thread per packed output word.
+__global__ __launch_bounds__(256) void w4a4_generic_u4_kernel(
+    const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, const ConvOut out) {
+    const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int wpr = gm.Cout / 8;
+    if (o >= (size_t)gm.M * wpr) return;
+    const int m = (int)(o / wpr), n0 = (int)(o % wpr) * 8;
+    const int b = m / (gm.OH * gm.OW);
+    const int rem = m - b * (gm.OH * gm.OW);
+    const int oh = rem / gm.OW, ow = rem - oh * gm.OW;
+    const int cw = gm.Cin / 8;
+    int acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int kh = 0; kh < gm.KH; ++kh)
+        for (int kwi = 0; kwi < gm.KW; ++kwi) {
+            const int ih = oh * gm.stride + kh - gm.pad, iw = ow * gm.stride + kwi - gm.pad;
+            if (ih < 0 || ih >= gm.H || iw < 0 || iw >= gm.W) continue;
+            const uint32_t* ap = a + ((size_t)(b * gm.H + ih) * gm.W + iw) * cw;
+            for (int c = 0; c < cw; ++c) {
+                const uint32_t av = ap[c];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t wv = w[((size_t)((n0 + e) * gm.KH + kh) * gm.KW + kwi) * cw + c];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        acc[e] += (int)((av >> (4 * j)) & 0xFu) * ((int)(((wv >> (4 * j)) & 0xFu) ^ 8u) - 8);
+                }
+            }
+        }
+    out.out_u4[o] = fused_word(acc, out, (size_t)m, n0, gm.Cout);
+}
+
 int conv_cus() {
     static int cus = 0;
     if (cus == 0) {
@@ -268,16 +399,16 @@ int conv_cus() {
 }
 
 template <int BM, int BN, int kDepth>
-void launch_tiled(const ConvGeom& gm, const uint32_t* a, const uint32_t* w, int32_t* acc, const float* scale,
-                  const float* bias, float* y, hipStream_t st) {
+void launch_tiled(const ConvGeom& gm, const uint32_t* a, const uint32_t* w, const ConvOut& out, hipStream_t st) {
     dim3 grid((gm.Cout + BN - 1) / BN, (gm.M + BM - 1) / BM);
-    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN, kDepth>), grid, dim3(256), 0, st, gm, a, w, acc, scale, bias, y);
+    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN, kDepth>), grid, dim3(256), 0, st, gm, a, w, out);
 }
 
 }  // namespace
 
-hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
-                            const float* scale, const float* bias, float* y, hipStream_t st) {
+namespace {
+hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const ConvOut& out,
+                       hipStream_t st) {
     ConvGeom gm;
     gm.B = d.B; gm.H = d.H; gm.W = d.W; gm.Cin = d.Cin; gm.Cout = d.Cout;
     gm.KH = d.KH; gm.KW = d.KW; gm.stride = d.stride; gm.pad = d.pad;
@@ -294,16 +425,34 @@ hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const ui
             return (long long)((gm.M + bm - 1) / bm) * ((gm.Cout + bn - 1) / bn);
         };
         const bool wide = gm.Cout > 64;
-        if (wide && blocks(128, 128) >= want) launch_tiled<128, 128, 2>(gm, a, w, acc, scale, bias, y, st);
-        else if (blocks(128, 64) >= want) launch_tiled<128, 64, 2>(gm, a, w, acc, scale, bias, y, st);
-        else if (wide && blocks(64, 128) >= want / 2) launch_tiled<64, 128, 2>(gm, a, w, acc, scale, bias, y, st);
-        else launch_tiled<64, 64, 2>(gm, a, w, acc, scale, bias, y, st);
+        if (wide && blocks(128, 128) >= want) launch_tiled<128, 128, 2>(gm, a, w, out, st);
+        else if (blocks(128, 64) >= want) launch_tiled<128, 64, 2>(gm, a, w, out, st);
+        else if (wide && blocks(64, 128) >= want / 2) launch_tiled<64, 128, 2>(gm, a, w, out, st);
+        else launch_tiled<64, 64, 2>(gm, a, w, out, st);
+    } else if (out.out_u4) {
+        const size_t words = (size_t)gm.M * (d.Cout / 8);
+        hipLaunchKernelGGL(w4a4_generic_u4_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, gm,
+                           a, w, out);
     } else {
         const size_t outs = (size_t)gm.M * d.Cout;
         hipLaunchKernelGGL(w4a4_generic_kernel, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st, gm,
-                           a, w, acc, scale, bias, y);
+                           a, w, out);
     }
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
+                            const float* scale, const float* bias, float* y, hipStream_t st) {
+    const ConvOut out{acc, scale, bias, y, nullptr, nullptr, nullptr, 1.f, 0.f};
+    return launch_conv(d, a, w, out, st);
+}
+
+hipError_t launch_w4a4_conv_u4(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const float* scale,
+                               const float* bias, float s_out, const uint32_t* res_u4, float res_scale,
+                               const float* res_f32, uint32_t* out_u4, hipStream_t st) {
+    const ConvOut out{nullptr, scale, bias, nullptr, out_u4, res_u4, res_f32, s_out, res_scale};
+    return launch_conv(d, a, w, out, st);
 }
 
 }  // namespace qail

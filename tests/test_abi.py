@@ -71,6 +71,17 @@ def test_argument_errors_are_reported_without_a_gpu(B):
     assert L.qail_w4a4_gemm(ctypes.byref(bad), ok, ok, ok, None, None, None, None, 0, None) == B.QAIL_ERR_SHAPE
     bad = B.qail_conv_desc(1, 2, 2, 8, 4, 5, 5, 1, 0)
     assert L.qail_w4a4_gemm(ctypes.byref(bad), ok, ok, ok, None, None, None, None, 0, None) == B.QAIL_ERR_SHAPE
+    # fused 4-bit output: argument order (d, a, w, scale, bias, s_out, res_u4, res_scale, res_f32, out, ws, n, stream)
+    c8 = B.qail_conv_desc(1, 4, 4, 8, 8, 3, 3, 1, 1)
+    f = L.qail_w4a4_conv_u4
+    assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, None, 0.0, None, None, None, 0, None) == B.QAIL_ERR_NULL
+    assert f(ctypes.byref(c8), ok, ok, None, ok, 0.5, None, 0.0, None, ok, None, 0, None) == B.QAIL_ERR_NULL
+    assert f(ctypes.byref(c), ok, ok, ok, ok, 0.5, None, 0.0, None, ok, None, 0, None) == B.QAIL_ERR_SHAPE   # Cout = 4
+    assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.0, None, 0.0, None, ok, None, 0, None) == B.QAIL_ERR_SHAPE
+    assert f(ctypes.byref(c8), ok, ok, ok, ok, float("nan"), None, 0.0, None, ok, None, 0, None) == B.QAIL_ERR_SHAPE
+    assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, ok, 0.1, ok, ok, None, 0, None) == B.QAIL_ERR_SHAPE    # two shortcuts
+    assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, ok, -1.0, None, ok, None, 0, None) == B.QAIL_ERR_SHAPE
+    assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, odd, 0.1, None, ok, None, 0, None) == B.QAIL_ERR_ALIGN
     sz = ctypes.c_size_t(99)
     assert L.qail_w4a4_workspace(ctypes.byref(c), ctypes.byref(sz)) == B.QAIL_OK
     assert L.qail_w4a16_workspace(ctypes.byref(d), 1, ctypes.byref(sz)) == B.QAIL_OK

@@ -116,3 +116,84 @@ def test_resnet34_shapes_full_batch_sampled_images(B, s):
         ref = O.w4a4_conv_acc(aw[b:b + 1], ww, *one, use_blas=True)
         assert np.array_equal(acc[b * per:(b + 1) * per], ref)
         check_requant(y[b * per:(b + 1) * per], ref, scale, bias)
+
+
+# ------------------------------------------------------------------ fused 4-bit output
+
+FUSED = [
+    synth.ConvShape("f0", 1, 8, 8, 64, 64, 3, 3, 1, 1),
+    synth.ConvShape("f1", 2, 9, 7, 64, 72, 3, 3, 2, 1),       # ragged M and N tiles
+    synth.ConvShape("f2", 3, 14, 14, 128, 128, 3, 3, 1, 1),   # 128-wide tile, several row tiles
+    synth.ConvShape("f3", 2, 12, 12, 64, 128, 1, 1, 2, 0),    # projection geometry
+    synth.ConvShape("f4", 2, 5, 5, 8, 16, 3, 3, 1, 1),        # generic kernel
+    synth.ConvShape("f5", 4, 28, 28, 128, 256, 3, 3, 2, 1),   # 128 x 128 tiles over many blocks
+]
+
+
+def gpu_conv_u4(B, s, aw, ww, scale, bias, s_out, res_codes=None, res_scale=0.0, res_f32=None):
+    import torch
+    out = torch.full((s.M * s.Cout // 8,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    B.qail_w4a4_conv_u4(*geom(s), dev(aw), dev(ww), dev(scale), dev(bias), float(s_out), out,
+                        res_u4=dev(O.pack_nibbles(res_codes)) if res_codes is not None else None,
+                        res_scale=float(res_scale),
+                        res_f32=dev(res_f32) if res_f32 is not None else None)
+    torch.cuda.synchronize()
+    return host(out, np.uint32).reshape(s.M, s.Cout // 8)
+
+
+@pytest.mark.parametrize("kind", ["none", "codes", "f32"])
+@pytest.mark.parametrize("s", FUSED, ids=[s.name for s in FUSED])
+def test_fused_u4_output_bit_exact(B, s, kind):
+    aw, ww, scale, bias = quantised_inputs(s, 500 + s.Cout)
+    acc_ref = O.w4a4_conv_acc(aw, ww, *geom(s))
+    y = O.requant(acc_ref, scale, bias)
+    s_out = np.float32(max(float(y.max()), 1e-3) / 20.0)      # the largest outputs clamp at 15
+    rng = np.random.default_rng(s.M)
+    rc = rs = rf = None
+    if kind == "codes":
+        rc, rs = rng.integers(0, 16, size=(s.M, s.Cout)).astype(np.uint8), np.float32(s_out * 0.8)
+    elif kind == "f32":
+        rf = (rng.standard_normal((s.M, s.Cout)) * float(s_out) * 3).astype(np.float32)
+    ref = O.fused_requant_u4(acc_ref, scale, bias, s_out, res_codes=rc, res_scale=rs, res_f32=rf)
+    assert ref.max() == 15 and ref.min() == 0
+    got = gpu_conv_u4(B, s, aw, ww, scale, bias, s_out, rc, rs if rs is not None else 0.0, rf)
+    assert np.array_equal(got, O.pack_nibbles(ref))
+
+
+def test_fused_u4_ties_and_clamps(B):
+    # operands exact in binary so that t / s_out lands on k + 0.5 for many elements: the kernel
+    # must round those to even and must not fuse the multiply into the add
+    s = synth.ConvShape("tie", 1, 6, 6, 64, 64, 1, 1, 1, 0)
+    a = synth.random_codes((s.B, s.H, s.W, s.Cin), 0, 3, 21).astype(np.uint8)
+    w = synth.random_codes((s.Cout, s.K), -2, 2, 22)
+    aw, ww = O.pack_nibbles(a), O.pack_nibbles(w)
+    acc_ref = O.w4a4_conv_acc(aw, ww, *geom(s))
+    scale = np.full(s.Cout, 0.25, np.float32)
+    bias = np.full(s.Cout, 0.125, np.float32)
+    ref = O.fused_requant_u4(acc_ref, scale, bias, np.float32(0.25))
+    t = acc_ref * 0.25 + 0.125
+    assert np.any((t > 0) & (t / 0.25 % 1 == 0.5))               # ties are present
+    got = gpu_conv_u4(B, s, aw, ww, scale, bias, 0.25)
+    assert np.array_equal(got, O.pack_nibbles(ref))
+
+
+def test_fused_output_feeds_the_next_layer(B):
+    # conv1 (fused) -> conv2 (int32): the codes written by the first call are the a_u4 of the second
+    import torch
+    s1 = synth.ConvShape("c1", 2, 10, 10, 64, 64, 3, 3, 1, 1)
+    s2 = synth.ConvShape("c2", 2, 10, 10, 64, 128, 3, 3, 2, 1)
+    aw, w1, scale1, bias1 = quantised_inputs(s1, 901)
+    _, w2, _, _ = quantised_inputs(s2, 902)
+    acc1 = O.w4a4_conv_acc(aw, w1, *geom(s1))
+    s_mid = np.float32(float(O.requant(acc1, scale1, bias1).max()) / 15.0)
+    res = O.unpack_nibbles_u4(aw.reshape(s1.M, s1.Cin // 8), s1.Cin)        # identity shortcut: the block input
+    mid_ref = O.fused_requant_u4(acc1, scale1, bias1, s_mid, res_codes=res, res_scale=np.float32(0.05))
+    mid = torch.zeros(s1.M * s1.Cout // 8, dtype=torch.int32, device="cuda")
+    B.qail_w4a4_conv_u4(*geom(s1), dev(aw), dev(w1), dev(scale1), dev(bias1), float(s_mid), mid,
+                        res_u4=dev(aw), res_scale=0.05)
+    acc2 = torch.zeros(s2.M * s2.Cout, dtype=torch.int32, device="cuda")
+    B.qail_w4a4_gemm(*geom(s2), mid, dev(w2), acc_out=acc2)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(mid, np.uint32).reshape(s1.M, -1), O.pack_nibbles(mid_ref))
+    ref2 = O.w4a4_conv_acc(O.pack_nibbles(mid_ref).reshape(s1.B, s1.H, s1.W, -1), w2, *geom(s2))
+    assert np.array_equal(host(acc2, np.int32).reshape(s2.M, s2.Cout), ref2)
