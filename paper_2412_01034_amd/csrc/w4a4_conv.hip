@@ -32,7 +32,6 @@ namespace qail {
 namespace {
 
 constexpr int kStepWords = 16;  // packed words per row per K step (128 codes)
-constexpr int kPitchW = 18;     // words per LDS row: 8-byte aligned, conflict-free for the fragment reads
 
 struct ConvGeom {
     int B, H, W, Cin, Cout, KH, KW, stride, pad, OH, OW, M;
@@ -106,22 +105,51 @@ __device__ __forceinline__ uint32_t fused_word(const int (&acc)[8], const ConvOu
     return word;
 }
 
-template <int BM, int BN, int kDepth>
+// Global -> LDS copy by the load unit through a buffer descriptor: lane l's 16 bytes at byte
+// offset `off` of the buffer land at LDS address lds + 16 l; a lane whose offset lies outside the
+// buffer writes 16 zero bytes (checked on the GPU with a probe), which is exactly what image
+// borders, the K tail and tile edges need.  Assembly on purpose: the compiler would make every
+// later LDS read wait for all such copies in flight (it cannot tell the ring slots apart).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_t make_rsrc_words(const void* p, uint32_t bytes) {
+    const uint64_t b = (uint64_t)(uintptr_t)p;
+    u32x4_t r = {(uint32_t)b, (uint32_t)(b >> 32) & 0xFFFFu, bytes, 0x00020000u};
+    r[0] = __builtin_amdgcn_readfirstlane(r[0]);
+    r[1] = __builtin_amdgcn_readfirstlane(r[1]);
+    r[2] = __builtin_amdgcn_readfirstlane(r[2]);
+    r[3] = __builtin_amdgcn_readfirstlane(r[3]);
+    return r;
+}
+__device__ __forceinline__ void dma16(u32x4_t rsrc, uint32_t off, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds), "v"(off), "s"(rsrc) : "memory", "m0");
+}
+__host__ __device__ constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }  // lgkmcnt 0 too
+
+constexpr int kStages = 3;  // ring of K steps in LDS: step s + 2 is loaded while step s is multiplied
+constexpr int kMaxSteps = 128;  // rows of the step table (K steps plus the ring's look-ahead)
+
+// Tiling: a block of 4 waves (2 x 2) owns a BM x BN output tile and walks K in steps of 128
+// codes (64 B per row; K is ordered (kh, kw, c) and Cin % 32 == 0, so every 16-byte chunk lies
+// inside one filter tap).  Rows are unpadded in LDS; chunk c of row r is kept at position
+// c ^ ((r / 4) % 4), chosen through the loading lane's address, which makes the 8-byte fragment
+// reads of 16 consecutive rows conflict-free.
+template <int BM, int BN>
 __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv_kernel(
     const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, const ConvOut out) {
-    int32_t* const acc_out = out.acc;
-    const float* const scale = out.scale;
-    const float* const bias = out.bias;
-    float* const y_out = out.y;
-    constexpr int kAR = BM / 64;   // A rows per thread
-    constexpr int kBR = BN / 64;   // B rows per thread
+    constexpr int kLA = BM / 64;   // wave-wide loads per wave and step for the activation tile
+    constexpr int kLB = BN / 64;   // ... for the weight tile
+    constexpr int kL = kLA + kLB;
     constexpr int kTM = BM / 32;   // MFMA tiles per wave along m
     constexpr int kTN = BN / 32;   // ... along n
-    // [2][BM] activation rows, then [2][BN] weight rows, kPitchW words each; the fused epilogue
-    // reuses the space as an int32 staging tile
-    __shared__ __attribute__((aligned(16))) uint32_t smem[2 * (BM + BN) * kPitchW];
-    uint32_t* const As0 = smem;
-    uint32_t* const Bs0 = smem + 2 * BM * kPitchW;
+    constexpr int kStageBytes = (BM + BN) * 64;
+    constexpr int kSPitch = BN + 4;  // words per row of the int32 staging tile of the epilogue
+    constexpr int kPasses = BM * kSPitch * 4 <= kStages * kStageBytes ? 1 : 2;  // epilogue passes over the rows
+    constexpr int kPassRows = BM / kPasses;
+    constexpr int kLdsBytes = kStages * kStageBytes > kPassRows * kSPitch * 4 ? kStages * kStageBytes
+                                                                               : kPassRows * kSPitch * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
+    __shared__ uint2 steptab[kMaxSteps * 4];
 
     const int t = threadIdx.x;
     const int lane = t % kWave;
@@ -133,17 +161,20 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
     const int steps = (kwords + kStepWords - 1) / kStepWords;
     const int ntaps = gm.KH * gm.KW;
 
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(a, (uint32_t)((size_t)gm.B * gm.H * gm.W * cw * 4));
-    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)((size_t)gm.Cout * kwords * 4));
+    const u32x4_t ra = make_rsrc_words(a, (uint32_t)((size_t)gm.B * gm.H * gm.W * cw * 4));
+    const u32x4_t rw = make_rsrc_words(w, (uint32_t)((size_t)gm.Cout * kwords * 4));
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)smem);
 
-    // Loader geometry: thread t loads words [4q, 4q+4) of a step for rows t/4 + 64*i: the four
-    // lanes of a row fetch 64 contiguous bytes.
-    const int q = t & 3, lrow = t >> 2;
-    int abase[kAR];       // byte offset of (b, ih0, iw0, 0); may be negative at the border
-    uint32_t amask[kAR];  // bit tap = the tap's pixel is inside the image
+    // Loader geometry: load i of this wave fills rows (4 i + wave) * 16 + lane / 4, position
+    // lane % 4, with the chunk that belongs there.
+    const int lrow = lane >> 2;
+    const int chunk = (lane & 3) ^ ((lrow >> 2) & 3);  // which 16 bytes of a step this lane fetches
+    int abase[kLA];       // byte offset of (b, ih0, iw0, 0); may be negative at the border
+    uint32_t amask[kLA];  // bit tap = the tap's pixel is inside the image
 #pragma unroll
-    for (int i = 0; i < kAR; ++i) {
-        const int m = bm + lrow + 64 * i;
+    for (int i = 0; i < kLA; ++i) {
+        const int m = bm + (4 * i + wave) * 16 + lrow;
         abase[i] = 0;
         amask[i] = 0;
         if (m < gm.M) {
@@ -152,64 +183,70 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
             const int oh = rem / gm.OW, ow = rem - oh * gm.OW;
             const int ih0 = oh * gm.stride - gm.pad, iw0 = ow * gm.stride - gm.pad;
             abase[i] = ((b * gm.H + ih0) * gm.W + iw0) * cw * 4;
-            for (int kh = 0; kh < gm.KH; ++kh)
-                for (int kwi = 0; kwi < gm.KW; ++kwi)
-                    if (ih0 + kh >= 0 && ih0 + kh < gm.H && iw0 + kwi >= 0 && iw0 + kwi < gm.W)
-                        amask[i] |= 1u << (kh * gm.KW + kwi);
+            // taps inside the image: kw in [kw_lo, kw_hi) for every kh in [kh_lo, kh_hi)
+            const int kw_lo = max(0, -iw0), kw_hi = min(gm.KW, gm.W - iw0);
+            const int kh_lo = max(0, -ih0), kh_hi = min(gm.KH, gm.H - ih0);
+            const uint32_t cols = kw_hi > kw_lo ? (0xFFFFFFFFu >> (32 - (kw_hi - kw_lo))) << kw_lo : 0u;
+            for (int kh = kh_lo; kh < kh_hi; ++kh) amask[i] |= cols << (kh * gm.KW);
         }
     }
-    uint32_t bbase[kBR];
+    uint32_t bbase[kLB];
 #pragma unroll
-    for (int i = 0; i < kBR; ++i) {
-        const int n = bn + lrow + 64 * i;
+    for (int i = 0; i < kLB; ++i) {
+        const int n = bn + (4 * i + wave) * 16 + lrow;
         bbase[i] = n < gm.Cout ? (uint32_t)n * kwords * 4 : kOut;
     }
 
-    // Register ring of kDepth K-steps of loads: a step's loads are issued kDepth steps before
-    // they are needed (a step is only a few hundred MFMA cycles, far less than a cache
-    // latency).  Nothing about a load is conditional, so the loads in flight at every wait are
-    // known at compile time.
-    u32x4_t ar[kDepth][kAR], br[kDepth][kBR];
-    // position of the next step to issue (per thread: it depends on q), advanced without divisions
-    int nkw0 = 4 * q, ncword = 4 * q, ntap = 0, ntapoff = 0, nkwi = 0;
-    auto advance = [&](int words) {
-        nkw0 += words;
-        ncword += words;
-        while (ncword >= cw) {
-            ncword -= cw;
-            ++ntap;
-            ntapoff += cw * 4;
-            if (++nkwi == gm.KW) { nkwi = 0; ntapoff += (gm.W - gm.KW) * cw * 4; }
+    // Where a K step's chunks come from is the same for every row and every block: a table in
+    // LDS, built once, holds for (step, chunk) the byte offset of the chunk from a pixel's
+    // (ih0, iw0, 0), its offset inside a filter row, and its tap; steps past the end of K are
+    // marked invalid (their loads read nothing and write zeros).
+    {
+        const int entries = (steps + kStages) * 4;
+        for (int e = t; e < entries; e += 256) {
+            const int kw0 = (e >> 2) * kStepWords + (e & 3) * 4;   // first word of the chunk
+            uint2 v = make_uint2(0u, 0xFFFFFFFFu);
+            if (kw0 < kwords) {
+                const int tap = kw0 / cw, cword = kw0 - tap * cw;
+                const int kh = tap / gm.KW, kwi = tap - kh * gm.KW;
+                v.x = (uint32_t)(((kh * gm.W + kwi) * cw + cword) * 4);
+                v.y = (uint32_t)(kw0 * 4) | ((uint32_t)tap << 26);
+            }
+            steptab[e] = v;
         }
+    }
+    __syncthreads();
+    int pstep = 0;
+    uint2 pent = steptab[chunk];  // entry of the next step to plan, read one step ahead
+    uint32_t poff[kL];
+    auto plan = [&]() {
+        const uint2 e = pent;
+        ++pstep;
+        pent = steptab[pstep * 4 + chunk];
+        const bool kin = (e.y >> 31) == 0;
+        const uint32_t tap = (e.y >> 26) & 31u, kw4 = e.y & 0x03FFFFFFu;
+#pragma unroll
+        for (int i = 0; i < kLA; ++i) {
+            const bool in = kin && ((amask[i] >> tap) & 1u);
+            poff[i] = in ? (uint32_t)(abase[i] + (int)e.x) : kOut;
+        }
+#pragma unroll
+        for (int i = 0; i < kLB; ++i) poff[kLA + i] = kin ? bbase[i] + kw4 : kOut;
     };
-    advance(0);
-    auto issue = [&](int d) {
-        const bool kin = ntap < ntaps;
-        const int koff = ntapoff + ncword * 4;  // bytes from (ih0, iw0, 0) to this tap's words
-#pragma unroll
-        for (int i = 0; i < kAR; ++i) {
-            const bool in = kin && ((amask[i] >> ntap) & 1u);
-            ar[d][i] = __builtin_amdgcn_raw_buffer_load_b128(ra, in ? (uint32_t)(abase[i] + koff) : kOut, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < kBR; ++i)
-            br[d][i] = __builtin_amdgcn_raw_buffer_load_b128(rw, kin ? bbase[i] + (uint32_t)nkw0 * 4 : kOut, 0, 0);
-        advance(kStepWords);
+    auto issue = [&](int i, int slot) {
+        if (i < kLA)
+            dma16(ra, poff[i], lds0 + slot * kStageBytes + (4 * i + wave) * 1024);
+        else
+            dma16(rw, poff[i], lds0 + slot * kStageBytes + BM * 64 + (4 * (i - kLA) + wave) * 1024);
     };
-    auto store_lds = [&](int d, int buf) {
+
+    // Fragment reads: lane (r16, kq) takes 8 bytes (16 codes) of row r16 of a 16-row tile for
+    // each of the two 64-code MFMA steps of a K step.
+    const int r16 = lane & 15, kq = lane >> 4;
+    int foff[2];
 #pragma unroll
-        for (int i = 0; i < kAR; ++i) {
-            uint2* dst = reinterpret_cast<uint2*>(&As0[buf * BM * kPitchW + (lrow + 64 * i) * kPitchW + 4 * q]);
-            dst[0] = make_uint2(ar[d][i].x, ar[d][i].y);
-            dst[1] = make_uint2(ar[d][i].z, ar[d][i].w);
-        }
-#pragma unroll
-        for (int i = 0; i < kBR; ++i) {
-            uint2* dst = reinterpret_cast<uint2*>(&Bs0[buf * BN * kPitchW + (lrow + 64 * i) * kPitchW + 4 * q]);
-            dst[0] = make_uint2(br[d][i].x, br[d][i].y);
-            dst[1] = make_uint2(br[d][i].z, br[d][i].w);
-        }
-    };
+    for (int sub = 0; sub < 2; ++sub)
+        foff[sub] = r16 * 64 + (((2 * sub + (kq >> 1)) ^ ((r16 >> 2) & 3)) << 4) + (kq & 1) * 8;
 
     i32x4_t acc[kTM][kTN];
 #pragma unroll
@@ -217,105 +254,133 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
 #pragma unroll
         for (int j = 0; j < kTN; ++j) acc[i][j] = i32x4_t{0, 0, 0, 0};
 
+    i32x4_t af[2][kTM], bf[2][kTN];
+    auto fetch = [&](int slot, int sub, int reg) {
+        const unsigned char* As = smem + slot * kStageBytes + wm * (BM / 2) * 64 + foff[sub];
+        const unsigned char* Bs = smem + slot * kStageBytes + BM * 64 + wn * (BN / 2) * 64 + foff[sub];
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) {
-        issue(d);  // steps past the end of K read nothing
-        __builtin_amdgcn_sched_barrier(0);
-    }
+        for (int i = 0; i < kTM; ++i) {
+            const uint2 p = *reinterpret_cast<const uint2*>(As + i * 16 * 64);
+            af[reg][i] = i32x4_t{(int)(p.x & 0x0F0F0F0Fu), (int)((p.x >> 4) & 0x0F0F0F0Fu),
+                                 (int)(p.y & 0x0F0F0F0Fu), (int)((p.y >> 4) & 0x0F0F0F0Fu)};
+        }
+#pragma unroll
+        for (int j = 0; j < kTN; ++j) {
+            const uint2 p = *reinterpret_cast<const uint2*>(Bs + j * 16 * 64);
+            bf[reg][j] = i32x4_t{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
+                                 (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
+        }
+    };
+    auto multiply = [&](int reg) {
+#pragma unroll
+        for (int i = 0; i < kTM; ++i)
+#pragma unroll
+            for (int j = 0; j < kTN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[reg][i], bf[reg][j], acc[i][j], 0, 0, 0);
+        // issue order: the LDS reads and the widening of the next fragments go between the MFMAs
+        constexpr int kM = kTM * kTN, kR = kTM + kTN;
+#pragma unroll
+        for (int u = 0; u < kM; ++u) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (u < kR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, (4 * kR + kM - 1) / kM, 0);
+        }
+    };
 
-    for (int s0 = 0; s0 < steps; s0 += kDepth) {
+    // steps 0 and 1 up front, then step s + 2 during step s
 #pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-            if (s0 + d >= steps) break;
-            const int buf = d & 1;  // kDepth is even
-            store_lds(d, buf);
-            issue(d);
+    for (int p = 0; p < kStages - 1; ++p) {
+        plan();
+#pragma unroll
+        for (int i = 0; i < kL; ++i) issue(i, p);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kL));
+    __syncthreads();
+    fetch(0, 0, 0);
+
+    for (int s0 = 0; s0 < steps; s0 += kStages) {
+#pragma unroll
+        for (int u = 0; u < kStages; ++u) {
+            if (s0 + u >= steps) break;
+            const int cur = u, nxt = (u + 1) % kStages, fill = (u + 2) % kStages;
             __builtin_amdgcn_sched_barrier(0);
+            fetch(cur, 1, 1);
+            multiply(0);
+            __builtin_amdgcn_sched_barrier(0);
+            // slot `fill` held step s - 1, whose last reads were issued before the previous barrier
+            plan();
+#pragma unroll
+            for (int i = 0; i < kL; ++i) issue(i, fill);
+            // in flight: step s + 1 (issued one step ago) and step s + 2 (just issued)
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(kL));
             __syncthreads();
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {  // two MFMA k-steps of 64 codes (8 words)
-                i32x4_t af[kTM], bf[kTN];
-#pragma unroll
-                for (int i = 0; i < kTM; ++i) {
-                    const uint2 p = *reinterpret_cast<const uint2*>(
-                        &As0[buf * BM * kPitchW + (wm * (BM / 2) + i * 16 + (lane & 15)) * kPitchW + sub * 8 + (lane >> 4) * 2]);
-                    af[i] = i32x4_t{(int)(p.x & 0x0F0F0F0Fu), (int)((p.x >> 4) & 0x0F0F0F0Fu),
-                                    (int)(p.y & 0x0F0F0F0Fu), (int)((p.y >> 4) & 0x0F0F0F0Fu)};
-                }
-#pragma unroll
-                for (int j = 0; j < kTN; ++j) {
-                    const uint2 p = *reinterpret_cast<const uint2*>(
-                        &Bs0[buf * BN * kPitchW + (wn * (BN / 2) + j * 16 + (lane & 15)) * kPitchW + sub * 8 + (lane >> 4) * 2]);
-                    bf[j] = i32x4_t{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
-                                    (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
-                }
-#pragma unroll
-                for (int i = 0; i < kTM; ++i)
-#pragma unroll
-                    for (int j = 0; j < kTN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
-            }
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(nxt, 0, 0);
+            multiply(1);
         }
     }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // nothing may still be writing LDS
+    __syncthreads();
 
-    if (out.out_u4) {
-        // Fused output: the accumulators of half the tile's rows at a time are staged in LDS
-        // (pitch BN + 4 words: conflict-free for the writes below), then every thread turns 8
-        // consecutive channels of a pixel into one packed word.
-        constexpr int kSPitch = BN + 4;
-        static_assert((BM / 2) * kSPitch <= 2 * (BM + BN) * kPitchW, "staging tile must fit");
-        int32_t* const stage = reinterpret_cast<int32_t*>(smem);
-        constexpr int kWordsPerRow = BN / 8;
+    // Epilogue: the accumulators (all rows at once if they fit, else half the rows at a time)
+    // are staged in LDS (pitch BN + 4 words: conflict-free for the writes below) and leave as
+    // whole pieces of rows.
+    int32_t* const stage = reinterpret_cast<int32_t*>(smem);
 #pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-            __syncthreads();  // the operand tiles (or the previous pass) are no longer read
-            if (wm == pass) {
+    for (int pass = 0; pass < kPasses; ++pass) {
+        if (pass) __syncthreads();  // the previous pass has been read
+        if (kPasses == 1 || wm == pass) {
+            const int rbase = kPasses == 1 ? wm * (BM / 2) : 0;
 #pragma unroll
-                for (int i = 0; i < kTM; ++i)
+            for (int i = 0; i < kTM; ++i)
 #pragma unroll
-                    for (int j = 0; j < kTN; ++j)
+                for (int j = 0; j < kTN; ++j)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            stage[(i * 16 + (lane >> 4) * 4 + r) * kSPitch + wn * (BN / 2) + j * 16 + (lane & 15)] =
-                                acc[i][j][r] >> 4;  // exact: the accumulator is 16 * result
-            }
-            __syncthreads();
-            for (int idx = t; idx < (BM / 2) * kWordsPerRow; idx += 256) {
+                    for (int r = 0; r < 4; ++r)
+                        stage[(rbase + i * 16 + (lane >> 4) * 4 + r) * kSPitch + wn * (BN / 2) + j * 16 + (lane & 15)] =
+                            acc[i][j][r] >> 4;  // exact: the accumulator is 16 * result
+        }
+        __syncthreads();
+        if (out.out_u4) {
+            // fused output: 8 consecutive channels of a pixel -> one packed word
+            constexpr int kWordsPerRow = BN / 8;
+            for (int idx = t; idx < kPassRows * kWordsPerRow; idx += 256) {
                 const int row = idx / kWordsPerRow, wd = idx % kWordsPerRow;
-                const int m = bm + pass * (BM / 2) + row, n0 = bn + wd * 8;
+                const int m = bm + pass * kPassRows + row, n0 = bn + wd * 8;
                 if (m >= gm.M || n0 >= gm.Cout) continue;
                 const i32x4_t v0 = *reinterpret_cast<const i32x4_t*>(&stage[row * kSPitch + wd * 8]);
                 const i32x4_t v1 = *reinterpret_cast<const i32x4_t*>(&stage[row * kSPitch + wd * 8 + 4]);
                 const int av[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
                 out.out_u4[(size_t)m * (gm.Cout / 8) + n0 / 8] = fused_word(av, out, (size_t)m, n0, gm.Cout);
             }
-        }
-        return;
-    }
-
-    // Epilogue through buffer stores: rows past M and columns past Cout get an offset past the
-    // end and are dropped.
-    const uint32_t out_bytes = (uint32_t)((size_t)gm.M * gm.Cout * 4);
-    const __amdgpu_buffer_rsrc_t racc = make_rsrc(acc_out, acc_out ? out_bytes : 0);
-    const __amdgpu_buffer_rsrc_t ry = make_rsrc(y_out, y_out ? out_bytes : 0);
-    const int m0 = bm + wm * (BM / 2) + (lane >> 4) * 4;
-    const int n0 = bn + wn * (BN / 2) + (lane & 15);
-#pragma unroll
-    for (int j = 0; j < kTN; ++j) {
-        const int n = n0 + j * 16;
-        const bool nin = n < gm.Cout;
-        const float sc = (y_out && nin) ? scale[n] : 0.f;
-        const float bi = (y_out && nin) ? bias[n] : 0.f;
-#pragma unroll
-        for (int i = 0; i < kTM; ++i)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int m = m0 + i * 16 + r;
-                const uint32_t off = (nin && m < gm.M) ? (uint32_t)(m * gm.Cout + n) * 4 : kOut;
-                const int v = acc[i][j][r] >> 4;  // exact: the accumulator is 16 * result
-                if (acc_out) __builtin_amdgcn_raw_buffer_store_b32((uint32_t)v, racc, off, 0, 0);
-                if (y_out) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, fmaf((float)v, sc, bi)), ry, off, 0, 0);
+        } else {
+            // plain outputs: 4 consecutive channels per thread, 16-byte stores when Cout allows
+            constexpr int kQuadsPerRow = BN / 4;
+            const bool vec = (gm.Cout % 4) == 0;
+            for (int idx = t; idx < kPassRows * kQuadsPerRow; idx += 256) {
+                const int row = idx / kQuadsPerRow, qd = idx % kQuadsPerRow;
+                const int m = bm + pass * kPassRows + row, n0 = bn + qd * 4;
+                if (m >= gm.M || n0 >= gm.Cout) continue;
+                const i32x4_t v = *reinterpret_cast<const i32x4_t*>(&stage[row * kSPitch + qd * 4]);
+                const size_t o = (size_t)m * gm.Cout + n0;
+                if (vec) {
+                    if (out.acc) *reinterpret_cast<i32x4_t*>(out.acc + o) = v;
+                    if (out.y) {
+                        const float4 sc = *reinterpret_cast<const float4*>(out.scale + n0);
+                        const float4 bi = *reinterpret_cast<const float4*>(out.bias + n0);
+                        *reinterpret_cast<float4*>(out.y + o) =
+                            make_float4(fmaf((float)v[0], sc.x, bi.x), fmaf((float)v[1], sc.y, bi.y),
+                                        fmaf((float)v[2], sc.z, bi.z), fmaf((float)v[3], sc.w, bi.w));
+                    }
+                } else {
+                    for (int e = 0; e < 4 && n0 + e < gm.Cout; ++e) {
+                        if (out.acc) out.acc[o + e] = v[e];
+                        if (out.y) out.y[o + e] = fmaf((float)v[e], out.scale[n0 + e], out.bias[n0 + e]);
+                    }
+                }
             }
+        }
     }
 }
 
@@ -398,10 +463,10 @@ int conv_cus() {
     return cus;
 }
 
-template <int BM, int BN, int kDepth>
+template <int BM, int BN>
 void launch_tiled(const ConvGeom& gm, const uint32_t* a, const uint32_t* w, const ConvOut& out, hipStream_t st) {
     dim3 grid((gm.Cout + BN - 1) / BN, (gm.M + BM - 1) / BM);
-    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN, kDepth>), grid, dim3(256), 0, st, gm, a, w, out);
+    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN>), grid, dim3(256), 0, st, gm, a, w, out);
 }
 
 }  // namespace
@@ -418,17 +483,18 @@ hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_
     const bool fits32 = (size_t)gm.B * gm.H * gm.W * (gm.Cin / 2) < 0xFFFFFFF0ull &&
                         (size_t)gm.Cout * gm.KH * gm.KW * (gm.Cin / 2) < 0xFFFFFFF0ull &&
                         (size_t)gm.M * gm.Cout * 4 < 0xFFFFFFF0ull;
-    if (d.Cin % 32 == 0 && d.KH * d.KW <= 32 && fits32) {
+    const int ksteps = (gm.KH * gm.KW * (gm.Cin / 8) + kStepWords - 1) / kStepWords;
+    if (d.Cin % 32 == 0 && d.KH * d.KW <= 32 && fits32 && ksteps + kStages <= kMaxSteps) {
         // the largest tile that still gives every CU about two blocks
         const long long want = 2LL * conv_cus();
         auto blocks = [&](int bm, int bn) {
             return (long long)((gm.M + bm - 1) / bm) * ((gm.Cout + bn - 1) / bn);
         };
         const bool wide = gm.Cout > 64;
-        if (wide && blocks(128, 128) >= want) launch_tiled<128, 128, 2>(gm, a, w, out, st);
-        else if (blocks(128, 64) >= want) launch_tiled<128, 64, 2>(gm, a, w, out, st);
-        else if (wide && blocks(64, 128) >= want / 2) launch_tiled<64, 128, 2>(gm, a, w, out, st);
-        else launch_tiled<64, 64, 2>(gm, a, w, out, st);
+        if (wide && blocks(128, 128) >= want) launch_tiled<128, 128>(gm, a, w, out, st);
+        else if (blocks(128, 64) >= want) launch_tiled<128, 64>(gm, a, w, out, st);
+        else if (wide && blocks(64, 128) >= want / 2) launch_tiled<64, 128>(gm, a, w, out, st);
+        else launch_tiled<64, 64>(gm, a, w, out, st);
     } else if (out.out_u4) {
         const size_t words = (size_t)gm.M * (d.Cout / 8);
         hipLaunchKernelGGL(w4a4_generic_u4_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, gm,
