@@ -134,8 +134,13 @@ constexpr int kMaxSteps = 128;  // rows of the step table (K steps plus the ring
 // inside one filter tap).  Rows are unpadded in LDS; chunk c of row r is kept at position
 // c ^ ((r / 4) % 4), chosen through the loading lane's address, which makes the 8-byte fragment
 // reads of 16 consecutive rows conflict-free.
-template <int BM, int BN>
-__global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv_kernel(
+//
+// KS > 1: KS groups of 4 waves share the tile and split K between them (group g takes steps
+// g, g + KS, ...), each with its own ring; their int32 partial tiles are added in the epilogue
+// (integer sums: exact in any order).  For the deep layers of a small batch, which have few
+// tiles and long K, this puts several waves on every SIMD instead of one.
+template <int BM, int BN, int KS>
+__global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 : 4))) void w4a4_conv_kernel(
     const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, const ConvOut out) {
     constexpr int kLA = BM / 64;   // wave-wide loads per wave and step for the activation tile
     constexpr int kLB = BN / 64;   // ... for the weight tile
@@ -146,20 +151,23 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
     constexpr int kSPitch = BN + 4;  // words per row of the int32 staging tile of the epilogue
     constexpr int kPasses = BM * kSPitch * 4 <= kStages * kStageBytes ? 1 : 2;  // epilogue passes over the rows
     constexpr int kPassRows = BM / kPasses;
-    constexpr int kLdsBytes = kStages * kStageBytes > kPassRows * kSPitch * 4 ? kStages * kStageBytes
-                                                                               : kPassRows * kSPitch * 4;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
+    constexpr int kGroupBytes = kStages * kStageBytes > kPassRows * kSPitch * 4 ? kStages * kStageBytes
+                                                                                 : kPassRows * kSPitch * 4;
+    constexpr int kThreads = 256 * KS;
+    __shared__ __attribute__((aligned(16))) unsigned char smem_all[KS * kGroupBytes];
     __shared__ uint2 steptab[kMaxSteps * 4];
 
     const int t = threadIdx.x;
     const int lane = t % kWave;
-    const int wave = __builtin_amdgcn_readfirstlane(t / kWave);
+    const int wave_all = __builtin_amdgcn_readfirstlane(t / kWave);
+    const int grp = wave_all / 4, wave = wave_all % 4;   // K group, wave inside the group
+    unsigned char* const smem = smem_all + grp * kGroupBytes;
     const int wm = wave / 2, wn = wave % 2;
     const int bm = blockIdx.y * BM, bn = blockIdx.x * BN;
     const int cw = gm.Cin / 8;                 // words per pixel
     const int kwords = gm.KH * gm.KW * cw;     // words per filter
-    const int steps = (kwords + kStepWords - 1) / kStepWords;
-    const int ntaps = gm.KH * gm.KW;
+    const int gsteps = (kwords + kStepWords - 1) / kStepWords;   // K steps of the whole problem
+    const int steps = (gsteps + KS - 1) / KS;                     // ... of one group (the same for all)
 
     const u32x4_t ra = make_rsrc_words(a, (uint32_t)((size_t)gm.B * gm.H * gm.W * cw * 4));
     const u32x4_t rw = make_rsrc_words(w, (uint32_t)((size_t)gm.Cout * kwords * 4));
@@ -202,8 +210,8 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
     // (ih0, iw0, 0), its offset inside a filter row, and its tap; steps past the end of K are
     // marked invalid (their loads read nothing and write zeros).
     {
-        const int entries = (steps + kStages) * 4;
-        for (int e = t; e < entries; e += 256) {
+        const int entries = (steps + kStages) * KS * 4;
+        for (int e = t; e < entries; e += kThreads) {
             const int kw0 = (e >> 2) * kStepWords + (e & 3) * 4;   // first word of the chunk
             uint2 v = make_uint2(0u, 0xFFFFFFFFu);
             if (kw0 < kwords) {
@@ -217,12 +225,12 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
     }
     __syncthreads();
     int pstep = 0;
-    uint2 pent = steptab[chunk];  // entry of the next step to plan, read one step ahead
+    uint2 pent = steptab[grp * 4 + chunk];  // entry of the next step to plan, read one step ahead
     uint32_t poff[kL];
     auto plan = [&]() {
         const uint2 e = pent;
         ++pstep;
-        pent = steptab[pstep * 4 + chunk];
+        pent = steptab[(pstep * KS + grp) * 4 + chunk];
         const bool kin = (e.y >> 31) == 0;
         const uint32_t tap = (e.y >> 26) & 31u, kw4 = e.y & 0x03FFFFFFu;
 #pragma unroll
@@ -345,12 +353,17 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
         if (out.out_u4) {
             // fused output: 8 consecutive channels of a pixel -> one packed word
             constexpr int kWordsPerRow = BN / 8;
-            for (int idx = t; idx < kPassRows * kWordsPerRow; idx += 256) {
+            for (int idx = t; idx < kPassRows * kWordsPerRow; idx += kThreads) {
                 const int row = idx / kWordsPerRow, wd = idx % kWordsPerRow;
                 const int m = bm + pass * kPassRows + row, n0 = bn + wd * 8;
                 if (m >= gm.M || n0 >= gm.Cout) continue;
-                const i32x4_t v0 = *reinterpret_cast<const i32x4_t*>(&stage[row * kSPitch + wd * 8]);
-                const i32x4_t v1 = *reinterpret_cast<const i32x4_t*>(&stage[row * kSPitch + wd * 8 + 4]);
+                i32x4_t v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
+#pragma unroll
+                for (int g = 0; g < KS; ++g) {
+                    const int32_t* sg = reinterpret_cast<const int32_t*>(smem_all + g * kGroupBytes);
+                    v0 += *reinterpret_cast<const i32x4_t*>(&sg[row * kSPitch + wd * 8]);
+                    v1 += *reinterpret_cast<const i32x4_t*>(&sg[row * kSPitch + wd * 8 + 4]);
+                }
                 const int av[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
                 out.out_u4[(size_t)m * (gm.Cout / 8) + n0 / 8] = fused_word(av, out, (size_t)m, n0, gm.Cout);
             }
@@ -358,11 +371,15 @@ __global__ __launch_bounds__(256, (BM * BN >= 128 * 128 ? 2 : 4)) void w4a4_conv
             // plain outputs: 4 consecutive channels per thread, 16-byte stores when Cout allows
             constexpr int kQuadsPerRow = BN / 4;
             const bool vec = (gm.Cout % 4) == 0;
-            for (int idx = t; idx < kPassRows * kQuadsPerRow; idx += 256) {
+            for (int idx = t; idx < kPassRows * kQuadsPerRow; idx += kThreads) {
                 const int row = idx / kQuadsPerRow, qd = idx % kQuadsPerRow;
                 const int m = bm + pass * kPassRows + row, n0 = bn + qd * 4;
                 if (m >= gm.M || n0 >= gm.Cout) continue;
-                const i32x4_t v = *reinterpret_cast<const i32x4_t*>(&stage[row * kSPitch + qd * 4]);
+                i32x4_t v = {0, 0, 0, 0};
+#pragma unroll
+                for (int g = 0; g < KS; ++g)
+                    v += *reinterpret_cast<const i32x4_t*>(
+                        &reinterpret_cast<const int32_t*>(smem_all + g * kGroupBytes)[row * kSPitch + qd * 4]);
                 const size_t o = (size_t)m * gm.Cout + n0;
                 if (vec) {
                     if (out.acc) *reinterpret_cast<i32x4_t*>(out.acc + o) = v;
@@ -463,10 +480,10 @@ int conv_cus() {
     return cus;
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int KS = 1>
 void launch_tiled(const ConvGeom& gm, const uint32_t* a, const uint32_t* w, const ConvOut& out, hipStream_t st) {
     dim3 grid((gm.Cout + BN - 1) / BN, (gm.M + BM - 1) / BM);
-    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN>), grid, dim3(256), 0, st, gm, a, w, out);
+    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN, KS>), grid, dim3(256 * KS), 0, st, gm, a, w, out);
 }
 
 }  // namespace
@@ -484,7 +501,7 @@ hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_
                         (size_t)gm.Cout * gm.KH * gm.KW * (gm.Cin / 2) < 0xFFFFFFF0ull &&
                         (size_t)gm.M * gm.Cout * 4 < 0xFFFFFFF0ull;
     const int ksteps = (gm.KH * gm.KW * (gm.Cin / 8) + kStepWords - 1) / kStepWords;
-    if (d.Cin % 32 == 0 && d.KH * d.KW <= 32 && fits32 && ksteps + kStages <= kMaxSteps) {
+    if (d.Cin % 32 == 0 && d.KH * d.KW <= 32 && fits32 && ksteps + 4 * (kStages + 1) <= kMaxSteps) {
         // the largest tile that still gives every CU about two blocks
         const long long want = 2LL * conv_cus();
         auto blocks = [&](int bm, int bn) {
@@ -494,6 +511,8 @@ hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_
         if (wide && blocks(128, 128) >= want) launch_tiled<128, 128>(gm, a, w, out, st);
         else if (blocks(128, 64) >= want) launch_tiled<128, 64>(gm, a, w, out, st);
         else if (wide && blocks(64, 128) >= want / 2) launch_tiled<64, 128>(gm, a, w, out, st);
+        else if (blocks(64, 64) <= conv_cus() && ksteps >= 16) launch_tiled<64, 64, 4>(gm, a, w, out, st);
+        else if (blocks(64, 64) <= 2 * conv_cus() && ksteps >= 8) launch_tiled<64, 64, 2>(gm, a, w, out, st);
         else launch_tiled<64, 64>(gm, a, w, out, st);
     } else if (out.out_u4) {
         const size_t words = (size_t)gm.M * (d.Cout / 8);
