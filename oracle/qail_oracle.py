@@ -195,6 +195,23 @@ def w4a16_row_norms(x_bf16_bits, qweight, scales, zeros_packed, group_size):
 # ---------------------------------------------------------------------------
 
 
+def w4a16_linear_lora(x_bf16_bits: np.ndarray, qweight: np.ndarray, scales: np.ndarray,
+                      zeros_packed: np.ndarray, group_size: int, a_bf16_bits: np.ndarray,
+                      b_bf16_bits: np.ndarray, scaling: float) -> np.ndarray:
+    """The 4-bit linear with an unmerged low-rank adapter beside it (Sec. 5.1: the
+    4-bit OpenVLA policy is fine-tuned with rank-32 adapters on the quantised
+    backbone, which then run next to the packed weights):
+
+        y[m, n] = sum_k x[m, k] w_hat[n, k]  +  scaling * sum_j (sum_k x[m, k] A[j, k]) B[n, j]
+
+    A [r, K] and B [N, r] are bfloat16 bit patterns; everything in float64, not
+    rounded."""
+    base = w4a16_linear(x_bf16_bits, qweight, scales, zeros_packed, group_size)
+    x = bf16_bits_to_f64(x_bf16_bits)
+    t = x @ bf16_bits_to_f64(a_bf16_bits).T          # [M, r]
+    return base + np.float64(scaling) * (t @ bf16_bits_to_f64(b_bf16_bits).T)
+
+
 def quantize_w4_sym_channel(w: np.ndarray):
     """w: float32 [Cout, ...]; per output channel n, in float32:
       s_w[n] = max |w[n]| / 7   (1 if the channel is all zero)

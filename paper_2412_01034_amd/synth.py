@@ -161,6 +161,16 @@ def llm_activation_bf16(M: int, K: int, seed: int, outlier_frac: float = 0.0,
     return f32_to_bf16_bits(x)
 
 
+def lora_factors(N: int, K: int, r: int, seed: int, std_a: float = 0.02, std_b: float = 0.02):
+    """bf16 bit patterns of the two low-rank factors of an adapter on an [N, K]
+    linear: A [r, K] and B [N, r], both N(0, std^2) (a trained adapter: neither
+    factor is zero)."""
+    rng = np.random.default_rng(seed)
+    a = _normal_f32(rng, (r, K), std_a)
+    b = _normal_f32(rng, (N, r), std_b)
+    return f32_to_bf16_bits(a), f32_to_bf16_bits(b)
+
+
 def conv_weight(shape: ConvShape, seed: int) -> np.ndarray:
     """He-normal fp32 [Cout, KH, KW, Cin], std = sqrt(2 / fan_in)."""
     rng = np.random.default_rng(seed)

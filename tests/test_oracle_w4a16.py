@@ -274,3 +274,51 @@ def test_packed_size_consistent_with_paper_memory_table():
     assert 3.2e9 < packed < 4.0e9
     assert 12.5e9 < params * 2 < 15.2e9
     assert abs(packed - 3.364e9) < 0.01e9
+
+
+# ------------------------------------------------------------------ low-rank adapter beside the 4-bit linear
+
+def _lora_case(N=24, K=256, g=64, M=3, r=8, seed=70):
+    w = synth.llm_weight(N, K, seed)
+    q, s, z = O.quantize_w4_asym_group(w, g)
+    qw, zw = O.pack_w4a16(q, z)
+    xb = synth.llm_activation_bf16(M, K, seed + 1)
+    ab, bb = synth.lora_factors(N, K, r, seed + 2, std_a=0.05, std_b=0.05)
+    return q, s, z, qw, zw, xb, ab, bb
+
+
+def test_lora_equals_the_merged_weight_matrix():
+    # (W_hat + scaling * B A) x, the textbook identity, with plain float64 matmuls
+    q, s, z, qw, zw, xb, ab, bb = _lora_case()
+    scaling = 1.75
+    w_hat = O.dequantize_w4_asym_group(q, s, z, 64)
+    A, Bm = O.bf16_bits_to_f64(ab), O.bf16_bits_to_f64(bb)
+    x = O.bf16_bits_to_f64(xb)
+    merged = x @ (w_hat + scaling * (Bm @ A)).T
+    got = O.w4a16_linear_lora(xb, qw, s, zw, 64, ab, bb, scaling)
+    assert np.allclose(got, merged, rtol=1e-12, atol=1e-12)
+    assert np.abs(got - O.w4a16_linear(xb, qw, s, zw, 64)).max() > 1e-3    # the adapter matters in this case
+
+
+def test_lora_special_cases():
+    q, s, z, qw, zw, xb, ab, bb = _lora_case()
+    base = O.w4a16_linear(xb, qw, s, zw, 64)
+    zero_a, zero_b = np.zeros_like(ab), np.zeros_like(bb)
+    assert np.array_equal(O.w4a16_linear_lora(xb, qw, s, zw, 64, zero_a, bb, 2.0), base)
+    assert np.array_equal(O.w4a16_linear_lora(xb, qw, s, zw, 64, ab, zero_b, 2.0), base)
+    assert np.array_equal(O.w4a16_linear_lora(xb, qw, s, zw, 64, ab, bb, 0.0), base)
+    # linear in the scaling
+    y1 = O.w4a16_linear_lora(xb, qw, s, zw, 64, ab, bb, 1.0)
+    y3 = O.w4a16_linear_lora(xb, qw, s, zw, 64, ab, bb, 3.0)
+    assert np.allclose(y3 - base, 3.0 * (y1 - base), rtol=1e-12, atol=1e-15)
+    # rank one with A = e_k (row 0) and B = e_n (column 0): only y[:, n] changes, by scaling * x[:, k]
+    N, K, r = 24, 256, 8
+    a1 = np.zeros((r, K), np.float32); a1[0, 17] = 1.0
+    b1 = np.zeros((N, r), np.float32); b1[5, 0] = 1.0
+    y = O.w4a16_linear_lora(xb, qw, s, zw, 64, synth.f32_to_bf16_bits(a1), synth.f32_to_bf16_bits(b1), 0.5)
+    d = y - base
+    x = O.bf16_bits_to_f64(xb)
+    assert np.allclose(d[:, 5], 0.5 * x[:, 17]) and np.count_nonzero(np.delete(d, 5, axis=1)) == 0
+    # a transposed factor would not even have the right shape; a swapped pair (B A vs A B) fails here:
+    assert not np.allclose(O.w4a16_linear_lora(xb, qw, s, zw, 64, ab, bb, 1.0),
+                           base + (O.bf16_bits_to_f64(xb) @ O.bf16_bits_to_f64(ab).T[:, ::-1]) @ O.bf16_bits_to_f64(bb).T)
