@@ -257,6 +257,32 @@ def main():
         stack["note"] = f"32 layer-steps per token over {L} distinct layers cycled"
         extra["decode_stack"] = stack
 
+        # the same decode layer with a rank-32 adapter beside each linear (unmerged, as the
+        # fine-tuned 4-bit policy runs): down-projections in one small launch, up-projections
+        # inside the streaming kernel's final store
+        R = 32
+        lora_io = []
+        for l in range(L):
+            lents = []
+            for i, (_, N, K) in enumerate(shapes):
+                ab, bb = synth.lora_factors(N, K, R, synth.seed_for(4, l * 4 + i, 5))
+                lents.append(dict(A=dev(ab), B=dev(bb), r=R, scaling=2.0, N=N, K=K))
+            lora_io.append((B.make_loras(lents), lents))
+        wsl = torch.empty(B.qail_w4a16_lora_workspace(dec[0][0], lora_io[0][0], 4, 1), dtype=torch.uint8, device="cuda")
+        cntl = [0]
+
+        def lora_step():
+            l = cntl[0] % L
+            B.qail_w4a16_linear_lora_batch(dec[l][0], lora_io[l][0], 4, 1, wsl, sh)
+            cntl[0] += 1
+        tl = timed(lora_step, 400)
+        lbytes = sum(R * (N + K) * 2 for _, N, K in shapes)
+        extra["decode_layer_lora_r32"] = {"us_per_layer": round(tl * 1e6, 2),
+                                          "GBps": round((bytes_per_step + lbytes) / tl / 1e9, 1),
+                                          "adapter_bytes": lbytes,
+                                          "launches_per_layer": 2}
+        del lora_io, wsl
+
         # prefill GEMM
         pre = {}
         for M in (288, 1024):

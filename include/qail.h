@@ -169,6 +169,28 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
 int qail_w4a16_batch_workspace(const qail_w4a16_item* items, int32_t count, int32_t M,
                                size_t* bytes);
 
+/* Low-rank adapter beside a 4-bit linear (Sec. 5.1: the 4-bit policy is fine-tuned with
+ * rank-32 adapters on the quantised backbone; they stay separate from the packed weights):
+ *     y[m][n] = sum_k x[m][k] w_hat[n][k]  +  scaling * sum_j (sum_k x[m][k] A[j][k]) B[n][j]
+ * A: bf16 [r][K], B: bf16 [N][r], device memory, 16-byte aligned; 8 <= r <= 64, r % 8 == 0. */
+typedef struct {
+    const uint16_t* A;
+    const uint16_t* B;
+    int32_t r;
+    float scaling;
+} qail_lora;
+
+/* Like qail_w4a16_linear_batch with one adapter per item (loras: HOST array of `count`).
+ * At M = 1 on shapes the streaming kernel takes, the up-projection joins the linear before
+ * the single bf16 rounding of y; otherwise it is added to the rounded y and rounded again
+ * (inside the W4A16 tolerance).  The workspace (query below; 256-byte aligned) holds the
+ * linear's own workspace and the down-projections x A^T in fp32.  Errors as for the batch
+ * call, plus QAIL_ERR_SHAPE for a rank outside the range above. */
+int qail_w4a16_lora_workspace(const qail_w4a16_item* items, const qail_lora* loras, int32_t count,
+                              int32_t M, size_t* bytes);
+int qail_w4a16_linear_lora_batch(const qail_w4a16_item* items, const qail_lora* loras, int32_t count,
+                                 int32_t M, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------- W4A4 --
  * acc[(b,oh,ow)][n] = sum_{kh,kw,c} a[b][oh*stride+kh-pad][ow*stride+kw-pad][c] * w[n][kh][kw][c]
  * with zero outside the image, exact in int32; then optionally

@@ -33,6 +33,7 @@ EXPORTS = (
     "qail_unpack_weights", "qail_act_scale_u4", "qail_quantize_act_u4", "qail_w4a16_workspace",
     "qail_w4a16_linear", "qail_w4a16_linear_batch", "qail_w4a16_batch_workspace",
     "qail_w4a4_workspace", "qail_w4a4_gemm", "qail_w4a4_conv_u4",
+    "qail_w4a16_lora_workspace", "qail_w4a16_linear_lora_batch",
 )
 
 
@@ -40,6 +41,10 @@ class QailError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class qail_lora(ctypes.Structure):
+    _fields_ = [("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("r", ctypes.c_int32), ("scaling", ctypes.c_float)]
 
 
 class qail_wdesc(ctypes.Structure):
@@ -82,6 +87,9 @@ def lib() -> ctypes.CDLL:
         L.qail_w4a16_linear.argtypes = [ctypes.POINTER(qail_wdesc), vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.qail_w4a16_linear_batch.argtypes = [ctypes.POINTER(qail_w4a16_item), i32, i32, vp, sz, vp]
         L.qail_w4a16_batch_workspace.argtypes = [ctypes.POINTER(qail_w4a16_item), i32, i32, psz]
+        L.qail_w4a16_lora_workspace.argtypes = [ctypes.POINTER(qail_w4a16_item), ctypes.POINTER(qail_lora), i32, i32, psz]
+        L.qail_w4a16_linear_lora_batch.argtypes = [ctypes.POINTER(qail_w4a16_item), ctypes.POINTER(qail_lora), i32,
+                                                   i32, vp, sz, vp]
         L.qail_w4a4_workspace.argtypes = [ctypes.POINTER(qail_conv_desc), psz]
         L.qail_w4a4_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.qail_w4a4_conv_u4.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, ctypes.c_float, vp,
@@ -291,3 +299,28 @@ def qail_w4a4_conv_u4(B, H, W, Cin, Cout, KH, KW, stride, pad, a_u4: torch.Tenso
                                    float(s_out), _ptr(res_u4), float(res_scale), _ptr(res_f32), _ptr(out_u4),
                                    _ptr(workspace), wsb, _stream() if stream is None else stream),
            "qail_w4a4_conv_u4")
+
+
+def make_loras(entries: Sequence[dict]):
+    """entries: dicts with A (bf16 [r, K]), B (bf16 [N, r]) device tensors, r, scaling, and the
+    linear's N and K for the size check.  The tensors must be kept alive by the caller."""
+    arr = (qail_lora * max(1, len(entries)))()
+    for i, e in enumerate(entries):
+        _need(e["A"], e["r"] * e["K"] * 2, "A")
+        _need(e["B"], e["N"] * e["r"] * 2, "B")
+        arr[i] = qail_lora(_ptr(e["A"]), _ptr(e["B"]), int(e["r"]), float(e["scaling"]))
+    return arr
+
+
+def qail_w4a16_lora_workspace(items, loras, count: int, M: int) -> int:
+    b = ctypes.c_size_t()
+    _check(lib().qail_w4a16_lora_workspace(items, loras, count, M, ctypes.byref(b)), "qail_w4a16_lora_workspace")
+    return b.value
+
+
+def qail_w4a16_linear_lora_batch(items, loras, count: int, M: int, workspace: torch.Tensor,
+                                 stream: Optional[int] = None) -> None:
+    wsb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().qail_w4a16_linear_lora_batch(items, loras, count, M, _ptr(workspace), wsb,
+                                              _stream() if stream is None else stream),
+           "qail_w4a16_linear_lora_batch")

@@ -213,6 +213,66 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
     return QAIL_OK;
 }
 
+namespace {
+constexpr int kLoraStride = 64;  // floats per row of a down-projection in the workspace (r <= 64)
+
+int check_loras(const qail_w4a16_item* items, const qail_lora* loras, int count) {
+    for (int i = 0; i < count; ++i) {
+        const qail_lora& l = loras[i];
+        if (l.r < 8 || l.r > kLoraStride || l.r % 8 != 0) return QAIL_ERR_SHAPE;
+        if (!(l.scaling > -3.0e38f && l.scaling < 3.0e38f)) return QAIL_ERR_SHAPE;
+        if (!l.A || !l.B) return QAIL_ERR_NULL;
+        if (!aligned16(l.A) || !aligned16(l.B)) return QAIL_ERR_ALIGN;
+        if (!lora_supports(items[i].d, l)) return QAIL_ERR_UNSUPPORTED;
+    }
+    return QAIL_OK;
+}
+
+size_t round256(size_t b) { return (b + 255) / 256 * 256; }
+}  // namespace
+
+int qail_w4a16_lora_workspace(const qail_w4a16_item* items, const qail_lora* loras, int32_t count, int32_t M,
+                              size_t* bytes) {
+    size_t base = 0;
+    const int e = qail_w4a16_batch_workspace(items, count, M, &base);
+    if (e != QAIL_OK) return e;
+    if (count > 0 && !loras) return QAIL_ERR_NULL;
+    *bytes = round256(base) + round256((size_t)count * M * kLoraStride * sizeof(float));
+    return QAIL_OK;
+}
+
+int qail_w4a16_linear_lora_batch(const qail_w4a16_item* items, const qail_lora* loras, int32_t count, int32_t M,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
+    if (count == 0) return QAIL_OK;
+    if (!items || !loras) return QAIL_ERR_NULL;
+    size_t base = 0;
+    for (int i = 0; i < count; ++i) {
+        const int e = check_item(items[i], M);
+        if (e != QAIL_OK) return e;
+        base = std::max(base, item_workspace(items[i].d, M));
+    }
+    const int el = check_loras(items, loras, count);
+    if (el != QAIL_OK) return el;
+    const size_t need = round256(base) + round256((size_t)count * M * kLoraStride * sizeof(float));
+    if (!workspace || workspace_bytes < need) return QAIL_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QAIL_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* t = reinterpret_cast<float*>(static_cast<char*>(workspace) + round256(base));
+
+    if (launch_lora_down(items, loras, t, kLoraStride, count, M, st) != hipSuccess) return QAIL_ERR_HIP;
+    bool fused = (M == 1);
+    for (int i = 0; fused && i < count; ++i) fused = gemv_supports(items[i].d);
+    if (fused)
+        return hip_status(launch_w4a16_gemv_lora(items, loras, t, kLoraStride, count, st));
+    const int e = qail_w4a16_linear_batch(items, count, M, workspace, round256(base), stream);
+    if (e != QAIL_OK) return e;
+    for (int i = 0; i < count; ++i)
+        if (launch_lora_up_add(items[i], loras[i], t + (size_t)i * M * kLoraStride, M, st) != hipSuccess)
+            return QAIL_ERR_HIP;
+    return QAIL_OK;
+}
+
 int qail_w4a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales,
                       const uint32_t* zeros, const uint16_t* x, uint16_t* y, int32_t M, void* workspace,
                       size_t workspace_bytes, void* stream) {

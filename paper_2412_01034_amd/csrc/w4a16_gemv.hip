@@ -53,6 +53,19 @@ struct GemvArgs {
     int count;
 };
 
+// Low-rank adapter of an item (Sec. 5.1: rank-32 adapters beside the 4-bit backbone):
+// y[n] += scaling * sum_j t[j] * B[n][j], with t = A x computed beforehand.
+struct GemvLora {
+    const uint16_t* B;   // bf16 [N][r]
+    const float* t;      // fp32 [r]
+    int r;               // multiple of 8
+    float scaling;
+};
+
+struct GemvLoraArgs {
+    GemvLora l[kGemvMaxItems];
+};
+
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 
 template <int kCtrl>
@@ -157,7 +170,8 @@ __device__ __forceinline__ void stage_x(const GemvItem& it, int nch, uint4* __re
 // product of its 32 codes with the 32 activations at the same k.  The other entries of D
 // are ignored.  The vector ALU only expands nibbles: 5 operations per 8 codes.
 template <int NCH, int kPR>
-__device__ __forceinline__ void stream_rows(const GemvItem& it, int rbase, int nrows, int lane,
+__device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* lo, const float4* lora_t,
+                                            int rbase, int nrows, int lane,
                                             uint4* __restrict__ xlds) {
     typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
     const int K = it.K, g = it.g;
@@ -328,11 +342,39 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, int rbase, int n
 #pragma unroll
     for (int p = 0; p < kPR; ++p)
         if (r + p < nrows) consume(p, r + p);
-    if (lane < nrows) it.y[rbase + lane * kGemvWaves] = f32_to_bf16_rne(ykeep);
+    if (lane < nrows) {
+        const int row = rbase + lane * kGemvWaves;
+        float v = ykeep;
+        if (lo) {
+            // The adapter's up-projection joins before the single rounding of the output.  All of
+            // the row's B is requested at once (up to 8 loads in flight); t was staged in LDS
+            // when the kernel started.
+            const uint4* brow = reinterpret_cast<const uint4*>(lo->B + (size_t)row * lo->r);
+            uint4 bv[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) bv[c] = (c * 8 < lo->r) ? brow[c] : make_uint4(0, 0, 0, 0);
+            float dot = 0.f;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                if (c * 8 < lo->r) {
+                    const float4 t0 = lora_t[2 * c], t1 = lora_t[2 * c + 1];
+                    const uint32_t w[4] = {bv[c].x, bv[c].y, bv[c].z, bv[c].w};
+                    const float tv[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        dot = fmaf(tv[2 * e], __builtin_bit_cast(float, w[e] << 16), dot);
+                        dot = fmaf(tv[2 * e + 1], __builtin_bit_cast(float, w[e] & 0xFFFF0000u), dot);
+                    }
+                }
+            }
+            v = fmaf(lo->scaling, dot, v);
+        }
+        it.y[row] = f32_to_bf16_rne(v);
+    }
 }
 
-template <int kUnits>
-__global__ __launch_bounds__(kGemvThreads) void w4a16_gemv_kernel(const GemvArgs args) {
+template <int kUnits, bool kLora>
+__device__ __forceinline__ void gemv_body(const GemvArgs& args, const GemvLoraArgs& lora) {
     extern __shared__ uint4 lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform: row
     const int lane = threadIdx.x % kWave;                                  // addresses stay scalar
@@ -341,8 +383,14 @@ __global__ __launch_bounds__(kGemvThreads) void w4a16_gemv_kernel(const GemvArgs
     while (idx + 1 < args.count && args.it[idx + 1].block_begin <= (int)blockIdx.x) ++idx;
     idx = __builtin_amdgcn_readfirstlane(idx);
     const GemvItem& it = args.it[idx];
+    const GemvLora* lo = kLora ? &lora.l[idx] : nullptr;
     const int K = it.K, N = it.N;
     const int nch = (K + kWaveK - 1) / kWaveK;
+    // the adapter's down-projection t (at most 64 floats) sits behind the staged activations; the
+    // barrier inside the staging makes it visible
+    float4* lora_t = reinterpret_cast<float4*>(lds + nch * kWave * 4 + nch * kWave / 4 + (nch > 4 ? nch * kWave : 0));
+    if (kLora && (int)threadIdx.x < 64)
+        reinterpret_cast<float*>(lora_t)[threadIdx.x] = (int)threadIdx.x < lo->r ? lo->t[threadIdx.x] : 0.f;
 
     // this block's slab of rows, then this wave's share of the slab
     const int b = (int)blockIdx.x - it.block_begin;
@@ -355,13 +403,24 @@ __global__ __launch_bounds__(kGemvThreads) void w4a16_gemv_kernel(const GemvArgs
 
     switch (nch) {
         // about kUnits wave-wide loads (1 KB each) in flight per wave
-        case 1: stream_rows<1, kUnits>(it, r0, r1, lane, lds); break;
-        case 2: stream_rows<2, kUnits / 2>(it, r0, r1, lane, lds); break;
-        case 3: stream_rows<3, kUnits / 3>(it, r0, r1, lane, lds); break;
-        case 4: stream_rows<4, kUnits / 4>(it, r0, r1, lane, lds); break;
-        case 5: stream_rows<5, 1>(it, r0, r1, lane, lds); break;
-        default: stream_rows<6, 1>(it, r0, r1, lane, lds); break;
+        case 1: stream_rows<1, kUnits>(it, lo, lora_t, r0, r1, lane, lds); break;
+        case 2: stream_rows<2, kUnits / 2>(it, lo, lora_t, r0, r1, lane, lds); break;
+        case 3: stream_rows<3, kUnits / 3>(it, lo, lora_t, r0, r1, lane, lds); break;
+        case 4: stream_rows<4, kUnits / 4>(it, lo, lora_t, r0, r1, lane, lds); break;
+        case 5: stream_rows<5, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
+        default: stream_rows<6, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
     }
+}
+
+template <int kUnits>
+__global__ __launch_bounds__(kGemvThreads) void w4a16_gemv_kernel(const GemvArgs args) {
+    gemv_body<kUnits, false>(args, GemvLoraArgs{});
+}
+
+// The same stream with the adapters' up-projection in the final store.
+template <int kUnits>
+__global__ __launch_bounds__(kGemvThreads) void w4a16_gemv_lora_kernel(const GemvArgs args, const GemvLoraArgs lora) {
+    gemv_body<kUnits, true>(args, lora);
 }
 
 int device_cus() {
@@ -381,7 +440,7 @@ size_t item_bytes(const qail_wdesc& d) {
     return (size_t)d.N * (d.K / 2 + G * 2 + ((G + 7) / 8) * 4);
 }
 
-hipError_t launch_chunk(const qail_w4a16_item* items, int count, hipStream_t st) {
+hipError_t launch_chunk(const qail_w4a16_item* items, const GemvLora* loras, int count, hipStream_t st) {
     GemvArgs a;
     int grid = device_cus();
     if (grid < count) grid = count;
@@ -430,7 +489,13 @@ hipError_t launch_chunk(const qail_w4a16_item* items, int count, hipStream_t st)
     a.count = count;
     const int nch = (maxK + kWaveK - 1) / kWaveK;
     const size_t lds = (size_t)nch * kWave * (4 * 16 + 4 + (nch > 4 ? 16 : 0));
-    hipLaunchKernelGGL(w4a16_gemv_kernel<8>, dim3(bb), dim3(kGemvThreads), lds, st, a);
+    if (loras) {
+        GemvLoraArgs la;
+        for (int i = 0; i < kGemvMaxItems; ++i) la.l[i] = loras[i < count ? i : count - 1];
+        hipLaunchKernelGGL(w4a16_gemv_lora_kernel<8>, dim3(bb), dim3(kGemvThreads), lds + 256, st, a, la);
+    } else {
+        hipLaunchKernelGGL(w4a16_gemv_kernel<8>, dim3(bb), dim3(kGemvThreads), lds, st, a);
+    }
     return hipGetLastError();
 }
 
@@ -443,7 +508,23 @@ bool gemv_supports(const qail_wdesc& d) {
 hipError_t launch_w4a16_gemv(const qail_w4a16_item* items, int count, hipStream_t st) {
     for (int i0 = 0; i0 < count; i0 += kGemvMaxItems) {
         const int c = (count - i0 < kGemvMaxItems) ? count - i0 : kGemvMaxItems;
-        const hipError_t e = launch_chunk(items + i0, c, st);
+        const hipError_t e = launch_chunk(items + i0, nullptr, c, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// t: fp32 [count][r_max] as written by launch_lora_down for M = 1 (stride t_stride floats).
+hipError_t launch_w4a16_gemv_lora(const qail_w4a16_item* items, const qail_lora* loras, const float* t,
+                                  int t_stride, int count, hipStream_t st) {
+    for (int i0 = 0; i0 < count; i0 += kGemvMaxItems) {
+        const int c = (count - i0 < kGemvMaxItems) ? count - i0 : kGemvMaxItems;
+        GemvLora gl[kGemvMaxItems];
+        for (int i = 0; i < c; ++i) {
+            const qail_lora& l = loras[i0 + i];
+            gl[i] = GemvLora{l.B, t + (size_t)(i0 + i) * t_stride, l.r, l.scaling};
+        }
+        const hipError_t e = launch_chunk(items + i0, gl, c, st);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

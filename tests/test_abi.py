@@ -82,6 +82,25 @@ def test_argument_errors_are_reported_without_a_gpu(B):
     assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, ok, 0.1, ok, ok, None, 0, None) == B.QAIL_ERR_SHAPE    # two shortcuts
     assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, ok, -1.0, None, ok, None, 0, None) == B.QAIL_ERR_SHAPE
     assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, odd, 0.1, None, ok, None, 0, None) == B.QAIL_ERR_ALIGN
+    # low-rank adapters: rank must be a multiple of 8 in [8, 64], factors present and aligned
+    it = B.qail_w4a16_item(d, ok, ok, ok, ok, ok)
+    its = (B.qail_w4a16_item * 1)(it)
+    f = L.qail_w4a16_linear_lora_batch
+    for bad_r in (0, 4, 12, 72):
+        lo = (B.qail_lora * 1)(B.qail_lora(ok, ok, bad_r, 1.0))
+        assert f(its, lo, 1, 1, ok, 1 << 20, None) == B.QAIL_ERR_SHAPE
+    lo = (B.qail_lora * 1)(B.qail_lora(None, ok, 32, 1.0))
+    assert f(its, lo, 1, 1, ok, 1 << 20, None) == B.QAIL_ERR_NULL
+    lo = (B.qail_lora * 1)(B.qail_lora(ok, odd, 32, 1.0))
+    assert f(its, lo, 1, 1, ok, 1 << 20, None) == B.QAIL_ERR_ALIGN
+    lo = (B.qail_lora * 1)(B.qail_lora(ok, ok, 32, float("inf")))
+    assert f(its, lo, 1, 1, ok, 1 << 20, None) == B.QAIL_ERR_SHAPE
+    lo = (B.qail_lora * 1)(B.qail_lora(ok, ok, 32, 1.0))
+    assert f(its, lo, 1, 1, None, 0, None) == B.QAIL_ERR_WORKSPACE          # the down-projection needs room
+    assert f(its, None, 1, 1, ok, 1 << 20, None) == B.QAIL_ERR_NULL
+    assert f(its, lo, 0, 1, None, 0, None) == B.QAIL_OK
+    szl = ctypes.c_size_t(0)
+    assert L.qail_w4a16_lora_workspace(its, lo, 1, 3, ctypes.byref(szl)) == B.QAIL_OK and szl.value == 768
     sz = ctypes.c_size_t(99)
     assert L.qail_w4a4_workspace(ctypes.byref(c), ctypes.byref(sz)) == B.QAIL_OK
     assert L.qail_w4a16_workspace(ctypes.byref(d), 1, ctypes.byref(sz)) == B.QAIL_OK

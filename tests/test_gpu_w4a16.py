@@ -249,3 +249,60 @@ def test_full_size_decode_linears_sampled(B):
 @pytest.mark.parametrize("M", [288, 1024])
 def test_full_size_prefill_linears_sampled(B, M):
     _sampled_full_size(B, M, dict(outlier_frac=0.005))
+
+
+# ------------------------------------------------------------------ low-rank adapters
+
+def _lora_run(B, specs, M, seed):
+    """specs: list of (N, K, g, r, scaling).  Returns [(y_gpu, y_ref, nx, n_eff)] per item."""
+    import torch
+    ents, lents, keep = [], [], []
+    for i, (N, K, g, r, scaling) in enumerate(specs):
+        w = synth.llm_weight(N, K, seed + 10 * i, outlier_frac=0.01)
+        xb = synth.llm_activation_bf16(M, K, seed + 10 * i + 1)
+        ab, bb = synth.lora_factors(N, K, r, seed + 10 * i + 2, std_a=0.03, std_b=0.03)
+        qw, s, zw = oracle_pack(w, g)
+        e = dict(N=N, K=K, group_size=g, qweight=dev(qw), scales=dev(s.view(np.uint16)), zeros=dev(zw), x=dev(xb),
+                 y=torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda"))
+        ents.append(e)
+        lents.append(dict(A=dev(ab), B=dev(bb), r=r, scaling=scaling, N=N, K=K))
+        keep.append((qw, s, zw, xb, ab, bb))
+    items = B.make_w4a16_items(ents, M)
+    loras = B.make_loras(lents)
+    ws = ws_for(B, B.qail_w4a16_lora_workspace(items, loras, len(ents), M))
+    B.qail_w4a16_linear_lora_batch(items, loras, len(ents), M, ws)
+    torch.cuda.synchronize()
+    out = []
+    for (N, K, g, r, scaling), e, (qw, s, zw, xb, ab, bb) in zip(specs, ents, keep):
+        y = host(e["y"], np.uint16).reshape(M, N)
+        ref = O.w4a16_linear_lora(xb, qw, s, zw, g, ab, bb, scaling)
+        # norms of the effective rows W_hat + scaling * B A
+        q = O.unpack_nibbles_u4(qw, K)
+        z = O.unpack_nibbles_u4(zw, K // g)
+        w_eff = O.dequantize_w4_asym_group(q, s, z, g) + scaling * (O.bf16_bits_to_f64(bb) @ O.bf16_bits_to_f64(ab))
+        nx = np.sqrt((O.bf16_bits_to_f64(xb) ** 2).sum(axis=1))
+        out.append((y, ref, nx, np.sqrt((w_eff ** 2).sum(axis=1))))
+    return out
+
+
+@pytest.mark.parametrize("M", [1, 4, 40])
+def test_lora_beside_the_linear(B, M):
+    specs = [(200, 4096, 128, 32, 2.0),      # the paper's rank
+             (96, 1024, 128, 8, -0.5),       # smallest rank, negative scaling
+             (130, 11008, 128, 64, 1.0),     # largest rank, 86 groups
+             (24, 40, 8, 16, 1.5)]           # a shape only the generic linear takes
+    for y, ref, nx, nw in _lora_run(B, specs, M, 300 + M):
+        assert w4a16_norm_err(y, ref, nx, nw) <= TOL_TINY_K       # widest bar: one shape has K < 512
+
+
+def test_lora_changes_the_output_and_zero_adapter_does_not(B):
+    import torch
+    N, K, g, M = 128, 2048, 128, 1
+    base = _lora_run(B, [(N, K, g, 32, 0.0)], M, 777)[0]
+    with_ad = _lora_run(B, [(N, K, g, 32, 4.0)], M, 777)[0]
+    # scaling 0: bit-identical to the plain linear (the adapter term is an exact zero)
+    w = synth.llm_weight(N, K, 777, outlier_frac=0.01)
+    qw, s, zw = oracle_pack(w, g)
+    plain = gpu_linear(B, qw, s, zw, synth.llm_activation_bf16(M, K, 778), g, N, K, M)
+    assert np.array_equal(synth.bf16_bits_to_f32(base[0]), synth.bf16_bits_to_f32(plain))
+    assert not np.array_equal(base[0], with_ad[0])
