@@ -323,3 +323,97 @@ def fused_requant_u4(acc: np.ndarray, scale: np.ndarray, bias: np.ndarray, s_out
     assert t.dtype == F32
     q = np.rint(t / F32(s_out))
     return np.clip(q, 0, 15).astype(np.uint8)
+
+
+# ===========================================================================
+# 8-bit variants (Sec. 5.4: the driving encoder is also deployed W8A8, the
+# backbone also with 8-bit weights only).  The paper names no quantiser for them;
+# the readings: symmetric round-to-nearest, weights per output channel (W8A8) or
+# per group with a float16 scale (weight-only), activations per tensor, codes in
+# [-127, 127] (the accumulating GEMM itself is exact for all of [-128, 127]).
+# ===========================================================================
+
+def pack_bytes(codes: np.ndarray) -> np.ndarray:
+    """[..., L] integer codes (low 8 bits kept, so signed codes become their
+    two's-complement byte), L % 4 == 0 -> uint32 [..., L/4]; code i of a word
+    occupies bits [8*(i%4), 8*(i%4)+7]."""
+    c = np.asarray(codes)
+    assert c.shape[-1] % 4 == 0
+    b = (c.astype(np.int64) & 0xFF).astype(np.uint32).reshape(*c.shape[:-1], c.shape[-1] // 4, 4)
+    shifts = (8 * np.arange(4, dtype=np.uint32))
+    return np.bitwise_or.reduce(b << shifts, axis=-1).astype(np.uint32)
+
+
+def unpack_bytes_s8(words: np.ndarray, L: int) -> np.ndarray:
+    """Inverse of pack_bytes for signed codes: [..., W] uint32 -> [..., L] int8."""
+    w = np.asarray(words, dtype=np.uint32)
+    shifts = (8 * np.arange(4, dtype=np.uint32))
+    b = ((w[..., None] >> shifts) & np.uint32(0xFF)).astype(np.uint8)
+    return b.reshape(*w.shape[:-1], -1)[..., :L].view(np.int8)
+
+
+def quantize_w8_sym_channel(w: np.ndarray):
+    """w: float32 [Cout, ...]; per output channel n, in float32:
+    s_w[n] = max|w[n]| / 127 (1 if the channel is all zero),
+    q = clamp(rint(w / s_w[n]), -127, 127).  Returns (q int8 same shape, s_w float32 [Cout])."""
+    w = np.asarray(w, dtype=F32)
+    flat = w.reshape(w.shape[0], -1)
+    amax = np.abs(flat).max(axis=1)
+    s = (amax / F32(127)).astype(F32)
+    s = np.where(amax == 0, F32(1), s).astype(F32)
+    q = np.clip(np.rint(flat / s[:, None]), -127, 127).astype(np.int8)
+    return q.reshape(w.shape), s
+
+
+def act_scale_s8(a: np.ndarray) -> np.float32:
+    """One step for a whole activation tensor: max|a| / 127 in float32 (1 if all zero)."""
+    amax = F32(np.abs(np.asarray(a, dtype=F32)).max()) if np.asarray(a).size else F32(0)
+    return F32(1) if amax == 0 else F32(amax / F32(127))
+
+
+def quantize_act_s8(a: np.ndarray, s_a) -> np.ndarray:
+    """q = clamp(rint(a / s_a), -127, 127), float32 arithmetic, int8 codes."""
+    a = np.asarray(a, dtype=F32)
+    return np.clip(np.rint(a / F32(s_a)), -127, 127).astype(np.int8)
+
+
+def w8a8_conv_acc(a_words: np.ndarray, w_words: np.ndarray, B: int, H: int, W: int, Cin: int,
+                  Cout: int, KH: int, KW: int, stride: int, pad: int) -> np.ndarray:
+    """The exact integer convolution of w4a4_conv_acc with signed 8-bit codes on both
+    sides: a_words uint32 [B, H, W, Cin/4], w_words uint32 [Cout, KH*KW*Cin/4], K ordered
+    (kh, kw, c), zero outside the image; summed in int64, checked against 128*128*K,
+    returned as int32 [M, Cout]."""
+    a = unpack_bytes_s8(np.asarray(a_words).reshape(B, H, W, Cin // 4), Cin).astype(np.int64)
+    K = KH * KW * Cin
+    wq = unpack_bytes_s8(np.asarray(w_words).reshape(Cout, K // 4), K).astype(np.int64)
+    acc = im2col_nhwc(a, KH, KW, stride, pad) @ wq.T
+    if acc.size and np.abs(acc).max() > 128 * 128 * K:
+        raise AssertionError("accumulator exceeds 128*128*K")
+    return acc.astype(np.int32)
+
+
+def quantize_w8_sym_group(w: np.ndarray, group_size: int):
+    """Weight-only 8-bit: per row n and group of g consecutive k, in float32:
+    s = float16 round-up of max|w| / 127, at least 2^-14 (1 for an all-zero group;
+    raises beyond the float16 range), q = clamp(rint(w / s), -127, 127).
+    Returns (q int8 [N, K], s float16 [N, K/g])."""
+    w = np.asarray(w, dtype=F32)
+    N, K = w.shape
+    assert K % group_size == 0
+    wg = w.reshape(N, K // group_size, group_size)
+    amax = np.abs(wg).max(axis=2)
+    s32 = (amax / F32(127)).astype(F32)
+    if np.any(s32 > F32(65504)):
+        raise ValueError("group range exceeds the float16 scale format")
+    s = np.maximum(fp16_round_up(s32), np.float16(2.0 ** -14)).astype(np.float16)
+    s = np.where(amax == 0, np.float16(1), s).astype(np.float16)
+    q = np.clip(np.rint(wg / s.astype(F32)[:, :, None]), -127, 127).astype(np.int8)
+    return q.reshape(N, K), s
+
+
+def w8a16_linear(x_bf16_bits: np.ndarray, codes: np.ndarray, scales: np.ndarray, group_size: int) -> np.ndarray:
+    """y[m, n] = sum_k x[m, k] * q[n, k] * s[n, k // g] in float64, not rounded."""
+    x = bf16_bits_to_f64(x_bf16_bits)
+    q = np.asarray(codes).astype(np.float64)
+    s = np.repeat(np.asarray(scales).astype(np.float64), group_size, axis=1)
+    return x @ (q * s).T
