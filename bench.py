@@ -357,6 +357,36 @@ def main():
                                                "TOPs": round(tot_ops / tf_ / 1e12, 1),
                                                "frac_int8_peak": round(tot_ops / tf_ / 1e12 / INT8_PEAK_TOPS, 4),
                                                "calls": len(fcalls), "per_shape": fper}
+        # 8-bit variants: the same 35 conv calls as W8A8, and the decode layer with 8-bit weights only
+        c8 = []
+        for s, a, ww, scale, bias, y in calls:
+            a8 = dev(rng.integers(0, 2 ** 32, size=s.B * s.H * s.W * s.Cin // 4, dtype=np.uint64).astype(np.uint32))
+            w8 = dev(rng.integers(0, 2 ** 32, size=s.Cout * s.K // 4, dtype=np.uint64).astype(np.uint32))
+            c8.append((s, a8, w8, scale, bias, y))
+
+        def body8():
+            for s, a8, w8, scale, bias, y in c8:
+                B.qail_w8a8_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a8, w8,
+                                 scale=scale, bias=bias, y_out=y, stream=sh)
+        t8 = timed(body8, 20)
+        extra["w8a8_resnet34_b32"] = {"ms_per_pass": round(t8 * 1e3, 4), "TOPs": round(tot_ops / t8 / 1e12, 1),
+                                      "frac_int8_peak": round(tot_ops / t8 / 1e12 / INT8_PEAK_TOPS, 4), "calls": len(c8)}
+        del c8
+        w8l = []
+        for i, (name, N, K) in enumerate(shapes):
+            q8 = dev(rng.integers(0, 2 ** 32, size=N * K // 4, dtype=np.uint64).astype(np.uint32))
+            s8 = torch.full((N * (K // GROUP),), 0x1C00, dtype=torch.int16, device="cuda")
+            w8l.append((N, K, q8, s8, dec[0][1][i]["x"], torch.empty(N, dtype=torch.int16, device="cuda")))
+
+        def layer8():
+            for N, K, q8, s8, x8, y8 in w8l:
+                B.qail_w8a16_linear(N, K, GROUP, q8, s8, x8, y8, 1, stream=sh)
+        tl8 = timed(layer8, 200)
+        b8 = sum(N * K + N * (K // GROUP) * 2 + 2 * (N + K) for N, K, *_ in w8l)
+        extra["w8a16_decode_layer"] = {"us_per_layer": round(tl8 * 1e6, 2), "GBps": round(b8 / tl8 / 1e9, 1),
+                                       "bytes": b8, "launches_per_layer": 4,
+                                       "note": "weights stay cache-resident here (one layer, 211 MB): an upper bound"}
+        del w8l
         result["extra"] = extra
         log("[bench] extra:", json.dumps(extra))
 

@@ -58,7 +58,14 @@ typedef enum {
     QAIL_W4_ASYM_GROUP = 0,
     /* Signed codes -8..7, one fp32 scale per row (output channel); group_size is
      * ignored (Sec. 5.1, driving policy). */
-    QAIL_W4_SYM_CHANNEL = 1
+    QAIL_W4_SYM_CHANNEL = 1,
+    /* 8-bit variants (Sec. 5.4: W8A8 driving encoder, 8-bit weight-only backbone).  The paper
+     * names no 8-bit quantiser; both are symmetric round-to-nearest with signed codes
+     * -127..127, packed 4 per word (code i of a word in bits 8*(i%4)..8*(i%4)+7):
+     * one fp32 scale max|w|/127 per row ... */
+    QAIL_W8_SYM_CHANNEL = 2,
+    /* ... or one fp16 scale per group of `group_size` consecutive k, rounded up, >= 2^-14. */
+    QAIL_W8_SYM_GROUP = 3
 } qail_scheme;
 
 /* A quantised weight matrix W[N][K] (row n = output channel, K contiguous). */
@@ -231,6 +238,30 @@ int qail_w4a4_conv_u4(const qail_conv_desc* d, const uint32_t* a_u4, const uint3
                       const float* scale, const float* bias, float s_out,
                       const uint32_t* res_u4, float res_scale, const float* res_f32,
                       uint32_t* out_u4, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------ 8-bit --
+ * Sec. 5.4 deploys the driving encoder also as W8A8 and the backbone also with 8-bit
+ * weights only.  Weights: qail_quantize_weights / qail_packed_sizes with the W8 schemes
+ * (zeros unused, may be NULL; qail_unpack_weights is not needed: the codes are bytes). */
+
+/* One activation step for a whole tensor: *s_a = max|a| / 127 in fp32, 1 if all zero. */
+int qail_act_scale_s8(const float* a, size_t n, float* s_a, void* stream);
+
+/* q = clamp(rint(a / *s_a), -127, 127), 4 codes per word along the flat index; n % 4 == 0. */
+int qail_quantize_act_s8(const float* a, size_t n, const float* s_a, uint32_t* a_s8, void* stream);
+
+/* qail_w4a4_gemm with signed 8-bit codes on both sides: a_s8 NHWC [B][H][W][Cin/4] words,
+ * w_s8 [Cout][KH][KW][Cin/4] words, Cin % 4 == 0, K = KH*KW*Cin <= 131071 (int32 exact for
+ * all codes in [-128, 127]).  Outputs, errors and ownership as for qail_w4a4_gemm. */
+int qail_w8a8_gemm(const qail_conv_desc* d, const uint32_t* a_s8, const uint32_t* w_s8,
+                   int32_t* acc_out, const float* scale, const float* bias, float* y_out,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* y[m][n] = sum_k x[m][k] * q[n][k] * s[n][k/g], d of scheme QAIL_W8_SYM_GROUP, x and y bf16,
+ * fp32 accumulation, one rounding.  M = 1 runs a bandwidth-bound streaming kernel (K % 16 == 0,
+ * group_size % 16 == 0, K + K/g <= 16384), anything else a plain one-thread-per-output kernel. */
+int qail_w8a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales,
+                      const uint16_t* x, uint16_t* y, int32_t M, void* stream);
 
 #ifdef __cplusplus
 }

@@ -34,6 +34,7 @@ EXPORTS = (
     "qail_w4a16_linear", "qail_w4a16_linear_batch", "qail_w4a16_batch_workspace",
     "qail_w4a4_workspace", "qail_w4a4_gemm", "qail_w4a4_conv_u4",
     "qail_w4a16_lora_workspace", "qail_w4a16_linear_lora_batch",
+    "qail_act_scale_s8", "qail_quantize_act_s8", "qail_w8a8_gemm", "qail_w8a16_linear",
 )
 
 
@@ -90,6 +91,10 @@ def lib() -> ctypes.CDLL:
         L.qail_w4a16_lora_workspace.argtypes = [ctypes.POINTER(qail_w4a16_item), ctypes.POINTER(qail_lora), i32, i32, psz]
         L.qail_w4a16_linear_lora_batch.argtypes = [ctypes.POINTER(qail_w4a16_item), ctypes.POINTER(qail_lora), i32,
                                                    i32, vp, sz, vp]
+        L.qail_act_scale_s8.argtypes = [vp, sz, vp, vp]
+        L.qail_quantize_act_s8.argtypes = [vp, sz, vp, vp, vp]
+        L.qail_w8a8_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.qail_w8a16_linear.argtypes = [ctypes.POINTER(qail_wdesc), vp, vp, vp, vp, i32, vp]
         L.qail_w4a4_workspace.argtypes = [ctypes.POINTER(qail_conv_desc), psz]
         L.qail_w4a4_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.qail_w4a4_conv_u4.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, ctypes.c_float, vp,
@@ -324,3 +329,45 @@ def qail_w4a16_linear_lora_batch(items, loras, count: int, M: int, workspace: to
     _check(lib().qail_w4a16_linear_lora_batch(items, loras, count, M, _ptr(workspace), wsb,
                                               _stream() if stream is None else stream),
            "qail_w4a16_linear_lora_batch")
+
+
+QAIL_W8_SYM_CHANNEL = 2
+QAIL_W8_SYM_GROUP = 3
+
+
+def qail_act_scale_s8(a: torch.Tensor, s_a: torch.Tensor) -> None:
+    _need(a, a.numel() * 4, "a")
+    _check(lib().qail_act_scale_s8(_ptr(a), a.numel(), _ptr(s_a), _stream()), "qail_act_scale_s8")
+
+
+def qail_quantize_act_s8(a: torch.Tensor, s_a: torch.Tensor, a_s8: torch.Tensor) -> None:
+    _need(a_s8, a.numel(), "a_s8")
+    _check(lib().qail_quantize_act_s8(_ptr(a), a.numel(), _ptr(s_a), _ptr(a_s8), _stream()), "qail_quantize_act_s8")
+
+
+def qail_w8a8_gemm(B, H, W, Cin, Cout, KH, KW, stride, pad, a_s8: torch.Tensor, w_s8: torch.Tensor,
+                   acc_out: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
+                   bias: Optional[torch.Tensor] = None, y_out: Optional[torch.Tensor] = None,
+                   stream: Optional[int] = None) -> None:
+    OH = (H + 2 * pad - KH) // stride + 1
+    OW = (W + 2 * pad - KW) // stride + 1
+    M = B * OH * OW
+    _need(a_s8, B * H * W * Cin, "a_s8")
+    _need(w_s8, Cout * KH * KW * Cin, "w_s8")
+    for t, nm in ((acc_out, "acc_out"), (y_out, "y_out")):
+        if t is not None:
+            _need(t, M * Cout * 4, nm)
+    d = qail_conv_desc(B, H, W, Cin, Cout, KH, KW, stride, pad)
+    _check(lib().qail_w8a8_gemm(ctypes.byref(d), _ptr(a_s8), _ptr(w_s8), _ptr(acc_out), _ptr(scale), _ptr(bias),
+                                _ptr(y_out), None, 0, _stream() if stream is None else stream), "qail_w8a8_gemm")
+
+
+def qail_w8a16_linear(N: int, K: int, group_size: int, qweight: torch.Tensor, scales: torch.Tensor,
+                      x: torch.Tensor, y: torch.Tensor, M: int, stream: Optional[int] = None) -> None:
+    _need(qweight, N * K, "qweight")
+    _need(scales, N * (K // group_size) * 2, "scales")
+    _need(x, M * K * 2, "x")
+    _need(y, M * N * 2, "y")
+    d = qail_wdesc(N, K, group_size, QAIL_W8_SYM_GROUP)
+    _check(lib().qail_w8a16_linear(ctypes.byref(d), _ptr(qweight), _ptr(scales), _ptr(x), _ptr(y), M,
+                                   _stream() if stream is None else stream), "qail_w8a16_linear")

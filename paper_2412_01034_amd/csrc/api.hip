@@ -13,23 +13,27 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 int check_wdesc(const qail_wdesc* d) {
     if (!d) return QAIL_ERR_NULL;
-    if (d->scheme != QAIL_W4_ASYM_GROUP && d->scheme != QAIL_W4_SYM_CHANNEL) return QAIL_ERR_UNSUPPORTED;
+    if (d->scheme != QAIL_W4_ASYM_GROUP && d->scheme != QAIL_W4_SYM_CHANNEL && d->scheme != QAIL_W8_SYM_CHANNEL &&
+        d->scheme != QAIL_W8_SYM_GROUP)
+        return QAIL_ERR_UNSUPPORTED;
     if (d->N < 1 || d->K < 8 || d->K % 8 != 0) return QAIL_ERR_SHAPE;
-    if (d->scheme == QAIL_W4_ASYM_GROUP) {
+    if (d->scheme == QAIL_W4_ASYM_GROUP || d->scheme == QAIL_W8_SYM_GROUP) {
         if (d->group_size < 8 || d->group_size % 8 != 0 || d->K % d->group_size != 0) return QAIL_ERR_SHAPE;
         if (d->K / d->group_size > 32768) return QAIL_ERR_UNSUPPORTED;  // zero-points of a row are staged in LDS
     }
     return QAIL_OK;
 }
 
-int check_conv(const qail_conv_desc* d) {
+int check_conv(const qail_conv_desc* d, int bits = 4) {
     if (!d) return QAIL_ERR_NULL;
-    if (d->B < 1 || d->H < 1 || d->W < 1 || d->Cin < 8 || d->Cin % 8 != 0 || d->Cout < 1 || d->KH < 1 ||
+    const int per_word = 32 / bits;
+    if (d->B < 1 || d->H < 1 || d->W < 1 || d->Cin < per_word || d->Cin % per_word != 0 || d->Cout < 1 || d->KH < 1 ||
         d->KW < 1 || d->stride < 1 || d->pad < 0)
         return QAIL_ERR_SHAPE;
     if (d->H + 2 * d->pad < d->KH || d->W + 2 * d->pad < d->KW) return QAIL_ERR_SHAPE;
     const long long K = (long long)d->KH * d->KW * d->Cin;
-    if (K > 1118480) return QAIL_ERR_UNSUPPORTED;  // 16 * 8 * 15 * K must fit int32
+    // 4-bit: 16 * 8 * 15 * K must fit int32; 8-bit: 128 * 128 * K
+    if (K > (bits == 4 ? 1118480 : 131071)) return QAIL_ERR_UNSUPPORTED;
     const long long OH = (d->H + 2 * d->pad - d->KH) / d->stride + 1;
     const long long OW = (d->W + 2 * d->pad - d->KW) / d->stride + 1;
     const long long M = (long long)d->B * OH * OW;
@@ -75,6 +79,12 @@ int qail_packed_sizes(const qail_wdesc* d, size_t* qweight_bytes, size_t* scales
     const int e = check_wdesc(d);
     if (e != QAIL_OK) return e;
     const size_t N = (size_t)d->N, K = (size_t)d->K;
+    if (d->scheme == QAIL_W8_SYM_CHANNEL || d->scheme == QAIL_W8_SYM_GROUP) {
+        if (qweight_bytes) *qweight_bytes = N * K;
+        if (scales_bytes) *scales_bytes = d->scheme == QAIL_W8_SYM_GROUP ? N * (K / (size_t)d->group_size) * 2 : N * 4;
+        if (zeros_bytes) *zeros_bytes = 0;
+        return QAIL_OK;
+    }
     if (qweight_bytes) *qweight_bytes = N * (K / 8) * 4;
     if (d->scheme == QAIL_W4_ASYM_GROUP) {
         const size_t G = K / (size_t)d->group_size;
@@ -97,6 +107,8 @@ int qail_quantize_weights(const qail_wdesc* d, const float* w, uint32_t* qweight
         return QAIL_ERR_ALIGN;
     if (range_errors && (reinterpret_cast<uintptr_t>(range_errors) & 3u)) return QAIL_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (d->scheme == QAIL_W8_SYM_CHANNEL || d->scheme == QAIL_W8_SYM_GROUP)
+        return hip_status(launch_quantize_s8(*d, w, qweight, scales, range_errors, st));
     if (asym)
         return hip_status(launch_quantize_asym(*d, w, qweight, static_cast<uint16_t*>(scales), zeros,
                                                range_errors, st));
@@ -106,6 +118,8 @@ int qail_quantize_weights(const qail_wdesc* d, const float* w, uint32_t* qweight
 int qail_unpack_weights(const qail_wdesc* d, const uint32_t* qweight, uint8_t* codes, void* stream) {
     const int e = check_wdesc(d);
     if (e != QAIL_OK) return e;
+    if (d->scheme == QAIL_W8_SYM_CHANNEL || d->scheme == QAIL_W8_SYM_GROUP)
+        return QAIL_ERR_UNSUPPORTED;  // 8-bit codes are bytes already: qweight read as int8 [N][K]
     if (!qweight || !codes) return QAIL_ERR_NULL;
     if (!aligned16(qweight) || !aligned16(codes)) return QAIL_ERR_ALIGN;
     return hip_status(launch_unpack(*d, qweight, codes, static_cast<hipStream_t>(stream)));
@@ -310,6 +324,48 @@ int qail_w4a4_gemm(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t
         return QAIL_ERR_ALIGN;
     return hip_status(launch_w4a4_conv(*d, a_u4, w_s4, acc_out, scale, bias, y_out,
                                        static_cast<hipStream_t>(stream)));
+}
+
+int qail_w8a8_gemm(const qail_conv_desc* d, const uint32_t* a_s8, const uint32_t* w_s8, int32_t* acc_out,
+                   const float* scale, const float* bias, float* y_out, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    const int e = check_conv(d, 8);
+    if (e != QAIL_OK) return e;
+    if (!a_s8 || !w_s8) return QAIL_ERR_NULL;
+    if (!acc_out && !y_out) return QAIL_ERR_NULL;
+    if (y_out && (!scale || !bias)) return QAIL_ERR_NULL;
+    if (!aligned16(a_s8) || !aligned16(w_s8) || (acc_out && !aligned16(acc_out)) || (y_out && !aligned16(y_out)) ||
+        (scale && !aligned16(scale)) || (bias && !aligned16(bias)))
+        return QAIL_ERR_ALIGN;
+    return hip_status(launch_w8a8_conv(*d, a_s8, w_s8, acc_out, scale, bias, y_out, static_cast<hipStream_t>(stream)));
+}
+
+int qail_act_scale_s8(const float* a, size_t n, float* s_a, void* stream) {
+    if (!s_a || (n > 0 && !a)) return QAIL_ERR_NULL;
+    if ((n > 0 && !aligned16(a)) || (reinterpret_cast<uintptr_t>(s_a) & 3u)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_act_scale_s8(a, n, s_a, static_cast<hipStream_t>(stream)));
+}
+
+int qail_quantize_act_s8(const float* a, size_t n, const float* s_a, uint32_t* a_s8, void* stream) {
+    if (n % 4 != 0) return QAIL_ERR_SHAPE;
+    if (n == 0) return QAIL_OK;
+    if (!a || !s_a || !a_s8) return QAIL_ERR_NULL;
+    if (!aligned16(a) || !aligned16(a_s8) || (reinterpret_cast<uintptr_t>(s_a) & 3u)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_act_quant_s8(a, n, s_a, a_s8, static_cast<hipStream_t>(stream)));
+}
+
+int qail_w8a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales, const uint16_t* x,
+                      uint16_t* y, int32_t M, void* stream) {
+    const int e = check_wdesc(d);
+    if (e != QAIL_OK) return e;
+    if (d->scheme != QAIL_W8_SYM_GROUP) return QAIL_ERR_UNSUPPORTED;
+    if (M < 1) return QAIL_ERR_SHAPE;
+    if ((long long)M * d->N > 0x7FFFFFFFll * 64) return QAIL_ERR_UNSUPPORTED;
+    if (!qweight || !scales || !x || !y) return QAIL_ERR_NULL;
+    if (!aligned16(qweight) || !aligned16(scales) || !aligned16(x) || !aligned16(y)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_w8a16_linear(*d, qweight, scales, x, y, M, static_cast<hipStream_t>(stream)));
 }
 
 int qail_w4a4_conv_u4(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t* w_s4, const float* scale,

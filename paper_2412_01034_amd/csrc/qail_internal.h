@@ -61,8 +61,18 @@ size_t gemm_f16_workspace(const qail_wdesc& d, int M);
 hipError_t launch_w4a16_gemm_f16(const qail_w4a16_item& it, int M, void* ws, hipStream_t st);
 hipError_t launch_w4a16_generic(const qail_w4a16_item& it, int M, hipStream_t st);
 
+// 8-bit variants.
+hipError_t launch_quantize_s8(const qail_wdesc& d, const float* w, uint32_t* qw, void* scales,
+                              uint32_t* range_errors, hipStream_t st);
+hipError_t launch_act_scale_s8(const float* a, size_t n, float* s_a, hipStream_t st);
+hipError_t launch_act_quant_s8(const float* a, size_t n, const float* s_a, uint32_t* out, hipStream_t st);
+hipError_t launch_w8a16_linear(const qail_wdesc& d, const uint32_t* qw, const uint16_t* sc, const uint16_t* x,
+                               uint16_t* y, int M, hipStream_t st);
+
 // W4A4.
 hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
+                            const float* scale, const float* bias, float* y, hipStream_t st);
+hipError_t launch_w8a8_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
                             const float* scale, const float* bias, float* y, hipStream_t st);
 hipError_t launch_w4a4_conv_u4(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const float* scale,
                                const float* bias, float s_out, const uint32_t* res_u4, float res_scale,

@@ -139,7 +139,10 @@ constexpr int kMaxSteps = 128;  // rows of the step table (K steps plus the ring
 // g, g + KS, ...), each with its own ring; their int32 partial tiles are added in the epilogue
 // (integer sums: exact in any order).  For the deep layers of a small batch, which have few
 // tiles and long K, this puts several waves on every SIMD instead of one.
-template <int BM, int BN, int KS>
+//
+// kBits = 8 is the W8A8 variant of the same kernel (Sec. 5.4): bytes are MFMA operands as they
+// are, a K step is 64 codes and one MFMA deep, nothing is widened and nothing shifted back.
+template <int BM, int BN, int KS, int kBits>
 __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 : 4))) void w4a4_conv_kernel(
     const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, const ConvOut out) {
     constexpr int kLA = BM / 64;   // wave-wide loads per wave and step for the activation tile
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
     unsigned char* const smem = smem_all + grp * kGroupBytes;
     const int wm = wave / 2, wn = wave % 2;
     const int bm = blockIdx.y * BM, bn = blockIdx.x * BN;
-    const int cw = gm.Cin / 8;                 // words per pixel
+    const int cw = gm.Cin / (32 / kBits);      // words per pixel
     const int kwords = gm.KH * gm.KW * cw;     // words per filter
     const int gsteps = (kwords + kStepWords - 1) / kStepWords;   // K steps of the whole problem
     const int steps = (gsteps + KS - 1) / KS;                     // ... of one group (the same for all)
@@ -248,13 +251,14 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
             dma16(rw, poff[i], lds0 + slot * kStageBytes + BM * 64 + (4 * (i - kLA) + wave) * 1024);
     };
 
-    // Fragment reads: lane (r16, kq) takes 8 bytes (16 codes) of row r16 of a 16-row tile for
-    // each of the two 64-code MFMA steps of a K step.
+    // Fragment reads.  4-bit: lane (r16, kq) takes 8 bytes (16 codes) of row r16 of a 16-row tile
+    // for each of the two 64-code MFMA steps of a K step.  8-bit: 16 bytes, one MFMA step.
     const int r16 = lane & 15, kq = lane >> 4;
     int foff[2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
-        foff[sub] = r16 * 64 + (((2 * sub + (kq >> 1)) ^ ((r16 >> 2) & 3)) << 4) + (kq & 1) * 8;
+        foff[sub] = kBits == 4 ? r16 * 64 + (((2 * sub + (kq >> 1)) ^ ((r16 >> 2) & 3)) << 4) + (kq & 1) * 8
+                               : r16 * 64 + ((kq ^ ((r16 >> 2) & 3)) << 4);
 
     i32x4_t acc[kTM][kTN];
 #pragma unroll
@@ -268,15 +272,23 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
         const unsigned char* Bs = smem + slot * kStageBytes + BM * 64 + wn * (BN / 2) * 64 + foff[sub];
 #pragma unroll
         for (int i = 0; i < kTM; ++i) {
-            const uint2 p = *reinterpret_cast<const uint2*>(As + i * 16 * 64);
-            af[reg][i] = i32x4_t{(int)(p.x & 0x0F0F0F0Fu), (int)((p.x >> 4) & 0x0F0F0F0Fu),
-                                 (int)(p.y & 0x0F0F0F0Fu), (int)((p.y >> 4) & 0x0F0F0F0Fu)};
+            if constexpr (kBits == 4) {
+                const uint2 p = *reinterpret_cast<const uint2*>(As + i * 16 * 64);
+                af[reg][i] = i32x4_t{(int)(p.x & 0x0F0F0F0Fu), (int)((p.x >> 4) & 0x0F0F0F0Fu),
+                                     (int)(p.y & 0x0F0F0F0Fu), (int)((p.y >> 4) & 0x0F0F0F0Fu)};
+            } else {
+                af[reg][i] = *reinterpret_cast<const i32x4_t*>(As + i * 16 * 64);
+            }
         }
 #pragma unroll
         for (int j = 0; j < kTN; ++j) {
-            const uint2 p = *reinterpret_cast<const uint2*>(Bs + j * 16 * 64);
-            bf[reg][j] = i32x4_t{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
-                                 (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
+            if constexpr (kBits == 4) {
+                const uint2 p = *reinterpret_cast<const uint2*>(Bs + j * 16 * 64);
+                bf[reg][j] = i32x4_t{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
+                                     (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
+            } else {
+                bf[reg][j] = *reinterpret_cast<const i32x4_t*>(Bs + j * 16 * 64);
+            }
         }
     };
     auto multiply = [&](int reg) {
@@ -291,7 +303,7 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
         for (int u = 0; u < kM; ++u) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             if (u < kR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, (4 * kR + kM - 1) / kM, 0);
+            if (kBits == 4) __builtin_amdgcn_sched_group_barrier(0x002, (4 * kR + kM - 1) / kM, 0);
         }
     };
 
@@ -306,25 +318,46 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
     __syncthreads();
     fetch(0, 0, 0);
 
-    for (int s0 = 0; s0 < steps; s0 += kStages) {
+    if constexpr (kBits == 4) {
+        for (int s0 = 0; s0 < steps; s0 += kStages) {
 #pragma unroll
-        for (int u = 0; u < kStages; ++u) {
-            if (s0 + u >= steps) break;
-            const int cur = u, nxt = (u + 1) % kStages, fill = (u + 2) % kStages;
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(cur, 1, 1);
-            multiply(0);
-            __builtin_amdgcn_sched_barrier(0);
-            // slot `fill` held step s - 1, whose last reads were issued before the previous barrier
-            plan();
+            for (int u = 0; u < kStages; ++u) {
+                if (s0 + u >= steps) break;
+                const int cur = u, nxt = (u + 1) % kStages, fill = (u + 2) % kStages;
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(cur, 1, 1);
+                multiply(0);
+                __builtin_amdgcn_sched_barrier(0);
+                // slot `fill` held step s - 1, whose last reads were issued before the previous barrier
+                plan();
 #pragma unroll
-            for (int i = 0; i < kL; ++i) issue(i, fill);
-            // in flight: step s + 1 (issued one step ago) and step s + 2 (just issued)
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(kL));
-            __syncthreads();
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(nxt, 0, 0);
-            multiply(1);
+                for (int i = 0; i < kL; ++i) issue(i, fill);
+                // in flight: step s + 1 (issued one step ago) and step s + 2 (just issued)
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(kL));
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(nxt, 0, 0);
+                multiply(1);
+            }
+        }
+    } else {
+        // one MFMA step per K step: the operand registers alternate with the step's parity, so
+        // the ring of three is unrolled twice
+        for (int s0 = 0; s0 < steps; s0 += 2 * kStages) {
+#pragma unroll
+            for (int u = 0; u < 2 * kStages; ++u) {
+                if (s0 + u >= steps) break;
+                const int nxt = (u + 1) % kStages, fill = (u + 2) % kStages, reg = u & 1;
+                __builtin_amdgcn_sched_barrier(0);
+                plan();
+#pragma unroll
+                for (int i = 0; i < kL; ++i) issue(i, fill);
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(kL));
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(nxt, 0, reg ^ 1);
+                multiply(reg);
+            }
         }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -347,7 +380,7 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
                         stage[(rbase + i * 16 + (lane >> 4) * 4 + r) * kSPitch + wn * (BN / 2) + j * 16 + (lane & 15)] =
-                            acc[i][j][r] >> 4;  // exact: the accumulator is 16 * result
+                            kBits == 4 ? acc[i][j][r] >> 4 : acc[i][j][r];  // 4-bit: the accumulator is 16 * result
         }
         __syncthreads();
         if (out.out_u4) {
@@ -401,8 +434,9 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
     }
 }
 
-// Any Cin % 8 == 0: one thread per output.  Slow; for shapes whose Cin is not a
+// Any Cin that fills whole words: one thread per output.  Slow; for shapes whose Cin is not a
 // multiple of 32, more than 32 filter taps, or tensors of 4 GB and more.
+template <int kBits>
 __global__ __launch_bounds__(256) void w4a4_generic_kernel(
     const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, const ConvOut out) {
     int32_t* const acc_out = out.acc;
@@ -415,7 +449,7 @@ __global__ __launch_bounds__(256) void w4a4_generic_kernel(
     const int b = m / (gm.OH * gm.OW);
     const int rem = m - b * (gm.OH * gm.OW);
     const int oh = rem / gm.OW, ow = rem - oh * gm.OW;
-    const int cw = gm.Cin / 8;
+    const int cw = gm.Cin / (32 / kBits);
     int acc = 0;
     for (int kh = 0; kh < gm.KH; ++kh)
         for (int kwi = 0; kwi < gm.KW; ++kwi) {
@@ -425,11 +459,16 @@ __global__ __launch_bounds__(256) void w4a4_generic_kernel(
             const uint32_t* wp = w + ((size_t)(n * gm.KH + kh) * gm.KW + kwi) * cw;
             for (int c = 0; c < cw; ++c) {
                 const uint32_t av = ap[c], wv = wp[c];
+                if (kBits == 4) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int qa = (av >> (4 * j)) & 0xF;
-                    const int qw = (int)(((wv >> (4 * j)) & 0xFu) ^ 8u) - 8;
-                    acc += qa * qw;
+                    for (int j = 0; j < 8; ++j) {
+                        const int qa = (av >> (4 * j)) & 0xF;
+                        const int qw = (int)(((wv >> (4 * j)) & 0xFu) ^ 8u) - 8;
+                        acc += qa * qw;
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc += (int)(int8_t)(av >> (8 * j)) * (int)(int8_t)(wv >> (8 * j));
                 }
             }
         }
@@ -480,47 +519,51 @@ int conv_cus() {
     return cus;
 }
 
-template <int BM, int BN, int KS = 1>
+template <int kBits, int BM, int BN, int KS = 1>
 void launch_tiled(const ConvGeom& gm, const uint32_t* a, const uint32_t* w, const ConvOut& out, hipStream_t st) {
     dim3 grid((gm.Cout + BN - 1) / BN, (gm.M + BM - 1) / BM);
-    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN, KS>), grid, dim3(256 * KS), 0, st, gm, a, w, out);
+    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN, KS, kBits>), grid, dim3(256 * KS), 0, st, gm, a, w, out);
 }
 
 }  // namespace
 
 namespace {
+template <int kBits>
 hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const ConvOut& out,
                        hipStream_t st) {
+    constexpr int kPerWord = 32 / kBits;
     ConvGeom gm;
     gm.B = d.B; gm.H = d.H; gm.W = d.W; gm.Cin = d.Cin; gm.Cout = d.Cout;
     gm.KH = d.KH; gm.KW = d.KW; gm.stride = d.stride; gm.pad = d.pad;
     gm.OH = (d.H + 2 * d.pad - d.KH) / d.stride + 1;
     gm.OW = (d.W + 2 * d.pad - d.KW) / d.stride + 1;
     gm.M = d.B * gm.OH * gm.OW;
-    const bool fits32 = (size_t)gm.B * gm.H * gm.W * (gm.Cin / 2) < 0xFFFFFFF0ull &&
-                        (size_t)gm.Cout * gm.KH * gm.KW * (gm.Cin / 2) < 0xFFFFFFF0ull &&
+    const size_t cwb = (size_t)gm.Cin / kPerWord * 4;  // bytes per pixel
+    const bool fits32 = (size_t)gm.B * gm.H * gm.W * cwb < 0xFFFFFFF0ull &&
+                        (size_t)gm.Cout * gm.KH * gm.KW * cwb < 0xFFFFFFF0ull &&
                         (size_t)gm.M * gm.Cout * 4 < 0xFFFFFFF0ull;
-    const int ksteps = (gm.KH * gm.KW * (gm.Cin / 8) + kStepWords - 1) / kStepWords;
-    if (d.Cin % 32 == 0 && d.KH * d.KW <= 32 && fits32 && ksteps + 4 * (kStages + 1) <= kMaxSteps) {
+    const int ksteps = (gm.KH * gm.KW * (gm.Cin / kPerWord) + kStepWords - 1) / kStepWords;
+    // a 16-byte chunk (32 or 16 codes) must lie inside one filter tap
+    if (d.Cin % (4 * kPerWord) == 0 && d.KH * d.KW <= 32 && fits32 && ksteps + 4 * (kStages + 1) <= kMaxSteps) {
         // the largest tile that still gives every CU about two blocks
         const long long want = 2LL * conv_cus();
         auto blocks = [&](int bm, int bn) {
             return (long long)((gm.M + bm - 1) / bm) * ((gm.Cout + bn - 1) / bn);
         };
         const bool wide = gm.Cout > 64;
-        if (wide && blocks(128, 128) >= want) launch_tiled<128, 128>(gm, a, w, out, st);
-        else if (blocks(128, 64) >= want) launch_tiled<128, 64>(gm, a, w, out, st);
-        else if (wide && blocks(64, 128) >= want / 2) launch_tiled<64, 128>(gm, a, w, out, st);
-        else if (blocks(64, 64) <= conv_cus() && ksteps >= 16) launch_tiled<64, 64, 4>(gm, a, w, out, st);
-        else if (blocks(64, 64) <= 2 * conv_cus() && ksteps >= 8) launch_tiled<64, 64, 2>(gm, a, w, out, st);
-        else launch_tiled<64, 64>(gm, a, w, out, st);
+        if (wide && blocks(128, 128) >= want) launch_tiled<kBits, 128, 128>(gm, a, w, out, st);
+        else if (blocks(128, 64) >= want) launch_tiled<kBits, 128, 64>(gm, a, w, out, st);
+        else if (wide && blocks(64, 128) >= want / 2) launch_tiled<kBits, 64, 128>(gm, a, w, out, st);
+        else if (blocks(64, 64) <= conv_cus() && ksteps >= 16) launch_tiled<kBits, 64, 64, 4>(gm, a, w, out, st);
+        else if (blocks(64, 64) <= 2 * conv_cus() && ksteps >= 8) launch_tiled<kBits, 64, 64, 2>(gm, a, w, out, st);
+        else launch_tiled<kBits, 64, 64>(gm, a, w, out, st);
     } else if (out.out_u4) {
         const size_t words = (size_t)gm.M * (d.Cout / 8);
         hipLaunchKernelGGL(w4a4_generic_u4_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, gm,
                            a, w, out);
     } else {
         const size_t outs = (size_t)gm.M * d.Cout;
-        hipLaunchKernelGGL(w4a4_generic_kernel, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st, gm,
+        hipLaunchKernelGGL(w4a4_generic_kernel<kBits>, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st, gm,
                            a, w, out);
     }
     return hipGetLastError();
@@ -530,14 +573,20 @@ hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_
 hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
                             const float* scale, const float* bias, float* y, hipStream_t st) {
     const ConvOut out{acc, scale, bias, y, nullptr, nullptr, nullptr, 1.f, 0.f};
-    return launch_conv(d, a, w, out, st);
+    return launch_conv<4>(d, a, w, out, st);
+}
+
+hipError_t launch_w8a8_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
+                            const float* scale, const float* bias, float* y, hipStream_t st) {
+    const ConvOut out{acc, scale, bias, y, nullptr, nullptr, nullptr, 1.f, 0.f};
+    return launch_conv<8>(d, a, w, out, st);
 }
 
 hipError_t launch_w4a4_conv_u4(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const float* scale,
                                const float* bias, float s_out, const uint32_t* res_u4, float res_scale,
                                const float* res_f32, uint32_t* out_u4, hipStream_t st) {
     const ConvOut out{nullptr, scale, bias, nullptr, out_u4, res_u4, res_f32, s_out, res_scale};
-    return launch_conv(d, a, w, out, st);
+    return launch_conv<4>(d, a, w, out, st);
 }
 
 }  // namespace qail

@@ -1,0 +1,135 @@
+"""GPU parity of the 8-bit variants against the CPU oracle: codes, scales and int32
+accumulators bit-exact, the weight-only linear within the W4A16 bar."""
+import numpy as np
+import pytest
+
+from oracle import qail_oracle as O
+from paper_2412_01034_amd import synth
+from tests.helpers import dev, ensure_built, host, w4a16_norm_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def B():
+    return ensure_built()
+
+
+def geom(s):
+    return (s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad)
+
+
+def test_weight_quantisers_bit_exact(B):
+    import torch
+    # per channel (the W8A8 encoder): a conv filter bank
+    s = synth.ConvShape("q", 1, 8, 8, 64, 40, 3, 3, 1, 1)
+    w = synth.conv_weight(s, 11)
+    w[7] = 0
+    q_ref, s_ref = O.quantize_w8_sym_channel(w)
+    qw = torch.zeros(s.Cout * s.K // 4, dtype=torch.int32, device="cuda")
+    sc = torch.zeros(s.Cout, dtype=torch.float32, device="cuda")
+    B.qail_quantize_weights(dev(w.reshape(s.Cout, -1)), s.K, B.QAIL_W8_SYM_CHANNEL, qw, sc, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(qw, np.uint32).reshape(s.Cout, -1), O.pack_bytes(q_ref.reshape(s.Cout, -1)))
+    assert np.array_equal(host(sc, np.float32), s_ref)
+    # per group (weight-only), with outlier columns and an all-zero group
+    N, K, g = 96, 1024, 128
+    w = synth.llm_weight(N, K, 12, outlier_frac=0.01)
+    w[3, 128:256] = 0
+    q_ref, s_ref = O.quantize_w8_sym_group(w, g)
+    qw = torch.zeros(N * K // 4, dtype=torch.int32, device="cuda")
+    sc = torch.zeros(N * K // g, dtype=torch.int16, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.qail_quantize_weights(dev(w), g, B.QAIL_W8_SYM_GROUP, qw, sc, None, err)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(qw, np.uint32).reshape(N, -1), O.pack_bytes(q_ref))
+    assert np.array_equal(host(sc, np.uint16).reshape(N, -1), s_ref.view(np.uint16))
+    assert int(err.item()) == 0
+    assert B.qail_packed_sizes(N, K, g, B.QAIL_W8_SYM_GROUP) == (N * K, N * (K // g) * 2, 0)
+    assert B.qail_packed_sizes(N, K, g, B.QAIL_W8_SYM_CHANNEL) == (N * K, N * 4, 0)
+
+
+def test_activation_quantiser_bit_exact(B):
+    import torch
+    rng = np.random.default_rng(13)
+    a = (rng.standard_normal(50000) * 3).astype(np.float32)
+    a[:4] = [0.0, -0.0, 1e-30, -7.5]
+    sa = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ad = dev(a)
+    B.qail_act_scale_s8(ad, sa)
+    out = torch.zeros(a.size // 4, dtype=torch.int32, device="cuda")
+    B.qail_quantize_act_s8(ad, sa, out)
+    torch.cuda.synchronize()
+    s_ref = O.act_scale_s8(a)
+    assert host(sa, np.float32)[0] == s_ref
+    assert np.array_equal(host(out, np.uint32), O.pack_bytes(O.quantize_act_s8(a, s_ref)))
+    z = torch.zeros(64, dtype=torch.float32, device="cuda")
+    B.qail_act_scale_s8(z, sa)
+    torch.cuda.synchronize()
+    assert host(sa, np.float32)[0] == 1.0
+
+
+SHAPES = [
+    synth.ConvShape("e0", 1, 4, 4, 64, 3, 3, 3, 1, 1),
+    synth.ConvShape("e1", 2, 9, 7, 64, 70, 3, 3, 2, 1),        # ragged M and N tiles
+    synth.ConvShape("e2", 3, 6, 6, 128, 64, 1, 1, 2, 0),
+    synth.ConvShape("e3", 1, 12, 12, 192, 40, 3, 3, 1, 1),     # K split over two wave groups
+    synth.ConvShape("e4", 2, 5, 5, 4, 6, 3, 3, 1, 1),          # Cin = 4: generic kernel
+    synth.ConvShape("e5", 1, 6, 6, 512, 32, 3, 3, 1, 1),       # K = 4608: four wave groups
+    synth.ConvShape("e6", 4, 28, 28, 128, 256, 3, 3, 2, 1),    # 128 x 128 tiles
+    synth.ConvShape("e7", 2, 20, 20, 64, 64, 3, 3, 1, 1),      # 128 x 64 / 64 x 64 tiles, several blocks
+]
+
+
+@pytest.mark.parametrize("s", SHAPES, ids=[s.name for s in SHAPES])
+def test_w8a8_conv_bit_exact(B, s):
+    import torch
+    a = synth.random_codes((s.B, s.H, s.W, s.Cin), -128, 127, 31).astype(np.int8)
+    w = synth.random_codes((s.Cout, s.K), -128, 127, 32).astype(np.int8)
+    aw, ww = O.pack_bytes(a), O.pack_bytes(w)
+    ref = O.w8a8_conv_acc(aw, ww, *geom(s))
+    scale = (np.random.default_rng(33).random(s.Cout) * 1e-3 + 1e-4).astype(np.float32)
+    bias = synth.conv_bias(s, 34)
+    acc = torch.full((s.M * s.Cout,), 0x55555555, dtype=torch.int32, device="cuda")
+    y = torch.full((s.M * s.Cout,), float("nan"), dtype=torch.float32, device="cuda")
+    B.qail_w8a8_gemm(*geom(s), dev(aw), dev(ww), acc_out=acc, scale=dev(scale), bias=dev(bias), y_out=y)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(acc, np.int32).reshape(s.M, s.Cout), ref)
+    yref = O.requant(ref, scale, bias)
+    bound = 2.0 ** -22 * (np.abs(ref.astype(np.float64) * scale.astype(np.float64)[None, :])
+                          + np.abs(bias.astype(np.float64))[None, :])
+    assert np.all(np.abs(host(y, np.float32).reshape(s.M, s.Cout).astype(np.float64) - yref) <= bound)
+
+
+def test_w8a8_extremes(B):
+    import torch
+    s = synth.ConvShape("x", 1, 6, 6, 512, 32, 3, 3, 1, 1)
+    a = np.full((1, 6, 6, 512), -128, np.int8)
+    w = np.empty((32, s.K), np.int8)
+    w[0::2], w[1::2] = -128, 127
+    acc = torch.zeros(s.M * s.Cout, dtype=torch.int32, device="cuda")
+    B.qail_w8a8_gemm(*geom(s), dev(O.pack_bytes(a)), dev(O.pack_bytes(w)), acc_out=acc)
+    torch.cuda.synchronize()
+    got = host(acc, np.int32).reshape(s.M, s.Cout)
+    centre = 2 * 6 + 2                                  # an interior pixel sees all 9 taps
+    assert got[centre, 0] == 128 * 128 * s.K and got[centre, 1] == -128 * 127 * s.K
+
+
+@pytest.mark.parametrize("M", [1, 5])
+@pytest.mark.parametrize("N,K,g", [(300, 4096, 128), (64, 11008, 128), (33, 256, 32), (7, 40, 8)])
+def test_w8a16_linear(B, M, N, K, g):
+    import torch
+    w = synth.llm_weight(N, K, 50 + N, outlier_frac=0.01)
+    xb = synth.llm_activation_bf16(M, K, 51 + N)
+    q, s = O.quantize_w8_sym_group(w, g)
+    y = torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")
+    B.qail_w8a16_linear(N, K, g, dev(O.pack_bytes(q)), dev(s.view(np.uint16)), dev(xb), y, M)
+    torch.cuda.synchronize()
+    ref = O.w8a16_linear(xb, q, s, g)
+    nx = np.sqrt((O.bf16_bits_to_f64(xb) ** 2).sum(axis=1))
+    wh = q.astype(np.float64) * np.repeat(s.astype(np.float64), g, axis=1)
+    nw = np.sqrt((wh ** 2).sum(axis=1))
+    tol = TOL if K >= 512 else 2.0 ** -8 * 1.01
+    assert w4a16_norm_err(host(y, np.uint16).reshape(M, N), ref, nx, nw) <= tol
