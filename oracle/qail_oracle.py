@@ -417,3 +417,56 @@ def w8a16_linear(x_bf16_bits: np.ndarray, codes: np.ndarray, scales: np.ndarray,
     q = np.asarray(codes).astype(np.float64)
     s = np.repeat(np.asarray(scales).astype(np.float64), group_size, axis=1)
     return x @ (q * s).T
+
+
+# ===========================================================================
+# Training-side operators (Sec. 3.2, Algorithm 1: the quantised policy is trained
+# through its quantisers with the straight-through estimator; Sec. 3.3, Eq. 3 and the
+# appendix's implementation details: the QBC term is the mean L2 distance between
+# the final logits of the quantised and the full-precision policy).
+# ===========================================================================
+
+def fake_quant_w4_group(w: np.ndarray, group_size: int) -> np.ndarray:
+    """Quantise-dequantise of a weight matrix with the 4-bit group quantiser above:
+    what the forward pass of quantisation-aware training sees.  float32 [N, K]; the
+    products (q - z) * s are exact in float32 (5-bit integer times 11-bit significand).
+    Its straight-through backward is the identity (Algorithm 1), so it has no code."""
+    q, s, z = quantize_w4_asym_group(w, group_size)
+    return dequantize_w4_asym_group(q, s, z, group_size).astype(F32)
+
+
+def lsq_fake_quant_fwd(v: np.ndarray, s, qn: int, qp: int) -> np.ndarray:
+    """Learned-step quantiser named in Sec. 5.1 for weights and activations:
+    v_hat = clamp(rint(v / s), qn, qp) * s, every operation in float32."""
+    v = np.asarray(v, dtype=F32)
+    return (np.clip(np.rint(v / F32(s)), qn, qp).astype(F32) * F32(s)).astype(F32)
+
+
+def lsq_fake_quant_bwd(v: np.ndarray, s, qn: int, qp: int, dout: np.ndarray, grad_scale: float):
+    """Straight-through backward of lsq_fake_quant_fwd (rint treated as the identity when
+    differentiating, clamp as it is):
+        dv = dout                         where qn <= v / s <= qp, else 0
+        ds = grad_scale * sum dout * t,   t = rint(v/s) - v/s inside, qn below, qp above.
+    The ratio v / s is the float32 one of the forward; the sum is in float64.
+    Returns (dv float32, ds float64 scalar)."""
+    v = np.asarray(v, dtype=F32)
+    dout = np.asarray(dout, dtype=F32)
+    r = v / F32(s)
+    inside = (r >= F32(qn)) & (r <= F32(qp))
+    dv = np.where(inside, dout, F32(0)).astype(F32)
+    t = np.where(inside, np.rint(r).astype(np.float64) - r.astype(np.float64),
+                 np.where(r < F32(qn), np.float64(qn), np.float64(qp)))
+    return dv, float(grad_scale) * float((dout.astype(np.float64) * t).sum())
+
+
+def qbc_loss(logits_q: np.ndarray, logits_fp: np.ndarray):
+    """Eq. 3 with the discrepancy the appendix states: the mean over the batch of the L2
+    distance between the two policies' final logits.  float64.
+    Returns (loss, d loss / d logits_q); rows with zero distance have zero gradient."""
+    a = np.asarray(logits_q, dtype=np.float64)
+    b = np.asarray(logits_fp, dtype=np.float64)
+    diff = a - b
+    dist = np.sqrt((diff * diff).sum(axis=1))
+    Bn = a.shape[0]
+    grad = np.where(dist[:, None] > 0, diff / np.where(dist > 0, dist, 1.0)[:, None], 0.0) / Bn
+    return float(dist.mean()), grad
