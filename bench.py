@@ -387,6 +387,29 @@ def main():
                                        "bytes": b8, "launches_per_layer": 4,
                                        "note": "weights stay cache-resident here (one layer, 211 MB): an upper bound"}
         del w8l
+        # training-side operators (HBM-bound elementwise / reduction kernels): GB/s of bytes touched
+        tr = {}
+        Nq, Kq = shapes[0][1], shapes[0][2]
+        wq_ = torch.randn(Nq, Kq, dtype=torch.float32, device="cuda") * 0.02
+        wh_ = torch.empty_like(wq_)
+        tt = timed(lambda: B.qail_fake_quant_w4(wq_, GROUP, wh_), 20)
+        tr["fake_quant_w4_12288x4096"] = {"us": round(tt * 1e6, 1), "GBps": round(2 * wq_.numel() * 4 / tt / 1e9, 1)}
+        sdev = torch.full((1,), 0.01, dtype=torch.float32, device="cuda")
+        dsd = torch.zeros(1, dtype=torch.float32, device="cuda")
+        wsl_ = torch.empty(B.qail_lsq_backward_workspace(), dtype=torch.uint8, device="cuda")
+        tt = timed(lambda: B.qail_lsq_forward(wq_, sdev, -8, 7, wh_), 20)
+        tr["lsq_forward_50M"] = {"us": round(tt * 1e6, 1), "GBps": round(2 * wq_.numel() * 4 / tt / 1e9, 1)}
+        dv_ = torch.empty_like(wq_)
+        tt = timed(lambda: B.qail_lsq_backward(wq_, wh_, sdev, -8, 7, 1e-4, dv_, dsd, wsl_), 20)
+        tr["lsq_backward_50M"] = {"us": round(tt * 1e6, 1), "GBps": round(3 * wq_.numel() * 4 / tt / 1e9, 1)}
+        lq_ = torch.randn(1024, 32000, dtype=torch.float32, device="cuda")
+        lf_ = torch.randn(1024, 32000, dtype=torch.float32, device="cuda")
+        gq_ = torch.empty_like(lq_)
+        wsq_ = torch.empty(1024, dtype=torch.float32, device="cuda")
+        tt = timed(lambda: B.qail_qbc_loss(lq_, lf_, dsd, gq_, wsq_), 20)
+        tr["qbc_loss_grad_1024x32000"] = {"us": round(tt * 1e6, 1), "GBps": round(5 * lq_.numel() * 4 / tt / 1e9, 1)}
+        extra["train_ops"] = tr
+        del wq_, wh_, dv_, lq_, lf_, gq_
         result["extra"] = extra
         log("[bench] extra:", json.dumps(extra))
 

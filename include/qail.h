@@ -263,6 +263,36 @@ int qail_w8a8_gemm(const qail_conv_desc* d, const uint32_t* a_s8, const uint32_t
 int qail_w8a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales,
                       const uint16_t* x, uint16_t* y, int32_t M, void* stream);
 
+/* ------------------------------------------------------- training-side operators --
+ * Sec. 3.2 / Algorithm 1: the quantised policy is trained through its quantisers with the
+ * straight-through estimator.  Sec. 3.3 / Eq. 3: the QBC term; the appendix instantiates its
+ * discrepancy as the mean L2 distance between the two policies' final logits. */
+
+/* Forward of quantisation-aware training for a 4-bit group-quantised weight: w_hat =
+ * dequantise(quantise(w)) with the ASYM_GROUP quantiser above, fp32 [N][K] -> fp32 [N][K]
+ * (exact: (q - z) * s has at most 16 significant bits).  Its straight-through backward is the
+ * identity, so no call exists for it. */
+int qail_fake_quant_w4(const qail_wdesc* d, const float* w, float* w_hat, void* stream);
+
+/* Learned-step quantiser (named in Sec. 5.1 for the driving policy): v_hat = clamp(rint(v / *s),
+ * qn, qp) * *s in fp32; s: device, one float; qn <= 0 <= qp. */
+int qail_lsq_forward(const float* v, size_t n, const float* s, int32_t qn, int32_t qp, float* v_hat,
+                     void* stream);
+
+/* Straight-through backward: dv = dout where qn <= v / s <= qp, else 0;
+ * *ds = grad_scale * sum dout * t, t = rint(v/s) - v/s inside, qn below, qp above (fp32 sums in
+ * a fixed order).  workspace: qail_lsq_backward_workspace bytes, 16-byte aligned. */
+int qail_lsq_backward_workspace(size_t* bytes);
+int qail_lsq_backward(const float* v, const float* dout, size_t n, const float* s, int32_t qn, int32_t qp,
+                      float grad_scale, float* dv, float* ds, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/* *loss = mean_b || logits_q[b] - logits_fp[b] ||_2 over fp32 [B][D]; grad_q (optional, [B][D]) =
+ * d loss / d logits_q = (diff / ||diff||) / B, zero for rows with zero distance.
+ * workspace: B floats, 16-byte aligned. */
+int qail_qbc_loss(const float* logits_q, const float* logits_fp, int32_t B, int32_t D, float* loss,
+                  float* grad_q, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

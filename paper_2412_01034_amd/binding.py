@@ -35,6 +35,7 @@ EXPORTS = (
     "qail_w4a4_workspace", "qail_w4a4_gemm", "qail_w4a4_conv_u4",
     "qail_w4a16_lora_workspace", "qail_w4a16_linear_lora_batch",
     "qail_act_scale_s8", "qail_quantize_act_s8", "qail_w8a8_gemm", "qail_w8a16_linear",
+    "qail_fake_quant_w4", "qail_lsq_forward", "qail_lsq_backward_workspace", "qail_lsq_backward", "qail_qbc_loss",
 )
 
 
@@ -91,6 +92,11 @@ def lib() -> ctypes.CDLL:
         L.qail_w4a16_lora_workspace.argtypes = [ctypes.POINTER(qail_w4a16_item), ctypes.POINTER(qail_lora), i32, i32, psz]
         L.qail_w4a16_linear_lora_batch.argtypes = [ctypes.POINTER(qail_w4a16_item), ctypes.POINTER(qail_lora), i32,
                                                    i32, vp, sz, vp]
+        L.qail_fake_quant_w4.argtypes = [ctypes.POINTER(qail_wdesc), vp, vp, vp]
+        L.qail_lsq_forward.argtypes = [vp, sz, vp, i32, i32, vp, vp]
+        L.qail_lsq_backward_workspace.argtypes = [psz]
+        L.qail_lsq_backward.argtypes = [vp, vp, sz, vp, i32, i32, ctypes.c_float, vp, vp, vp, sz, vp]
+        L.qail_qbc_loss.argtypes = [vp, vp, i32, i32, vp, vp, vp, sz, vp]
         L.qail_act_scale_s8.argtypes = [vp, sz, vp, vp]
         L.qail_quantize_act_s8.argtypes = [vp, sz, vp, vp, vp]
         L.qail_w8a8_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -371,3 +377,41 @@ def qail_w8a16_linear(N: int, K: int, group_size: int, qweight: torch.Tensor, sc
     d = qail_wdesc(N, K, group_size, QAIL_W8_SYM_GROUP)
     _check(lib().qail_w8a16_linear(ctypes.byref(d), _ptr(qweight), _ptr(scales), _ptr(x), _ptr(y), M,
                                    _stream() if stream is None else stream), "qail_w8a16_linear")
+
+
+def qail_fake_quant_w4(w: torch.Tensor, group_size: int, w_hat: torch.Tensor) -> None:
+    N = w.shape[0]
+    K = w.numel() // N
+    _need(w_hat, N * K * 4, "w_hat")
+    d = qail_wdesc(N, K, group_size, QAIL_W4_ASYM_GROUP)
+    _check(lib().qail_fake_quant_w4(ctypes.byref(d), _ptr(w), _ptr(w_hat), _stream()), "qail_fake_quant_w4")
+
+
+def qail_lsq_forward(v: torch.Tensor, s: torch.Tensor, qn: int, qp: int, v_hat: torch.Tensor) -> None:
+    _need(v_hat, v.numel() * 4, "v_hat")
+    _check(lib().qail_lsq_forward(_ptr(v), v.numel(), _ptr(s), qn, qp, _ptr(v_hat), _stream()), "qail_lsq_forward")
+
+
+def qail_lsq_backward(v: torch.Tensor, dout: torch.Tensor, s: torch.Tensor, qn: int, qp: int, grad_scale: float,
+                      dv: torch.Tensor, ds: torch.Tensor, workspace: torch.Tensor) -> None:
+    _need(dout, v.numel() * 4, "dout")
+    _need(dv, v.numel() * 4, "dv")
+    _check(lib().qail_lsq_backward(_ptr(v), _ptr(dout), v.numel(), _ptr(s), qn, qp, float(grad_scale), _ptr(dv),
+                                   _ptr(ds), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+           "qail_lsq_backward")
+
+
+def qail_lsq_backward_workspace() -> int:
+    b = ctypes.c_size_t()
+    _check(lib().qail_lsq_backward_workspace(ctypes.byref(b)), "qail_lsq_backward_workspace")
+    return b.value
+
+
+def qail_qbc_loss(logits_q: torch.Tensor, logits_fp: torch.Tensor, loss: torch.Tensor,
+                  grad_q: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    Bn, D = logits_q.shape
+    _need(logits_fp, Bn * D * 4, "logits_fp")
+    if grad_q is not None:
+        _need(grad_q, Bn * D * 4, "grad_q")
+    _check(lib().qail_qbc_loss(_ptr(logits_q), _ptr(logits_fp), Bn, D, _ptr(loss), _ptr(grad_q), _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _stream()), "qail_qbc_loss")

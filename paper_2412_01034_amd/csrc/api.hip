@@ -368,6 +368,55 @@ int qail_w8a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16
     return hip_status(launch_w8a16_linear(*d, qweight, scales, x, y, M, static_cast<hipStream_t>(stream)));
 }
 
+int qail_fake_quant_w4(const qail_wdesc* d, const float* w, float* w_hat, void* stream) {
+    const int e = check_wdesc(d);
+    if (e != QAIL_OK) return e;
+    if (d->scheme != QAIL_W4_ASYM_GROUP) return QAIL_ERR_UNSUPPORTED;
+    if (!w || !w_hat) return QAIL_ERR_NULL;
+    if (!aligned16(w) || !aligned16(w_hat)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_fake_quant_w4(*d, w, w_hat, static_cast<hipStream_t>(stream)));
+}
+
+int qail_lsq_forward(const float* v, size_t n, const float* s, int32_t qn, int32_t qp, float* v_hat, void* stream) {
+    if (qn > 0 || qp < 0 || qn < -32768 || qp > 32767) return QAIL_ERR_SHAPE;
+    if (n == 0) return QAIL_OK;
+    if (!v || !s || !v_hat) return QAIL_ERR_NULL;
+    if (!aligned16(v) || !aligned16(v_hat) || (reinterpret_cast<uintptr_t>(s) & 3u)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_lsq_fwd(v, n, s, qn, qp, v_hat, static_cast<hipStream_t>(stream)));
+}
+
+int qail_lsq_backward_workspace(size_t* bytes) {
+    if (!bytes) return QAIL_ERR_NULL;
+    *bytes = lsq_bwd_workspace();
+    return QAIL_OK;
+}
+
+int qail_lsq_backward(const float* v, const float* dout, size_t n, const float* s, int32_t qn, int32_t qp,
+                      float grad_scale, float* dv, float* ds, void* workspace, size_t workspace_bytes, void* stream) {
+    if (qn > 0 || qp < 0 || qn < -32768 || qp > 32767) return QAIL_ERR_SHAPE;
+    if (!s || !ds || (n > 0 && (!v || !dout || !dv))) return QAIL_ERR_NULL;
+    if ((n > 0 && (!aligned16(v) || !aligned16(dout) || !aligned16(dv))) || (reinterpret_cast<uintptr_t>(s) & 3u) ||
+        (reinterpret_cast<uintptr_t>(ds) & 3u))
+        return QAIL_ERR_ALIGN;
+    if (!workspace || workspace_bytes < lsq_bwd_workspace()) return QAIL_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_lsq_bwd(v, dout, n, s, qn, qp, grad_scale, dv, ds, static_cast<float*>(workspace),
+                                     static_cast<hipStream_t>(stream)));
+}
+
+int qail_qbc_loss(const float* logits_q, const float* logits_fp, int32_t B, int32_t D, float* loss, float* grad_q,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+    if (B < 1 || D < 1 || B > 65535 * 16) return QAIL_ERR_SHAPE;
+    if (!logits_q || !logits_fp || !loss) return QAIL_ERR_NULL;
+    if (!aligned16(logits_q) || !aligned16(logits_fp) || (grad_q && !aligned16(grad_q)) ||
+        (reinterpret_cast<uintptr_t>(loss) & 3u))
+        return QAIL_ERR_ALIGN;
+    if (!workspace || workspace_bytes < (size_t)B * sizeof(float)) return QAIL_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return QAIL_ERR_ALIGN;
+    return hip_status(launch_qbc(logits_q, logits_fp, B, D, loss, grad_q, static_cast<float*>(workspace),
+                                 static_cast<hipStream_t>(stream)));
+}
+
 int qail_w4a4_conv_u4(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t* w_s4, const float* scale,
                       const float* bias, float s_out, const uint32_t* res_u4, float res_scale,
                       const float* res_f32, uint32_t* out_u4, void* workspace, size_t workspace_bytes,

@@ -69,6 +69,14 @@ hipError_t launch_act_quant_s8(const float* a, size_t n, const float* s_a, uint3
 hipError_t launch_w8a16_linear(const qail_wdesc& d, const uint32_t* qw, const uint16_t* sc, const uint16_t* x,
                                uint16_t* y, int M, hipStream_t st);
 
+// Training-side operators.
+hipError_t launch_fake_quant_w4(const qail_wdesc& d, const float* w, float* out, hipStream_t st);
+hipError_t launch_lsq_fwd(const float* v, size_t n, const float* s, int qn, int qp, float* out, hipStream_t st);
+size_t lsq_bwd_workspace();
+hipError_t launch_lsq_bwd(const float* v, const float* dout, size_t n, const float* s, int qn, int qp, float grad_scale,
+                          float* dv, float* ds, float* ws, hipStream_t st);
+hipError_t launch_qbc(const float* lq, const float* lf, int B, int D, float* loss, float* grad, float* ws, hipStream_t st);
+
 // W4A4.
 hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
                             const float* scale, const float* bias, float* y, hipStream_t st);
