@@ -32,8 +32,8 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/w4a16_gemv_decode_layer_pmc.txt), and the sha256 of the kernel source the
 # counters were taken on; reported as null once the kernel has changed.
-GEMV_TRAFFIC_BYTES = 106270000
-GEMV_TRAFFIC_SOURCE_SHA256 = "38bc9d7ae2ac4a69ee29901584db01c64aef69ae81a9e200d3e4be35f445f4b5"
+GEMV_TRAFFIC_BYTES = 106283151
+GEMV_TRAFFIC_SOURCE_SHA256 = "a280cc51410a102fd4a435b5518114ce32816731907a7a11babe7948c93ee598"
 
 HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0     # dense bf16 MFMA, published
