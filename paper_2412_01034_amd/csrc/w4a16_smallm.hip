@@ -7,21 +7,20 @@
 //   * A tile is 16 weight rows.  For v_mfma_f32_16x16x32_bf16 lane l = 16*kb + i supplies, as
 //     B operand, 8 consecutive k of column (weight row) i starting at 8*kb: exactly one packed
 //     word.  A lane loads 16 bytes = 4 words = 32 k of its row, so one wave-wide load covers
-//     16 rows x 128 k (64 contiguous bytes per row) and feeds 4 MFMAs; 128 k is one
+//     16 rows x 128 k (64 contiguous bytes per row) and feeds 4 MFMAs; 128 k lies inside one
 //     quantisation group (group_size is a multiple of 128), so the group's scale and
 //     zero-point are applied to the 16 x 16 result of those 4 MFMAs:
 //         sum_k x (q - z) s = s * ( sum_k x (q + 128)  -  (128 + z) * sum_k x )
 //     with (q + 128) as bf16 = 0x4300 | q (one AND-OR per nibble pair) and sum_k x per
-//     (row of x, 128-k step) computed once per wave.
-//   * The 16 waves of a block split K among themselves (whole 128-k steps), so a wave's share
-//     of x fits in registers as ready-made A operands (16 registers per step) and is never
-//     re-read; every wave walks all tiles of the block's slab of rows, keeping about 8
-//     wave-wide loads in flight in a register ring, and the 16 partial 16 x 16 results of a
-//     tile are summed through LDS in a fixed order (deterministic).
-//   * Nothing is stored to global memory while loads are in flight (a store would break the
-//     in-order completion the exact load waits rely on): results are collected in LDS and
-//     written once at the end.  K beyond 6144 is walked in several passes over the slab, each
-//     adding to the collected results.
+//     (row of x, 128-k step) computed once per block.
+//   * The activations of the block's linear are staged once in LDS as ready-made A operands
+//     (all of K when M * K * 2 bytes fit in 128 KB, else pass by pass), so a wave can walk any
+//     stretch of K of a tile without holding x in registers and the stream has no barrier.
+//   * A block owns at most 16 tiles.  Its 16 waves are dealt to (tile, K part) pairs, with as many
+//     K parts (a power of two) as keeps all waves busy; every wave keeps a ring of loads in
+//     flight with exact load waits (unconditional loads, program order = consumption order,
+//     nothing stored while loads fly).  The K parts' 16 x 16 partial results meet once, after the
+//     stream, in LDS and are added in a fixed order (deterministic).
 //   * As for M = 1, one launch serves a list of linears, blocks divided by bytes.
 #include "qail_internal.h"
 
@@ -32,11 +31,10 @@ namespace {
 constexpr int kSmMaxItems = 16;
 constexpr int kSmWaves = 16;
 constexpr int kSmThreads = kSmWaves * kWave;
-constexpr int kStepK = 128;         // k per wave-wide load
-constexpr int kSmMaxSteps = 3;      // steps per wave and pass (x operands held in registers)
-constexpr int kSmMaxPasses = 4;     // passes over K: K <= 4 * 16 * 3 * 128 = 24576
-constexpr int kSmMaxTiles = 48;     // tiles per block (LDS result buffer)
-constexpr int kRound = 4;           // tiles per LDS reduction round
+constexpr int kStepK = 128;               // k per wave-wide load
+constexpr int kRing = 8;                  // wave-wide loads in flight per wave
+constexpr int kXBytes = 128 * 1024;       // LDS for the staged activations
+constexpr int kTilesPerBlock = 16;
 
 struct SmItem {
     const uint32_t* qw;
@@ -54,196 +52,194 @@ struct SmArgs {
     int M;
 };
 
-// LDS: partial sums [kRound][16 waves][4][64] fp32, results [kSmMaxTiles][4][64] fp32, and the
-// per-wave table of step sums of x [16 waves][3 steps][16 rows] fp32.
-constexpr int kPartialFloats = kRound * kSmWaves * 256;
-constexpr size_t kSmLdsBytes = (size_t)kPartialFloats * 4 + (size_t)kSmMaxTiles * 256 * 4 +
-                               (size_t)kSmWaves * kSmMaxSteps * 16 * 4;
-
-template <int SPW, int PT>
-__device__ __forceinline__ void smallm_tiles(const SmItem& it, int M, int tile0, int nt, int wave, int lane,
-                                             int npass, float* __restrict__ partial,
-                                             float* __restrict__ result, float* __restrict__ xs_tab) {
-    const int K = it.K, N = it.N, g = it.g;
-    const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
-    const int Sall = K / kStepK;
-  for (int pass = 0; pass < npass; ++pass) {
-    // one pass: the 128-k steps [sb, se) of every tile of the slab, split among the 16 waves
-    const int sb = (int)(((long long)Sall * pass) / npass), se = (int)(((long long)Sall * (pass + 1)) / npass);
-    const bool first_pass = pass == 0;
-    const int S = se - sb;
-    const int ks0 = sb + (int)(((long long)S * wave) / kSmWaves), ks1 = sb + (int)(((long long)S * (wave + 1)) / kSmWaves);
-    const int li = lane & 15, kb = lane >> 4;
-
-    // ---- register ring of PT tiles x SPW steps of weight loads, issued first: the loads of x
-    // below then overlap with them
-    uint4 q[PT][SPW];
-    _Float16 sh[PT][SPW];  // kept in its loaded type: a widening at the load would wait there
-    uint32_t zw[PT][SPW];
-    int stepw[SPW], grp[SPW];
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-        const int st = max(sb, min(ks0 + i, max(ks1, sb + 1) - 1));  // steps past the wave's share re-read its last one
-        stepw[i] = st * (kStepK / 8) + 4 * kb;
-        grp[i] = (st * kStepK) / g;
-    }
-    auto issue = [&](int p, int i, int tile) {
-        const int row = min(tile * 16 + li, N - 1);
-        q[p][i] = *reinterpret_cast<const uint4*>(it.qw + (size_t)row * kw + stepw[i]);
-        sh[p][i] = reinterpret_cast<const _Float16*>(it.sc)[(size_t)row * G + grp[i]];
-        zw[p][i] = it.zr[(size_t)row * zwords + (grp[i] >> 3)];
-    };
-    const int tlast = tile0 + nt - 1;
-#pragma unroll
-    for (int p = 0; p < PT; ++p)
-#pragma unroll
-        for (int i = 0; i < SPW; ++i) {
-            issue(p, i, min(tile0 + p, tlast));
-            __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
-        }
-
-    // ---- this wave's share of x as A operands: row li of x, k = 128*step + 32*kb + 8*j + (0..7),
-    // in the pair order x0,x4 | x1,x5 | x2,x6 | x3,x7 that the nibble expansion produces
-    uint4 xa[SPW][4];
-    // sum of x over each step, per row of x: parked in the wave's LDS table [step][m] and read
-    // back four rows at a time (a lane's results are rows m = 4*kb .. 4*kb + 3)
-    float* xs_w = xs_tab + wave * (kSmMaxSteps * 16);
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-        const bool live = (ks0 + i < ks1) && (li < M);
-        float part = 0.f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (live)
-                v = *reinterpret_cast<const uint4*>(it.x + (size_t)li * K + (size_t)(ks0 + i) * kStepK + 32 * kb + 8 * j);
-            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                part += __builtin_bit_cast(float, u[e] << 16) + __builtin_bit_cast(float, u[e] & 0xFFFF0000u);
-            xa[i][j].x = (v.x & 0xFFFFu) | (v.z << 16);      // x0,x4
-            xa[i][j].y = (v.x >> 16) | (v.z & 0xFFFF0000u);  // x1,x5
-            xa[i][j].z = (v.y & 0xFFFFu) | (v.w << 16);      // x2,x6
-            xa[i][j].w = (v.y >> 16) | (v.w & 0xFFFF0000u);  // x3,x7
-        }
-        part += __shfl_xor(part, 16, kWave);
-        part += __shfl_xor(part, 32, kWave);  // every lane with the same li now holds sum_k x[li][step]
-        if (kb == 0) xs_w[i * 16 + li] = part;
-    }
-    __syncthreads();  // makes the table visible to the wave's other lanes (and ends the last pass's reads)
-    __builtin_amdgcn_sched_barrier(0);
-
-    uint32_t magic = 0x43004300u;    // bf16 pair (128, 128); in a vector register so that the
-    asm volatile("" : "+v"(magic));  // AND-OR needs only one scalar operand
-
-    // The arithmetic of one tile (slot p of the ring); its 16 x 16 partial result goes to LDS.
-    auto consume = [&](int p, int slot) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        int xo = 4 * kb;  // opaque, so that the table reads below stay in the loop instead of
-        asm volatile("" : "+v"(xo));  // being hoisted into (and spilled from) registers
-#pragma unroll
-        for (int i = 0; i < SPW; ++i) {
-            const uint32_t w[4] = {q[p][i].x, q[p][i].y, q[p][i].z, q[p][i].w};
-            f32x4_t d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint4 b = make_uint4((w[j] & 0x000F000Fu) | magic, ((w[j] >> 4) & 0x000F000Fu) | magic,
-                                           ((w[j] >> 8) & 0x000F000Fu) | magic, ((w[j] >> 12) & 0x000F000Fu) | magic);
-                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xa[i][j]),
-                                                            __builtin_bit_cast(bf16x8_t, b), d, 0, 0, 0);
-            }
-            const float s = (float)sh[p][i];
-            const float zc = (float)(128u + ((zw[p][i] >> (4 * (grp[i] & 7))) & 0xFu));
-            const float4 xs = *reinterpret_cast<const float4*>(xs_w + i * 16 + xo);
-            acc[0] = fmaf(s, fmaf(-zc, xs.x, d[0]), acc[0]);
-            acc[1] = fmaf(s, fmaf(-zc, xs.y, d[1]), acc[1]);
-            acc[2] = fmaf(s, fmaf(-zc, xs.z, d[2]), acc[2]);
-            acc[3] = fmaf(s, fmaf(-zc, xs.w, d[3]), acc[3]);
-        }
-        float* dst = partial + (slot * kSmWaves + wave) * 256 + lane;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) dst[r * kWave] = acc[r];
-    };
-
-    // Sums the 16 partial results of the first `nslots` tiles of a round into the block's
-    // result buffer (same (register, lane) layout as the partials).
-    auto reduce_round = [&](int first_local_tile, int nslots) {
-        __syncthreads();
-        const int slot = threadIdx.x >> 8, o = threadIdx.x & 255;
-        if (slot < nslots) {
-            float sum = 0.f;
-#pragma unroll
-            for (int wv = 0; wv < kSmWaves; ++wv) sum += partial[(slot * kSmWaves + wv) * 256 + o];
-            float* dst = result + (first_local_tile + slot) * 256 + o;
-            *dst = first_pass ? sum : *dst + sum;
-        }
-        __syncthreads();
-    };
-
-    int t = 0;
-    for (; t + PT < nt; t += PT) {
-#pragma unroll
-        for (int p = 0; p < PT; ++p) {
-            consume(p, p % kRound);
-#pragma unroll
-            for (int i = 0; i < SPW; ++i) {
-                issue(p, i, min(tile0 + t + p + PT, tlast));
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            if (p % kRound == kRound - 1 || p == PT - 1) reduce_round(t + p - (p % kRound), (p % kRound) + 1);
-        }
-    }
-    // drain: the last (up to PT) tiles, no further loads
-#pragma unroll
-    for (int p = 0; p < PT; ++p) {
-        if (t + p < nt) {
-            consume(p, p % kRound);
-            const bool last = (t + p == nt - 1);
-            if (p % kRound == kRound - 1 || p == PT - 1 || last) reduce_round(t + p - (p % kRound), (p % kRound) + 1);
-        }
-    }
-  }  // pass
-
-}
+// LDS: [kXBytes] activations, [max steps per pass][16] fp32 step sums, [16 waves][256] fp32 partials.
+constexpr int kMaxPassSteps = kXBytes / (16 * 3 * 16) + 6;  // M >= 2 (3 rows per block): steps per pass, rounded up
+constexpr size_t kSmLdsBytes = (size_t)kXBytes + (size_t)kMaxPassSteps * 16 * 4 + (size_t)kSmWaves * 256 * 4;
 
 __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs args) {
-    extern __shared__ __attribute__((aligned(16))) float sm_lds[];
-    float* partial = sm_lds;
-    float* result = sm_lds + kPartialFloats;
-    float* xs_tab = result + kSmMaxTiles * 256;
+    extern __shared__ __attribute__((aligned(16))) unsigned char sm_lds[];
+    unsigned char* xl = sm_lds;
+    float* xs_tab = reinterpret_cast<float*>(sm_lds + kXBytes);
+    float* partial = xs_tab + kMaxPassSteps * 16;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
+    const int li = lane & 15, kb = lane >> 4;
+    const int M = args.M;
 
     int idx = 0;
     while (idx + 1 < args.count && args.it[idx + 1].block_begin <= (int)blockIdx.x) ++idx;
     idx = __builtin_amdgcn_readfirstlane(idx);
     const SmItem& it = args.it[idx];
-    const int ntiles = (it.N + 15) / 16;
+    const int K = it.K, N = it.N, g = it.g;
+    const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
+    const int ntiles = (N + 15) / 16;
     const int b = (int)blockIdx.x - it.block_begin;
     const int tile0 = (int)(((long long)ntiles * b) / it.blocks);
     const int tile1 = (int)(((long long)ntiles * (b + 1)) / it.blocks);
-    const int nt = tile1 - tile0;
-    if (nt <= 0) return;  // block-uniform
+    const int nt = tile1 - tile0;   // at most kTilesPerBlock (the launcher sees to it)
+    if (nt <= 0) return;            // block-uniform
 
-    // K is walked in passes of at most 16 waves x 3 steps, so that a wave's x operands fit in
-    // registers; a pass adds its sums to the results of the passes before it.
-    const int S = it.K / kStepK;
-    const int npass = (S + kSmWaves * kSmMaxSteps - 1) / (kSmWaves * kSmMaxSteps);
-    const int spw = ((S + npass - 1) / npass + kSmWaves - 1) / kSmWaves;  // the same in every pass
-    switch (spw) {
-        case 1: smallm_tiles<1, 6>(it, args.M, tile0, nt, wave, lane, npass, partial, result, xs_tab); break;
-        case 2: smallm_tiles<2, 3>(it, args.M, tile0, nt, wave, lane, npass, partial, result, xs_tab); break;
-        default: smallm_tiles<3, 2>(it, args.M, tile0, nt, wave, lane, npass, partial, result, xs_tab); break;
+    // (tile, K part) of this wave: as many K parts as keep the 16 waves busy
+    int ksplit = 1;
+    while (nt * ksplit * 2 <= kSmWaves) ksplit *= 2;
+    const int slot = wave / ksplit, kpart = wave % ksplit;
+    const bool active = slot < nt;
+    const int S = K / kStepK;
+    const int my0 = (int)(((long long)S * kpart) / ksplit), my1 = (int)(((long long)S * (kpart + 1)) / ksplit);
+    const int row = min((tile0 + min(slot, nt - 1)) * 16 + li, N - 1);
+
+    // LDS layout of x: block (step, j, kb) holds, for each row m, the 16 bytes that lane (m, kb)
+    // feeds to MFMA j of that step: x[m][128 step + 32 kb + 8 j + (0..7)] in the pair order
+    // x0,x4 | x1,x5 | x2,x6 | x3,x7 that the nibble expansion produces.  Rows beyond M read a
+    // row of zeros appended to every block (M = 16 needs none).
+    const int Mp = M == 16 ? 16 : M + 1;
+    const int step_bytes = 16 * Mp * 16;                       // 16 (j, kb) blocks per step
+    const int pass_steps = min(S, kXBytes / step_bytes);
+    const int npass = (S + pass_steps - 1) / pass_steps;
+    const int xrow = min(li, Mp - 1) * 16;                     // this lane's row inside a block
+
+    uint32_t magic = 0x43004300u;    // bf16 pair (128, 128); in a vector register so that the
+    asm volatile("" : "+v"(magic));  // AND-OR needs only one scalar operand
+
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+
+    // register ring of wave-wide weight loads
+    uint4 q[kRing];
+    _Float16 sh[kRing];  // kept in its loaded type: a widening at the load would wait there
+    uint32_t zw[kRing];
+    // addresses as a uniform base plus a 32-bit byte offset (the launcher checks that the tensors
+    // are below 4 GB); the group of a step is a shift when a group is a power-of-two number of steps
+    const char* qbase = reinterpret_cast<const char*>(it.qw);
+    const char* sbase = reinterpret_cast<const char*>(it.sc);
+    const char* zbase = reinterpret_cast<const char*>(it.zr);
+    const uint32_t qoff = (uint32_t)row * (uint32_t)kw * 4u + 16u * kb;
+    const uint32_t soff = (uint32_t)row * (uint32_t)G * 2u;
+    const uint32_t zoff = (uint32_t)row * (uint32_t)zwords * 4u;
+    const int spg = g / kStepK;                                   // steps per group
+    const int gshift = __builtin_ctz(spg);                         // spg is a power of two (host check)
+    auto group_of = [&](int step) { return step >> gshift; };
+    auto issue = [&](int p, int step) {
+        const uint32_t grp = (uint32_t)group_of(step);
+        q[p] = *reinterpret_cast<const uint4*>(qbase + (qoff + (uint32_t)step * (kStepK / 2)));
+        sh[p] = *reinterpret_cast<const _Float16*>(sbase + (soff + grp * 2u));
+        zw[p] = *reinterpret_cast<const uint32_t*>(zbase + (zoff + (grp >> 3) * 4u));
+    };
+    auto prologue = [&](int k0, int k1) {
+#pragma unroll
+        for (int p = 0; p < kRing; ++p) {
+            issue(p, min(k0 + p, k1 - 1));  // slots past the end re-read the last step and are not consumed
+            __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
+        }
+    };
+    // the first pass's weights are requested before the activations are staged: they do not
+    // depend on x, and the staging then hides their latency
+    {
+        const int k0 = max(my0, 0), k1 = min(my1, min(S, pass_steps));
+        if (active && k1 > k0) prologue(k0, k1);
     }
 
-    // write the block's results: result[tile][r][l] holds y[m = 4*(l/16) + r][(tile0 + tile)*16 + l%16]
-    const int M = args.M, N = it.N;
-    for (int idx = threadIdx.x; idx < nt * 256; idx += kSmThreads) {
-        const int tile = idx >> 8, rem = idx & 255;
-        const int m = rem >> 4, n = rem & 15;           // consecutive threads -> consecutive n
-        const int row = (tile0 + tile) * 16 + n;
-        if (m < M && row < N)
-            it.y[(size_t)m * N + row] = f32_to_bf16_rne(result[tile * 256 + (m & 3) * 64 + (m >> 2) * 16 + n]);
+    for (int pass = 0; pass < npass; ++pass) {
+        const int p0 = pass * pass_steps, p1 = min(S, p0 + pass_steps);
+        if (pass) __syncthreads();  // the previous pass's activations are no longer read
+        // ---- stage x[:, 128 p0 .. 128 p1) and the zero rows
+        {
+            const int chunks = (p1 - p0) * 16;  // 16-byte pieces per row
+            for (int e = threadIdx.x; e < chunks * M; e += kSmThreads) {
+                const int m = e / chunks, c = e - m * chunks;
+                const uint4 v = *reinterpret_cast<const uint4*>(it.x + (size_t)m * K + (size_t)p0 * kStepK + c * 8);
+                uint4 o;
+                o.x = (v.x & 0xFFFFu) | (v.z << 16);      // x0,x4
+                o.y = (v.x >> 16) | (v.z & 0xFFFF0000u);  // x1,x5
+                o.z = (v.y & 0xFFFFu) | (v.w << 16);      // x2,x6
+                o.w = (v.y >> 16) | (v.w & 0xFFFF0000u);  // x3,x7
+                const int s = c >> 4, kbb = (c >> 2) & 3, j = c & 3;
+                *reinterpret_cast<uint4*>(xl + s * step_bytes + (j * 4 + kbb) * (Mp * 16) + m * 16) = o;
+            }
+            if (Mp != M)
+                for (int e = threadIdx.x; e < (p1 - p0) * 16; e += kSmThreads)
+                    *reinterpret_cast<uint4*>(xl + (e >> 4) * step_bytes + (e & 15) * (Mp * 16) + M * 16) = make_uint4(0, 0, 0, 0);
+        }
+        __syncthreads();
+        // ---- sums of x over each step, per row, in a fixed order
+        for (int e = threadIdx.x; e < (p1 - p0) * 16; e += kSmThreads) {
+            const int s = e >> 4, m = e & 15;
+            float t = 0.f;
+            if (m < M) {
+#pragma unroll
+                for (int blk = 0; blk < 16; ++blk) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(xl + s * step_bytes + blk * (Mp * 16) + m * 16);
+                    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        t += __builtin_bit_cast(float, u[q] << 16) + __builtin_bit_cast(float, u[q] & 0xFFFF0000u);
+                }
+            }
+            xs_tab[e] = t;
+        }
+        __syncthreads();
+
+        // ---- this wave's steps inside the pass
+        const int k0 = max(my0, p0), k1 = min(my1, p1);
+        const int n = active ? max(0, k1 - k0) : 0;
+        if (n > 0) {
+            auto consume = [&](int p, int step) {
+                const unsigned char* xb = xl + (step - p0) * step_bytes + kb * (Mp * 16) + xrow;
+                const uint32_t w[4] = {q[p].x, q[p].y, q[p].z, q[p].w};
+                f32x4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint4 a = *reinterpret_cast<const uint4*>(xb + j * 4 * (Mp * 16));
+                    const uint4 bq = make_uint4((w[j] & 0x000F000Fu) | magic, ((w[j] >> 4) & 0x000F000Fu) | magic,
+                                                ((w[j] >> 8) & 0x000F000Fu) | magic, ((w[j] >> 12) & 0x000F000Fu) | magic);
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                __builtin_bit_cast(bf16x8_t, bq), d, 0, 0, 0);
+                }
+                const int grp = group_of(step);
+                const float s = (float)sh[p];
+                const float zc = (float)(128u + ((zw[p] >> (4 * (grp & 7))) & 0xFu));
+                const float4 xs = *reinterpret_cast<const float4*>(xs_tab + (step - p0) * 16 + 4 * kb);
+                acc[0] = fmaf(s, fmaf(-zc, xs.x, d[0]), acc[0]);
+                acc[1] = fmaf(s, fmaf(-zc, xs.y, d[1]), acc[1]);
+                acc[2] = fmaf(s, fmaf(-zc, xs.z, d[2]), acc[2]);
+                acc[3] = fmaf(s, fmaf(-zc, xs.w, d[3]), acc[3]);
+            };
+            const int last = k1 - 1;
+            if (pass) prologue(k0, k1);
+            int t = 0;
+            // Refills go out four at a time: the four loads of a row then cover 256 contiguous
+            // bytes and reach DRAM together, instead of 64 isolated bytes from each of 16 rows.
+            for (; t + kRing < n; t += kRing) {
+#pragma unroll
+                for (int h = 0; h < kRing; h += 4) {
+#pragma unroll
+                    for (int p = h; p < h + 4; ++p) consume(p, k0 + t + p);
+#pragma unroll
+                    for (int p = h; p < h + 4; ++p) {
+                        issue(p, min(k0 + t + p + kRing, last));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < kRing; ++p)
+                if (t + p < n) consume(p, k0 + t + p);
+        }
+    }
+
+    // ---- the K parts of a tile meet in LDS; y[m][tile*16 + n] = sum over parts, parts in order
+    float* dst = partial + wave * 256 + lane;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) dst[r * kWave] = acc[r];
+    __syncthreads();
+    for (int e = threadIdx.x; e < nt * 256; e += kSmThreads) {
+        const int tl = e >> 8, rem = e & 255;
+        const int m = rem >> 4, nn = rem & 15;   // consecutive threads -> consecutive n
+        // register r of lane l holds row m = 4 (l / 16) + r, column n = l % 16
+        const int o = (m & 3) * kWave + (m >> 2) * 16 + nn;
+        float sum = 0.f;
+        for (int kp = 0; kp < ksplit; ++kp) sum += partial[(tl * ksplit + kp) * 256 + o];
+        const int rown = (tile0 + tl) * 16 + nn;
+        if (m < M && rown < N) it.y[(size_t)m * N + rown] = f32_to_bf16_rne(sum);
     }
 }
 
@@ -282,7 +278,7 @@ hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipSt
     int used = 0;
     for (int i = 0; i < count; ++i) {
         const int ntiles = (items[i].d.N + 15) / 16;
-        lo[i] = (ntiles + kSmMaxTiles - 1) / kSmMaxTiles;  // the LDS result buffer bounds a block's tiles
+        lo[i] = (ntiles + kTilesPerBlock - 1) / kTilesPerBlock;  // a block owns at most 16 tiles
         hi[i] = ntiles;
         const double share = (double)sm_item_bytes(items[i].d) / total * grid;
         nb[i] = (int)share;
@@ -320,8 +316,9 @@ hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipSt
 }  // namespace
 
 bool smallm_supports(const qail_wdesc& d, int M) {
-    return M >= 2 && M <= 16 && d.K % kStepK == 0 && d.group_size % kStepK == 0 &&
-           d.K <= kSmMaxPasses * kSmWaves * kSmMaxSteps * kStepK;
+    const int spg = d.group_size / kStepK;
+    return M >= 2 && M <= 16 && d.K % kStepK == 0 && d.group_size % kStepK == 0 && (spg & (spg - 1)) == 0 &&
+           (unsigned long long)d.N * d.K / 2 <= 0xFFFFFFFFull;   // 32-bit byte offsets in the kernel
 }
 
 hipError_t launch_w4a16_smallm(const qail_w4a16_item* items, int count, int M, hipStream_t st) {
