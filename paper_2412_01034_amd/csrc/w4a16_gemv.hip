@@ -23,6 +23,8 @@
 // One launch serves a list of independent linears: the blocks of the grid are
 // divided among the linears in proportion to their bytes, so a decoder layer's
 // four GEMVs ramp up once and finish together.
+#include <string.h>
+
 #include "qail_internal.h"
 
 namespace qail {
@@ -36,7 +38,9 @@ constexpr int kChunkK = 32;                       // k per lane per load (16 byt
 constexpr int kWaveK = kWave * kChunkK;           // 2048 k per wave-wide load
 constexpr int kGemvMaxChunks = 6;                 // K <= 12288 (more chunks would spill registers)
 constexpr int kGemvMaxK = kGemvMaxChunks * kWaveK;
+constexpr int kGemvMaxBlocks = 4096;              // blocks of a launch that serves more than one item
 
+// 64 bytes, so that a block fetches everything it needs to know with one scalar load.
 struct GemvItem {
     const uint32_t* qw;
     const uint16_t* sc;
@@ -45,12 +49,13 @@ struct GemvItem {
     uint16_t* y;
     int N, K, g;
     int block_begin;  // first block of the grid that works on this item
-    int blocks;       // number of blocks that share its rows
+    int rows_base;    // block b of the item owns rows_base rows, one more if b < rows_rem,
+    int rows_rem;     // in the order of the blocks
 };
 
 struct GemvArgs {
     GemvItem it[kGemvMaxItems];
-    int count;
+    uint32_t item_of_block[kGemvMaxBlocks / 8];  // 4 bits per block; blocks past the table work on item 0
 };
 
 // Low-rank adapter of an item (Sec. 5.1: rank-32 adapters beside the 4-bit backbone):
@@ -93,10 +98,10 @@ __device__ __forceinline__ float wave_sum(float v) {
             __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 48)));
 }
 
-// LDS map of a block (uint4 units unless noted), nch = ceil(K / 2048):
+// LDS map of a block (uint4 units), nch = ceil(K / 2048):
 //   [0, nch*256)       staged activations: word j of lane L in chunk c at (c*4 + j)*64 + L
-//   then nch*64 float  the power of two 2^e of lane L's chunk c, at c*64 + L
-//   then nch*64 float4 (nch > 4 only) per-chunk constants of lane L, see stream_rows
+//   then nch*64 float4 per-chunk constants of lane L's chunk c at c*64 + L:
+//                      (1024 * sum of the staged values, sum of x * 2^-e, 2^e, unused)
 // Lane L of a wave owns, in chunk c, the 32 k starting at c*2048 + 32*L.  Its staged word j
 // holds those k's 8j..8j+7 as fp16 in the order x0,x4 | x1/16,x5/16 | x2,x6 | x3/16,x7/16
 // (all times 2^-e), matching the four registers the weight nibbles are expanded into.
@@ -114,7 +119,7 @@ template <int kMaxRuns>
 __device__ __forceinline__ void stage_x(const GemvItem& it, int nch, uint4* __restrict__ lds,
                                         const uint4 (&xr)[kMaxRuns]) {
     const int K = it.K;
-    float* post = reinterpret_cast<float*>(lds + nch * 4 * kWave);
+    float4* consts = reinterpret_cast<float4*>(lds + nch * 4 * kWave);
     const int runs = nch * (kWaveK / 8);
 #pragma unroll
     for (int u = 0; u < kMaxRuns; ++u) {
@@ -136,22 +141,31 @@ __device__ __forceinline__ void stage_x(const GemvItem& it, int nch, uint4* __re
         int down = (amax > 0.f) ? (ex - 141) : 0;                                 // 141 = 127 + 14
         down = max(-126, min(113, down));  // keeps both exponent fields valid
         const float pre = __builtin_bit_cast(float, (uint32_t)(127 - down) << 23);
+        // the staged values as the matrix cores will see them (rounded to fp16), and their sums
+        // over the chunk: even positions as they are, odd positions carry the factor 1/16
+        const float pre16 = pre * 0.0625f;
+        const bool live = i < K / 8;
+        _Float16 h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = live ? (_Float16)(f[e] * ((e & 1) ? pre16 : pre)) : (_Float16)0.f;
+        float se = ((float)h[0] + (float)h[4]) + ((float)h[2] + (float)h[6]);
+        float so = ((float)h[1] + (float)h[5]) + ((float)h[3] + (float)h[7]);
+        se = dpp_add<0xB1>(se);
+        se = dpp_add<0x4E>(se);
+        so = dpp_add<0xB1>(so);
+        so = dpp_add<0x4E>(so);
         if (i < runs) {
-            auto pk = [](float lo, float hi) {
+            auto pk = [](_Float16 lo, _Float16 hi) {
                 typedef __attribute__((ext_vector_type(2))) _Float16 h2;
-                const h2 v = {(_Float16)lo, (_Float16)hi};
+                const h2 v = {lo, hi};
                 return __builtin_bit_cast(uint32_t, v);
             };
-            const float pre16 = pre * 0.0625f;
-            uint4 o;
-            o.x = pk(f[0] * pre, f[4] * pre);
-            o.y = pk(f[1] * pre16, f[5] * pre16);
-            o.z = pk(f[2] * pre, f[6] * pre);
-            o.w = pk(f[3] * pre16, f[7] * pre16);
-            if (i >= K / 8) o = make_uint4(0, 0, 0, 0);
+            const uint4 o = make_uint4(pk(h[0], h[4]), pk(h[1], h[5]), pk(h[2], h[6]), pk(h[3], h[7]));
             const int c = i / (kWaveK / 8), r = i % (kWaveK / 8);
             lds[(c * 4 + (r & 3)) * kWave + (r >> 2)] = o;
-            if ((r & 3) == 0) post[c * kWave + (r >> 2)] = __builtin_bit_cast(float, (uint32_t)(127 + down) << 23);
+            if ((r & 3) == 0)
+                consts[c * kWave + (r >> 2)] = make_float4(1024.f * (se + so), se + 16.f * so,
+                                                           __builtin_bit_cast(float, (uint32_t)(127 + down) << 23), 0.f);
         }
     }
     __syncthreads();
@@ -227,34 +241,20 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
 
     stage_x<kMaxRuns>(it, NCH, xlds, xr);
 
-    // Per chunk, from the lane's own staged activations:
+    // Per chunk, for the lane's own 32 k (written by the staging):
     //   xoff = 1024 * (sum of the staged values): what the fp16 offsets add to the MFMA result
     //   xsum = sum of x * 2^-e
     //   post = 2^e
-    // kept in registers for short rows; for long ones parked in an LDS table behind the 2^e
-    // table (every wave writes the same values to the same slots, and reads only its own
-    // lanes' slots after its own writes, so no barrier is needed)
+    // kept in registers for short rows, re-read from LDS per row for long ones
     constexpr bool kParked = NCH > 4;
-    float* postl = reinterpret_cast<float*>(xlds + NCH * 4 * kWave);
-    float4* parked = reinterpret_cast<float4*>(postl + NCH * kWave);
+    const float4* parked = reinterpret_cast<const float4*>(xlds + NCH * 4 * kWave);
     float xoff[NCH], xsum[NCH], post[NCH];
+    if (!kParked) {
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) post[c] = postl[c * kWave + lane];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        typedef __attribute__((ext_vector_type(2))) _Float16 h2;
-        float se = 0.f, so = 0.f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint4 v = xlds[(c * 4 + j) * kWave + lane];
-            const h2 a = __builtin_bit_cast(h2, v.x), b = __builtin_bit_cast(h2, v.y);
-            const h2 c2 = __builtin_bit_cast(h2, v.z), d = __builtin_bit_cast(h2, v.w);
-            se += ((float)a[0] + (float)a[1]) + ((float)c2[0] + (float)c2[1]);
-            so += ((float)b[0] + (float)b[1]) + ((float)d[0] + (float)d[1]);
+        for (int c = 0; c < NCH; ++c) {
+            const float4 t = parked[c * kWave + lane];
+            xoff[c] = t.x; xsum[c] = t.y; post[c] = t.z;
         }
-        xoff[c] = 1024.f * (se + so);
-        xsum[c] = se + 16.f * so;
-        if (kParked) parked[c * kWave + lane] = make_float4(xoff[c], xsum[c], post[c], 0.f);
     }
     if (nrows <= 0) return;
     uint32_t magic = 0x64006400u;   // fp16 pair (1024, 1024); held in a vector register so that
@@ -267,8 +267,10 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
 
     const bool odd = lane & 1, hi = lane & 2;
 
-    // The arithmetic of the wave's i-th row, whose codes sit in slot p.
-    auto consume = [&](int p, int i) {
+    // The arithmetic of the wave's i-th row, whose codes sit in slot p.  With `next` >= 0 every
+    // chunk's registers are refilled with the same chunk of row `next` as soon as they have
+    // been used, so the number of loads in flight stays level instead of dipping once per row.
+    auto consume = [&](int p, int i, int next) {
         float acc = 0.f;
         // x is the same for every row, but holding all of it in registers costs 16 per
         // chunk.  It is re-read from LDS per row, one chunk ahead of the arithmetic; the
@@ -310,16 +312,22 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
             const float e0 = odd ? d0[1] : d0[0], e1 = odd ? d0[3] : d0[2];
             const float f0 = odd ? d1[1] : d1[0], f1 = odd ? d1[3] : d1[2];
             const float dsel = (hi ? e1 : e0) + (hi ? f1 : f0);
-            float cxoff = xoff[c], cxsum = xsum[c], cpost = post[c];
+            float cxoff, cxsum, cpost;
             if (kParked) {
                 const float4 t = parked[c * kWave + xo];
                 cxoff = t.x; cxsum = t.y; cpost = t.z;
+            } else {
+                cxoff = xoff[c]; cxsum = xsum[c]; cpost = post[c];
             }
             const float s = (float)sh[p][c] * cpost;
             const float z = (float)((zw[p][c] >> (4 * (goff[c] & 7))) & 0xFu);
             // sum_k x_k (q_k - z) = (D - xoff) - z * xsum
             acc = fmaf(s, dsel - fmaf(z, cxsum, cxoff), acc);
             asm volatile("" : "+v"(acc), "+v"(xo));
+            if (next >= 0) {
+                issue(p, c, next);
+                __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
+            }
         }
         const float v = wave_sum(acc);
         ykeep = (lane == i) ? v : ykeep;
@@ -330,18 +338,12 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
     int r = 0;
     for (; r + kPR < nrows; r += kPR) {
 #pragma unroll
-        for (int p = 0; p < kPR; ++p) {
-            consume(p, r + p);
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                issue(p, c, min(rbase + min(r + p + kPR, ilast) * kGemvWaves, it.N - 1));
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
+        for (int p = 0; p < kPR; ++p)
+            consume(p, r + p, min(rbase + min(r + p + kPR, ilast) * kGemvWaves, it.N - 1));
     }
 #pragma unroll
     for (int p = 0; p < kPR; ++p)
-        if (r + p < nrows) consume(p, r + p);
+        if (r + p < nrows) consume(p, r + p, -1);
     if (lane < nrows) {
         const int row = rbase + lane * kGemvWaves;
         float v = ykeep;
@@ -379,23 +381,25 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& args, const GemvLoraAr
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform: row
     const int lane = threadIdx.x % kWave;                                  // addresses stay scalar
 
+    // two dependent scalar loads and no division between the start of the block and its first
+    // weight load: the block's item from a 4-bit table, then the item's 64-byte record
     int idx = 0;
-    while (idx + 1 < args.count && args.it[idx + 1].block_begin <= (int)blockIdx.x) ++idx;
+    if (blockIdx.x < (unsigned)kGemvMaxBlocks) idx = (args.item_of_block[blockIdx.x / 8] >> (4 * (blockIdx.x % 8))) & 15;
     idx = __builtin_amdgcn_readfirstlane(idx);
-    const GemvItem& it = args.it[idx];
+    const GemvItem it = args.it[idx];
     const GemvLora* lo = kLora ? &lora.l[idx] : nullptr;
     const int K = it.K, N = it.N;
     const int nch = (K + kWaveK - 1) / kWaveK;
     // the adapter's down-projection t (at most 64 floats) sits behind the staged activations; the
     // barrier inside the staging makes it visible
-    float4* lora_t = reinterpret_cast<float4*>(lds + nch * kWave * 4 + nch * kWave / 4 + (nch > 4 ? nch * kWave : 0));
+    float4* lora_t = reinterpret_cast<float4*>(lds + nch * kWave * 5);
     if (kLora && (int)threadIdx.x < 64)
         reinterpret_cast<float*>(lora_t)[threadIdx.x] = (int)threadIdx.x < lo->r ? lo->t[threadIdx.x] : 0.f;
 
     // this block's slab of rows, then this wave's share of the slab
     const int b = (int)blockIdx.x - it.block_begin;
-    const int s0 = (int)(((long long)N * b) / it.blocks);
-    const int s1 = (int)(((long long)N * (b + 1)) / it.blocks);
+    const int s0 = b * it.rows_base + min(b, it.rows_rem);
+    const int s1 = s0 + it.rows_base + (b < it.rows_rem ? 1 : 0);
     // Rows are dealt to the waves of the block in turn, so that at any moment the block's
     // 16 waves read 16 adjacent rows: one contiguous stretch of memory per block.
     const int r0 = s0 + wave;
@@ -442,6 +446,7 @@ size_t item_bytes(const qail_wdesc& d) {
 
 hipError_t launch_chunk(const qail_w4a16_item* items, const GemvLora* loras, int count, hipStream_t st) {
     GemvArgs a;
+    memset(a.item_of_block, 0, sizeof(a.item_of_block));
     int grid = device_cus();
     if (grid < count) grid = count;
     // blocks per item in proportion to its bytes (largest remainder), at least one each
@@ -474,6 +479,14 @@ hipError_t launch_chunk(const qail_w4a16_item* items, const GemvLora* loras, int
         frac[best] = -1.0;
         ++used;
     }
+    if (count > 1 && used > kGemvMaxBlocks) {
+        // the block-to-item table is too short: one launch per item (a lone item needs no table)
+        for (int i = 0; i < count; ++i) {
+            const hipError_t e = launch_chunk(items + i, loras ? loras + i : nullptr, 1, st);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
     int maxK = 0, bb = 0;
     for (int i = 0; i < count; ++i) {
         const qail_w4a16_item& s = items[i];
@@ -481,14 +494,15 @@ hipError_t launch_chunk(const qail_w4a16_item* items, const GemvLora* loras, int
         t.qw = s.qweight; t.sc = s.scales; t.zr = s.zeros; t.x = s.x; t.y = s.y;
         t.N = s.d.N; t.K = s.d.K; t.g = s.d.group_size;
         t.block_begin = bb;
-        t.blocks = nb[i];
+        t.rows_base = s.d.N / nb[i];
+        t.rows_rem = s.d.N % nb[i];
+        for (int b = bb; b < bb + nb[i] && b < kGemvMaxBlocks; ++b) a.item_of_block[b / 8] |= (uint32_t)i << (4 * (b % 8));
         bb += nb[i];
         if (s.d.K > maxK) maxK = s.d.K;
     }
     for (int i = count; i < kGemvMaxItems; ++i) a.it[i] = a.it[count - 1];
-    a.count = count;
     const int nch = (maxK + kWaveK - 1) / kWaveK;
-    const size_t lds = (size_t)nch * kWave * (4 * 16 + 4 + (nch > 4 ? 16 : 0));
+    const size_t lds = (size_t)nch * kWave * (4 * 16 + 16);
     if (loras) {
         GemvLoraArgs la;
         for (int i = 0; i < kGemvMaxItems; ++i) la.l[i] = loras[i < count ? i : count - 1];
