@@ -72,6 +72,7 @@ struct GemvLoraArgs {
 };
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 template <int kCtrl>
 __device__ __forceinline__ float dpp_add(float v) {
@@ -214,17 +215,29 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
     const int last_w = tail_out ? 0 : (NCH - 1) * (kWaveK / 8) + lane_w;
 
     uint4 q[kPR][NCH];
-    _Float16 sh[kPR][NCH];  // kept in its loaded type: a widening at the load would force a wait there
+    uint16_t sh[kPR][NCH];  // fp16 bits, kept as loaded: a widening at the load would force a wait there
     uint32_t zw[kPR][NCH];
 
+    // Loads go through buffer descriptors (one per tensor, in scalar registers): the address
+    // is descriptor base + scalar row offset + a 32-bit lane offset that never changes, so a
+    // load costs one scalar multiply and no vector arithmetic.  The host checks that each
+    // tensor is shorter than 4 GB.
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.qw), 0, it.N * kw * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(it.sc), 0, it.N * G * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.zr), 0, it.N * zwords * 4, 0x00020000);
+    const int lane_b = lane_w * 4, last_b = last_w * 4;  // byte offsets of the lane's codes in a row
+    int soff[NCH], zoff[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        soff[c] = goff[c] * 2;
+        zoff[c] = (goff[c] >> 3) * 4;
+    }
     auto issue = [&](int p, int c, int row) {
-        const uint32_t* qrow = it.qw + (size_t)row * kw;
-        const _Float16* srow = reinterpret_cast<const _Float16*>(it.sc) + (size_t)row * G;
-        const uint32_t* zrow = it.zr + (size_t)row * zwords;
-        const int wo = (c == NCH - 1) ? last_w : c * (kWaveK / 8) + lane_w;
-        q[p][c] = *reinterpret_cast<const uint4*>(qrow + wo);
-        sh[p][c] = srow[goff[c]];
-        zw[p][c] = zrow[goff[c] >> 3];
+        const int qb = (c == NCH - 1) ? last_b : c * (kWaveK / 2) + lane_b;
+        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rq, qb, row * (kw * 4), 0);
+        q[p][c] = make_uint4(v[0], v[1], v[2], v[3]);
+        sh[p][c] = __builtin_amdgcn_raw_buffer_load_b16(rs, soff[c], row * (G * 2), 0);
+        zw[p][c] = __builtin_amdgcn_raw_buffer_load_b32(rz, zoff[c], row * (zwords * 4), 0);
     };
 
     // Every load below is issued unconditionally (rows past the end are clamped to the last
@@ -295,7 +308,7 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
                 for (int j = 0; j < 4; ++j) xv[0][j] = xlds[(c * 4 + j) * kWave + xo];
             }
             const uint32_t w[4] = {q[p][c].x, q[p][c].y, q[p][c].z, q[p][c].w};
-            f32x4_t d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+            f32x4_t d0 = {0.f, 0.f, 0.f, 0.f};  // one chain: the expansion between two MFMAs covers their latency
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 // codes 0,4 | 16*codes 1,5 | codes 2,6 | 16*codes 3,7, each plus 1024, as fp16
@@ -305,13 +318,12 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
                 const uint4 xj = xv[c & (kXB - 1)][j];
                 d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a01),
                                                         __builtin_bit_cast(f16x4_t, make_uint2(xj.x, xj.y)), d0, 0, 0, 0);
-                d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a23),
-                                                        __builtin_bit_cast(f16x4_t, make_uint2(xj.z, xj.w)), d1, 0, 0, 0);
+                d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a23),
+                                                        __builtin_bit_cast(f16x4_t, make_uint2(xj.z, xj.w)), d0, 0, 0, 0);
             }
             // D[j][j] is register j = lane % 4
             const float e0 = odd ? d0[1] : d0[0], e1 = odd ? d0[3] : d0[2];
-            const float f0 = odd ? d1[1] : d1[0], f1 = odd ? d1[3] : d1[2];
-            const float dsel = (hi ? e1 : e0) + (hi ? f1 : f0);
+            const float dsel = hi ? e1 : e0;
             float cxoff, cxsum, cpost;
             if (kParked) {
                 const float4 t = parked[c * kWave + xo];
@@ -319,7 +331,7 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
             } else {
                 cxoff = xoff[c]; cxsum = xsum[c]; cpost = post[c];
             }
-            const float s = (float)sh[p][c] * cpost;
+            const float s = (float)__builtin_bit_cast(_Float16, sh[p][c]) * cpost;
             const float z = (float)((zw[p][c] >> (4 * (goff[c] & 7))) & 0xFu);
             // sum_k x_k (q_k - z) = (D - xoff) - z * xsum
             acc = fmaf(s, dsel - fmaf(z, cxsum, cxoff), acc);
@@ -516,7 +528,9 @@ hipError_t launch_chunk(const qail_w4a16_item* items, const GemvLora* loras, int
 }  // namespace
 
 bool gemv_supports(const qail_wdesc& d) {
-    return d.K % kChunkK == 0 && d.group_size % kChunkK == 0 && d.K <= kGemvMaxK;
+    // the kernel addresses each tensor through a 32-bit byte offset (codes are the largest)
+    return d.K % kChunkK == 0 && d.group_size % kChunkK == 0 && d.K <= kGemvMaxK &&
+           (unsigned long long)d.N * d.K / 2 < 0x80000000ull;
 }
 
 hipError_t launch_w4a16_gemv(const qail_w4a16_item* items, int count, hipStream_t st) {
