@@ -99,12 +99,17 @@ __device__ __forceinline__ float wave_sum(float v) {
             __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 48)));
 }
 
-// LDS map of a block (uint4 units), nch = ceil(K / 2048):
-//   [0, nch*256)       staged activations: word j of lane L in chunk c at (c*4 + j)*64 + L
-//   then nch*64 float4 per-chunk constants of lane L's chunk c at c*64 + L:
+// A lane owns 32 * kSub consecutive k of every wave-wide unit of a row (kSub = 2 whenever
+// the group size and K are multiples of 64, else 1): its codes are kSub 16-byte loads, and
+// everything that exists once per lane and unit (scale, zero-point, the constants below, the
+// pick of the MFMA diagonal) is shared by 64 instead of 32 codes.
+//
+// LDS map of a block (uint4 units), nu = ceil(K / (2048 * kSub)) units per row:
+//   [0, nu*kSub*256)   staged activations: word j of lane L in unit c at (c*4*kSub + j)*64 + L
+//   then nu*64 float4  per-unit constants of lane L's unit c at c*64 + L:
 //                      (1024 * sum of the staged values, sum of x * 2^-e, 2^e, unused)
-// Lane L of a wave owns, in chunk c, the 32 k starting at c*2048 + 32*L.  Its staged word j
-// holds those k's 8j..8j+7 as fp16 in the order x0,x4 | x1/16,x5/16 | x2,x6 | x3/16,x7/16
+// Lane L of a wave owns, in unit c, the 32*kSub k starting at (c*64 + L)*32*kSub.  Its staged
+// word j holds those k's 8j..8j+7 as fp16 in the order x0,x4 | x1/16,x5/16 | x2,x6 | x3/16,x7/16
 // (all times 2^-e), matching the four registers the weight nibbles are expanded into.
 // Everything past K is zero.
 
@@ -112,19 +117,20 @@ __device__ __forceinline__ float wave_sum(float v) {
 //
 // x is bf16; the matrix cores take fp16 here because fp16 has room for a 4-bit code at two
 // mantissa positions (see stream_rows).  Every bf16 significand fits fp16, the range does
-// not, so each 32-k chunk is scaled by the power of two that brings its largest magnitude
-// into [2^14, 2^15); the dot product of the chunk is multiplied back by 2^e in fp32.
-// Elements more than 2^-28 below the chunk's maximum lose bits or vanish, which is far
+// not, so each lane's stretch of a unit is scaled by the power of two that brings its largest
+// magnitude into [2^14, 2^15); its dot product is multiplied back by 2^e in fp32.
+// Elements more than 2^-28 below that maximum lose bits or vanish, which is far
 // below the fp32 accumulation noise of the products.
-template <int kMaxRuns>
-__device__ __forceinline__ void stage_x(const GemvItem& it, int nch, uint4* __restrict__ lds,
+template <int kMaxRuns, int kSub>
+__device__ __forceinline__ void stage_x(const GemvItem& it, int nu, uint4* __restrict__ lds,
                                         const uint4 (&xr)[kMaxRuns]) {
+    constexpr int kUnitRuns = kWave * 4 * kSub;  // runs of 8 k per unit
     const int K = it.K;
-    float4* consts = reinterpret_cast<float4*>(lds + nch * 4 * kWave);
-    const int runs = nch * (kWaveK / 8);
+    float4* consts = reinterpret_cast<float4*>(lds + nu * kUnitRuns);
+    const int runs = nu * kUnitRuns;
 #pragma unroll
     for (int u = 0; u < kMaxRuns; ++u) {
-        // run i = 8 consecutive k; the 4 threads of a quad hold the 4 runs of one chunk
+        // run i = 8 consecutive k; 4 * kSub neighbouring threads hold the runs of one lane's stretch
         const int i = threadIdx.x + u * kGemvThreads;
         const uint32_t w[4] = {xr[u].x, xr[u].y, xr[u].z, xr[u].w};
         float f[8];
@@ -137,13 +143,14 @@ __device__ __forceinline__ void stage_x(const GemvItem& it, int nch, uint4* __re
         }
         amax = dpp_max<0xB1>(amax);  // quad_perm [1,0,3,2]
         amax = dpp_max<0x4E>(amax);  // quad_perm [2,3,0,1]
+        if (kSub == 2) amax = dpp_max<0x141>(amax);  // row_half_mirror: the other quad of the 8
         // 2^-e with amax * 2^-e in [2^14, 2^15): exponent arithmetic on the bit pattern
         const int ex = (int)((__builtin_bit_cast(uint32_t, amax) >> 23) & 0xFF);  // biased exponent
         int down = (amax > 0.f) ? (ex - 141) : 0;                                 // 141 = 127 + 14
         down = max(-126, min(113, down));  // keeps both exponent fields valid
         const float pre = __builtin_bit_cast(float, (uint32_t)(127 - down) << 23);
         // the staged values as the matrix cores will see them (rounded to fp16), and their sums
-        // over the chunk: even positions as they are, odd positions carry the factor 1/16
+        // over the stretch: even positions as they are, odd positions carry the factor 1/16
         const float pre16 = pre * 0.0625f;
         const bool live = i < K / 8;
         _Float16 h[8];
@@ -155,6 +162,10 @@ __device__ __forceinline__ void stage_x(const GemvItem& it, int nch, uint4* __re
         se = dpp_add<0x4E>(se);
         so = dpp_add<0xB1>(so);
         so = dpp_add<0x4E>(so);
+        if (kSub == 2) {
+            se = dpp_add<0x141>(se);
+            so = dpp_add<0x141>(so);
+        }
         if (i < runs) {
             auto pk = [](_Float16 lo, _Float16 hi) {
                 typedef __attribute__((ext_vector_type(2))) _Float16 h2;
@@ -162,18 +173,19 @@ __device__ __forceinline__ void stage_x(const GemvItem& it, int nch, uint4* __re
                 return __builtin_bit_cast(uint32_t, v);
             };
             const uint4 o = make_uint4(pk(h[0], h[4]), pk(h[1], h[5]), pk(h[2], h[6]), pk(h[3], h[7]));
-            const int c = i / (kWaveK / 8), r = i % (kWaveK / 8);
-            lds[(c * 4 + (r & 3)) * kWave + (r >> 2)] = o;
-            if ((r & 3) == 0)
-                consts[c * kWave + (r >> 2)] = make_float4(1024.f * (se + so), se + 16.f * so,
-                                                           __builtin_bit_cast(float, (uint32_t)(127 + down) << 23), 0.f);
+            const int c = i / kUnitRuns, r = i % kUnitRuns;
+            const int L = r / (4 * kSub), j = r % (4 * kSub);
+            lds[(c * 4 * kSub + j) * kWave + L] = o;
+            if (j == 0)
+                consts[c * kWave + L] = make_float4(1024.f * (se + so), se + 16.f * so,
+                                                    __builtin_bit_cast(float, (uint32_t)(127 + down) << 23), 0.f);
         }
     }
     __syncthreads();
 }
 
-// Rows [r0, r1) of one item, streamed by one wave.  The wave keeps NCH * kPR wave-wide
-// loads (1 KB each) in flight: a register slot is refilled with the same chunk of a later
+// Rows [r0, r1) of one item, streamed by one wave.  The wave keeps NU * kSub * kPR wave-wide
+// loads (1 KB each) in flight: a register slot is refilled with the same unit of a later
 // row as soon as its codes have been consumed.  The first loads go out before the
 // activations are staged, so the two latencies overlap.
 //
@@ -184,7 +196,7 @@ __device__ __forceinline__ void stage_x(const GemvItem& it, int nch, uint4* __re
 // eight such instructions, chained through the accumulator, give every lane the dot
 // product of its 32 codes with the 32 activations at the same k.  The other entries of D
 // are ignored.  The vector ALU only expands nibbles: 5 operations per 8 codes.
-template <int NCH, int kPR>
+template <int NU, int kPR, int kSub>
 __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* lo, const float4* lora_t,
                                             int rbase, int nrows, int lane,
                                             uint4* __restrict__ xlds) {
@@ -193,7 +205,9 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
     const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
 
     // x first: it is needed first and loads return in order
-    constexpr int kMaxRuns = (NCH * (kWaveK / 8) + kGemvThreads - 1) / kGemvThreads;
+    constexpr int kLaneK = kChunkK * kSub;  // k per lane and unit
+    constexpr int kUnitK = kWave * kLaneK;  // k per wave-wide unit
+    constexpr int kMaxRuns = (NU * (kUnitK / 8) + kGemvThreads - 1) / kGemvThreads;
     uint4 xr[kMaxRuns];
 #pragma unroll
     for (int u = 0; u < kMaxRuns; ++u) {
@@ -202,21 +216,22 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
     }
     __builtin_amdgcn_sched_barrier(0);  // the scheduler must not move the x load behind the weights
 
-    // Per-chunk constants of this lane.  Only the last chunk of a row can run past K;
-    // there the lane reads the start of the row instead (valid data) and meets zeros in x.
-    const bool tail_out = (NCH - 1) * kWaveK + lane * kChunkK >= K;
-    int goff[NCH];
+    // Per-unit constants of this lane.  Only the last unit of a row can run past K (a lane's
+    // stretch lies entirely inside or outside: K is a multiple of its length); there the lane
+    // reads the start of the row instead (valid data) and meets zeros in x.
+    const bool tail_out = (NU - 1) * kUnitK + lane * kLaneK >= K;
+    int goff[NU];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int kc = c * kWaveK + lane * kChunkK;
-        goff[c] = ((c == NCH - 1 && tail_out) ? 0 : kc) / g;
+    for (int c = 0; c < NU; ++c) {
+        const int kc = c * kUnitK + lane * kLaneK;
+        goff[c] = ((c == NU - 1 && tail_out) ? 0 : kc) / g;
     }
-    const int lane_w = lane * (kChunkK / 8);  // word offset within chunk 0
-    const int last_w = tail_out ? 0 : (NCH - 1) * (kWaveK / 8) + lane_w;
+    const int lane_b = lane * (kLaneK / 2);  // byte offset of the lane's codes within unit 0
+    const int last_b = tail_out ? 0 : (NU - 1) * (kUnitK / 2) + lane_b;
 
-    uint4 q[kPR][NCH];
-    uint16_t sh[kPR][NCH];  // fp16 bits, kept as loaded: a widening at the load would force a wait there
-    uint32_t zw[kPR][NCH];
+    uint4 q[kPR][NU][kSub];
+    uint16_t sh[kPR][NU];  // fp16 bits, kept as loaded: a widening at the load would force a wait there
+    uint32_t zw[kPR][NU];
 
     // Loads go through buffer descriptors (one per tensor, in scalar registers): the address
     // is descriptor base + scalar row offset + a 32-bit lane offset that never changes, so a
@@ -225,17 +240,19 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.qw), 0, it.N * kw * 4, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(it.sc), 0, it.N * G * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.zr), 0, it.N * zwords * 4, 0x00020000);
-    const int lane_b = lane_w * 4, last_b = last_w * 4;  // byte offsets of the lane's codes in a row
-    int soff[NCH], zoff[NCH];
+    int soff[NU], zoff[NU];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
+    for (int c = 0; c < NU; ++c) {
         soff[c] = goff[c] * 2;
         zoff[c] = (goff[c] >> 3) * 4;
     }
     auto issue = [&](int p, int c, int row) {
-        const int qb = (c == NCH - 1) ? last_b : c * (kWaveK / 2) + lane_b;
-        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rq, qb, row * (kw * 4), 0);
-        q[p][c] = make_uint4(v[0], v[1], v[2], v[3]);
+        const int qb = (c == NU - 1) ? last_b : c * (kUnitK / 2) + lane_b;
+#pragma unroll
+        for (int h = 0; h < kSub; ++h) {
+            const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rq, qb + 16 * h, row * (kw * 4), 0);
+            q[p][c][h] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
         sh[p][c] = __builtin_amdgcn_raw_buffer_load_b16(rs, soff[c], row * (G * 2), 0);
         zw[p][c] = __builtin_amdgcn_raw_buffer_load_b32(rz, zoff[c], row * (zwords * 4), 0);
     };
@@ -247,24 +264,24 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
 #pragma unroll
     for (int p = 0; p < kPR; ++p)
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
+        for (int c = 0; c < NU; ++c) {
             issue(p, c, min(rbase + min(p, ilast) * kGemvWaves, it.N - 1));
             __builtin_amdgcn_sched_barrier(0);  // program order = consumption order, see above
         }
 
-    stage_x<kMaxRuns>(it, NCH, xlds, xr);
+    stage_x<kMaxRuns, kSub>(it, NU, xlds, xr);
 
-    // Per chunk, for the lane's own 32 k (written by the staging):
+    // Per unit, for the lane's own stretch (written by the staging):
     //   xoff = 1024 * (sum of the staged values): what the fp16 offsets add to the MFMA result
     //   xsum = sum of x * 2^-e
     //   post = 2^e
     // kept in registers for short rows, re-read from LDS per row for long ones
-    constexpr bool kParked = NCH > 4;
-    const float4* parked = reinterpret_cast<const float4*>(xlds + NCH * 4 * kWave);
-    float xoff[NCH], xsum[NCH], post[NCH];
+    constexpr bool kParked = NU > 4;
+    const float4* parked = reinterpret_cast<const float4*>(xlds + NU * kSub * 4 * kWave);
+    float xoff[NU], xsum[NU], post[NU];
     if (!kParked) {
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
+        for (int c = 0; c < NU; ++c) {
             const float4 t = parked[c * kWave + lane];
             xoff[c] = t.x; xsum[c] = t.y; post[c] = t.z;
         }
@@ -298,28 +315,32 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
             for (int j = 0; j < 4; ++j) xv[0][j] = xlds[j * kWave + xo];
         }
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            if (kXB == 2 && c + 1 < NCH) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) xv[(c + 1) & 1][j] = xlds[((c + 1) * 4 + j) * kWave + xo];
-            }
-            if (kXB == 1) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) xv[0][j] = xlds[(c * 4 + j) * kWave + xo];
-            }
-            const uint32_t w[4] = {q[p][c].x, q[p][c].y, q[p][c].z, q[p][c].w};
+        for (int c = 0; c < NU; ++c) {
             f32x4_t d0 = {0.f, 0.f, 0.f, 0.f};  // one chain: the expansion between two MFMAs covers their latency
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                // codes 0,4 | 16*codes 1,5 | codes 2,6 | 16*codes 3,7, each plus 1024, as fp16
-                const uint32_t w8 = w[j] >> 8;
-                const uint2 a01 = make_uint2((w[j] & 0x000F000Fu) | magic, (w[j] & 0x00F000F0u) | magic);
-                const uint2 a23 = make_uint2((w8 & 0x000F000Fu) | magic, (w8 & 0x00F000F0u) | magic);
-                const uint4 xj = xv[c & (kXB - 1)][j];
-                d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a01),
-                                                        __builtin_bit_cast(f16x4_t, make_uint2(xj.x, xj.y)), d0, 0, 0, 0);
-                d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a23),
-                                                        __builtin_bit_cast(f16x4_t, make_uint2(xj.z, xj.w)), d0, 0, 0, 0);
+            for (int h = 0; h < kSub; ++h) {
+                const int sc = c * kSub + h;  // 32-k piece of the row, in k order
+                if (kXB == 2 && sc + 1 < NU * kSub) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) xv[(sc + 1) & 1][j] = xlds[((sc + 1) * 4 + j) * kWave + xo];
+                }
+                if (kXB == 1) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) xv[0][j] = xlds[(sc * 4 + j) * kWave + xo];
+                }
+                const uint32_t w[4] = {q[p][c][h].x, q[p][c][h].y, q[p][c][h].z, q[p][c][h].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    // codes 0,4 | 16*codes 1,5 | codes 2,6 | 16*codes 3,7, each plus 1024, as fp16
+                    const uint32_t w8 = w[j] >> 8;
+                    const uint2 a01 = make_uint2((w[j] & 0x000F000Fu) | magic, (w[j] & 0x00F000F0u) | magic);
+                    const uint2 a23 = make_uint2((w8 & 0x000F000Fu) | magic, (w8 & 0x00F000F0u) | magic);
+                    const uint4 xj = xv[sc & (kXB - 1)][j];
+                    d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a01),
+                                                            __builtin_bit_cast(f16x4_t, make_uint2(xj.x, xj.y)), d0, 0, 0, 0);
+                    d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a23),
+                                                            __builtin_bit_cast(f16x4_t, make_uint2(xj.z, xj.w)), d0, 0, 0, 0);
+                }
             }
             // D[j][j] is register j = lane % 4
             const float e0 = odd ? d0[1] : d0[0], e1 = odd ? d0[3] : d0[2];
@@ -401,10 +422,12 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& args, const GemvLoraAr
     const GemvItem it = args.it[idx];
     const GemvLora* lo = kLora ? &lora.l[idx] : nullptr;
     const int K = it.K, N = it.N;
-    const int nch = (K + kWaveK - 1) / kWaveK;
+    // 64 k per lane and unit where the layout allows it, else 32
+    const bool wide = it.g % (2 * kChunkK) == 0 && K % (2 * kChunkK) == 0;
+    const int nu = wide ? (K + 2 * kWaveK - 1) / (2 * kWaveK) : (K + kWaveK - 1) / kWaveK;
     // the adapter's down-projection t (at most 64 floats) sits behind the staged activations; the
     // barrier inside the staging makes it visible
-    float4* lora_t = reinterpret_cast<float4*>(lds + nch * kWave * 5);
+    float4* lora_t = reinterpret_cast<float4*>(lds + nu * kWave * (wide ? 9 : 5));
     if (kLora && (int)threadIdx.x < 64)
         reinterpret_cast<float*>(lora_t)[threadIdx.x] = (int)threadIdx.x < lo->r ? lo->t[threadIdx.x] : 0.f;
 
@@ -417,14 +440,22 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& args, const GemvLoraAr
     const int r0 = s0 + wave;
     const int r1 = max(0, (s1 - s0 - wave + kGemvWaves - 1) / kGemvWaves);  // number of rows
 
-    switch (nch) {
-        // about kUnits wave-wide loads (1 KB each) in flight per wave
-        case 1: stream_rows<1, kUnits>(it, lo, lora_t, r0, r1, lane, lds); break;
-        case 2: stream_rows<2, kUnits / 2>(it, lo, lora_t, r0, r1, lane, lds); break;
-        case 3: stream_rows<3, kUnits / 3>(it, lo, lora_t, r0, r1, lane, lds); break;
-        case 4: stream_rows<4, kUnits / 4>(it, lo, lora_t, r0, r1, lane, lds); break;
-        case 5: stream_rows<5, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
-        default: stream_rows<6, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
+    // about kUnits wave-wide loads (1 KB each) in flight per wave
+    if (wide) {
+        switch (nu) {
+            case 1: stream_rows<1, kUnits / 2, 2>(it, lo, lora_t, r0, r1, lane, lds); break;
+            case 2: stream_rows<2, kUnits / 4, 2>(it, lo, lora_t, r0, r1, lane, lds); break;
+            default: stream_rows<3, 1, 2>(it, lo, lora_t, r0, r1, lane, lds); break;
+        }
+        return;
+    }
+    switch (nu) {
+        case 1: stream_rows<1, kUnits, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
+        case 2: stream_rows<2, kUnits / 2, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
+        case 3: stream_rows<3, kUnits / 3, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
+        case 4: stream_rows<4, kUnits / 4, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
+        case 5: stream_rows<5, 1, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
+        default: stream_rows<6, 1, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
     }
 }
 
@@ -499,7 +530,8 @@ hipError_t launch_chunk(const qail_w4a16_item* items, const GemvLora* loras, int
         }
         return hipSuccess;
     }
-    int maxK = 0, bb = 0;
+    size_t lds = 0;
+    int bb = 0;
     for (int i = 0; i < count; ++i) {
         const qail_w4a16_item& s = items[i];
         GemvItem& t = a.it[i];
@@ -510,11 +542,13 @@ hipError_t launch_chunk(const qail_w4a16_item* items, const GemvLora* loras, int
         t.rows_rem = s.d.N % nb[i];
         for (int b = bb; b < bb + nb[i] && b < kGemvMaxBlocks; ++b) a.item_of_block[b / 8] |= (uint32_t)i << (4 * (b % 8));
         bb += nb[i];
-        if (s.d.K > maxK) maxK = s.d.K;
+        // staged activations and per-unit constants, as laid out by the kernel
+        const bool wide = s.d.group_size % (2 * kChunkK) == 0 && s.d.K % (2 * kChunkK) == 0;
+        const int nu = wide ? (s.d.K + 2 * kWaveK - 1) / (2 * kWaveK) : (s.d.K + kWaveK - 1) / kWaveK;
+        const size_t need_lds = (size_t)nu * kWave * (wide ? 9 : 5) * 16;
+        if (need_lds > lds) lds = need_lds;
     }
     for (int i = count; i < kGemvMaxItems; ++i) a.it[i] = a.it[count - 1];
-    const int nch = (maxK + kWaveK - 1) / kWaveK;
-    const size_t lds = (size_t)nch * kWave * (4 * 16 + 16);
     if (loras) {
         GemvLoraArgs la;
         for (int i = 0; i < kGemvMaxItems; ++i) la.l[i] = loras[i < count ? i : count - 1];
