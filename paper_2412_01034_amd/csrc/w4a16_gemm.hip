@@ -37,6 +37,7 @@ typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 128;                // k per step
+constexpr int kMaxGemmBlocks = 512;     // upper bound of the grid (the workspace has two slots per block)
 constexpr int kRowPad = 128;            // workspace rows are padded to this
 
 __host__ __device__ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
@@ -155,7 +156,16 @@ struct GemmArgs {
     const float* wmul;      // [N]
     uint16_t* y;
     int M, N, K, Kpad, g;
+    // work decomposition: tiles are numbered with m running fastest.  The first `whole` tiles
+    // are dealt whole, tile i to block i % P; the K steps of the others are dealt as units (one
+    // K step of one tile): block b of P owns the units [b * units / P, (b + 1) * units / P)
+    int Tm, tiles, steps, whole;
+    float* partial;  // [2 P][tile] fp32: sums of tiles whose K range is shared between blocks
 };
+
+// First unit of block b when `units` units are dealt to P blocks, and the block that owns unit u.
+__host__ __device__ inline long long first_unit(long long b, long long units, int P) { return b * units / P; }
+__host__ __device__ inline int owner_of(long long u, long long units, int P) { return (int)(((u + 1) * P - 1) / units); }
 
 // Block tile (32 * MB) x (128 * WN): 4 waves side by side along n, each (32 * MB) x (32 * WN).
 //
@@ -176,6 +186,15 @@ struct GemmArgs {
 // 32 x 32 output block): the LDS reads and the expansion for sub-step u + 1 are issued
 // among the MFMAs of sub-step u.  The tile of step s + 1 must be complete one sub-step
 // before step s ends, so the wait + barrier sits between sub-steps 6 and 7.
+//
+// The grid has at most one block per CU.  Tiles are dealt whole to the blocks as long as they
+// fill complete rounds; what is left (fewer tiles than blocks) can be dealt in K steps instead:
+// every block gets the same number of (tile, K step) units, a contiguous run of them, so no CU
+// idles through a last, mostly empty round.  A block therefore works on a sequence of
+// segments (a tile and a range of its K steps).  A segment that covers a tile's whole K is
+// finished on the spot; otherwise its fp32 sums go to a slot of the workspace (two slots per
+// block: one for its first shared segment, one for any later one) and a second kernel adds the
+// slots of each such tile in K order, which keeps the result independent of timing.
 constexpr int kStages = 3;
 
 // s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt untouched.
@@ -195,12 +214,37 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
     const int lane = t % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(t / kWave);
     const int c = lane & 31, kb = lane >> 5;
-    const int bm = blockIdx.x * kBM, bn = blockIdx.y * kBN;
     const int G = ga.K / ga.g, zwords = (G + 7) / 8, kw = ga.K / 8;
-    const int steps = ga.Kpad / kBK;
 
     uint32_t magic = 0x64006400u;
     asm volatile("" : "+v"(magic));  // in a VGPR: v_and_or_b32 takes one scalar operand only
+
+    const long long units = (long long)(ga.tiles - ga.whole) * ga.steps;
+    const int unit0 = (int)first_unit(blockIdx.x, units, gridDim.x);
+    const int unit1 = (int)first_unit(blockIdx.x + 1, units, gridDim.x);
+    int wtile = blockIdx.x, unit = unit0;
+    for (;;) {
+    // ---- one segment: K steps [ka, ka + steps) of one tile
+    int tile, ka, steps;
+    bool first_shared = false;
+    if (wtile < ga.whole) {
+        tile = wtile;
+        ka = 0;
+        steps = ga.steps;
+        wtile += gridDim.x;
+    } else if (unit < unit1) {
+        const int tt = unit / ga.steps;
+        tile = ga.whole + tt;
+        ka = unit - tt * ga.steps;
+        steps = min(ga.steps - ka, unit1 - unit);
+        first_shared = unit == unit0;
+        unit += steps;
+    } else {
+        break;
+    }
+    const bool whole = steps == ga.steps;
+    float* const pslot = ga.partial + (size_t)(2 * blockIdx.x + (first_shared ? 0 : 1)) * (kBM * kBN);
+    const int bm = (tile % ga.Tm) * kBM, bn = (tile / ga.Tm) * kBN;
 
     // Byte offsets of this lane's weight rows (WN 32-column blocks).  All tensors here are
     // below 4 GB (checked by the host), so addresses are a uniform base plus a 32-bit offset.
@@ -247,10 +291,10 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
     unsigned char* const Bs = As + kStages * kBufBytes;  // [kStages][4 waves][WN][2560 B]
     constexpr int kBLane = 2560;                          // 2 x 1024 (codes) + 256 (scale) + 256 (zero)
     constexpr int kBStage = 4 * WN * kBLane;
-    int lk = 64 * kb, lgrp = lk / ga.g, lkin = lk - lgrp * ga.g;  // position of the next planned step
-    int pstep = 0;
+    int lk = ka * kBK + 64 * kb, lgrp = lk / ga.g, lkin = lk - lgrp * ga.g;  // position of the next planned step
+    int pstep = ka;
     auto plan = [&]() {
-        pk0b = (uint32_t)(min(pstep, steps - 1) * kBK) * 2u;
+        pk0b = (uint32_t)(min(pstep, ga.steps - 1) * kBK) * 2u;  // past the end of K: the last tile again, unused
         ++pstep;
         const bool v = lk < ga.K;
         const uint32_t kc = v ? (uint32_t)lk : 0u;  // past the end: any valid address, the scale becomes 0
@@ -286,7 +330,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
     // operands of the step being multiplied; ck / cgrp follow the consumed steps like lk / lgrp
     uint32_t wq[WN][8];
     f16x2_t nz[WN], nz6[WN], s2[WN];
-    int ck = 64 * kb, cgrp = ck / ga.g, ckin = ck - cgrp * ga.g;
+    int ck = ka * kBK + 64 * kb, cgrp = ck / ga.g, ckin = ck - cgrp * ga.g;
     auto take = [&](int stage) {
         const bool v = ck < ga.K;
         const uint32_t grp = v ? (uint32_t)cgrp : 0u;
@@ -398,6 +442,30 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // nothing may still be writing LDS
     __syncthreads();
 
+    if (!whole) {
+        // part of a tile's K: the raw sums go to this block's slot, tile-shaped [kBM][kBN],
+        // through LDS so that they leave as 16-byte pieces of full lines
+        constexpr int kPPitch = kBN + 4;  // floats per staged row
+        static_assert(kBM * kPPitch * 4 <= kStages * (kBufBytes + 4 * WN * 2560), "the fp32 tile fits in the ring");
+        float* const stage = reinterpret_cast<float*>(As) + (4 * kb) * kPPitch + wave * WN * 32 + c;
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    stage[(i * 32 + 8 * (r / 4) + (r % 4)) * kPPitch + j * 32] = acc[i][j][r];
+        __syncthreads();
+        for (int idx = t; idx < kBM * (kBN / 4); idx += 256) {
+            const int row = idx / (kBN / 4), c4 = idx % (kBN / 4);
+            *reinterpret_cast<f32x4_t*>(pslot + row * kBN + c4 * 4) =
+                *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(As) + row * kPPitch + c4 * 4);
+        }
+        // the next segment counts its loads in flight exactly and reuses LDS
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        __syncthreads();
+        continue;
+    }
     // y = acc * 2^-p(m) * 2^E(n), rounded once to bf16, staged in LDS so that rows leave as
     // 16-byte pieces of full lines.
 #pragma unroll
@@ -429,6 +497,73 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
             for (int e = 0; e < 8 && n + e < ga.N; ++e) dst[e] = (uint16_t)(w[e / 2] >> (16 * (e & 1)));
         }
     }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __syncthreads();  // the staging tile is about to be overwritten by the next segment's loads
+    }  // segments
+}
+
+// Adds up the slots of every tile whose K range was shared between blocks (in K order) and
+// finishes it like the main kernel does: y = sum * 2^-p(m) * 2^E(n), rounded once to bf16.
+// Grid: (tiles dealt in K steps, pieces of 256 4-float groups per tile); a thread owns one group.
+template <int MB, int WN>
+__global__ __launch_bounds__(256) void w4a16_gemm_fixup_kernel(const GemmArgs ga, int P) {
+    constexpr int kBM = 32 * MB, kBN = 128 * WN;
+    static_assert((kBM * kBN / 4) % 256 == 0, "tiles split into whole pieces");
+    const int t = threadIdx.x, lane = t % kWave, wave = t / kWave;
+    const int tile = ga.whole + blockIdx.x;
+    const long long units = (long long)(ga.tiles - ga.whole) * ga.steps;
+    const long long u_first = (long long)blockIdx.x * ga.steps, u_last = u_first + ga.steps - 1;
+    const int b_lo = owner_of(u_first, units, P), b_hi = owner_of(u_last, units, P);
+    if (b_lo == b_hi) return;  // one block had the whole tile and has finished it
+
+    // The slots to add, in K order, worked out once per block (the divisions are slow) and
+    // packed, so that the loads below can be issued several at a time.
+    __shared__ int slots[kMaxGemmBlocks];
+    __shared__ int wave_count[4];
+    int count = 0;
+    for (int b0 = b_lo; b0 <= b_hi; b0 += 256) {
+        const int b = b0 + t;
+        int sl = -1;  // with fewer units than blocks some blocks own none
+        if (b <= b_hi) {
+            const long long fu = first_unit(b, units, P);
+            // a block's first shared segment is in its slot 0, a later one in slot 1
+            if (fu != first_unit(b + 1, units, P)) sl = 2 * b + ((int)blockIdx.x == (int)(fu / ga.steps) ? 0 : 1);
+        }
+        const unsigned long long have = __ballot(sl >= 0);
+        if (lane == 0) wave_count[wave] = __popcll(have);
+        __syncthreads();
+        int at = count + __popcll(have & ((1ull << lane) - 1ull));
+        for (int w = 0; w < wave; ++w) at += wave_count[w];
+        if (sl >= 0) slots[at] = sl;
+        count += wave_count[0] + wave_count[1] + wave_count[2] + wave_count[3];
+        __syncthreads();
+    }
+
+    const int idx = blockIdx.y * 256 + t;
+    const int row = idx / (kBN / 4), c4 = idx % (kBN / 4);
+    const int m = (tile % ga.Tm) * kBM + row, n = (tile / ga.Tm) * kBN + c4 * 4;
+    if (m >= ga.M || n >= ga.N) return;
+    const float* src = ga.partial + row * kBN + c4 * 4;
+    f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+    int i = 0;
+    for (; i + 4 <= count; i += 4) {
+        f32x4_t v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = *reinterpret_cast<const f32x4_t*>(src + (size_t)slots[i + e] * (kBM * kBN));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum += v[e];
+    }
+    for (; i < count; ++i) sum += *reinterpret_cast<const f32x4_t*>(src + (size_t)slots[i] * (kBM * kBN));
+    const float rs = ga.rscale[m];
+    uint16_t* dst = ga.y + (size_t)m * ga.N + n;
+    uint16_t h[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) h[e] = f32_to_bf16_rne(sum[e] * rs * ga.wmul[min(n + e, ga.N - 1)]);
+    if ((ga.N % 4) == 0) {
+        *reinterpret_cast<uint2*>(dst) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+    } else {
+        for (int e = 0; e < 4 && n + e < ga.N; ++e) dst[e] = h[e];
+    }
 }
 
 int gemm_cus() {
@@ -443,8 +578,10 @@ int gemm_cus() {
     return cus;
 }
 
+int gemm_max_blocks() { return gemm_cus() < kMaxGemmBlocks ? gemm_cus() : kMaxGemmBlocks; }
+
 template <int MB, int WN>
-hipError_t launch_tile(const GemmArgs& ga, hipStream_t st) {
+hipError_t launch_tile(GemmArgs ga, bool split_tail, hipStream_t st) {
     constexpr int kBM = 32 * MB, kBN = 128 * WN;
     const size_t lds = (size_t)kStages * (kBM * 256 + 4 * WN * 2560);
     static bool attr_set = false;
@@ -454,18 +591,58 @@ hipError_t launch_tile(const GemmArgs& ga, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((ga.M + kBM - 1) / kBM, (ga.N + kBN - 1) / kBN);
-    hipLaunchKernelGGL((w4a16_gemm_f16_kernel<MB, WN>), grid, dim3(256), lds, st, ga);
-    return hipGetLastError();
+    const int cus = gemm_max_blocks();
+    ga.Tm = (ga.M + kBM - 1) / kBM;
+    ga.tiles = ga.Tm * ((ga.N + kBN - 1) / kBN);
+    ga.steps = ga.Kpad / kBK;
+    ga.whole = split_tail ? ga.tiles / cus * cus : ga.tiles;
+    const int tail = ga.tiles - ga.whole;
+    const long long units = (long long)tail * ga.steps;
+    int P = ga.whole >= cus ? cus : ga.whole;
+    if (tail > 0 && P < cus) P = units < cus ? (int)units : cus;  // here whole == 0
+    hipLaunchKernelGGL((w4a16_gemm_f16_kernel<MB, WN>), dim3(P), dim3(256), lds, st, ga);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // the second kernel is only needed when some block boundary falls inside a tile
+    bool shared = false;
+    for (int b = 1; b < P && tail > 0 && !shared; ++b) shared = first_unit(b, units, P) % ga.steps != 0;
+    if (shared) {
+        hipLaunchKernelGGL((w4a16_gemm_fixup_kernel<MB, WN>), dim3(tail, kBM * kBN / 4 / 256), dim3(256), 0,
+                           st, ga, P);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
-// 64-column waves spread the expansion of a weight word over more MFMAs; 32-column waves
-// double the number of blocks.  The narrow tile is taken when the wide one would leave CUs idle.
+// Tile width and the treatment of the last, incomplete round of tiles.
 template <int MB>
 hipError_t launch_rows(const GemmArgs& ga, hipStream_t st) {
-    const long long wide = (long long)((ga.M + 32 * MB - 1) / (32 * MB)) * ((ga.N + 255) / 256);
-    if (wide >= 3LL * gemm_cus() / 2) return launch_tile<MB, 2>(ga, st);
-    return launch_tile<MB, 1>(ga, st);
+    // Measured on the four linears of a 7B decoder layer at M = 288 and 1024 (256 CUs):
+    //   * a round or more of wide tiles: wide tiles, and the incomplete last round is dealt in
+    //     K steps only when it is short (a fuller one is cheaper left as it is: blocks that
+    //     share tiles pay for slots and a second kernel, and a chip that is not full clocks higher);
+    //   * between half a round and a round of wide tiles: wide tiles, whole;
+    //   * less: narrow tiles (twice as many), dealt in K steps when K is long.
+    const int cus = gemm_max_blocks();
+    const int t2 = ((ga.M + 32 * MB - 1) / (32 * MB)) * ((ga.N + 255) / 256);
+    int wn = 2;
+    bool split = false;
+    if (ga.N <= 128) {
+        wn = 1;
+        split = ga.Kpad / kBK >= 64;
+    } else if (t2 >= cus) {
+        split = (t2 % cus) * 5 <= cus * 2;
+    } else if (t2 * 2 <= cus) {
+        wn = 1;
+        split = ga.Kpad / kBK >= 64;
+    }
+    return wn == 2 ? launch_tile<MB, 2>(ga, split, st) : launch_tile<MB, 1>(ga, split, st);
+}
+
+// tile height: the multiple of 32 rows (at most 128) that pads M least
+int tile_rows(int M) {
+    if (M <= 96) return round_up(M, 32);
+    return round_up(M, 96) < round_up(M, 128) ? 96 : 128;
 }
 
 }  // namespace
@@ -483,7 +660,11 @@ size_t gemm_f16_workspace(const qail_wdesc& d, int M) {
     size_t b = Mpad * Kpad * 2;                       // xh
     b += Mpad * 4;                                    // rscale
     b += (size_t)round_up(d.N, 64) * 4;               // wmul
-    return (b + 255) / 256 * 256;
+    b = (b + 255) / 256 * 256;
+    // two tile-shaped fp32 slots per block for tiles whose K range is shared between blocks
+    const size_t tile = (size_t)tile_rows(M) * (d.N > 128 ? 256 : 128) * 4;
+    b += 2 * (size_t)gemm_max_blocks() * tile;
+    return b;
 }
 
 hipError_t launch_w4a16_gemm_f16(const qail_w4a16_item& it, int M, void* ws, hipStream_t st) {
@@ -492,17 +673,19 @@ hipError_t launch_w4a16_gemm_f16(const qail_w4a16_item& it, int M, void* ws, hip
     uint16_t* xh = static_cast<uint16_t*>(ws);
     float* rscale = reinterpret_cast<float*>(xh + (size_t)Mpad * Kpad);
     float* wmul = rscale + Mpad;
+    const size_t head = ((size_t)Mpad * Kpad * 2 + (size_t)Mpad * 4 + (size_t)round_up(d.N, 64) * 4 + 255) / 256 * 256;
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(ws) + head);
     hipLaunchKernelGGL(gemm_prep_kernel, dim3(Mpad + (d.N + 31) / 32), dim3(256), 0, st, it.x, it.scales, xh,
                        rscale, wmul, M, Mpad, d.N, d.K, Kpad, G);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    GemmArgs ga{it.qweight, it.scales, it.zeros, xh, rscale, wmul, it.y, M, d.N, d.K, Kpad, d.group_size};
-    // tile height: the multiple of 32 rows (at most 128) that pads M least
-    if (M <= 32) return launch_rows<1>(ga, st);
-    if (M <= 64) return launch_rows<2>(ga, st);
-    if (M <= 96) return launch_rows<3>(ga, st);
-    const int pad3 = round_up(M, 96), pad4 = round_up(M, 128);
-    return pad3 < pad4 ? launch_rows<3>(ga, st) : launch_rows<4>(ga, st);
+    GemmArgs ga{it.qweight, it.scales, it.zeros, xh, rscale, wmul, it.y, M, d.N, d.K, Kpad, d.group_size, 0, 0, 0, 0, partial};
+    switch (tile_rows(M)) {
+        case 32: return launch_rows<1>(ga, st);
+        case 64: return launch_rows<2>(ga, st);
+        case 96: return launch_rows<3>(ga, st);
+        default: return launch_rows<4>(ga, st);
+    }
 }
 
 }  // namespace qail

@@ -106,14 +106,16 @@ def test_argument_errors_are_reported_without_a_gpu(B):
     assert L.qail_w4a16_workspace(ctypes.byref(d), 1, ctypes.byref(sz)) == B.QAIL_OK
     assert L.qail_w4a16_workspace(ctypes.byref(d), 0, ctypes.byref(sz)) == B.QAIL_ERR_SHAPE
     # the matrix-core GEMM (M > 16) needs a workspace: fp16 copy of x padded to 128 rows and
-    # 128 columns, one float per padded row, one per output column, rounded up to 256 bytes
+    # 128 columns, one float per padded row, one per output column, rounded up to 256 bytes;
+    # then two tile-shaped fp32 slots (here 32 x 256) per block of the largest grid (one block per
+    # CU; 256 CUs on the target, which is also what the library assumes when it sees no device)
     dg = B.qail_wdesc(300, 4096 + 64, 64, B.QAIL_W4_ASYM_GROUP)
     assert L.qail_w4a16_workspace(ctypes.byref(dg), 1, ctypes.byref(sz)) == B.QAIL_OK and sz.value == 0
     d7 = B.qail_wdesc(4096, 4096, 128, B.QAIL_W4_ASYM_GROUP)   # M <= 16 streams without a workspace
     assert L.qail_w4a16_workspace(ctypes.byref(d7), 16, ctypes.byref(sz)) == B.QAIL_OK and sz.value == 0
     assert L.qail_w4a16_workspace(ctypes.byref(dg), 17, ctypes.byref(sz)) == B.QAIL_OK
     want = 128 * 4224 * 2 + 128 * 4 + 320 * 4
-    assert sz.value == (want + 255) // 256 * 256
+    assert sz.value == (want + 255) // 256 * 256 + 2 * 256 * 32 * 256 * 4
     assert L.qail_w4a16_linear(ctypes.byref(dg), ok, ok, ok, ok, ok, 17, None, 0, None) == B.QAIL_ERR_WORKSPACE
     assert L.qail_w4a16_linear(ctypes.byref(dg), ok, ok, ok, ok, ok, 17, ok, sz.value - 1, None) == B.QAIL_ERR_WORKSPACE
     assert L.qail_w4a16_linear(ctypes.byref(dg), ok, ok, ok, ok, ok, 17, ok + 16, sz.value, None) == B.QAIL_ERR_ALIGN

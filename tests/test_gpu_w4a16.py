@@ -98,6 +98,16 @@ def test_matrix_core_gemm_edges(B, M, N, K, g):
           tol=TOL if K >= 512 else TOL_TINY_K)
 
 
+@pytest.mark.parametrize("M,N,K,g", [(33, 260, 8256, 64),     # few narrow tiles, long K: every tile's K is shared
+                                     #   between many blocks (one K step each), ragged last step
+                                     (200, 300, 8192, 128),    # two row tiles of 96, 64 steps shared by 256 blocks
+                                     (130, 8200, 2048, 128)])  # 2 x 33 wide tiles: whole tiles only, ragged N
+def test_matrix_core_gemm_work_split(B, M, N, K, g):
+    # the tile / K-step dealing of the M > 16 kernel: tiles finished by one block and tiles whose
+    # partial sums meet in the second kernel must both match the oracle
+    check(B, N, K, g, M, 5 * M + N, w_kw=dict(outlier_frac=0.01), x_kw=dict(outlier_frac=0.005), tol=TOL)
+
+
 def test_matrix_core_gemm_value_ranges(B):
     # rows of x and rows of W spanning 60 binades each: the per-row powers of two that keep the
     # fp16 operands in range must come back out exactly
