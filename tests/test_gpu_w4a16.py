@@ -68,6 +68,9 @@ def test_config0_tiny_gemv(B):
     (37, 11008, 128),        # 86 groups: wave-wide load with a partial tail
     (130, 2048, 32),
     (64, 32, 32),            # a single 32-k chunk
+    (33, 8192, 64),          # two 4096-k units per row (64 k per lane and unit)
+    (20, 11040, 32),         # K and g not multiples of 64: 32 k per lane, six chunks, constants re-read per row
+    (18, 6176, 32),          # the same with four chunks, the last nearly empty
     (16, 12288, 128),        # largest K of the streaming kernel
     (3, 14336, 128),         # just beyond it
     (5, 40, 8),              # shape only the generic kernel takes
