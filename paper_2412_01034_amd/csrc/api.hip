@@ -142,7 +142,7 @@ int qail_quantize_act_u4(const float* a, size_t n, const float* s_a, uint32_t* a
 
 // Workspace one linear needs at batch M: only the matrix-core GEMM (M > 16) uses any.
 static size_t item_workspace(const qail_wdesc& d, int M) {
-    if (M == 1 || smallm_supports(d, M) || !gemm_f16_supports(d, M)) return 0;
+    if (M == 1 || decode4_supports(d, M) || smallm_supports(d, M) || !gemm_f16_supports(d, M)) return 0;
     return gemm_f16_workspace(d, M);
 }
 
@@ -207,9 +207,15 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
     }
     int i = 0;
     while (i < count) {
-        // runs of items the small-batch streaming kernel takes go out together
+        // runs of items one of the streaming kernels takes go out together
         int j = i;
-        while (j < count && smallm_supports(items[j].d, M)) ++j;
+        while (j < count && decode4_supports(items[j].d, M)) ++j;
+        if (j > i) {
+            if (launch_w4a16_decode4(items + i, j - i, M, st) != hipSuccess) return QAIL_ERR_HIP;
+            i = j;
+            continue;
+        }
+        while (j < count && smallm_supports(items[j].d, M) && !decode4_supports(items[j].d, M)) ++j;
         if (j > i) {
             if (launch_w4a16_smallm(items + i, j - i, M, st) != hipSuccess) return QAIL_ERR_HIP;
             i = j;

@@ -53,6 +53,9 @@ bool lora_supports(const qail_wdesc& d, const qail_lora& l);
 hipError_t launch_lora_down(const qail_w4a16_item* items, const qail_lora* loras, float* t, int t_stride,
                             int count, int M, hipStream_t st);
 hipError_t launch_lora_up_add(const qail_w4a16_item& it, const qail_lora& l, const float* t, int M, hipStream_t st);
+// 2 <= M <= 4: the M = 1 stream with four rows of x (preferred over the small-batch kernel).
+bool decode4_supports(const qail_wdesc& d, int M);
+hipError_t launch_w4a16_decode4(const qail_w4a16_item* items, int count, int M, hipStream_t st);
 bool smallm_supports(const qail_wdesc& d, int M);
 hipError_t launch_w4a16_smallm(const qail_w4a16_item* items, int count, int M, hipStream_t st);
 // fp16-MFMA GEMM for M > 16; needs gemm_f16_workspace() bytes of 256-byte aligned device memory.

@@ -135,6 +135,22 @@ def test_matrix_core_gemm_value_ranges(B):
     assert w4a16_norm_err(y, ref, nx, nw) <= TOL
 
 
+@pytest.mark.parametrize("M", [2, 3, 4])
+@pytest.mark.parametrize("N,K,g", [(4, 512, 512),         # one quad, one chunk, one group
+                                   (260, 4096, 64),       # eight groups per 512-k chunk
+                                   (128, 2048, 256),      # two groups per chunk
+                                   (64, 2048, 512),       # a group is a chunk
+                                   (36, 4096, 1024),      # a group is two chunks
+                                   (20, 12288, 128),      # the longest K of the four-row stream
+                                   (8, 4160, 64),         # K = 8.125 chunks: 14 of the last chunk's 16 stretches are empty
+                                   (24, 960, 64),         # K just short of two chunks
+                                   (5000, 1152, 128),     # five quads per block
+                                   (263000, 64, 64)])     # more quads than 256 blocks x 16 waves x 16 hold: extra blocks
+def test_four_row_stream_shapes(B, M, N, K, g):
+    check(B, N, K, g, M, 17 * M + N + K, w_kw=dict(outlier_frac=0.01), x_kw=dict(outlier_frac=0.005),
+          tol=TOL if K >= 512 else TOL_TINY_K)
+
+
 @pytest.mark.parametrize("M", [3, 7, 15])
 def test_small_batch_odd_row_counts(B, M):
     check(B, 333, 4096, 128, M, 900 + M, w_kw=dict(outlier_frac=0.01), x_kw=dict(outlier_frac=0.005))
