@@ -72,11 +72,25 @@ __device__ __forceinline__ float dpp_f(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xF, 0xF, true));
 }
 
-// Value of lane 4b + i of the caller's quad, for every lane of the quad.
+// acc += (v of lane 4b + i of the caller's quad) * m, in one instruction: the multiply-add reads
+// its first operand through the quad permute.  Written as assembly because the compiler emits
+// a separate v_mov_b32_dpp per operand instead; the s_nop covers the two wait states a DPP read
+// needs after a vector write of the same register, which the compiler cannot see in here.
 template <int i>
-__device__ __forceinline__ float quad_bcast(float v) {
-    return dpp_f<i * 0x55>(v);  // quad_perm [i, i, i, i]
-}
+__device__ __forceinline__ void quad_fmac(float& acc, float v, float m);
+#define QAIL_QUAD_FMAC(i)                                                                                   \
+    template <>                                                                                             \
+    __device__ __forceinline__ void quad_fmac<i>(float& acc, float v, float m) {                            \
+        asm("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 quad_perm:[" #i "," #i "," #i "," #i                      \
+            "] row_mask:0xf bank_mask:0xf bound_ctrl:1"                                                     \
+            : "+v"(acc)                                                                                     \
+            : "v"(v), "v"(m));                                                                              \
+    }
+QAIL_QUAD_FMAC(0)
+QAIL_QUAD_FMAC(1)
+QAIL_QUAD_FMAC(2)
+QAIL_QUAD_FMAC(3)
+#undef QAIL_QUAD_FMAC
 
 // Sum over the 16 lanes that share lane % 4 (all stretches b of one row of x); every lane gets it.
 __device__ __forceinline__ float sum_over_stretches(float v) {
@@ -89,8 +103,8 @@ __device__ __forceinline__ float sum_over_stretches(float v) {
 
 // LDS map of a block (uint4 units), nc = ceil(K / 512) chunks per row:
 //   [0, nc*256)        staged activations: word e of lane L in chunk c at (c*4 + e)*64 + L
-//   then nc*64 float4  constants of lane L's stretch of chunk c at c*64 + L:
-//                      (1024 * sum of the staged values, sum of x * 2^-e, 2^e, unused)
+//   then nc*64 float4  constants of lane L's stretch of chunk c at c*64 + L, with P = 2^e:
+//                      (P * 1024 * sum of the staged values, -P * sum of x * 2^-e, P, unused)
 // Lane L = 4b + j owns, in chunk c, the 32 k starting at 512 c + 32 b of row j of x (rows past
 // M are zero).  Its staged word e holds those k's 8e..8e+7 as fp16 in the order
 // x0,x4 | x1/16,x5/16 | x2,x6 | x3/16,x7/16 (all times 2^-e), matching the four registers the
@@ -121,6 +135,7 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
         const int e = threadIdx.x + u * kD4Threads;
         const int j = e / row_runs, r = e - j * row_runs;
         xr[u] = (j < M) ? reinterpret_cast<const uint4*>(it.x + (size_t)j * K)[r] : make_uint4(0, 0, 0, 0);
+        if ((u + 1) * kD4Threads >= 4 * row_runs) break;  // block-uniform: the rest would be past the fourth row
     }
     __builtin_amdgcn_sched_barrier(0);  // the scheduler must not move the x loads behind the weights
 
@@ -149,7 +164,9 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
     const int zlane = li * zwords * 4;
     // the zero-point word of group (chunk part + lane part) is the chunk part's word: the lane
     // part stays below 8 and the chunk part is a multiple of gpc (8 or a divisor of 8)
-    auto chunk_group = [&](int c) { return (c / cpg) * gpc; };
+    // (both counts are powers of two: host check)
+    const int cpg_shift = __builtin_ctz(cpg), gpc_shift = __builtin_ctz(gpc);
+    auto chunk_group = [&](int c) { return (c >> cpg_shift) << gpc_shift; };
 
     uint4 q[kD4Ring];
     uint32_t sh[kD4Ring];  // fp16 bits as loaded (zero-extended): a conversion at the load would wait there
@@ -186,6 +203,7 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
     {
 #pragma unroll
         for (int u = 0; u < kD4XRuns; ++u) {
+            if (u * kD4Threads >= 4 * row_runs) break;  // block-uniform
             const int e = threadIdx.x + u * kD4Threads;
             const int j = e / row_runs, r = e - j * row_runs;
             const uint32_t w[4] = {xr[u].x, xr[u].y, xr[u].z, xr[u].w};
@@ -226,8 +244,10 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
                 const int L = 4 * (rr >> 2) + j, t = rr & 3;
                 xl[(c * 4 + t) * kWave + L] = o;
                 if (t == 0)
-                    consts[c * kWave + L] = make_float4(1024.f * (se + so), se + 16.f * so,
-                                                        __builtin_bit_cast(float, (uint32_t)(127 + down) << 23), 0.f);
+                {
+                    const float P = __builtin_bit_cast(float, (uint32_t)(127 + down) << 23);  // exact factors
+                    consts[c * kWave + L] = make_float4(P * (1024.f * (se + so)), -P * (se + 16.f * so), P, 0.f);
+                }
             }
         }
         // the part of the last chunk past K, for all four rows
@@ -279,25 +299,28 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
         const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)sh[p]);
         const float z = (float)((zw[p] >> (4 * (grp & 7))) & 0xFu);
         // register i of d belongs to weight row n0 + i, whose scale and zero-point lane 4b + i holds:
-        //   sum_k x_k (q_k - z) = (D - xoff) - z * xsum, times 2^e of the stretch of x, times s
-        const float nxsum = -cst.y;
-#define QAIL_D4_ROW(i)                                                     \
-    {                                                                      \
-        const float t = fmaf(quad_bcast<i>(z), nxsum, d[i] - cst.x);       \
-        acc[i] = fmaf(quad_bcast<i>(s), t * cst.z, acc[i]);                \
+        //   s * P * sum_k x_k (q_k - z) = s * (P D - P xoff) + (s z) * (-P xsum)
+        const float sz = s * z;
+#define QAIL_D4_ROW(i)                                          \
+    {                                                           \
+        quad_fmac<i>(acc[i], s, fmaf(cst.z, d[i], -cst.x));     \
+        quad_fmac<i>(acc[i], sz, cst.y);                        \
     }
         QAIL_D4_ROW(0) QAIL_D4_ROW(1) QAIL_D4_ROW(2) QAIL_D4_ROW(3)
 #undef QAIL_D4_ROW
-        if (last) {
-            // the quad is complete: add up its 16 stretches and park the result
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float v = sum_over_stretches(acc[i]);
-                keep[i] = (lb == cq) ? v : keep[i];
-                acc[i] = 0.f;
-            }
-        }
         asm volatile("" : "+v"(xo));
+    };
+    // A quad is complete: add up its 16 stretches and park the result.  Kept out of the chunk
+    // code and behind a scalar branch: folded into it, the compiler runs the cross-lane adds
+    // for every chunk and selects.
+    auto finish_quad = [&](int cq) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float v = sum_over_stretches(acc[i]);
+            keep[i] = (lb == cq) ? v : keep[i];
+            acc[i] = 0.f;
+        }
+        asm volatile("" ::: "memory");
     };
 
     int t = 0;
@@ -305,6 +328,7 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
 #pragma unroll
         for (int p = 0; p < kD4Ring; ++p) {
             consume(p, cq, cc);
+            if (__builtin_amdgcn_readfirstlane(cc == nc - 1)) finish_quad(cq);
             advance(cq, cc);
             issue(p, iq, ic);
             advance(iq, ic);
@@ -315,6 +339,7 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
     for (int p = 0; p < kD4Ring; ++p)
         if (t + p < total) {
             consume(p, cq, cc);
+            if (__builtin_amdgcn_readfirstlane(cc == nc - 1)) finish_quad(cq);
             advance(cq, cc);
         }
 
@@ -426,8 +451,8 @@ hipError_t d4_launch_chunk(const qail_w4a16_item* items, int count, int M, hipSt
 
 bool decode4_supports(const qail_wdesc& d, int M) {
     const int g = d.group_size;
-    // a chunk of 512 k holds 1, 2, 4 or 8 whole groups, or a group a whole number of chunks
-    const bool groups_ok = g == 64 || g == 128 || g == 256 || g % kD4ChunkK == 0;
+    // a chunk of 512 k holds 1, 2, 4 or 8 whole groups, or a group a power-of-two number of chunks
+    const bool groups_ok = g == 64 || g == 128 || g == 256 || (g % kD4ChunkK == 0 && (g & (g - 1)) == 0);
     return M >= 2 && M <= 4 && d.N % 4 == 0 && d.K % 32 == 0 && d.K <= kD4MaxChunks * kD4ChunkK && groups_ok &&
            (unsigned long long)d.N * d.K / 2 < 0x80000000ull;  // 32-bit byte offsets in the kernel
 }
