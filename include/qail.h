@@ -137,15 +137,18 @@ int qail_quantize_act_u4(const float* a, size_t n, const float* s_a, uint32_t* a
 
 /* Bytes of device scratch the call below needs for this (d, M).  0 for the streaming
  * kernels (M <= 16 on shapes they take); for the matrix-core GEMM it holds an fp16 copy
- * of x (rows padded to a multiple of 128, K to a multiple of 128) plus one float per
- * padded row and per output column.  The workspace must be 256-byte aligned, is
+ * of x (rows padded to a multiple of 128, K to a multiple of 128), one float per padded
+ * row and per output column, and two tile-shaped fp32 slots per block of the grid (one
+ * block per compute unit) for output tiles whose K range is shared between blocks (tens
+ * of MB at prefill sizes).  The workspace must be 256-byte aligned, is
  * overwritten by every call and carries nothing between calls; calls that share one
  * must be ordered on one stream. */
 int qail_w4a16_workspace(const qail_wdesc* d, int32_t M, size_t* bytes);
 
 /* d must be ASYM_GROUP.  x: bf16 [M][K]; y: bf16 [M][N].  Products are accumulated
  * in fp32 and rounded once to bf16 (nearest even).  M = 1 (decode) is served by a
- * bandwidth-bound streaming kernel, 2 <= M <= 16 by a weight-streaming MFMA kernel,
+ * bandwidth-bound streaming kernel, 2 <= M <= 4 by the same stream with four rows of x,
+ * up to M = 16 by a weight-streaming MFMA kernel,
  * larger M (prefill) by an fp16 MFMA kernel that expands the codes in registers
  * ((q - z) * s rounded once to fp16, x rescaled per row by a power of two).
  * workspace may be NULL when the query returns 0; otherwise a missing or short one
