@@ -32,7 +32,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/w4a16_gemv_decode_layer_pmc.txt), and the sha256 of the kernel source the
 # counters were taken on; reported as null once the kernel has changed.
-GEMV_TRAFFIC_BYTES = 106021831
+GEMV_TRAFFIC_BYTES = 106022244
 GEMV_TRAFFIC_SOURCE_SHA256 = "c1cb59950d42957865a77e789abaeec79f31594cf0564795b98330734ff883c6"
 
 HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
