@@ -468,19 +468,24 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
     }
     // y = acc * 2^-p(m) * 2^E(n), rounded once to bf16, staged in LDS so that rows leave as
     // 16-byte pieces of full lines.
+    float wm[WN];
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
-        const int col = (wave * WN + j) * 32 + c;
-        const float wm = ga.wmul[min(bn + col, ga.N - 1)];
+    for (int j = 0; j < WN; ++j) wm[j] = ga.wmul[min(bn + (wave * WN + j) * 32 + c, ga.N - 1)];
 #pragma unroll
-        for (int i = 0; i < MB; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
-                const float v = acc[i][j][r] * ga.rscale[bm + row] * wm;
-                *reinterpret_cast<uint16_t*>(As + row * kCPitch + col * 2) = f32_to_bf16_rne(v);
+        for (int r = 0; r < 16; r += 2) {
+            // registers r and r + 1 are two neighbouring rows of the lane's column
+            const int row = i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
+            const float rs0 = ga.rscale[bm + row], rs1 = ga.rscale[bm + row + 1];
+#pragma unroll
+            for (int j = 0; j < WN; ++j) {
+                const int col = (wave * WN + j) * 32 + c;
+                const uint32_t h = f32x2_to_bf16x2_rne(acc[i][j][r] * rs0 * wm[j], acc[i][j][r + 1] * rs1 * wm[j]);
+                *reinterpret_cast<uint16_t*>(As + row * kCPitch + col * 2) = (uint16_t)h;
+                *reinterpret_cast<uint16_t*>(As + (row + 1) * kCPitch + col * 2) = (uint16_t)(h >> 16);
             }
-    }
+        }
     __syncthreads();
     constexpr int kChunks = kBN / 8;  // 16-byte pieces per row
     const bool vec_ok = (ga.N % 8) == 0;
