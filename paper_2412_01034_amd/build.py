@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqail.so")
 
-SOURCES = ("api.hip", "quantize.hip", "w4a16_gemv.hip", "w4a16_decode4.hip", "w4a16_smallm.hip", "w4a16_gemm.hip", "w4a16_generic.hip", "w4a16_lora.hip", "w8.hip", "train_ops.hip", "w4a4_conv.hip")
+SOURCES = ("api.hip", "quantize.hip", "w4a16_gemv.hip", "w4a16_decode4.hip", "w4a16_smallm.hip", "w4a16_gemm.hip", "w4a16_generic.hip", "w4a16_lora.hip", "w8.hip", "w8a16_gemv.hip", "train_ops.hip", "w4a4_conv.hip")
 
 HIPCC_FLAGS = (
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

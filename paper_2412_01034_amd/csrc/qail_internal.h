@@ -78,6 +78,10 @@ hipError_t launch_act_scale_s8(const float* a, size_t n, float* s_a, hipStream_t
 hipError_t launch_act_quant_s8(const float* a, size_t n, const float* s_a, uint32_t* out, hipStream_t st);
 hipError_t launch_w8a16_linear(const qail_wdesc& d, const uint32_t* qw, const uint16_t* sc, const uint16_t* x,
                                uint16_t* y, int M, hipStream_t st);
+// M = 1 on the shapes the streaming kernel takes (w8a16_gemv.hip); launch_w8a16_linear dispatches.
+bool w8a16_stream_supports(const qail_wdesc& d, int M);
+hipError_t launch_w8a16_stream(const qail_wdesc& d, const uint32_t* qw, const uint16_t* sc, const uint16_t* x,
+                               uint16_t* y, hipStream_t st);
 
 // Training-side operators.
 hipError_t launch_fake_quant_w4(const qail_wdesc& d, const float* w, float* out, hipStream_t st);

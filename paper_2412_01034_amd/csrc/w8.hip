@@ -87,8 +87,8 @@ __global__ __launch_bounds__(256) void act_quant_s8_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------------------------------
-// Weight-only 8-bit linear, M = 1: y[n] = sum_k x[k] q[n][k] s[n][k/g].  Bandwidth-bound like the
-// 4-bit decode kernel, at twice the bytes.  One wave per row at a time, 16 codes per lane and
+// Weight-only 8-bit linear, M = 1: y[n] = sum_k x[k] q[n][k] s[n][k/g], for the shapes the
+// streaming kernel (w8a16_gemv.hip) does not take.  One wave per row at a time, 16 codes per lane and
 // load; bytes are converted with v_cvt_f32_ubyte after flipping the sign bit (u = q + 128), so
 //   sum_k x q = sum_k x u - 128 sum_k x,   with sum_k x per group staged beside x in LDS.
 constexpr int kW8Waves = 16;
@@ -206,6 +206,7 @@ hipError_t launch_act_quant_s8(const float* a, size_t n, const float* s_a, uint3
 
 hipError_t launch_w8a16_linear(const qail_wdesc& d, const uint32_t* qw, const uint16_t* sc, const uint16_t* x,
                                uint16_t* y, int M, hipStream_t st) {
+    if (w8a16_stream_supports(d, M)) return launch_w8a16_stream(d, qw, sc, x, y, st);
     const int G = d.K / d.group_size;
     const size_t lds = ((size_t)d.K + G) * 4;
     if (M == 1 && d.K % 16 == 0 && d.group_size % 16 == 0 && lds <= 64 * 1024) {

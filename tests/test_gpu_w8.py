@@ -118,7 +118,13 @@ def test_w8a8_extremes(B):
 
 
 @pytest.mark.parametrize("M", [1, 5])
-@pytest.mark.parametrize("N,K,g", [(300, 4096, 128), (64, 11008, 128), (33, 256, 32), (7, 40, 8)])
+@pytest.mark.parametrize("N,K,g", [(300, 4096, 128), (64, 11008, 128), (33, 256, 32), (7, 40, 8),
+                                   (5, 16, 16),            # one stretch of one chunk
+                                   (40, 4096, 1024),       # a group is a chunk
+                                   (24, 8192, 2048),       # a group is two chunks
+                                   (18, 12288, 64),        # the longest K of the streaming kernel
+                                   (20, 12304, 16),        # just beyond it: row-wise kernel
+                                   (300000, 16, 16)])      # more rows than 256 blocks x 16 waves x 64 hold: extra blocks
 def test_w8a16_linear(B, M, N, K, g):
     import torch
     w = synth.llm_weight(N, K, 50 + N, outlier_frac=0.01)
