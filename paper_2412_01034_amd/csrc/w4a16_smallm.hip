@@ -22,6 +22,8 @@
 //     nothing stored while loads fly).  The K parts' 16 x 16 partial results meet once, after the
 //     stream, in LDS and are added in a fixed order (deterministic).
 //   * As for M = 1, one launch serves a list of linears, blocks divided by bytes.
+#include <string.h>
+
 #include "qail_internal.h"
 
 namespace qail {
@@ -36,6 +38,7 @@ constexpr int kRing = 8;                  // wave-wide loads in flight per wave
 constexpr int kXBytes = 128 * 1024;       // LDS for the staged activations
 constexpr int kTilesPerBlock = 16;
 
+// 64 bytes, so that a block fetches everything it needs to know with one scalar load.
 struct SmItem {
     const uint32_t* qw;
     const uint16_t* sc;
@@ -43,12 +46,16 @@ struct SmItem {
     const uint16_t* x;
     uint16_t* y;
     int N, K, g;
-    int block_begin, blocks;
+    int block_begin;  // first block of the grid that works on this item
+    int tiles_base;   // block b of the item owns tiles_base tiles, one more if b < tiles_rem,
+    int tiles_rem;    // in the order of the blocks
 };
+
+constexpr int kSmMaxBlocks = 4096;  // blocks of a launch that serves more than one item
 
 struct SmArgs {
     SmItem it[kSmMaxItems];
-    int count;
+    uint32_t item_of_block[kSmMaxBlocks / 8];  // 4 bits per block; blocks past the table work on item 0
     int M;
 };
 
@@ -66,17 +73,17 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     const int li = lane & 15, kb = lane >> 4;
     const int M = args.M;
 
+    // two dependent scalar loads and no division between the start of the block and its first
+    // weight load: the block's item from a 4-bit table, then the item's 64-byte record
     int idx = 0;
-    while (idx + 1 < args.count && args.it[idx + 1].block_begin <= (int)blockIdx.x) ++idx;
+    if (blockIdx.x < (unsigned)kSmMaxBlocks) idx = (args.item_of_block[blockIdx.x / 8] >> (4 * (blockIdx.x % 8))) & 15;
     idx = __builtin_amdgcn_readfirstlane(idx);
-    const SmItem& it = args.it[idx];
+    const SmItem it = args.it[idx];
     const int K = it.K, N = it.N, g = it.g;
     const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
-    const int ntiles = (N + 15) / 16;
     const int b = (int)blockIdx.x - it.block_begin;
-    const int tile0 = (int)(((long long)ntiles * b) / it.blocks);
-    const int tile1 = (int)(((long long)ntiles * (b + 1)) / it.blocks);
-    const int nt = tile1 - tile0;   // at most kTilesPerBlock (the launcher sees to it)
+    const int tile0 = b * it.tiles_base + min(b, it.tiles_rem);
+    const int nt = it.tiles_base + (b < it.tiles_rem ? 1 : 0);   // at most kTilesPerBlock (the launcher sees to it)
     if (nt <= 0) return;            // block-uniform
 
     // (tile, K part) of this wave: as many K parts as keep the 16 waves busy
@@ -296,18 +303,29 @@ hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipSt
         frac[best] = -1.0;
         ++used;
     }
+    if (count > 1 && used > kSmMaxBlocks) {
+        // the block-to-item table is too short: one launch per item (a lone item needs no table)
+        for (int i = 0; i < count; ++i) {
+            const hipError_t e = sm_launch_chunk(items + i, 1, M, st);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    memset(a.item_of_block, 0, sizeof(a.item_of_block));
     int bb = 0;
     for (int i = 0; i < count; ++i) {
         const qail_w4a16_item& s = items[i];
         SmItem& t = a.it[i];
+        const int ntiles = (s.d.N + 15) / 16;
         t.qw = s.qweight; t.sc = s.scales; t.zr = s.zeros; t.x = s.x; t.y = s.y;
         t.N = s.d.N; t.K = s.d.K; t.g = s.d.group_size;
         t.block_begin = bb;
-        t.blocks = nb[i];
+        t.tiles_base = ntiles / nb[i];
+        t.tiles_rem = ntiles % nb[i];
+        for (int b = bb; b < bb + nb[i] && b < kSmMaxBlocks; ++b) a.item_of_block[b / 8] |= (uint32_t)i << (4 * (b % 8));
         bb += nb[i];
     }
     for (int i = count; i < kSmMaxItems; ++i) a.it[i] = a.it[count - 1];
-    a.count = count;
     a.M = M;
     hipLaunchKernelGGL(w4a16_smallm_kernel, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
     return hipGetLastError();
