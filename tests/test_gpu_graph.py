@@ -1,0 +1,76 @@
+"""The library under HIP graph capture: every entry point only launches kernels on the caller's
+stream (no allocation, no memset, no synchronisation), so a decode step or a whole encoder pass
+can be captured once and replayed.  Each replay must reproduce the eager results bit for bit."""
+import numpy as np
+import pytest
+
+from tests.helpers import dev, ensure_built, host, ws_for
+from paper_2412_01034_amd import synth
+from oracle import qail_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    return ensure_built()
+
+
+def _linear_case(B, N, K, g, M, seed):
+    import torch
+    w = synth.llm_weight(N, K, seed, outlier_frac=0.01)
+    xb = synth.llm_activation_bf16(M, K, seed + 1)
+    q, s, z = O.quantize_w4_asym_group(w, g)
+    qw, zw = O.pack_w4a16(q, z)
+    t = dict(N=N, K=K, g=g, M=M, qw=dev(qw), s=dev(s.view(np.uint16)), z=dev(zw), x=dev(xb),
+             y=torch.zeros(M * N, dtype=torch.int16, device="cuda"),
+             ws=ws_for(B, B.qail_w4a16_workspace(N, K, g, M)))
+    return t
+
+
+def _run_linear(B, t):
+    B.qail_w4a16_linear(t["N"], t["K"], t["g"], t["qw"], t["s"], t["z"], t["x"], t["y"], t["M"], t["ws"])
+
+
+def test_replays_match_eager(B):
+    import torch
+    # one case per W4A16 kernel: M = 1 stream, four-row stream, small batch, matrix-core GEMM with
+    # tiles shared between blocks (K = 8192: 64 steps), and a convolution
+    lin = [_linear_case(B, 256, 4096, 128, 1, 11), _linear_case(B, 64, 11008, 128, 4, 12),
+           _linear_case(B, 80, 4096, 128, 16, 13), _linear_case(B, 300, 8192, 128, 100, 14)]
+    s = synth.ConvShape("graph", B=2, H=14, W=14, Cin=64, Cout=64, KH=3, KW=3, stride=1, pad=1)
+    rng = np.random.default_rng(5)
+    a = dev(rng.integers(0, 2 ** 32, size=s.B * s.H * s.W * s.Cin // 8, dtype=np.uint64).astype(np.uint32))
+    ww = dev(rng.integers(0, 2 ** 32, size=s.Cout * s.K // 8, dtype=np.uint64).astype(np.uint32))
+    acc = torch.zeros(s.M * s.Cout, dtype=torch.int32, device="cuda")
+
+    def step():
+        for t in lin:
+            _run_linear(B, t)
+        B.qail_w4a4_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww, acc_out=acc)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [host(t["y"], np.uint16).copy() for t in lin] + [host(acc, np.int32).copy()]
+
+    def clear():
+        for t in lin:
+            t["y"].fill_(0x7FC0)
+        acc.fill_(-1)
+
+    gs = torch.cuda.Stream()
+    with torch.cuda.stream(gs):
+        clear()
+        step()          # eager; also the first call of every kernel (attributes are set here, not under capture)
+        want = snapshot()
+        clear()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=gs):
+            step()
+        for _ in range(3):
+            clear()                   # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            got = snapshot()
+            for g_, w_ in zip(got, want):
+                assert np.array_equal(g_, w_)
