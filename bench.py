@@ -374,6 +374,34 @@ def main():
                                                "TOPs": round(tot_ops / tf_ / 1e12, 1),
                                                "frac_int8_peak": round(tot_ops / tf_ / 1e12 / INT8_PEAK_TOPS, 4),
                                                "calls": len(fcalls), "per_shape": fper}
+        # the same body at batch 256 with the fused 4-bit output: the matrix-core-bound regime of the
+        # same kernels (batch 32 above is bound by per-call fixed cost); one code tensor per input
+        # shape, one output tensor per output shape
+        convs256 = synth.resnet34_convs(256)
+        big, ops256, cache_a, cache_o = [], 0, {}, {}
+        for s2 in convs256:
+            ka, ko = (s2.H, s2.Cin), (s2.M, s2.Cout)
+            if ka not in cache_a:
+                cache_a[ka] = dev(rng.integers(0, 2 ** 32, size=s2.B * s2.H * s2.W * s2.Cin // 8,
+                                               dtype=np.uint64).astype(np.uint32))
+            if ko not in cache_o:
+                cache_o[ko] = torch.empty(s2.M * s2.Cout // 8, dtype=torch.int32, device="cuda")
+            w2 = dev(rng.integers(0, 2 ** 32, size=s2.Cout * s2.K // 8, dtype=np.uint64).astype(np.uint32))
+            sc2 = torch.full((s2.Cout,), 1e-3, dtype=torch.float32, device="cuda")
+            bi2 = torch.zeros(s2.Cout, dtype=torch.float32, device="cuda")
+            big.append((s2, cache_a[ka], w2, sc2, bi2, cache_o[ko]))
+            ops256 += s2.ops
+
+        def body256():
+            for s2, a2, w2, sc2, bi2, o2 in big:
+                B.qail_w4a4_conv_u4(s2.B, s2.H, s2.W, s2.Cin, s2.Cout, s2.KH, s2.KW, s2.stride, s2.pad, a2, w2, sc2, bi2,
+                                    0.37, o2, stream=sh)
+        t256 = timed(body256, 5, settle=True)
+        extra["w4a4_resnet34_b256_fused_u4"] = {"ms_per_pass": round(t256 * 1e3, 4),
+                                                "TOPs": round(ops256 / t256 / 1e12, 1),
+                                                "frac_int8_peak": round(ops256 / t256 / 1e12 / INT8_PEAK_TOPS, 4),
+                                                "calls": len(big)}
+        del big, cache_a, cache_o
         # 8-bit variants: the same 35 conv calls as W8A8, and the decode layer with 8-bit weights only
         c8 = []
         for s, a, ww, scale, bias, y in calls:
