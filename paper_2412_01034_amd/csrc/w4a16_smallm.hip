@@ -17,7 +17,7 @@
 //     (all of K when M * K * 2 bytes fit in 128 KB, else pass by pass), so a wave can walk any
 //     stretch of K of a tile without holding x in registers and the stream has no barrier.
 //   * A block owns at most 16 tiles.  Its 16 waves are dealt to (tile, K part) pairs, with as many
-//     K parts (a power of two) as keeps all waves busy; every wave keeps a ring of loads in
+//     K parts as the 16 waves allow (16 / tiles); every wave keeps a ring of loads in
 //     flight with exact load waits (unconditional loads, program order = consumption order,
 //     nothing stored while loads fly).  The K parts' 16 x 16 partial results meet once, after the
 //     stream, in LDS and are added in a fixed order (deterministic).
@@ -35,7 +35,7 @@ constexpr int kSmWaves = 16;
 constexpr int kSmThreads = kSmWaves * kWave;
 constexpr int kStepK = 128;               // k per wave-wide load
 constexpr int kRing = 8;                  // wave-wide loads in flight per wave
-constexpr int kXBytes = 128 * 1024;       // LDS for the staged activations
+constexpr int kXBytes = 32 * 16 * 17 * 16; // LDS for the staged activations: M = 16 at K = 4096 in one pass
 constexpr int kTilesPerBlock = 16;
 
 // 64 bytes, so that a block fetches everything it needs to know with one scalar load.
@@ -59,15 +59,32 @@ struct SmArgs {
     int M;
 };
 
-// LDS: [kXBytes] activations, [max steps per pass][16] fp32 step sums, [16 waves][256] fp32 partials.
+// LDS: [kXBytes] activations (after the stream: [16 waves][256] fp32 partials), [max steps per pass][16]
+// fp32 step sums.
 constexpr int kMaxPassSteps = kXBytes / (16 * 3 * 16) + 6;  // M >= 2 (3 rows per block): steps per pass, rounded up
-constexpr size_t kSmLdsBytes = (size_t)kXBytes + (size_t)kMaxPassSteps * 16 * 4 + (size_t)kSmWaves * 256 * 4;
+constexpr size_t kSmLdsBytes = (size_t)kXBytes + (size_t)kMaxPassSteps * 16 * 4;
+static_assert(kSmWaves * 256 * 4 <= kXBytes, "the partial tiles reuse the activations' space");
+
+// Rows per LDS block and 128-k steps per pass over K for a batch of M rows and S steps in all.
+// Rows beyond M read a row of zeros appended to every block (M = 16 needs none).  A block holds
+// an odd number of 16-byte rows, so that the 16 pieces of one row of x in one step, which 16
+// neighbouring threads write into the step's 16 blocks, fall into 16 different groups of LDS
+// banks -- unless that costs a pass more over K.  A pass is at most 512 (row, step) pairs, so
+// that its x travels through 8 registers per thread.
+__host__ __device__ inline void sm_plan(int M, int S, int* rows, int* pass_steps) {
+    const int rmin = M == 16 ? 16 : M + 1;
+    const int cap = 512 / M;
+    const int smin = min(min(kXBytes / (256 * rmin), cap), S), sodd = min(min(kXBytes / (256 * (rmin | 1)), cap), S);
+    const bool odd = (S + sodd - 1) / sodd <= (S + smin - 1) / smin;
+    *rows = odd ? (rmin | 1) : rmin;
+    *pass_steps = odd ? sodd : smin;
+}
 
 __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs args) {
     extern __shared__ __attribute__((aligned(16))) unsigned char sm_lds[];
     unsigned char* xl = sm_lds;
     float* xs_tab = reinterpret_cast<float*>(sm_lds + kXBytes);
-    float* partial = xs_tab + kMaxPassSteps * 16;
+    float* partial = reinterpret_cast<float*>(sm_lds);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
     const int li = lane & 15, kb = lane >> 4;
@@ -87,8 +104,7 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     if (nt <= 0) return;            // block-uniform
 
     // (tile, K part) of this wave: as many K parts as keep the 16 waves busy
-    int ksplit = 1;
-    while (nt * ksplit * 2 <= kSmWaves) ksplit *= 2;
+    const int ksplit = kSmWaves / nt;
     const int slot = wave / ksplit, kpart = wave % ksplit;
     const bool active = slot < nt;
     const int S = K / kStepK;
@@ -97,13 +113,12 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
 
     // LDS layout of x: block (step, j, kb) holds, for each row m, the 16 bytes that lane (m, kb)
     // feeds to MFMA j of that step: x[m][128 step + 32 kb + 8 j + (0..7)] in the pair order
-    // x0,x4 | x1,x5 | x2,x6 | x3,x7 that the nibble expansion produces.  Rows beyond M read a
-    // row of zeros appended to every block (M = 16 needs none).
-    const int Mp = M == 16 ? 16 : M + 1;
+    // x0,x4 | x1,x5 | x2,x6 | x3,x7 that the nibble expansion produces.
+    int Mp, pass_steps;
+    sm_plan(M, S, &Mp, &pass_steps);
     const int step_bytes = 16 * Mp * 16;                       // 16 (j, kb) blocks per step
-    const int pass_steps = min(S, kXBytes / step_bytes);
     const int npass = (S + pass_steps - 1) / pass_steps;
-    const int xrow = min(li, Mp - 1) * 16;                     // this lane's row inside a block
+    const int xrow = min(li, M) * 16;                          // this lane's row inside a block (li <= 15)
 
     uint32_t magic = 0x43004300u;    // bf16 pair (128, 128); in a vector register so that the
     asm volatile("" : "+v"(magic));  // AND-OR needs only one scalar operand
@@ -138,56 +153,68 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
             __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
         }
     };
-    // the first pass's weights are requested before the activations are staged: they do not
-    // depend on x, and the staging then hides their latency
-    {
-        const int k0 = max(my0, 0), k1 = min(my1, min(S, pass_steps));
-        if (active && k1 > k0) prologue(k0, k1);
-    }
+    // Staging: 16 neighbouring threads take the 16 pieces (16 bytes each) of one (step, row) pair,
+    // pair p = step * M + row; p / M for p < 4096 is a multiplication.
+    const uint32_t inv_m = (65536u + (uint32_t)M - 1u) / (uint32_t)M;
+    const int tg = threadIdx.x >> 4, t16 = threadIdx.x & 15;
+    const int blk_off = ((t16 & 3) * 4 + (t16 >> 2)) * (Mp * 16);   // block (j, kb) of piece 4 kb + j
+    uint4 xr[8];
+    const char* xbase = reinterpret_cast<const char*>(it.x);   // M * K < 2^31 elements: 32-bit offsets
 
     for (int pass = 0; pass < npass; ++pass) {
         const int p0 = pass * pass_steps, p1 = min(S, p0 + pass_steps);
+        const int pairs = (p1 - p0) * M;
         if (pass) __syncthreads();  // the previous pass's activations are no longer read
-        // ---- stage x[:, 128 p0 .. 128 p1) and the zero rows
-        {
-            const int chunks = (p1 - p0) * 16;  // 16-byte pieces per row
-            for (int e = threadIdx.x; e < chunks * M; e += kSmThreads) {
-                const int m = e / chunks, c = e - m * chunks;
-                const uint4 v = *reinterpret_cast<const uint4*>(it.x + (size_t)m * K + (size_t)p0 * kStepK + c * 8);
+        // ---- the pass's x is requested first, then the first weights of the pass: loads return
+        // in order, x is needed first, and the staging then hides the weights' latency
+        int tg1 = tg;                    // worked out per pass rather than kept in registers
+        asm volatile("" : "+v"(tg1));
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int pi = tg1 + 64 * u;
+            if (pi < pairs) {
+                const int sx = (int)(((uint32_t)pi * inv_m) >> 16), m = pi - sx * M;
+                xr[u] = *reinterpret_cast<const uint4*>(xbase + ((uint32_t)(m * K + (p0 + sx) * kStepK + t16 * 8) * 2u));
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const int k0 = max(my0, p0), k1 = min(my1, p1);
+        const int n = active ? max(0, k1 - k0) : 0;
+        if (n > 0) prologue(k0, k1);
+        // ---- stage x[:, 128 p0 .. 128 p1), its sums over each step, and the zero rows
+        int tg2 = tg;                    // the pairs are worked out again rather than kept in
+        asm volatile("" : "+v"(tg2));    // registers across the loads
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int pi = tg2 + 64 * u;
+            if (pi < pairs) {
+                const int sx = (int)(((uint32_t)pi * inv_m) >> 16), m = pi - sx * M;
+                const uint4 v = xr[u];
                 uint4 o;
                 o.x = (v.x & 0xFFFFu) | (v.z << 16);      // x0,x4
                 o.y = (v.x >> 16) | (v.z & 0xFFFF0000u);  // x1,x5
                 o.z = (v.y & 0xFFFFu) | (v.w << 16);      // x2,x6
                 o.w = (v.y >> 16) | (v.w & 0xFFFF0000u);  // x3,x7
-                const int s = c >> 4, kbb = (c >> 2) & 3, j = c & 3;
-                *reinterpret_cast<uint4*>(xl + s * step_bytes + (j * 4 + kbb) * (Mp * 16) + m * 16) = o;
-            }
-            if (Mp != M)
-                for (int e = threadIdx.x; e < (p1 - p0) * 16; e += kSmThreads)
-                    *reinterpret_cast<uint4*>(xl + (e >> 4) * step_bytes + (e & 15) * (Mp * 16) + M * 16) = make_uint4(0, 0, 0, 0);
-        }
-        __syncthreads();
-        // ---- sums of x over each step, per row, in a fixed order
-        for (int e = threadIdx.x; e < (p1 - p0) * 16; e += kSmThreads) {
-            const int s = e >> 4, m = e & 15;
-            float t = 0.f;
-            if (m < M) {
+                *reinterpret_cast<uint4*>(xl + sx * step_bytes + blk_off + m * 16) = o;
+                // the step's sum of this row: 8 values here, then the 16 pieces in a fixed tree
+                const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+                float t = 0.f;
 #pragma unroll
-                for (int blk = 0; blk < 16; ++blk) {
-                    const uint4 v = *reinterpret_cast<const uint4*>(xl + s * step_bytes + blk * (Mp * 16) + m * 16);
-                    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        t += __builtin_bit_cast(float, u[q] << 16) + __builtin_bit_cast(float, u[q] & 0xFFFF0000u);
-                }
+                for (int q4 = 0; q4 < 4; ++q4)
+                    t += __builtin_bit_cast(float, w4[q4] << 16) + __builtin_bit_cast(float, w4[q4] & 0xFFFF0000u);
+                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x128, 0xF, 0xF, true));  // row_ror:8
+                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x124, 0xF, 0xF, true));  // row_ror:4
+                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x122, 0xF, 0xF, true));  // row_ror:2
+                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x121, 0xF, 0xF, true));  // row_ror:1
+                if (t16 == 0) xs_tab[sx * 16 + m] = t;
             }
-            xs_tab[e] = t;
         }
+        if (Mp != M)
+            for (int e = threadIdx.x; e < (p1 - p0) * 16; e += kSmThreads)
+                *reinterpret_cast<uint4*>(xl + (e >> 4) * step_bytes + (e & 15) * (Mp * 16) + M * 16) = make_uint4(0, 0, 0, 0);
         __syncthreads();
 
         // ---- this wave's steps inside the pass
-        const int k0 = max(my0, p0), k1 = min(my1, p1);
-        const int n = active ? max(0, k1 - k0) : 0;
         if (n > 0) {
             auto consume = [&](int p, int step) {
                 const unsigned char* xb = xl + (step - p0) * step_bytes + kb * (Mp * 16) + xrow;
@@ -211,7 +238,6 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
                 acc[3] = fmaf(s, fmaf(-zc, xs.w, d[3]), acc[3]);
             };
             const int last = k1 - 1;
-            if (pass) prologue(k0, k1);
             int t = 0;
             // Refills go out four at a time: the four loads of a row then cover 256 contiguous
             // bytes and reach DRAM together, instead of 64 isolated bytes from each of 16 rows.
@@ -234,6 +260,7 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     }
 
     // ---- the K parts of a tile meet in LDS; y[m][tile*16 + n] = sum over parts, parts in order
+    __syncthreads();  // x is no longer read
     float* dst = partial + wave * 256 + lane;
 #pragma unroll
     for (int r = 0; r < 4; ++r) dst[r * kWave] = acc[r];
@@ -278,29 +305,54 @@ hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipSt
     SmArgs a;
     int grid = sm_device_cus();
     if (grid < count) grid = count;
-    double total = 0;
-    for (int i = 0; i < count; ++i) total += (double)sm_item_bytes(items[i].d);
+    // Blocks per item: a block's time is taken as its bytes plus, per pass over K, the bytes it could
+    // have streamed while a pass's activations are fetched and staged (a figure measured on this GPU);
+    // the smallest common bound T on that cost that the grid can meet decides the division.
+    constexpr double kPassCost = 100.0 * 1024;
     int nb[kSmMaxItems], lo[kSmMaxItems], hi[kSmMaxItems];
-    double frac[kSmMaxItems];
-    int used = 0;
+    double bytes[kSmMaxItems], fixed[kSmMaxItems];
+    double t_lo = 0, t_hi = 0;
     for (int i = 0; i < count; ++i) {
         const int ntiles = (items[i].d.N + 15) / 16;
         lo[i] = (ntiles + kTilesPerBlock - 1) / kTilesPerBlock;  // a block owns at most 16 tiles
         hi[i] = ntiles;
-        const double share = (double)sm_item_bytes(items[i].d) / total * grid;
-        nb[i] = (int)share;
-        if (nb[i] < lo[i]) nb[i] = lo[i];
-        if (nb[i] > hi[i]) nb[i] = hi[i];
-        frac[i] = share - (int)share;
-        used += nb[i];
+        int rows, ps;
+        const int S = items[i].d.K / kStepK;
+        sm_plan(M, S, &rows, &ps);
+        bytes[i] = (double)sm_item_bytes(items[i].d);
+        fixed[i] = kPassCost * ((S + ps - 1) / ps);
+        if (fixed[i] + bytes[i] > t_hi) t_hi = fixed[i] + bytes[i];
     }
-    while (used < grid) {
+    auto blocks_for = [&](double T, int* out) {
+        int used = 0;
+        for (int i = 0; i < count; ++i) {
+            int n = hi[i];
+            if (T > fixed[i]) {
+                const double need = bytes[i] / (T - fixed[i]);
+                n = need >= (double)hi[i] ? hi[i] : (int)need + 1;
+            }
+            if (n < lo[i]) n = lo[i];
+            if (n > hi[i]) n = hi[i];
+            out[i] = n;
+            used += n;
+        }
+        return used;
+    };
+    for (int iter = 0; iter < 40; ++iter) {
+        const double T = 0.5 * (t_lo + t_hi);
+        if (blocks_for(T, nb) <= grid) t_hi = T;
+        else t_lo = T;
+    }
+    int used = blocks_for(t_hi, nb);
+    while (used < grid) {   // left-over blocks go where a block's cost is highest
         int best = -1;
-        for (int i = 0; i < count; ++i)
-            if (nb[i] < hi[i] && (best < 0 || frac[i] > frac[best])) best = i;
+        double best_cost = 0;
+        for (int i = 0; i < count; ++i) {
+            const double c = fixed[i] + bytes[i] / nb[i];
+            if (nb[i] < hi[i] && (best < 0 || c > best_cost)) best = i, best_cost = c;
+        }
         if (best < 0) break;
         ++nb[best];
-        frac[best] = -1.0;
         ++used;
     }
     if (count > 1 && used > kSmMaxBlocks) {
