@@ -208,7 +208,7 @@ def test_homogeneity_and_determinism(B):
 def test_batch_equals_single_calls(B):
     import torch
     shapes = [(160, 4096, 128), (48, 4096, 128), (70, 11008, 128), (33, 1024, 64), (9, 40, 8)]
-    for M in (1, 4):
+    for M in (1, 4, 9, 16):
         ents, singles = [], []
         for i, (N, K, g) in enumerate(shapes):
             w = synth.llm_weight(N, K, 40 + i)
@@ -226,10 +226,11 @@ def test_batch_equals_single_calls(B):
             assert np.array_equal(host(e["y"], np.uint16).reshape(ref.shape), ref)
 
 
-def _sampled_full_size(B, M, x_kw, rows_per_linear=96, m_rows=8):
+def _sampled_full_size(B, M, x_kw, rows_per_linear=96, m_rows=8, batched=True):
     """The four Llama-2-7B linears at full size through the batched call (the
-    launch configuration the benchmark times); the GPU quantises the full
-    matrices, the oracle re-derives sampled rows only (rows are independent)."""
+    launch configuration the benchmark times) or one call per linear; the GPU
+    quantises the full matrices, the oracle re-derives sampled rows only (rows
+    are independent)."""
     import torch
     rng = np.random.default_rng(77)
     ents, keep = [], []
@@ -250,9 +251,14 @@ def _sampled_full_size(B, M, x_kw, rows_per_linear=96, m_rows=8):
                          y=torch.zeros(M * N, dtype=torch.int16, device="cuda")))
         keep.append((w[rows], xb, rows))
         del w
-    items = B.make_w4a16_items(ents, M)
-    ws = ws_for(B, B.qail_w4a16_batch_workspace(items, len(ents), M))
-    B.qail_w4a16_linear_batch(items, len(ents), M, ws)
+    if batched:
+        items = B.make_w4a16_items(ents, M)
+        ws = ws_for(B, B.qail_w4a16_batch_workspace(items, len(ents), M))
+        B.qail_w4a16_linear_batch(items, len(ents), M, ws)
+    else:
+        for e in ents:
+            ws = ws_for(B, B.qail_w4a16_workspace(e["N"], e["K"], 128, M))
+            B.qail_w4a16_linear(e["N"], e["K"], 128, e["qweight"], e["scales"], e["zeros"], e["x"], e["y"], M, ws)
     torch.cuda.synchronize()
     ms = np.unique(np.linspace(0, M - 1, m_rows).astype(int))
     worst = 0.0
@@ -271,8 +277,18 @@ def _sampled_full_size(B, M, x_kw, rows_per_linear=96, m_rows=8):
     assert worst <= TOL, worst
 
 
-def test_full_size_decode_linears_sampled(B):
-    _sampled_full_size(B, 1, {})
+@pytest.mark.parametrize("M", [1, 4, 5, 16])
+def test_full_size_decode_linears_sampled(B, M):
+    # M = 1: the benchmark's headline launch; 4, 16: its decode-stack lines (four-row stream, small-batch
+    # kernel with 10-11 tiles per block and, at M = 16, three passes over the down projection's K)
+    _sampled_full_size(B, M, {})
+
+
+@pytest.mark.parametrize("M", [3, 6, 16])
+def test_full_size_decode_linears_one_call_each(B, M):
+    # alone, a linear gets the whole grid: 1 to 6 tiles per block in the small-batch kernel, hence
+    # 16, 5, 3 and 2 K parts per tile
+    _sampled_full_size(B, M, {}, rows_per_linear=48, batched=False)
 
 
 @pytest.mark.parametrize("M", [288, 1024])
