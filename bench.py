@@ -260,12 +260,14 @@ def main():
 
         # decode stack walk: 32 layer-steps per token (the loaded layers cycled), 7 tokens
         stack = {}
-        for M in (1, 4, 16):
+        for M in (1, 4, 16, 64):
             io = dec if M == 1 else with_io(M)
+            nws = B.qail_w4a16_batch_workspace(io[0][0], 4, M)   # M > 16: the matrix-core GEMM's
+            wsk = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
 
             def walk():
                 for l in range(32):
-                    B.qail_w4a16_linear_batch(io[l % L][0], 4, M, None, sh)
+                    B.qail_w4a16_linear_batch(io[l % L][0], 4, M, wsk, sh)
             t = timed(walk, 7, warm=1)
             stack[f"M={M}"] = {"ms_per_token_step": round(t * 1e3, 4), "tokens_per_s": round(M / t, 1),
                                "GBps": round(32 * sum(linear_bytes(N, K, M) for _, N, K in shapes) / t / 1e9, 1)}
@@ -312,6 +314,13 @@ def main():
                 tf = 2.0 * M * N * K / t / 1e12
                 pre[f"{name}_M{M}"] = {"us": round(t * 1e6, 1), "TFLOPs": round(tf, 1),
                                        "frac_bf16_peak": round(tf / BF16_PEAK_TFLOPS, 4)}
+            # the same four linears as one batched call: they share launches, each on a share of the blocks
+            nws = B.qail_w4a16_batch_workspace(io[0][0], 4, M)
+            ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+            t = timed(lambda: B.qail_w4a16_linear_batch(io[0][0], 4, M, ws, sh), 20, settle=True)
+            tf = sum(2.0 * M * N * K for _, N, K in shapes) / t / 1e12
+            pre[f"layer_batched_M{M}"] = {"us": round(t * 1e6, 1), "TFLOPs": round(tf, 1),
+                                          "frac_bf16_peak": round(tf / BF16_PEAK_TFLOPS, 4)}
             del io
         extra["prefill_gemm"] = pre
 

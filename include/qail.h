@@ -170,12 +170,17 @@ typedef struct {
 /* `count` linears with the same M, given as a HOST array, enqueued on one stream
  * (appendix "Analysis": a decode step is a fixed sequence of such linears, 4 per
  * layer).  The items must be independent: no item may read what another writes.
- * Result is the same as `count` calls of qail_w4a16_linear; the library may run
- * them in fewer launches.  count >= 0 (0 is a no-op). */
+ * The library may run them in fewer launches, items side by side on shares of the
+ * GPU.  The result is that of `count` calls of qail_w4a16_linear: bit for bit for
+ * M <= 4; for larger M an item's sum over K may be divided between waves or blocks
+ * at other places than in a call of its own, so the two can differ by the rounding
+ * of fp32 partial sums (far inside the W4A16 tolerance); the same call on the same
+ * GPU always gives the same bits.  count >= 0 (0 is a no-op). */
 int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t M,
                             void* workspace, size_t workspace_bytes, void* stream);
-/* Workspace for the batch call: the largest need of any item (the items run one after
- * the other on the stream and share it). */
+/* Workspace for the batch call.  Items that share a launch (M > 16: up to 8 at a time)
+ * keep their prepared activations side by side in it, so the need can exceed that of
+ * any single item; launches that follow each other on the stream reuse it. */
 int qail_w4a16_batch_workspace(const qail_w4a16_item* items, int32_t count, int32_t M,
                                size_t* bytes);
 

@@ -146,6 +146,29 @@ static size_t item_workspace(const qail_wdesc& d, int M) {
     return gemm_f16_workspace(d, M);
 }
 
+// Whether item `it` of a batch at M goes to the matrix-core GEMM.
+static bool takes_gemm(const qail_wdesc& d, int M) {
+    return M > 1 && !decode4_supports(d, M) && !smallm_supports(d, M) && gemm_f16_supports(d, M);
+}
+
+// Workspace of a batch: consecutive linears of the matrix-core GEMM share launches and lie side
+// by side in it; runs follow each other on the stream and reuse it.
+static size_t batch_need(const qail_w4a16_item* items, int count, int M) {
+    size_t need = 0;
+    int i = 0;
+    while (i < count) {
+        int j = i;
+        while (j < count && takes_gemm(items[j].d, M)) ++j;
+        if (j > i) {
+            need = std::max(need, gemm_f16_batch_workspace(items + i, j - i, M));
+            i = j;
+        } else {
+            ++i;
+        }
+    }
+    return need;
+}
+
 int qail_w4a16_workspace(const qail_wdesc* d, int32_t M, size_t* bytes) {
     const int e = check_wdesc(d);
     if (e != QAIL_OK) return e;
@@ -164,10 +187,7 @@ int qail_w4a16_batch_workspace(const qail_w4a16_item* items, int32_t count, int3
         if (e != QAIL_OK) return e;
         if (items[i].d.scheme != QAIL_W4_ASYM_GROUP) return QAIL_ERR_UNSUPPORTED;
     }
-    // the linears of a batch run one after the other on the stream and share the workspace
-    size_t need = 0;
-    for (int i = 0; i < count; ++i) need = std::max(need, item_workspace(items[i].d, M));
-    *bytes = need;
+    *bytes = batch_need(items, count, M);
     return QAIL_OK;
 }
 
@@ -176,12 +196,11 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
     if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
     if (count == 0) return QAIL_OK;
     if (!items) return QAIL_ERR_NULL;
-    size_t need = 0;
     for (int i = 0; i < count; ++i) {
         const int e = check_item(items[i], M);
         if (e != QAIL_OK) return e;
-        need = std::max(need, item_workspace(items[i].d, M));
     }
+    const size_t need = batch_need(items, count, M);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return QAIL_ERR_WORKSPACE;
         if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QAIL_ERR_ALIGN;
@@ -221,13 +240,13 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
             i = j;
             continue;
         }
-        const qail_wdesc& d = items[i].d;
-        hipError_t e;
-        if (gemm_f16_supports(d, M))
-            e = launch_w4a16_gemm_f16(items[i], M, workspace, st);
-        else
-            e = launch_w4a16_generic(items[i], M, st);
-        if (e != hipSuccess) return QAIL_ERR_HIP;
+        while (j < count && takes_gemm(items[j].d, M)) ++j;
+        if (j > i) {
+            if (launch_w4a16_gemm_f16_batch(items + i, j - i, M, workspace, st) != hipSuccess) return QAIL_ERR_HIP;
+            i = j;
+            continue;
+        }
+        if (launch_w4a16_generic(items[i], M, st) != hipSuccess) return QAIL_ERR_HIP;
         ++i;
     }
     return QAIL_OK;
@@ -266,12 +285,11 @@ int qail_w4a16_linear_lora_batch(const qail_w4a16_item* items, const qail_lora* 
     if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
     if (count == 0) return QAIL_OK;
     if (!items || !loras) return QAIL_ERR_NULL;
-    size_t base = 0;
     for (int i = 0; i < count; ++i) {
         const int e = check_item(items[i], M);
         if (e != QAIL_OK) return e;
-        base = std::max(base, item_workspace(items[i].d, M));
     }
+    const size_t base = batch_need(items, count, M);
     const int el = check_loras(items, loras, count);
     if (el != QAIL_OK) return el;
     const size_t need = round256(base) + round256((size_t)count * M * kLoraStride * sizeof(float));

@@ -69,6 +69,10 @@ hipError_t launch_w4a16_smallm(const qail_w4a16_item* items, int count, int M, h
 bool gemm_f16_supports(const qail_wdesc& d, int M);
 size_t gemm_f16_workspace(const qail_wdesc& d, int M);
 hipError_t launch_w4a16_gemm_f16(const qail_w4a16_item& it, int M, void* ws, hipStream_t st);
+// Several such linears (all supported, same M) in shared launches, each on a share of the blocks;
+// needs gemm_f16_batch_workspace() bytes.
+size_t gemm_f16_batch_workspace(const qail_w4a16_item* items, int count, int M);
+hipError_t launch_w4a16_gemm_f16_batch(const qail_w4a16_item* items, int count, int M, void* ws, hipStream_t st);
 hipError_t launch_w4a16_generic(const qail_w4a16_item& it, int M, hipStream_t st);
 
 // 8-bit variants.

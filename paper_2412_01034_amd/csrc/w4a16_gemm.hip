@@ -26,6 +26,8 @@
 // MFMA operand layout (32x32x16, wave64): lane l supplies row (A) / column (B) l%32 and
 // the 8 consecutive k starting at 8*(l/32); it receives D[8*(r/4) + 4*(l/32) + r%4][l%32]
 // for r = 0..15.  A = activations (rows m), B = weights (columns n).
+#include <algorithm>
+
 #include "qail_internal.h"
 
 namespace qail {
@@ -42,14 +44,35 @@ constexpr int kRowPad = 128;            // workspace rows are padded to this
 
 __host__ __device__ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
+constexpr int kGemmBatch = 8;           // linears that can share one launch
+
 // ---------------------------------------------------------------------------------------
-// Preparation: blocks [0, Mpad) rewrite one row of x each, the rest find the power of two
-// of each weight row's largest scale.
-__global__ __launch_bounds__(256) void gemm_prep_kernel(
-    const uint16_t* __restrict__ x, const uint16_t* __restrict__ sc, uint16_t* __restrict__ xh,
-    float* __restrict__ rscale, float* __restrict__ wmul, int M, int Mpad, int N, int K, int Kpad, int G) {
+// Preparation, for up to kGemmBatch linears at once (blockIdx.y): blocks [0, Mpad) rewrite one
+// row of x each, the rest find the power of two of each weight row's largest scale.
+struct PrepItem {
+    const uint16_t* x;
+    const uint16_t* sc;
+    uint16_t* xh;
+    float* rscale;
+    float* wmul;
+    int N, K, Kpad, G;
+};
+struct PrepBatch {
+    PrepItem it[kGemmBatch];
+    int M, Mpad;
+};
+
+__global__ __launch_bounds__(256) void gemm_prep_kernel(const PrepBatch args) {
     __shared__ uint32_t red[4];
     const int t = threadIdx.x;
+    const PrepItem pi = args.it[blockIdx.y];
+    const uint16_t* __restrict__ x = pi.x;
+    const uint16_t* __restrict__ sc = pi.sc;
+    uint16_t* __restrict__ xh = pi.xh;
+    float* __restrict__ rscale = pi.rscale;
+    float* __restrict__ wmul = pi.wmul;
+    const int M = args.M, Mpad = args.Mpad, N = pi.N, K = pi.K, Kpad = pi.Kpad, G = pi.G;
+    if ((int)blockIdx.x >= Mpad + (N + 31) / 32) return;   // the grid is as wide as the largest linear needs
     if ((int)blockIdx.x < Mpad) {
         const int m = blockIdx.x;
         uint4* dst = reinterpret_cast<uint4*>(xh + (size_t)m * Kpad);
@@ -161,6 +184,14 @@ struct GemmArgs {
     // K step of one tile): block b of P owns the units [b * units / P, (b + 1) * units / P)
     int Tm, tiles, steps, whole;
     float* partial;  // [2 P][tile] fp32: sums of tiles whose K range is shared between blocks
+    int block_begin, P;  // the linear is worked on by blocks [block_begin, block_begin + P) of the grid
+};
+
+// Up to kGemmBatch linears share a launch: each gets a share of the grid and is dealt to its
+// blocks exactly as if it had a launch of P blocks to itself.
+struct GemmBatch {
+    GemmArgs it[kGemmBatch];
+    int count;
 };
 
 // First unit of block b when `units` units are dealt to P blocks, and the block that owns unit u.
@@ -201,7 +232,7 @@ constexpr int kStages = 3;
 __host__ __device__ constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
 template <int MB, int WN>
-__global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) {
+__global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch args) {
     constexpr int kBM = 32 * MB;
     constexpr int kBN = 128 * WN;
     constexpr int kALoads = kBM / 16;             // wave-wide 1 KB loads per wave per step
@@ -214,15 +245,21 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
     const int lane = t % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(t / kWave);
     const int c = lane & 31, kb = lane >> 5;
+    int item = 0;
+#pragma unroll
+    for (int i = 1; i < kGemmBatch; ++i)
+        if (i < args.count && (int)blockIdx.x >= args.it[i].block_begin) item = i;
+    const GemmArgs ga = args.it[item];
+    const int bid = (int)blockIdx.x - ga.block_begin, P = ga.P;   // this block among the linear's own
     const int G = ga.K / ga.g, zwords = (G + 7) / 8, kw = ga.K / 8;
 
     uint32_t magic = 0x64006400u;
     asm volatile("" : "+v"(magic));  // in a VGPR: v_and_or_b32 takes one scalar operand only
 
     const long long units = (long long)(ga.tiles - ga.whole) * ga.steps;
-    const int unit0 = (int)first_unit(blockIdx.x, units, gridDim.x);
-    const int unit1 = (int)first_unit(blockIdx.x + 1, units, gridDim.x);
-    int wtile = blockIdx.x, unit = unit0;
+    const int unit0 = (int)first_unit(bid, units, P);
+    const int unit1 = (int)first_unit(bid + 1, units, P);
+    int wtile = bid, unit = unit0;
     for (;;) {
     // ---- one segment: K steps [ka, ka + steps) of one tile
     int tile, ka, steps;
@@ -231,7 +268,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
         tile = wtile;
         ka = 0;
         steps = ga.steps;
-        wtile += gridDim.x;
+        wtile += P;
     } else if (unit < unit1) {
         const int tt = unit / ga.steps;
         tile = ga.whole + tt;
@@ -243,7 +280,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
         break;
     }
     const bool whole = steps == ga.steps;
-    float* const pslot = ga.partial + (size_t)(2 * blockIdx.x + (first_shared ? 0 : 1)) * (kBM * kBN);
+    float* const pslot = ga.partial + (size_t)(2 * bid + (first_shared ? 0 : 1)) * (kBM * kBN);
     const int bm = (tile % ga.Tm) * kBM, bn = (tile / ga.Tm) * kBN;
 
     // Byte offsets of this lane's weight rows (WN 32-column blocks).  All tensors here are
@@ -509,12 +546,15 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmArgs ga) 
 
 // Adds up the slots of every tile whose K range was shared between blocks (in K order) and
 // finishes it like the main kernel does: y = sum * 2^-p(m) * 2^E(n), rounded once to bf16.
-// Grid: (tiles dealt in K steps, pieces of 256 4-float groups per tile); a thread owns one group.
+// Grid: (tiles dealt in K steps, pieces of 256 4-float groups per tile, linears); a thread owns one group.
 template <int MB, int WN>
-__global__ __launch_bounds__(256) void w4a16_gemm_fixup_kernel(const GemmArgs ga, int P) {
+__global__ __launch_bounds__(256) void w4a16_gemm_fixup_kernel(const GemmBatch args) {
     constexpr int kBM = 32 * MB, kBN = 128 * WN;
     static_assert((kBM * kBN / 4) % 256 == 0, "tiles split into whole pieces");
     const int t = threadIdx.x, lane = t % kWave, wave = t / kWave;
+    const GemmArgs ga = args.it[blockIdx.z];
+    const int P = ga.P;
+    if ((int)blockIdx.x >= ga.tiles - ga.whole) return;   // the grid is as wide as the largest tail
     const int tile = ga.whole + blockIdx.x;
     const long long units = (long long)(ga.tiles - ga.whole) * ga.steps;
     const long long u_first = (long long)blockIdx.x * ga.steps, u_last = u_first + ga.steps - 1;
@@ -585,8 +625,25 @@ int gemm_cus() {
 
 int gemm_max_blocks() { return gemm_cus() < kMaxGemmBlocks ? gemm_cus() : kMaxGemmBlocks; }
 
+// Fills in the work decomposition of one linear on `cus` blocks; returns the blocks it uses.
 template <int MB, int WN>
-hipError_t launch_tile(GemmArgs ga, bool split_tail, hipStream_t st) {
+int plan_tiles(GemmArgs& ga, bool split_tail, int cus) {
+    constexpr int kBM = 32 * MB, kBN = 128 * WN;
+    ga.Tm = (ga.M + kBM - 1) / kBM;
+    ga.tiles = ga.Tm * ((ga.N + kBN - 1) / kBN);
+    ga.steps = ga.Kpad / kBK;
+    ga.whole = split_tail ? ga.tiles / cus * cus : ga.tiles;
+    const int tail = ga.tiles - ga.whole;
+    const long long units = (long long)tail * ga.steps;
+    int P = ga.whole >= cus ? cus : ga.whole;
+    if (tail > 0 && P < cus) P = units < cus ? (int)units : cus;  // here whole == 0
+    ga.P = P;
+    return P;
+}
+
+// One launch for `n` linears that use the same tile, each on its own blocks (ga[i].block_begin, P set).
+template <int MB, int WN>
+hipError_t launch_tile(const GemmArgs* gas, int n, hipStream_t st) {
     constexpr int kBM = 32 * MB, kBN = 128 * WN;
     const size_t lds = (size_t)kStages * (kBM * 256 + 4 * WN * 2560);
     static bool attr_set = false;
@@ -596,39 +653,43 @@ hipError_t launch_tile(GemmArgs ga, bool split_tail, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int cus = gemm_max_blocks();
-    ga.Tm = (ga.M + kBM - 1) / kBM;
-    ga.tiles = ga.Tm * ((ga.N + kBN - 1) / kBN);
-    ga.steps = ga.Kpad / kBK;
-    ga.whole = split_tail ? ga.tiles / cus * cus : ga.tiles;
-    const int tail = ga.tiles - ga.whole;
-    const long long units = (long long)tail * ga.steps;
-    int P = ga.whole >= cus ? cus : ga.whole;
-    if (tail > 0 && P < cus) P = units < cus ? (int)units : cus;  // here whole == 0
-    hipLaunchKernelGGL((w4a16_gemm_f16_kernel<MB, WN>), dim3(P), dim3(256), lds, st, ga);
+    GemmBatch gb;
+    int grid = 0, max_tail = 0;
+    for (int i = 0; i < kGemmBatch; ++i) {
+        gb.it[i] = gas[i < n ? i : n - 1];
+        if (i < n) {
+            grid += gas[i].P;
+            // the second kernel is only needed when some block boundary falls inside a tile
+            const int tail = gas[i].tiles - gas[i].whole;
+            const long long units = (long long)tail * gas[i].steps;
+            bool shared = false;
+            for (int b = 1; b < gas[i].P && tail > 0 && !shared; ++b) shared = first_unit(b, units, gas[i].P) % gas[i].steps != 0;
+            if (shared && tail > max_tail) max_tail = tail;
+        }
+    }
+    gb.count = n;
+    hipLaunchKernelGGL((w4a16_gemm_f16_kernel<MB, WN>), dim3(grid), dim3(256), lds, st, gb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // the second kernel is only needed when some block boundary falls inside a tile
-    bool shared = false;
-    for (int b = 1; b < P && tail > 0 && !shared; ++b) shared = first_unit(b, units, P) % ga.steps != 0;
-    if (shared) {
-        hipLaunchKernelGGL((w4a16_gemm_fixup_kernel<MB, WN>), dim3(tail, kBM * kBN / 4 / 256), dim3(256), 0,
-                           st, ga, P);
+    if (max_tail > 0) {
+        hipLaunchKernelGGL((w4a16_gemm_fixup_kernel<MB, WN>), dim3(max_tail, kBM * kBN / 4 / 256, n), dim3(256), 0, st, gb);
         e = hipGetLastError();
     }
     return e;
 }
 
-// Tile width and the treatment of the last, incomplete round of tiles.
+// Tile width and the treatment of the last, incomplete round of tiles, for a linear that has
+// `cus` blocks to itself.
 template <int MB>
-hipError_t launch_rows(const GemmArgs& ga, hipStream_t st) {
-    // Measured on the four linears of a 7B decoder layer at M = 288 and 1024 (256 CUs):
+void choose_tile(const GemmArgs& ga, int cus, bool alone, int* wn_out, bool* split_out) {
+    // Measured on the four linears of a 7B decoder layer at M = 288 and 1024 (256 CUs), one launch each:
     //   * a round or more of wide tiles: wide tiles, and the incomplete last round is dealt in
     //     K steps only when it is short (a fuller one is cheaper left as it is: blocks that
     //     share tiles pay for slots and a second kernel, and a chip that is not full clocks higher);
     //   * between half a round and a round of wide tiles: wide tiles, whole;
     //   * less: narrow tiles (twice as many), dealt in K steps when K is long.
-    const int cus = gemm_max_blocks();
+    // A linear that shares the launch with others has only its share of the blocks, which it must
+    // keep busy to the end because the others cannot use them: less than a round is dealt in K steps.
     const int t2 = ((ga.M + 32 * MB - 1) / (32 * MB)) * ((ga.N + 255) / 256);
     int wn = 2;
     bool split = false;
@@ -637,11 +698,14 @@ hipError_t launch_rows(const GemmArgs& ga, hipStream_t st) {
         split = ga.Kpad / kBK >= 64;
     } else if (t2 >= cus) {
         split = (t2 % cus) * 5 <= cus * 2;
+    } else if (!alone) {
+        split = true;
     } else if (t2 * 2 <= cus) {
         wn = 1;
         split = ga.Kpad / kBK >= 64;
     }
-    return wn == 2 ? launch_tile<MB, 2>(ga, split, st) : launch_tile<MB, 1>(ga, split, st);
+    *wn_out = wn;
+    *split_out = split;
 }
 
 // tile height: the multiple of 32 rows (at most 128) that pads M least
@@ -660,37 +724,136 @@ bool gemm_f16_supports(const qail_wdesc& d, int M) {
     return (unsigned long long)d.N * d.K / 2 <= lim && Mpad * Kpad * 2 <= lim && (unsigned long long)M * d.N * 2 <= lim;
 }
 
-size_t gemm_f16_workspace(const qail_wdesc& d, int M) {
+// Workspace of one linear without the slots: x as fp16, the row scales, the weight rows' powers of two.
+static size_t gemm_head_bytes(const qail_wdesc& d, int M) {
     const size_t Mpad = (size_t)round_up(M, kRowPad), Kpad = (size_t)round_up(d.K, kBK);
-    size_t b = Mpad * Kpad * 2;                       // xh
-    b += Mpad * 4;                                    // rscale
-    b += (size_t)round_up(d.N, 64) * 4;               // wmul
-    b = (b + 255) / 256 * 256;
-    // two tile-shaped fp32 slots per block for tiles whose K range is shared between blocks
-    const size_t tile = (size_t)tile_rows(M) * (d.N > 128 ? 256 : 128) * 4;
-    b += 2 * (size_t)gemm_max_blocks() * tile;
-    return b;
+    const size_t b = Mpad * Kpad * 2 + Mpad * 4 + (size_t)round_up(d.N, 64) * 4;
+    return (b + 255) / 256 * 256;
+}
+
+// Two tile-shaped fp32 slots per block of the grid for tiles whose K range is shared between blocks.
+static size_t gemm_slot_bytes(int M, bool wide) {
+    return 2 * (size_t)gemm_max_blocks() * (size_t)tile_rows(M) * (wide ? 256 : 128) * 4;
+}
+
+size_t gemm_f16_workspace(const qail_wdesc& d, int M) { return gemm_head_bytes(d, M) + gemm_slot_bytes(M, d.N > 128); }
+
+size_t gemm_f16_batch_workspace(const qail_w4a16_item* items, int count, int M) {
+    // linears that share a launch (kGemmBatch at a time) need their heads side by side; the
+    // slots are shared out with the blocks
+    size_t need = 0;
+    for (int i0 = 0; i0 < count; i0 += kGemmBatch) {
+        size_t b = 0;
+        bool wide = false;
+        for (int i = i0; i < count && i < i0 + kGemmBatch; ++i) {
+            b += gemm_head_bytes(items[i].d, M);
+            wide = wide || items[i].d.N > 128;
+        }
+        b += gemm_slot_bytes(M, wide);
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+template <int MB>
+static hipError_t launch_chunk(const qail_w4a16_item* items, int n, int M, void* ws, hipStream_t st) {
+    const int Mpad = round_up(M, kRowPad);
+    const int cus = gemm_max_blocks();
+    GemmArgs ga[kGemmBatch];
+    PrepBatch pb;
+    pb.M = M;
+    pb.Mpad = Mpad;
+    char* at = static_cast<char*>(ws);
+    int prep_blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        const qail_wdesc& d = items[i].d;
+        const int Kpad = round_up(d.K, kBK), G = d.K / d.group_size;
+        uint16_t* xh = reinterpret_cast<uint16_t*>(at);
+        float* rscale = reinterpret_cast<float*>(xh + (size_t)Mpad * Kpad);
+        float* wmul = rscale + Mpad;
+        at += gemm_head_bytes(d, M);
+        pb.it[i] = PrepItem{items[i].x, items[i].scales, xh, rscale, wmul, d.N, d.K, Kpad, G};
+        ga[i] = GemmArgs{items[i].qweight, items[i].scales, items[i].zeros, xh, rscale, wmul, items[i].y,
+                         M, d.N, d.K, Kpad, d.group_size, 0, 0, 0, 0, nullptr, 0, 0};
+        prep_blocks = std::max(prep_blocks, Mpad + (d.N + 31) / 32);
+    }
+    for (int i = n; i < kGemmBatch; ++i) pb.it[i] = pb.it[n - 1];
+    float* slots = reinterpret_cast<float*>(at);
+    hipLaunchKernelGGL(gemm_prep_kernel, dim3(prep_blocks, n), dim3(256), 0, st, pb);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    // every linear gets blocks in proportion to its weights (at least one), then its own tiling
+    int share[kGemmBatch], wn[kGemmBatch];
+    bool split[kGemmBatch];
+    auto deal = [&](const int* idx, int m, int avail) {
+        double sum = 0;
+        for (int j = 0; j < m; ++j) sum += (double)items[idx[j]].d.N * items[idx[j]].d.K;
+        int used = 0;
+        for (int j = 0; j < m; ++j) {
+            const int i = idx[j];
+            share[i] = std::max(1, (int)((double)items[i].d.N * items[i].d.K / sum * avail));
+            used += share[i];
+        }
+        for (int j = 0; used < avail; j = (j + 1) % m, ++used) ++share[idx[j]];
+        while (used > avail) {   // the floors of one block each were too many: take from the largest
+            int big = idx[0];
+            for (int j = 1; j < m; ++j)
+                if (share[idx[j]] > share[big]) big = idx[j];
+            --share[big];
+            --used;
+        }
+    };
+    int all[kGemmBatch];
+    for (int i = 0; i < n; ++i) all[i] = i;
+    deal(all, n, std::max(cus, n));
+    for (int i = 0; i < n; ++i) choose_tile<MB>(ga[i], share[i], n == 1, &wn[i], &split[i]);
+    // linears with the same tile width go out together, each group on the whole chip
+    for (int w = 2; w >= 1; --w) {
+        int idx[kGemmBatch], m = 0;
+        for (int i = 0; i < n; ++i)
+            if (wn[i] == w) idx[m++] = i;
+        if (m == 0) continue;
+        if (m < n) {
+            deal(idx, m, std::max(cus, m));
+            for (int j = 0; j < m; ++j) {
+                int w2;
+                choose_tile<MB>(ga[idx[j]], share[idx[j]], n == 1, &w2, &split[idx[j]]);
+            }
+        }
+        GemmArgs grp[kGemmBatch];
+        int begin = 0;
+        for (int j = 0; j < m; ++j) {
+            GemmArgs& g = ga[idx[j]];
+            const int P = w == 2 ? plan_tiles<MB, 2>(g, split[idx[j]], share[idx[j]]) : plan_tiles<MB, 1>(g, split[idx[j]], share[idx[j]]);
+            g.block_begin = begin;
+            g.partial = slots + (size_t)2 * begin * (32 * MB) * (128 * w);
+            begin += P;
+            grp[j] = g;
+        }
+        e = w == 2 ? launch_tile<MB, 2>(grp, m, st) : launch_tile<MB, 1>(grp, m, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_w4a16_gemm_f16_batch(const qail_w4a16_item* items, int count, int M, void* ws, hipStream_t st) {
+    for (int i0 = 0; i0 < count; i0 += kGemmBatch) {
+        const int n = std::min(kGemmBatch, count - i0);
+        hipError_t e;
+        switch (tile_rows(M)) {
+            case 32: e = launch_chunk<1>(items + i0, n, M, ws, st); break;
+            case 64: e = launch_chunk<2>(items + i0, n, M, ws, st); break;
+            case 96: e = launch_chunk<3>(items + i0, n, M, ws, st); break;
+            default: e = launch_chunk<4>(items + i0, n, M, ws, st); break;
+        }
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_w4a16_gemm_f16(const qail_w4a16_item& it, int M, void* ws, hipStream_t st) {
-    const qail_wdesc& d = it.d;
-    const int Mpad = round_up(M, kRowPad), Kpad = round_up(d.K, kBK), G = d.K / d.group_size;
-    uint16_t* xh = static_cast<uint16_t*>(ws);
-    float* rscale = reinterpret_cast<float*>(xh + (size_t)Mpad * Kpad);
-    float* wmul = rscale + Mpad;
-    const size_t head = ((size_t)Mpad * Kpad * 2 + (size_t)Mpad * 4 + (size_t)round_up(d.N, 64) * 4 + 255) / 256 * 256;
-    float* partial = reinterpret_cast<float*>(static_cast<char*>(ws) + head);
-    hipLaunchKernelGGL(gemm_prep_kernel, dim3(Mpad + (d.N + 31) / 32), dim3(256), 0, st, it.x, it.scales, xh,
-                       rscale, wmul, M, Mpad, d.N, d.K, Kpad, G);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    GemmArgs ga{it.qweight, it.scales, it.zeros, xh, rscale, wmul, it.y, M, d.N, d.K, Kpad, d.group_size, 0, 0, 0, 0, partial};
-    switch (tile_rows(M)) {
-        case 32: return launch_rows<1>(ga, st);
-        case 64: return launch_rows<2>(ga, st);
-        case 96: return launch_rows<3>(ga, st);
-        default: return launch_rows<4>(ga, st);
-    }
+    return launch_w4a16_gemm_f16_batch(&it, 1, M, ws, st);
 }
 
 }  // namespace qail

@@ -206,6 +206,8 @@ def test_homogeneity_and_determinism(B):
 
 
 def test_batch_equals_single_calls(B):
+    # bit for bit: guaranteed for M <= 4; at M = 9, 16 these shapes have one 16-row tile per block in
+    # the batch as in a call of their own, hence the same division of K
     import torch
     shapes = [(160, 4096, 128), (48, 4096, 128), (70, 11008, 128), (33, 1024, 64), (9, 40, 8)]
     for M in (1, 4, 9, 16):
@@ -224,6 +226,32 @@ def test_batch_equals_single_calls(B):
         torch.cuda.synchronize()
         for e, ref in zip(ents, singles):
             assert np.array_equal(host(e["y"], np.uint16).reshape(ref.shape), ref)
+
+
+@pytest.mark.parametrize("M", [17, 40, 130, 300])
+def test_batched_matrix_core_gemm(B, M):
+    """Linears of the matrix-core path share launches, each on a share of the blocks (a different
+    division of K than in a call of its own, so compared with the oracle, not bit for bit); the
+    narrow one (N <= 128) uses another tile and goes out in a launch of its own."""
+    import torch
+    shapes = [(300, 4096, 128), (1000, 2048, 64), (96, 11008, 128), (520, 8192, 128), (64, 256, 64),
+              (2100, 1024, 256), (40, 4096, 128), (777, 512, 128), (260, 8256, 64), (33, 192, 64)]
+    ents, refs = [], []
+    for i, (N, K, g) in enumerate(shapes):
+        w = synth.llm_weight(N, K, 400 + i, outlier_frac=0.01)
+        xb = synth.llm_activation_bf16(M, K, 500 + i, outlier_frac=0.005)
+        qw, s, zw = oracle_pack(w, g)
+        ents.append(dict(N=N, K=K, group_size=g, qweight=dev(qw), scales=dev(s.view(np.uint16)), zeros=dev(zw),
+                         x=dev(xb), y=torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")))
+        refs.append((O.w4a16_linear(xb, qw, s, zw, g), O.w4a16_row_norms(xb, qw, s, zw, g)))
+    items = B.make_w4a16_items(ents, M)
+    ws = ws_for(B, B.qail_w4a16_batch_workspace(items, len(ents), M))
+    B.qail_w4a16_linear_batch(items, len(ents), M, ws)
+    torch.cuda.synchronize()
+    for e, (ref, (nx, nw)) in zip(ents, refs):
+        y = host(e["y"], np.uint16).reshape(M, e["N"])
+        tol = TOL if e["K"] >= 512 else TOL_TINY_K
+        assert w4a16_norm_err(y, ref, nx, nw) <= tol, (e["N"], e["K"])
 
 
 def _sampled_full_size(B, M, x_kw, rows_per_linear=96, m_rows=8, batched=True):
