@@ -14,7 +14,9 @@ def B():
     return ensure_built()
 
 
-@pytest.mark.parametrize("N,K,g", [(64, 1024, 128), (33, 256, 64), (5, 4096, 4096), (300, 64, 8)])
+@pytest.mark.parametrize("N,K,g", [(64, 1024, 128), (33, 256, 64), (5, 4096, 4096), (300, 64, 8), (40, 768, 192),
+                                   (16, 2048, 256), (9, 1536, 512),
+                                   (3000, 2048, 128)])   # more groups than one sweep of the grid
 def test_fake_quant_w4_bit_exact(B, N, K, g):
     import torch
     w = synth.llm_weight(N, K, 7 + N, outlier_frac=0.01)
@@ -29,7 +31,7 @@ def test_fake_quant_w4_bit_exact(B, N, K, g):
 def test_lsq_forward_and_backward(B, qn, qp):
     import torch
     rng = np.random.default_rng(qp)
-    n = 100003 - 100003 % 4
+    n = 100003      # not a multiple of 4: the last three values take the scalar path
     v = (rng.standard_normal(n) * 2).astype(np.float32)
     v[:6] = [0.0, 0.25, 0.75, -0.25, 1e9, -1e9]           # ties and both clamps with s = 0.5
     dout = rng.standard_normal(n).astype(np.float32)
@@ -57,7 +59,7 @@ def test_lsq_forward_and_backward(B, qn, qp):
         assert ds.item() == ds2.item()                       # fixed reduction order
 
 
-@pytest.mark.parametrize("Bn,D", [(1, 7), (64, 256), (300, 1000)])
+@pytest.mark.parametrize("Bn,D", [(1, 7), (64, 256), (300, 1000), (9, 32000), (5, 32768), (3, 32772), (4, 4098)])
 def test_qbc_loss(B, Bn, D):
     import torch
     rng = np.random.default_rng(Bn)
