@@ -448,6 +448,15 @@ def main():
         wh_ = torch.empty_like(wq_)
         tt = timed(lambda: B.qail_fake_quant_w4(wq_, GROUP, wh_), 20)
         tr["fake_quant_w4_12288x4096"] = {"us": round(tt * 1e6, 1), "GBps": round(2 * wq_.numel() * 4 / tt / 1e9, 1)}
+        # the offline quantise-and-pack of the same matrix: 4 B read, 0.52 B written per weight
+        qb_, sb_, zb_ = B.qail_packed_sizes(Nq, Kq, GROUP, B.QAIL_W4_ASYM_GROUP)
+        qq_ = torch.empty(qb_ // 4, dtype=torch.int32, device="cuda")
+        sq_ = torch.empty(sb_ // 2, dtype=torch.int16, device="cuda")
+        zq_ = torch.empty(zb_ // 4, dtype=torch.int32, device="cuda")
+        tt = timed(lambda: B.qail_quantize_weights(wq_, GROUP, B.QAIL_W4_ASYM_GROUP, qq_, sq_, zq_), 20)
+        tr["quantize_pack_w4_12288x4096"] = {"us": round(tt * 1e6, 1),
+                                             "GBps": round((wq_.numel() * 4 + qb_ + sb_ + zb_) / tt / 1e9, 1)}
+        del qq_, sq_, zq_
         sdev = torch.full((1,), 0.01, dtype=torch.float32, device="cuda")
         dsd = torch.zeros(1, dtype=torch.float32, device="cuda")
         wsl_ = torch.empty(B.qail_lsq_backward_workspace(), dtype=torch.uint8, device="cuda")
