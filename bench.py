@@ -271,6 +271,19 @@ def main():
             t = timed(walk, 7, warm=1)
             stack[f"M={M}"] = {"ms_per_token_step": round(t * 1e3, 4), "tokens_per_s": round(M / t, 1),
                                "GBps": round(32 * sum(linear_bytes(N, K, M) for _, N, K in shapes) / t / 1e9, 1)}
+            if M in (1, 16):
+                # the same walk with one launch per linear: stream order then makes every linear wait for
+                # the one before it, as the data dependences of a real decoder layer would
+                ones = [[B.make_w4a16_items([io[l][1][i]], M) for i in range(4)] for l in range(L)]
+
+                def walk_dep():
+                    for l in range(32):
+                        for i in range(4):
+                            B.qail_w4a16_linear_batch(ones[l % L][i], 1, M, wsk, sh)
+                t = timed(walk_dep, 7, warm=1)
+                stack[f"M={M}, one launch per linear"] = {"ms_per_token_step": round(t * 1e3, 4),
+                                                          "tokens_per_s": round(M / t, 1)}
+                del ones
             if M != 1:
                 del io
         stack["note"] = f"32 layer-steps per token over {L} distinct layers cycled"
