@@ -271,6 +271,22 @@ int qail_w8a8_gemm(const qail_conv_desc* d, const uint32_t* a_s8, const uint32_t
 int qail_w8a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales,
                       const uint16_t* x, uint16_t* y, int32_t M, void* stream);
 
+/* One linear of a batch for qail_w8a16_linear_batch (device pointers, 16-byte aligned). */
+typedef struct {
+    qail_wdesc d;
+    const uint32_t* qweight;
+    const uint16_t* scales;
+    const uint16_t* x;   /* bf16 [M][K] */
+    uint16_t* y;         /* bf16 [M][N] */
+} qail_w8a16_item;
+
+/* `count` independent 8-bit weight-only linears with the same M, given as a HOST array
+ * (Sec. 5.4 also deploys the backbone with 8-bit weights: a decode step is again four such
+ * linears per layer).  Same results, bit for bit, as `count` calls of qail_w8a16_linear; at
+ * M = 1 the items the streaming kernel takes share launches (up to 8 each), every item on a
+ * share of the blocks.  count >= 0 (0 is a no-op); errors as for the single call. */
+int qail_w8a16_linear_batch(const qail_w8a16_item* items, int32_t count, int32_t M, void* stream);
+
 /* ------------------------------------------------------- training-side operators --
  * Sec. 3.2 / Algorithm 1: the quantised policy is trained through its quantisers with the
  * straight-through estimator.  Sec. 3.3 / Eq. 3: the QBC term; the appendix instantiates its

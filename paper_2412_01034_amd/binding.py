@@ -35,6 +35,7 @@ EXPORTS = (
     "qail_w4a4_workspace", "qail_w4a4_gemm", "qail_w4a4_conv_u4",
     "qail_w4a16_lora_workspace", "qail_w4a16_linear_lora_batch",
     "qail_act_scale_s8", "qail_quantize_act_s8", "qail_w8a8_gemm", "qail_w8a16_linear",
+    "qail_w8a16_linear_batch",
     "qail_fake_quant_w4", "qail_lsq_forward", "qail_lsq_backward_workspace", "qail_lsq_backward", "qail_qbc_loss",
 )
 
@@ -61,6 +62,11 @@ class qail_conv_desc(ctypes.Structure):
 class qail_w4a16_item(ctypes.Structure):
     _fields_ = [("d", qail_wdesc), ("qweight", ctypes.c_void_p), ("scales", ctypes.c_void_p),
                 ("zeros", ctypes.c_void_p), ("x", ctypes.c_void_p), ("y", ctypes.c_void_p)]
+
+
+class qail_w8a16_item(ctypes.Structure):
+    _fields_ = [("d", qail_wdesc), ("qweight", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("x", ctypes.c_void_p), ("y", ctypes.c_void_p)]
 
 
 _lib = None
@@ -101,6 +107,7 @@ def lib() -> ctypes.CDLL:
         L.qail_quantize_act_s8.argtypes = [vp, sz, vp, vp, vp]
         L.qail_w8a8_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.qail_w8a16_linear.argtypes = [ctypes.POINTER(qail_wdesc), vp, vp, vp, vp, i32, vp]
+        L.qail_w8a16_linear_batch.argtypes = [ctypes.POINTER(qail_w8a16_item), i32, i32, vp]
         L.qail_w4a4_workspace.argtypes = [ctypes.POINTER(qail_conv_desc), psz]
         L.qail_w4a4_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.qail_w4a4_conv_u4.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, ctypes.c_float, vp,
@@ -377,6 +384,29 @@ def qail_w8a16_linear(N: int, K: int, group_size: int, qweight: torch.Tensor, sc
     d = qail_wdesc(N, K, group_size, QAIL_W8_SYM_GROUP)
     _check(lib().qail_w8a16_linear(ctypes.byref(d), _ptr(qweight), _ptr(scales), _ptr(x), _ptr(y), M,
                                    _stream() if stream is None else stream), "qail_w8a16_linear")
+
+
+def make_w8a16_items(entries: Sequence[dict], M: int):
+    """entries: dicts with N, K, group_size, qweight, scales, x, y (device tensors).  Returns a ctypes
+    array for qail_w8a16_linear_batch (the tensors must be kept alive by the caller)."""
+    arr = (qail_w8a16_item * max(1, len(entries)))()
+    for i, e in enumerate(entries):
+        N, K, g = e["N"], e["K"], e["group_size"]
+        _need(e["qweight"], N * K, "qweight")
+        _need(e["scales"], N * (K // g) * 2, "scales")
+        _need(e["x"], M * K * 2, "x")
+        _need(e["y"], M * N * 2, "y")
+        arr[i].d = qail_wdesc(N, K, g, QAIL_W8_SYM_GROUP)
+        arr[i].qweight = _ptr(e["qweight"])
+        arr[i].scales = _ptr(e["scales"])
+        arr[i].x = _ptr(e["x"])
+        arr[i].y = _ptr(e["y"])
+    return arr
+
+
+def qail_w8a16_linear_batch(items, count: int, M: int, stream: Optional[int] = None) -> None:
+    _check(lib().qail_w8a16_linear_batch(items, count, M, _stream() if stream is None else stream),
+           "qail_w8a16_linear_batch")
 
 
 def qail_fake_quant_w4(w: torch.Tensor, group_size: int, w_hat: torch.Tensor) -> None:

@@ -392,6 +392,36 @@ int qail_w8a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16
     return hip_status(launch_w8a16_linear(*d, qweight, scales, x, y, M, static_cast<hipStream_t>(stream)));
 }
 
+int qail_w8a16_linear_batch(const qail_w8a16_item* items, int32_t count, int32_t M, void* stream) {
+    if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
+    if (count == 0) return QAIL_OK;
+    if (!items) return QAIL_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const qail_w8a16_item& it = items[i];
+        const int e = check_wdesc(&it.d);
+        if (e != QAIL_OK) return e;
+        if (it.d.scheme != QAIL_W8_SYM_GROUP) return QAIL_ERR_UNSUPPORTED;
+        if ((long long)M * it.d.N > 0x7FFFFFFFll * 64) return QAIL_ERR_UNSUPPORTED;
+        if (!it.qweight || !it.scales || !it.x || !it.y) return QAIL_ERR_NULL;
+        if (!aligned16(it.qweight) || !aligned16(it.scales) || !aligned16(it.x) || !aligned16(it.y)) return QAIL_ERR_ALIGN;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int i = 0;
+    while (i < count) {
+        int j = i;
+        while (j < count && w8a16_stream_supports(items[j].d, M)) ++j;
+        if (j > i) {
+            if (launch_w8a16_stream_batch(items + i, j - i, st) != hipSuccess) return QAIL_ERR_HIP;
+            i = j;
+            continue;
+        }
+        const qail_w8a16_item& it = items[i];
+        if (launch_w8a16_linear(it.d, it.qweight, it.scales, it.x, it.y, M, st) != hipSuccess) return QAIL_ERR_HIP;
+        ++i;
+    }
+    return QAIL_OK;
+}
+
 int qail_fake_quant_w4(const qail_wdesc* d, const float* w, float* w_hat, void* stream) {
     const int e = check_wdesc(d);
     if (e != QAIL_OK) return e;

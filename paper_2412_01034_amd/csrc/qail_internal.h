@@ -84,6 +84,8 @@ hipError_t launch_w8a16_linear(const qail_wdesc& d, const uint32_t* qw, const ui
                                uint16_t* y, int M, hipStream_t st);
 // M = 1 on the shapes the streaming kernel takes (w8a16_gemv.hip); launch_w8a16_linear dispatches.
 bool w8a16_stream_supports(const qail_wdesc& d, int M);
+// `count` linears, all supported at M = 1, in shared launches
+hipError_t launch_w8a16_stream_batch(const qail_w8a16_item* items, int count, hipStream_t st);
 hipError_t launch_w8a16_stream(const qail_wdesc& d, const uint32_t* qw, const uint16_t* sc, const uint16_t* x,
                                uint16_t* y, hipStream_t st);
 

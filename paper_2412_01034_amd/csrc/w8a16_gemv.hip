@@ -16,6 +16,8 @@
 //   sum_k x_k q_k  =  sum_k x_k (1024 + u_k)  -  1152 sum_k x_k ,
 //
 // with the second term per stretch computed once per block at staging.
+#include <algorithm>
+
 #include "qail_internal.h"
 
 namespace qail {
@@ -39,6 +41,14 @@ struct W8Args {
     uint16_t* y;
     int N, K, g;
     int rows_base, rows_rem;  // block b owns rows_base rows, one more if b < rows_rem, in the order of the blocks
+    int block_begin;          // first block of the grid that works on this linear
+};
+
+// Up to kW8Batch linears share a launch, each on its own run of blocks.
+constexpr int kW8Batch = 8;
+struct W8Batch {
+    W8Args it[kW8Batch];
+    int count;
 };
 
 template <int kCtrl>
@@ -65,10 +75,15 @@ __device__ __forceinline__ float wave_sum8(float v) {
 //                      (P * 1152 * sum of the staged values, P)
 // Lane L owns, in chunk c, the 16 k starting at 1024 c + 16 L; they are staged as fp16 times 2^-e
 // (largest magnitude of the stretch in [2^14, 2^15)).  Everything past K is zero.
-__global__ __launch_bounds__(kW8Threads) void w8a16_stream_kernel(const W8Args a) {
+__global__ __launch_bounds__(kW8Threads) void w8a16_stream_kernel(const W8Batch args) {
     extern __shared__ uint4 w8_lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
+    int item = 0;
+#pragma unroll
+    for (int i = 1; i < kW8Batch; ++i)
+        if (i < args.count && (int)blockIdx.x >= args.it[i].block_begin) item = i;
+    const W8Args a = args.it[item];
     const int K = a.K, N = a.N, g = a.g;
     const int G = K / g;
     const int nc = (K + kW8ChunkK - 1) / kW8ChunkK;
@@ -87,7 +102,7 @@ __global__ __launch_bounds__(kW8Threads) void w8a16_stream_kernel(const W8Args a
     __builtin_amdgcn_sched_barrier(0);  // the scheduler must not move the x loads behind the weights
 
     // this block's rows, dealt to its waves in turn
-    const int bk = blockIdx.x;
+    const int bk = (int)blockIdx.x - a.block_begin;
     const int s0 = bk * a.rows_base + min(bk, a.rows_rem);
     const int nrows = a.rows_base + (bk < a.rows_rem ? 1 : 0);
     const int nrw = max(0, (nrows - wave + kW8Waves - 1) / kW8Waves);  // rows of this wave: at most 64
@@ -277,20 +292,46 @@ bool w8a16_stream_supports(const qail_wdesc& d, int M) {
            (unsigned long long)d.N * d.K < 0x80000000ull;  // 32-bit byte offsets in the kernel
 }
 
+hipError_t launch_w8a16_stream_batch(const qail_w8a16_item* items, int count, hipStream_t st) {
+    for (int i0 = 0; i0 < count; i0 += kW8Batch) {
+        const int n = count - i0 < kW8Batch ? count - i0 : kW8Batch;
+        const qail_w8a16_item* its = items + i0;
+        // blocks in proportion to the bytes, one block per CU in all; per linear fewer when there
+        // are fewer than 16 rows for each block, more when a block would get more rows than its
+        // waves can park results for (64 each)
+        const int cus = w8_cus();
+        double total = 0;
+        for (int i = 0; i < n; ++i) total += (double)its[i].d.N * its[i].d.K;
+        W8Batch b;
+        size_t lds = 0;
+        int begin = 0;
+        for (int i = 0; i < n; ++i) {
+            const qail_wdesc& d = its[i].d;
+            int blocks = (int)((double)d.N * d.K / total * cus + 0.5);
+            if (blocks < 1) blocks = 1;
+            const int by_rows = (d.N + kW8Waves - 1) / kW8Waves;
+            if (blocks > by_rows) blocks = by_rows;
+            const int need = (d.N + kW8Waves * kWave - 1) / (kW8Waves * kWave);
+            if (blocks < need) blocks = need;
+            const size_t nc = ((size_t)d.K + kW8ChunkK - 1) / kW8ChunkK;
+            lds = std::max(lds, nc * kWave * (2 * 16 + 8));
+            b.it[i] = W8Args{its[i].qweight, its[i].scales, its[i].x, its[i].y, d.N, d.K, d.group_size,
+                             d.N / blocks, d.N % blocks, begin};
+            begin += blocks;
+        }
+        for (int i = n; i < kW8Batch; ++i) b.it[i] = b.it[n - 1];
+        b.count = n;
+        hipLaunchKernelGGL(w8a16_stream_kernel, dim3(begin), dim3(kW8Threads), lds, st, b);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_w8a16_stream(const qail_wdesc& d, const uint32_t* qw, const uint16_t* sc, const uint16_t* x,
                                uint16_t* y, hipStream_t st) {
-    // one block per CU, fewer when there are fewer than 16 rows for each, more when a block would
-    // get more rows than its waves can park results for (64 each)
-    int blocks = w8_cus();
-    const int by_rows = (d.N + kW8Waves - 1) / kW8Waves;
-    if (blocks > by_rows) blocks = by_rows;
-    const int need = (d.N + kW8Waves * kWave - 1) / (kW8Waves * kWave);
-    if (blocks < need) blocks = need;
-    const size_t nc = ((size_t)d.K + kW8ChunkK - 1) / kW8ChunkK;
-    const size_t lds = nc * kWave * (2 * 16 + 8);
-    W8Args a{qw, sc, x, y, d.N, d.K, d.group_size, d.N / blocks, d.N % blocks};
-    hipLaunchKernelGGL(w8a16_stream_kernel, dim3(blocks), dim3(kW8Threads), lds, st, a);
-    return hipGetLastError();
+    const qail_w8a16_item it{d, qw, sc, x, y};
+    return launch_w8a16_stream_batch(&it, 1, st);
 }
 
 }  // namespace qail

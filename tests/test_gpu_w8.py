@@ -139,3 +139,30 @@ def test_w8a16_linear(B, M, N, K, g):
     nw = np.sqrt((wh ** 2).sum(axis=1))
     tol = TOL if K >= 512 else 2.0 ** -8 * 1.01
     assert w4a16_norm_err(host(y, np.uint16).reshape(M, N), ref, nx, nw) <= tol
+
+
+@pytest.mark.parametrize("M", [1, 3])
+def test_w8a16_batch_equals_single_calls(B, M):
+    """Up to 8 linears share a launch at M = 1, each on its own run of blocks; more than 8 and
+    shapes the streaming kernel does not take (K beyond its range) go out on their own.  Rows are
+    summed in the same order either way: bit for bit the single calls' results."""
+    import torch
+    shapes = [(300, 4096, 128), (64, 11008, 128), (33, 256, 32), (20, 12304, 16), (1000, 2048, 64), (5, 16, 16),
+              (40, 4096, 1024), (700, 1024, 128), (18, 12288, 64), (129, 512, 16), (257, 8192, 2048)]
+    ents, singles = [], []
+    for i, (N, K, g) in enumerate(shapes):
+        w = synth.llm_weight(N, K, 600 + i, outlier_frac=0.01)
+        xb = synth.llm_activation_bf16(M, K, 700 + i)
+        q, s = O.quantize_w8_sym_group(w, g)
+        e = dict(N=N, K=K, group_size=g, qweight=dev(O.pack_bytes(q)), scales=dev(s.view(np.uint16)), x=dev(xb),
+                 y=torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda"))
+        y1 = torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")
+        B.qail_w8a16_linear(N, K, g, e["qweight"], e["scales"], e["x"], y1, M)
+        ents.append(e)
+        singles.append(y1)
+    items = B.make_w8a16_items(ents, M)
+    B.qail_w8a16_linear_batch(items, len(ents), M)
+    B.qail_w8a16_linear_batch(items, 0, M)     # a no-op
+    torch.cuda.synchronize()
+    for e, y1 in zip(ents, singles):
+        assert np.array_equal(host(e["y"], np.uint16), host(y1, np.uint16))
