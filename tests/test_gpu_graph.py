@@ -44,18 +44,36 @@ def test_replays_match_eager(B):
     ww = dev(rng.integers(0, 2 ** 32, size=s.Cout * s.K // 8, dtype=np.uint64).astype(np.uint32))
     acc = torch.zeros(s.M * s.Cout, dtype=torch.int32, device="cuda")
 
+    # three linears of the matrix-core path in one batched call (they share launches), and an 8-bit batch
+    bat = [_linear_case(B, 300, 4096, 128, 40, 21), _linear_case(B, 96, 11008, 128, 40, 22),
+           _linear_case(B, 64, 256, 64, 40, 23)]
+    bitems = B.make_w4a16_items([dict(N=t["N"], K=t["K"], group_size=t["g"], qweight=t["qw"], scales=t["s"],
+                                      zeros=t["z"], x=t["x"], y=t["y"]) for t in bat], 40)
+    bws = ws_for(B, B.qail_w4a16_batch_workspace(bitems, 3, 40))
+    w8 = []
+    for i, (N, K, g) in enumerate([(200, 4096, 128), (64, 1024, 64)]):
+        q, s8 = O.quantize_w8_sym_group(synth.llm_weight(N, K, 31 + i), g)
+        w8.append(dict(N=N, K=K, group_size=g, qweight=dev(O.pack_bytes(q)), scales=dev(s8.view(np.uint16)),
+                       x=dev(synth.llm_activation_bf16(1, K, 41 + i)), y=torch.zeros(N, dtype=torch.int16, device="cuda")))
+    w8items = B.make_w8a16_items(w8, 1)
+
     def step():
         for t in lin:
             _run_linear(B, t)
+        B.qail_w4a16_linear_batch(bitems, 3, 40, bws)
+        B.qail_w8a16_linear_batch(w8items, 2, 1)
         B.qail_w4a4_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww, acc_out=acc)
 
     def snapshot():
         torch.cuda.synchronize()
-        return [host(t["y"], np.uint16).copy() for t in lin] + [host(acc, np.int32).copy()]
+        return ([host(t["y"], np.uint16).copy() for t in lin + bat] + [host(e["y"], np.uint16).copy() for e in w8] +
+                [host(acc, np.int32).copy()])
 
     def clear():
-        for t in lin:
+        for t in lin + bat:
             t["y"].fill_(0x7FC0)
+        for e in w8:
+            e["y"].fill_(0x7FC0)
         acc.fill_(-1)
 
     gs = torch.cuda.Stream()
