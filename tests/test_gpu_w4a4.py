@@ -197,3 +197,85 @@ def test_fused_output_feeds_the_next_layer(B):
     assert np.array_equal(host(mid, np.uint32).reshape(s1.M, -1), O.pack_nibbles(mid_ref))
     ref2 = O.w4a4_conv_acc(O.pack_nibbles(mid_ref).reshape(s1.B, s1.H, s1.W, -1), w2, *geom(s2))
     assert np.array_equal(host(acc2, np.int32).reshape(s2.M, s2.Cout), ref2)
+
+
+def test_chained_resnet34_body_bit_exact(B):
+    """The whole ResNet-34 body (16 residual blocks, 32 3x3 convolutions and the 3 projection
+    shortcuts) chained on the 4-bit path at a small image: every convolution but the projections
+    writes the next layer's packed codes, identity shortcuts come in as the block input's codes,
+    projection shortcuts as fp32.  Every step of every tensor is fixed by the oracle's own chain
+    (the largest pre-quantisation value / 15), so the GPU chain must reproduce the oracle's codes
+    bit for bit down to the last layer."""
+    import torch
+    Bn, H = 2, 16
+    stages = [(64, 3), (128, 4), (256, 6), (512, 3)]
+    seed = [7000]
+
+    def layer(shape):
+        seed[0] += 3
+        w = synth.conv_weight(shape, seed[0])
+        qw, s_w = O.quantize_w4_sym_channel(w)
+        return O.pack_nibbles(qw.reshape(shape.Cout, -1)), s_w, synth.conv_bias(shape, seed[0] + 1)
+
+    def step_of(acc, scale, bias, r=None):
+        t = acc.astype(np.float32) * scale[None, :] + bias[None, :]
+        if r is not None:
+            t = t + r
+        return np.float32(max(float(np.maximum(t, 0).max()), 1e-3) / 15.0)
+
+    s0 = synth.ConvShape("in", Bn, H, H, 64, 64, 3, 3, 1, 1)
+    a = synth.conv_activation(s0, 6999)
+    s_in = O.act_scale_u4(a)
+    codes = O.quantize_act_u4(a, s_in).reshape(Bn * H * H, 64)       # oracle chain: codes [M, C] and their step
+    g_codes = dev(O.pack_nibbles(codes))                              # GPU chain: packed words
+    Cin = 64
+    for si, (C, nblocks) in enumerate(stages):
+        for bi in range(nblocks):
+            stride = 2 if (si > 0 and bi == 0) else 1
+            c1 = synth.ConvShape(f"s{si}b{bi}c1", Bn, H, H, Cin, C, 3, 3, stride, 1)
+            Ho = c1.OH
+            c2 = synth.ConvShape(f"s{si}b{bi}c2", Bn, Ho, Ho, C, C, 3, 3, 1, 1)
+            w1, sw1, b1 = layer(c1)
+            w2, sw2, b2 = layer(c2)
+            a_words = O.pack_nibbles(codes).reshape(Bn, H, H, Cin // 8)
+            # ---- oracle: conv1 + ReLU -> codes
+            acc1 = O.w4a4_conv_acc(a_words, w1, *geom(c1))
+            sc1 = O.requant_scale(s_in, sw1)
+            s_mid = step_of(acc1, sc1, b1)
+            mid = O.fused_requant_u4(acc1, sc1, b1, s_mid)
+            # ---- oracle: shortcut
+            res_codes = res_f32 = None
+            if stride == 2:
+                cd = synth.ConvShape(f"s{si}b{bi}d", Bn, H, H, Cin, C, 1, 1, 2, 0)
+                wd, swd, bd = layer(cd)
+                accd = O.w4a4_conv_acc(a_words, wd, *geom(cd))
+                scd = O.requant_scale(s_in, swd)
+                # one fp32 fused multiply-add per element; float64 holds the product exactly and the sum to
+                # 53 bits, so rounding it to float32 is that result (bar a double rounding of probability 2^-29)
+                res_f32 = (accd.astype(np.float64) * scd.astype(np.float64)[None, :] + bd.astype(np.float64)[None, :]).astype(np.float32)
+            else:
+                res_codes = codes
+            # ---- oracle: conv2 + shortcut + ReLU -> codes
+            acc2 = O.w4a4_conv_acc(O.pack_nibbles(mid).reshape(Bn, Ho, Ho, C // 8), w2, *geom(c2))
+            sc2 = O.requant_scale(s_mid, sw2)
+            r = res_f32 if res_f32 is not None else np.float32(s_in) * res_codes.astype(np.float32)
+            s_out = step_of(acc2, sc2, b2, r)
+            out = O.fused_requant_u4(acc2, sc2, b2, s_out, res_codes=res_codes,
+                                     res_scale=np.float32(s_in) if res_codes is not None else None, res_f32=res_f32)
+            # ---- GPU: the same three or two calls
+            g_mid = torch.zeros(c1.M * C // 8, dtype=torch.int32, device="cuda")
+            B.qail_w4a4_conv_u4(*geom(c1), g_codes, dev(w1), dev(sc1), dev(b1), float(s_mid), g_mid)
+            g_out = torch.zeros(c2.M * C // 8, dtype=torch.int32, device="cuda")
+            if stride == 2:
+                g_res = torch.zeros(cd.M * C, dtype=torch.float32, device="cuda")
+                B.qail_w4a4_gemm(*geom(cd), g_codes, dev(wd), scale=dev(scd), bias=dev(bd), y_out=g_res)
+                B.qail_w4a4_conv_u4(*geom(c2), g_mid, dev(w2), dev(sc2), dev(b2), float(s_out), g_out, res_f32=g_res)
+            else:
+                B.qail_w4a4_conv_u4(*geom(c2), g_mid, dev(w2), dev(sc2), dev(b2), float(s_out), g_out,
+                                    res_u4=g_codes, res_scale=float(s_in))
+            torch.cuda.synchronize()
+            assert np.array_equal(host(g_mid, np.uint32).reshape(c1.M, -1), O.pack_nibbles(mid)), c1.name
+            assert np.array_equal(host(g_out, np.uint32).reshape(c2.M, -1), O.pack_nibbles(out)), c2.name
+            assert out.max() == 15 and mid.max() == 15       # the steps use the full code range
+            codes, s_in, g_codes, Cin, H = out, s_out, g_out, C, Ho
+    assert H == 2 and Cin == 512 and codes.any()
