@@ -121,6 +121,58 @@ def test_argument_errors_are_reported_without_a_gpu(B):
     assert L.qail_w4a16_linear(ctypes.byref(dg), ok, ok, ok, ok, ok, 17, ok + 16, sz.value, None) == B.QAIL_ERR_ALIGN
 
 
+def test_batch_workspace_is_host_arithmetic(B):
+    """Linears of the matrix-core path that share launches (up to 8) keep their prepared activations
+    side by side and share one pool of slots; runs that other kernels interrupt, and launches after
+    the eighth linear, reuse the space.  All of it is computed on the host, no GPU needed."""
+    L = B.lib()
+    ok = ctypes.c_void_p(0x1000)
+
+    def items(shapes):
+        arr = (B.qail_w4a16_item * len(shapes))()
+        for i, (N, K, g) in enumerate(shapes):
+            arr[i].d = B.qail_wdesc(N, K, g, B.QAIL_W4_ASYM_GROUP)
+            arr[i].qweight = arr[i].scales = arr[i].zeros = arr[i].x = arr[i].y = 0x1000
+        return arr
+
+    def single(N, K, g, M):
+        sz = ctypes.c_size_t(0)
+        assert L.qail_w4a16_workspace(ctypes.byref(B.qail_wdesc(N, K, g, B.QAIL_W4_ASYM_GROUP)), M, ctypes.byref(sz)) == B.QAIL_OK
+        return sz.value
+
+    def batch(shapes, M):
+        sz = ctypes.c_size_t(0)
+        assert L.qail_w4a16_batch_workspace(items(shapes), len(shapes), M, ctypes.byref(sz)) == B.QAIL_OK
+        return sz.value
+
+    def head(N, K, M):     # fp16 x padded to 128 rows x 128 columns, row scales, per-column powers of two
+        return (128 * ((M + 127) // 128) * ((K + 127) // 128 * 128) * 2 + 128 * ((M + 127) // 128) * 4
+                + (N + 63) // 64 * 64 * 4 + 255) // 256 * 256
+
+    M = 40                                    # 64-row tiles
+    pool = 2 * 256 * 64 * 256 * 4             # two slots of 64 x 256 floats per block of the grid
+    a, b_, c = (300, 4096, 128), (1000, 2048, 64), (96, 11008, 128)
+    assert single(*a, M) == head(a[0], a[1], M) + pool
+    assert batch([a], M) == single(*a, M)
+    assert batch([a, b_, c], M) == sum(head(s[0], s[1], M) for s in (a, b_, c)) + pool
+    assert batch([(64, 256, 64)], M) == head(64, 256, M) + pool // 2          # N <= 128: narrow slots
+    # nine linears: the ninth goes out after the first eight and reuses their space
+    assert batch([a] * 9, M) == 8 * head(a[0], a[1], M) + pool
+    # a linear the matrix-core path does not take (K not a multiple of 64) splits the run
+    odd = (64, 40, 8)
+    assert batch([a, odd, b_], M) == max(single(*a, M), single(*b_, M))
+    assert batch([a, c], 16) == 0 and batch([a, b_, c], 1) == 0               # streaming kernels need none
+    assert batch([a, b_, c], 16) == single(*b_, 16) > 0                       # groups of 64 at M = 16: matrix cores
+    assert batch([], 5) == 0
+    # the batch call checks against the same figure
+    its = items([a, b_])
+    need = batch([a, b_], M)
+    f = L.qail_w4a16_linear_batch
+    assert f(its, 2, M, ok, need - 1, None) == B.QAIL_ERR_WORKSPACE
+    assert f(its, 2, M, None, 0, None) == B.QAIL_ERR_WORKSPACE
+    assert f(its, 2, M, ctypes.c_void_p(0x1010), need, None) == B.QAIL_ERR_ALIGN
+
+
 def test_binding_refuses_host_tensors(B):
     import torch
     t = torch.zeros(16, 64)
