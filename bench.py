@@ -245,6 +245,22 @@ def main():
             torch.cuda.synchronize()
             return a.elapsed_time(b) * 1e-3 / iters
 
+        # the headline launch again: spread of single launches (an event pair around each of 300), and the
+        # same layer launched over and over, labelled as what it is: its 105 MB stay in the last-level cache
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(300)]
+        for i, (e0, e1) in enumerate(evs):
+            e0.record(stream)
+            step(i)
+            e1.record(stream)
+        torch.cuda.synchronize()
+        us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)
+        tcr = timed(lambda: step(0), 400)
+        extra["decode_layer_launch_spread"] = {
+            "us_p10_p50_p90": [round(us[len(us) // 10], 2), round(us[len(us) // 2], 2), round(us[len(us) * 9 // 10], 2)],
+            "note": "event pair around every launch (includes the events' own gap)",
+            "cache_resident_one_layer_us": round(tcr * 1e6, 2),
+            "cache_resident_one_layer_GBps": round(bytes_per_step / tcr / 1e9, 1)}
+
         # single-linear decode launches (cold weights: rotate layers)
         per = {}
         for i, (name, N, K) in enumerate(shapes):
@@ -367,9 +383,21 @@ def main():
             tt = timed(lambda: B.qail_w4a4_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad,
                                                 a, ww, scale=scale, bias=bias, y_out=y, stream=sh), 50, settle=True)
             per_shape[key] = {"us": round(tt * 1e6, 2), "TOPs": round(s.ops / tt / 1e12, 1)}
+        # the same 35 calls captured once into a graph and replayed (the library only launches kernels)
+        gs = torch.cuda.Stream()
+        with torch.cuda.stream(gs):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=gs):
+                for s, a, ww, scale, bias, y in calls:
+                    B.qail_w4a4_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww,
+                                     scale=scale, bias=bias, y_out=y, stream=gs.cuda_stream)
+        torch.cuda.synchronize()
+        tg = timed(graph.replay, 20, settle=True)
+        del graph
         extra["w4a4_resnet34_b32"] = {"ms_per_pass": round(t * 1e3, 4), "TOPs": round(tot_ops / t / 1e12, 1),
                                       "frac_int8_peak": round(tot_ops / t / 1e12 / INT8_PEAK_TOPS, 4),
-                                      "calls": len(calls), "per_shape": per_shape}
+                                      "calls": len(calls), "ms_per_pass_graph_replay": round(tg * 1e3, 4),
+                                      "per_shape": per_shape}
 
         # the same 35 calls with the fused 4-bit output (ReLU + shortcut + quantise for the next
         # layer): every call writes 0.5 B per output instead of 4 B
