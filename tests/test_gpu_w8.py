@@ -166,3 +166,43 @@ def test_w8a16_batch_equals_single_calls(B, M):
     torch.cuda.synchronize()
     for e, y1 in zip(ents, singles):
         assert np.array_equal(host(e["y"], np.uint16), host(y1, np.uint16))
+
+
+def test_w8a16_full_size_decode_layer_batched_sampled(B):
+    """The four Llama-2-7B linears at full size with 8-bit weights through the batched call, M = 1 (the
+    launch the benchmark times): the GPU quantises the full matrices, the oracle re-derives sampled
+    rows only (rows are independent)."""
+    import torch
+    rng = np.random.default_rng(88)
+    ents, keep = [], []
+    for i, (name, N, K) in enumerate(synth.LLAMA7B_LINEARS):
+        w = synth.llm_weight(N, K, synth.seed_for(1, i, 0), outlier_frac=0.01)
+        xb = synth.llm_activation_bf16(1, K, synth.seed_for(1, i, 1))
+        qw = torch.zeros(N * K // 4, dtype=torch.int32, device="cuda")
+        sc = torch.zeros(N * (K // 128), dtype=torch.int16, device="cuda")
+        wd = dev(w)
+        B.qail_quantize_weights(wd, 128, B.QAIL_W8_SYM_GROUP, qw, sc, None)
+        torch.cuda.synchronize()
+        del wd
+        rows = np.sort(rng.choice(N, 64, replace=False))
+        rows[0], rows[-1] = 0, N - 1
+        ents.append(dict(N=N, K=K, group_size=128, qweight=qw, scales=sc, x=dev(xb),
+                         y=torch.full((N,), 0x7FC0, dtype=torch.int16, device="cuda")))
+        keep.append((w[rows], xb, rows))
+        del w
+    items = B.make_w8a16_items(ents, 1)
+    B.qail_w8a16_linear_batch(items, len(ents), 1)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for e, (w_rows, xb, rows) in zip(ents, keep):
+        N, K = e["N"], e["K"]
+        q, s = O.quantize_w8_sym_group(w_rows, 128)
+        assert np.array_equal(host(e["qweight"], np.uint32).reshape(N, K // 4)[rows], O.pack_bytes(q))
+        assert np.array_equal(host(e["scales"], np.uint16).reshape(N, K // 128)[rows], s.view(np.uint16))
+        y = host(e["y"], np.uint16).reshape(1, N)[:, rows]
+        ref = O.w8a16_linear(xb, q, s, 128)
+        nx = np.sqrt((O.bf16_bits_to_f64(xb) ** 2).sum(axis=1))
+        wh = q.astype(np.float64) * np.repeat(s.astype(np.float64), 128, axis=1)
+        nw = np.sqrt((wh ** 2).sum(axis=1))
+        worst = max(worst, w4a16_norm_err(y, ref, nx, nw))
+    assert worst <= TOL, worst
