@@ -279,3 +279,36 @@ def test_chained_resnet34_body_bit_exact(B):
             assert out.max() == 15 and mid.max() == 15       # the steps use the full code range
             codes, s_in, g_codes, Cin, H = out, s_out, g_out, C, Ho
     assert H == 2 and Cin == 512 and codes.any()
+
+
+@pytest.mark.parametrize("batch", [32, 256])
+def test_fused_u4_full_batch_sampled_images(B, batch):
+    """The fused-output calls as the benchmark issues them (batch 32: all ten shapes; batch 256: the
+    largest, a middle and the deepest one), identity shortcut where the block has one; the oracle
+    recomputes three images of each (images are independent)."""
+    import torch
+    shapes = distinct_resnet_shapes(batch)
+    if batch == 256:
+        shapes = [shapes[0], shapes[len(shapes) // 2], shapes[-1]]
+    for n, s in enumerate(shapes):
+        rng = np.random.default_rng(8100 + n)
+        a_words = rng.integers(0, 2 ** 32, size=(s.B, s.H, s.W, s.Cin // 8), dtype=np.uint64).astype(np.uint32)
+        one = synth.ConvShape(s.name, 1, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad)
+        _, ww, scale, bias = quantised_inputs(one, 8200 + n)
+        identity = s.Cin == s.Cout and s.stride == 1
+        rs = np.float32(0.05)
+        acc0 = O.w4a4_conv_acc(a_words[:1], ww, *geom(one), use_blas=True)
+        s_out = np.float32(max(float(O.requant(acc0, scale, bias).max()), 1e-3) / 15.0)
+        out = torch.full((s.M * s.Cout // 8,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+        a_dev = dev(a_words)
+        B.qail_w4a4_conv_u4(*geom(s), a_dev, dev(ww), dev(scale), dev(bias), float(s_out), out,
+                            res_u4=a_dev if identity else None, res_scale=float(rs) if identity else 0.0)
+        torch.cuda.synchronize()
+        got = host(out, np.uint32).reshape(s.M, s.Cout // 8)
+        per = s.OH * s.OW
+        for b in (0, s.B // 2 - 3, s.B - 1):
+            acc = O.w4a4_conv_acc(a_words[b:b + 1], ww, *geom(one), use_blas=True)
+            res = O.unpack_nibbles_u4(a_words[b].reshape(per, s.Cin // 8), s.Cin) if identity else None
+            ref = O.fused_requant_u4(acc, scale, bias, s_out, res_codes=res, res_scale=rs if identity else None)
+            assert np.array_equal(got[b * per:(b + 1) * per], O.pack_nibbles(ref)), (s.name, b)
+        del out, a_dev
