@@ -103,6 +103,31 @@ def test_w8a8_conv_bit_exact(B, s):
     assert np.all(np.abs(host(y, np.float32).reshape(s.M, s.Cout).astype(np.float64) - yref) <= bound)
 
 
+def test_w8a8_resnet34_shapes_full_batch_sampled_images(B):
+    """The ten distinct ResNet-34 body shapes at batch 32, as the benchmark's W8A8 line issues them;
+    the oracle recomputes images 0, 13 and 31 (images are independent)."""
+    import torch
+    seen, shapes = set(), []
+    for s in synth.resnet34_convs(32):
+        key = (s.H, s.Cin, s.Cout, s.KH, s.stride)
+        if key not in seen:
+            seen.add(key)
+            shapes.append(s)
+    for n, s in enumerate(shapes):
+        rng = np.random.default_rng(8300 + n)
+        aw = rng.integers(0, 2 ** 32, size=(s.B, s.H, s.W, s.Cin // 4), dtype=np.uint64).astype(np.uint32)
+        ww = rng.integers(0, 2 ** 32, size=(s.Cout, s.K // 4), dtype=np.uint64).astype(np.uint32)
+        acc = torch.full((s.M * s.Cout,), 0x55555555, dtype=torch.int32, device="cuda")
+        B.qail_w8a8_gemm(*geom(s), dev(aw), dev(ww), acc_out=acc)
+        torch.cuda.synchronize()
+        got = host(acc, np.int32).reshape(s.M, s.Cout)
+        per = s.OH * s.OW
+        for b in (0, 13, 31):
+            ref = O.w8a8_conv_acc(aw[b:b + 1], ww, 1, *geom(s)[1:])
+            assert np.array_equal(got[b * per:(b + 1) * per], ref), (s.name, b)
+        del acc
+
+
 def test_w8a8_extremes(B):
     import torch
     s = synth.ConvShape("x", 1, 6, 6, 512, 32, 3, 3, 1, 1)
