@@ -319,7 +319,7 @@ def test_full_size_decode_linears_one_call_each(B, M):
     _sampled_full_size(B, M, {}, rows_per_linear=48, batched=False)
 
 
-@pytest.mark.parametrize("M", [288, 1024])
+@pytest.mark.parametrize("M", [64, 288, 1024])      # 64: the benchmark's largest decode batch, on the matrix cores
 def test_full_size_prefill_linears_sampled(B, M):
     _sampled_full_size(B, M, dict(outlier_frac=0.005))
 
@@ -366,6 +366,50 @@ def test_lora_beside_the_linear(B, M):
              (24, 40, 8, 16, 1.5)]           # a shape only the generic linear takes
     for y, ref, nx, nw in _lora_run(B, specs, M, 300 + M):
         assert w4a16_norm_err(y, ref, nx, nw) <= TOL_TINY_K       # widest bar: one shape has K < 512
+
+
+def test_lora_full_size_decode_layer_sampled(B):
+    """The decode layer with rank-32 adapters as the benchmark launches it (four Llama-2-7B linears,
+    M = 1, one batched call); the GPU quantises the full matrices, the oracle re-derives sampled rows."""
+    import torch
+    rng = np.random.default_rng(99)
+    M, r, scaling = 1, 32, 2.0
+    ents, lents, keep = [], [], []
+    for i, (name, N, K) in enumerate(synth.LLAMA7B_LINEARS):
+        w = synth.llm_weight(N, K, synth.seed_for(1, i, 0), outlier_frac=0.01)
+        xb = synth.llm_activation_bf16(M, K, synth.seed_for(1, i, 1))
+        ab, bb = synth.lora_factors(N, K, r, synth.seed_for(4, i, 5))
+        qb, sb, zb = B.qail_packed_sizes(N, K, 128, B.QAIL_W4_ASYM_GROUP)
+        qw = torch.zeros(qb // 4, dtype=torch.int32, device="cuda")
+        sc = torch.zeros(sb // 2, dtype=torch.int16, device="cuda")
+        zr = torch.zeros(zb // 4, dtype=torch.int32, device="cuda")
+        wd = dev(w)
+        B.qail_quantize_weights(wd, 128, B.QAIL_W4_ASYM_GROUP, qw, sc, zr)
+        torch.cuda.synchronize()
+        del wd
+        rows = np.sort(rng.choice(N, 64, replace=False))
+        rows[0], rows[-1] = 0, N - 1
+        ents.append(dict(N=N, K=K, group_size=128, qweight=qw, scales=sc, zeros=zr, x=dev(xb),
+                         y=torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")))
+        lents.append(dict(A=dev(ab), B=dev(bb), r=r, scaling=scaling, N=N, K=K))
+        keep.append((w[rows], xb, ab, bb[rows], rows))
+        del w
+    items = B.make_w4a16_items(ents, M)
+    loras = B.make_loras(lents)
+    ws = ws_for(B, B.qail_w4a16_lora_workspace(items, loras, len(ents), M))
+    B.qail_w4a16_linear_lora_batch(items, loras, len(ents), M, ws)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for e, (w_rows, xb, ab, bb_rows, rows) in zip(ents, keep):
+        N, K = e["N"], e["K"]
+        q, s_, z = O.quantize_w4_asym_group(w_rows, 128)
+        qw_ref, zw_ref = O.pack_w4a16(q, z)
+        y = host(e["y"], np.uint16).reshape(M, N)[:, rows]
+        ref = O.w4a16_linear_lora(xb, qw_ref, s_, zw_ref, 128, ab, bb_rows, scaling)
+        w_eff = O.dequantize_w4_asym_group(q, s_, z, 128) + scaling * (O.bf16_bits_to_f64(bb_rows) @ O.bf16_bits_to_f64(ab))
+        nx = np.sqrt((O.bf16_bits_to_f64(xb) ** 2).sum(axis=1))
+        worst = max(worst, w4a16_norm_err(y, ref, nx, np.sqrt((w_eff ** 2).sum(axis=1))))
+    assert worst <= TOL, worst
 
 
 def test_lora_changes_the_output_and_zero_adapter_does_not(B):
