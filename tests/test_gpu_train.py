@@ -78,3 +78,52 @@ def test_qbc_loss(B, Bn, D):
     assert np.all(np.abs(g - g_ref) <= 2e-6 * np.abs(g_ref).max() + 1e-12)
     if Bn > 1:
         assert not g[1].any()
+
+
+def test_training_operators_at_the_benchmark_sizes(B):
+    """The sizes bench.py times: fake quantisation of a 12288 x 4096 matrix in groups of 128 (bit for
+    bit), the learned-step quantiser over the same 50 M values (forward and masked gradient bit for
+    bit, step gradient against the float64 sum), the QBC loss and gradient of 1024 x 32000 logits."""
+    import torch
+    N, K, g = 12288, 4096, 128
+    w = synth.llm_weight(N, K, 4242, outlier_frac=0.01)
+    wd = dev(w)
+    out = torch.empty(N * K, dtype=torch.float32, device="cuda")
+    B.qail_fake_quant_w4(wd, g, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(out, np.float32).reshape(N, K), O.fake_quant_w4_group(w, g))
+    # learned-step quantiser on the same values
+    s = np.float32(0.004)
+    sd = dev(np.array([s], np.float32))
+    B.qail_lsq_forward(wd.view(-1), sd, -8, 7, out)
+    torch.cuda.synchronize()
+    v = w.reshape(-1)
+    assert np.array_equal(host(out, np.float32), O.lsq_fake_quant_fwd(v, s, -8, 7))
+    rng = np.random.default_rng(4243)
+    dout = rng.standard_normal(v.size).astype(np.float32)
+    dv = torch.empty(v.size, dtype=torch.float32, device="cuda")
+    ds = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.qail_lsq_backward_workspace(), dtype=torch.uint8, device="cuda")
+    gs = 1.0 / np.sqrt(v.size * 7)
+    B.qail_lsq_backward(wd.view(-1), dev(dout), sd, -8, 7, gs, dv, ds, ws)
+    torch.cuda.synchronize()
+    dv_ref, ds_ref = O.lsq_fake_quant_bwd(v, s, -8, 7, dout, gs)
+    assert np.array_equal(host(dv, np.float32), dv_ref)
+    r = v / s
+    t = np.where((r >= -8) & (r <= 7), np.rint(r) - r, np.clip(r, -8, 7)).astype(np.float64)
+    mag = gs * float(np.abs(dout.astype(np.float64) * t).sum())
+    assert abs(float(ds.item()) - ds_ref) <= 1e-5 * mag
+    del out, dv, wd
+    # QBC
+    Bn, D = 1024, 32000
+    lq = rng.standard_normal((Bn, D)).astype(np.float32)
+    lf = (lq + 0.1 * rng.standard_normal((Bn, D))).astype(np.float32)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    grad = torch.empty(Bn * D, dtype=torch.float32, device="cuda")
+    wsq = torch.empty(Bn, dtype=torch.float32, device="cuda")
+    B.qail_qbc_loss(dev(lq), dev(lf), loss, grad.view(Bn, D), wsq)
+    torch.cuda.synchronize()
+    l_ref, g_ref = O.qbc_loss(lq, lf)
+    assert abs(float(loss.item()) - l_ref) <= 2e-6 * l_ref
+    gh = host(grad, np.float32).reshape(Bn, D).astype(np.float64)
+    assert np.all(np.abs(gh - g_ref) <= 2e-6 * np.abs(g_ref).max())
