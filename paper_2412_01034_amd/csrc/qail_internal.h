@@ -65,6 +65,9 @@ bool decode4_supports(const qail_wdesc& d, int M);
 hipError_t launch_w4a16_decode4(const qail_w4a16_item* items, int count, int M, hipStream_t st);
 bool smallm_supports(const qail_wdesc& d, int M);
 hipError_t launch_w4a16_smallm(const qail_w4a16_item* items, int count, int M, hipStream_t st);
+// Compute units of the current device (256 when none can be asked); the launchers size their grids by it.
+int device_cu_count();
+
 // fp16-MFMA GEMM for M > 16; needs gemm_f16_workspace() bytes of 256-byte aligned device memory.
 bool gemm_f16_supports(const qail_wdesc& d, int M);
 size_t gemm_f16_workspace(const qail_wdesc& d, int M);

@@ -355,18 +355,6 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
     }
 }
 
-int d4_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
 size_t d4_item_bytes(const qail_wdesc& d) {
     const size_t G = (size_t)d.K / d.group_size;
     return (size_t)d.N * (d.K / 2 + G * 2 + ((G + 7) / 8) * 4);
@@ -388,7 +376,7 @@ hipError_t d4_launch_chunk(const qail_w4a16_item* items, int count, int M, hipSt
     }
     D4Args a;
     memset(a.item_of_block, 0, sizeof(a.item_of_block));
-    int grid = d4_cus();
+    int grid = device_cu_count();
     if (grid < count) grid = count;
     // blocks per item in proportion to its bytes (largest remainder), at least one each
     double total = 0;

@@ -611,19 +611,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_fixup_kernel(const GemmBatch a
     }
 }
 
-int gemm_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
-int gemm_max_blocks() { return gemm_cus() < kMaxGemmBlocks ? gemm_cus() : kMaxGemmBlocks; }
+int gemm_max_blocks() { return device_cu_count() < kMaxGemmBlocks ? device_cu_count() : kMaxGemmBlocks; }
 
 // Fills in the work decomposition of one linear on `cus` blocks; returns the blocks it uses.
 template <int MB, int WN>

@@ -470,18 +470,6 @@ __global__ __launch_bounds__(kGemvThreads) void w4a16_gemv_lora_kernel(const Gem
     gemv_body<kUnits, true>(args, lora);
 }
 
-int device_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
 size_t item_bytes(const qail_wdesc& d) {
     const size_t G = (size_t)d.K / d.group_size;
     return (size_t)d.N * (d.K / 2 + G * 2 + ((G + 7) / 8) * 4);
@@ -490,7 +478,7 @@ size_t item_bytes(const qail_wdesc& d) {
 hipError_t launch_chunk(const qail_w4a16_item* items, const GemvLora* loras, int count, hipStream_t st) {
     GemvArgs a;
     memset(a.item_of_block, 0, sizeof(a.item_of_block));
-    int grid = device_cus();
+    int grid = device_cu_count();
     if (grid < count) grid = count;
     // blocks per item in proportion to its bytes (largest remainder), at least one each
     double total = 0;

@@ -277,18 +277,6 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     }
 }
 
-int sm_device_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
 size_t sm_item_bytes(const qail_wdesc& d) {
     const size_t G = (size_t)d.K / d.group_size;
     return (size_t)d.N * (d.K / 2 + G * 2 + ((G + 7) / 8) * 4);
@@ -303,7 +291,7 @@ hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipSt
         attr_done = true;
     }
     SmArgs a;
-    int grid = sm_device_cus();
+    int grid = device_cu_count();
     if (grid < count) grid = count;
     // Blocks per item: a block's time is taken as its bytes plus, per pass over K, the bytes it could
     // have streamed while a pass's activations are fetched and staged (a figure measured on this GPU);

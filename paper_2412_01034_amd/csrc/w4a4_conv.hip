@@ -507,18 +507,6 @@ __global__ __launch_bounds__(256) void w4a4_generic_u4_kernel(
     out.out_u4[o] = fused_word(acc, out, (size_t)m, n0, gm.Cout);
 }
 
-int conv_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
 template <int kBits, int BM, int BN, int KS = 1>
 void launch_tiled(const ConvGeom& gm, const uint32_t* a, const uint32_t* w, const ConvOut& out, hipStream_t st) {
     dim3 grid((gm.Cout + BN - 1) / BN, (gm.M + BM - 1) / BM);
@@ -546,7 +534,7 @@ hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_
     // a 16-byte chunk (32 or 16 codes) must lie inside one filter tap
     if (d.Cin % (4 * kPerWord) == 0 && d.KH * d.KW <= 32 && fits32 && ksteps + 4 * (kStages + 1) <= kMaxSteps) {
         // the largest tile that still gives every CU about two blocks
-        const long long want = 2LL * conv_cus();
+        const long long want = 2LL * device_cu_count();
         auto blocks = [&](int bm, int bn) {
             return (long long)((gm.M + bm - 1) / bm) * ((gm.Cout + bn - 1) / bn);
         };
@@ -554,8 +542,8 @@ hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_
         if (wide && blocks(128, 128) >= want) launch_tiled<kBits, 128, 128>(gm, a, w, out, st);
         else if (blocks(128, 64) >= want) launch_tiled<kBits, 128, 64>(gm, a, w, out, st);
         else if (wide && blocks(64, 128) >= want / 2) launch_tiled<kBits, 64, 128>(gm, a, w, out, st);
-        else if (blocks(64, 64) <= conv_cus() && ksteps >= 16) launch_tiled<kBits, 64, 64, 4>(gm, a, w, out, st);
-        else if (blocks(64, 64) <= 2 * conv_cus() && ksteps >= 8) launch_tiled<kBits, 64, 64, 2>(gm, a, w, out, st);
+        else if (blocks(64, 64) <= device_cu_count() && ksteps >= 16) launch_tiled<kBits, 64, 64, 4>(gm, a, w, out, st);
+        else if (blocks(64, 64) <= 2 * device_cu_count() && ksteps >= 8) launch_tiled<kBits, 64, 64, 2>(gm, a, w, out, st);
         else launch_tiled<kBits, 64, 64>(gm, a, w, out, st);
     } else if (out.out_u4) {
         const size_t words = (size_t)gm.M * (d.Cout / 8);

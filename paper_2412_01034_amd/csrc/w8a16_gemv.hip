@@ -269,18 +269,6 @@ __global__ __launch_bounds__(kW8Threads) void w8a16_stream_kernel(const W8Batch 
     if (lane < nrw) a.y[s0 + wave + kW8Waves * lane] = f32_to_bf16_rne(ykeep);
 }
 
-int w8_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cus = prop.multiProcessorCount;
-        if (cus <= 0) cus = 256;
-    }
-    return cus;
-}
-
 }  // namespace
 
 bool w8a16_stream_supports(const qail_wdesc& d, int M) {
@@ -299,7 +287,7 @@ hipError_t launch_w8a16_stream_batch(const qail_w8a16_item* items, int count, hi
         // blocks in proportion to the bytes, one block per CU in all; per linear fewer when there
         // are fewer than 16 rows for each block, more when a block would get more rows than its
         // waves can park results for (64 each)
-        const int cus = w8_cus();
+        const int cus = device_cu_count();
         double total = 0;
         for (int i = 0; i < n; ++i) total += (double)its[i].d.N * its[i].d.K;
         W8Batch b;
