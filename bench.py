@@ -32,8 +32,8 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/w4a16_gemv_decode_layer_pmc.txt), and the sha256 of the kernel source the
 # counters were taken on; reported as null once the kernel has changed.
-GEMV_TRAFFIC_BYTES = 106022244
-GEMV_TRAFFIC_SOURCE_SHA256 = "c1cb59950d42957865a77e789abaeec79f31594cf0564795b98330734ff883c6"
+GEMV_TRAFFIC_BYTES = 106026773
+GEMV_TRAFFIC_SOURCE_SHA256 = "024f04c2898fe415d94a1b883e8a1bb3ee68a85633a18a1442ba7d406ed56e53"
 
 HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0     # dense bf16 MFMA, published
