@@ -24,7 +24,7 @@ namespace qail {
 
 namespace {
 
-constexpr int kW8Waves = 16;
+constexpr int kW8Waves = 8;    // two blocks share a CU
 constexpr int kW8Threads = kW8Waves * kWave;
 constexpr int kW8Ring = 8;            // wave-wide loads (1 KB each) in flight per wave
 constexpr int kW8ChunkK = 1024;       // k of a row per wave-wide load (16 per lane)
@@ -284,10 +284,15 @@ hipError_t launch_w8a16_stream_batch(const qail_w8a16_item* items, int count, hi
     for (int i0 = 0; i0 < count; i0 += kW8Batch) {
         const int n = count - i0 < kW8Batch ? count - i0 : kW8Batch;
         const qail_w8a16_item* its = items + i0;
-        // blocks in proportion to the bytes, one block per CU in all; per linear fewer when there
+        // blocks in proportion to the bytes, one or two blocks per CU in all; per linear fewer when there
         // are fewer than 16 rows for each block, more when a block would get more rows than its
         // waves can park results for (64 each)
-        const int cus = device_cu_count();
+        // two blocks of eight waves per CU when that leaves every wave three rows or more, else one
+        // (as for the 4-bit stream: the second helping evens out the finish)
+        long long rows_total = 0;
+        for (int i = 0; i < n; ++i) rows_total += its[i].d.N;
+        int cus = device_cu_count();
+        if (rows_total >= 2LL * cus * kW8Waves * 3) cus *= 2;
         double total = 0;
         for (int i = 0; i < n; ++i) total += (double)its[i].d.N * its[i].d.K;
         W8Batch b;
