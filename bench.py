@@ -79,7 +79,7 @@ def linear_bytes(N, K, M, g=GROUP):
 def main():
     args = parse()
     if args.gpus != 1:
-        log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        log("bench.py: the library runs on one GPU only (no collectives, no sharding); use --gpus 1")
         sys.exit(2)
 
     import numpy as np
