@@ -5,7 +5,7 @@
 // Sec. 2.1 / Sec. 5.1: the driving policy's convolutions are compute-bound, so both
 // GEMM operands are 4-bit integers.  CDNA4 has no 4-bit integer matrix
 // instruction, so nibbles are widened to int8 in registers and fed to
-// v_mfma_i32_16x16x64_i8 (int32 accumulate):
+// v_mfma_i32_32x32x32_i8 (int32 accumulate):
 //   * unsigned activation codes:  w & 0x0F0F0F0F  and (w >> 4) & 0x0F0F0F0F
 //     give the even and the odd codes of a word as bytes;
 //   * signed weight codes are moved to the HIGH nibble of each byte,
@@ -15,15 +15,18 @@
 // The two operands are permuted along k in the same way (even codes, then odd
 // codes of each word), which leaves the sum unchanged.
 //
-// MFMA operand layout (16x16x64 int8, wave64): lane l supplies row (A) / column
-// (B) l%16 and the 16 consecutive k starting at 16*(l/16); it receives
-// D[4*(l/16)+r][l%16], r = 0..3.  A = activations (rows m), B = weights (columns n).
+// MFMA operand layout (32x32x32 int8, wave64): lane l supplies row (A) / column
+// (B) l%32 and the 16 consecutive k starting at 16*(l/32); register r of its 16
+// results is D[8*(r/4) + 4*(l/32) + r%4][l%32].  A = activations (rows m),
+// B = weights (columns n).  The 16x16x64 form has the same operand volume per
+// multiply-add but a wave issuing nothing else reaches only 0.6 of the matrix
+// rate with it (2.7 against 4.5 POP/s over the chip, measured), the 32x32x32 form all of it.
 //
 // Tiling: a block of 4 waves (2 x 2) owns a BM x BN output tile and walks K in
 // steps of 128 codes (16 packed words per row; K is ordered (kh, kw, c), so a step
 // is a run of channels of one or two filter taps).  Nibbles stay packed in LDS
-// (half the LDS traffic of int8); global loads run several steps ahead in a register
-// ring and are moved to one of two LDS buffers when they are due, one barrier per step.
+// (half the LDS traffic of int8); the load unit writes the tiles of the next two steps
+// straight into a ring of three LDS slots, one barrier per step.
 // Zero padding costs nothing: code 0 of the unsigned activations is the value 0.
 #include "qail_internal.h"
 
@@ -148,8 +151,9 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
     constexpr int kLA = BM / 64;   // wave-wide loads per wave and step for the activation tile
     constexpr int kLB = BN / 64;   // ... for the weight tile
     constexpr int kL = kLA + kLB;
-    constexpr int kTM = BM / 32;   // MFMA tiles per wave along m
-    constexpr int kTN = BN / 32;   // ... along n
+    constexpr int kUM = BM / 64;   // 32 x 32 MFMA tiles per wave along m
+    constexpr int kUN = BN / 64;   // ... along n
+    constexpr int kAccs = kUM * kUN == 1 ? 2 : 1;  // a lone tile alternates between two accumulators (no dependent pair)
     constexpr int kStageBytes = (BM + BN) * 64;
     constexpr int kSPitch = BN + 4;  // words per row of the int32 staging tile of the epilogue
     constexpr int kPasses = BM * kSPitch * 4 <= kStages * kStageBytes ? 1 : 2;  // epilogue passes over the rows
@@ -251,58 +255,74 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
             dma16(rw, poff[i], lds0 + slot * kStageBytes + BM * 64 + (4 * (i - kLA) + wave) * 1024);
     };
 
-    // Fragment reads.  4-bit: lane (r16, kq) takes 8 bytes (16 codes) of row r16 of a 16-row tile
-    // for each of the two 64-code MFMA steps of a K step.  8-bit: 16 bytes, one MFMA step.
-    const int r16 = lane & 15, kq = lane >> 4;
-    int foff[2];
+    // Fragment reads for the 32 x 32 x 32 MFMA (a wave issuing only 16 x 16 x 64 ones reaches 0.6 of
+    // the matrix rate, measured): lane (r32, kh) holds 16 consecutive codes of row r32, the
+    // half kh of the MFMA's 32.  4-bit: a K step is two 64-code halves (sub), each two MFMAs (h)
+    // deep; the lane takes 8 bytes of chunk 2 sub + h.  8-bit: a K step is two MFMAs deep; the
+    // lane takes the 16 bytes of chunk 2 h + kh.
+    const int r32 = lane & 31, kh = lane >> 5;
+    int foff[2][2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
-        foff[sub] = kBits == 4 ? r16 * 64 + (((2 * sub + (kq >> 1)) ^ ((r16 >> 2) & 3)) << 4) + (kq & 1) * 8
-                               : r16 * 64 + ((kq ^ ((r16 >> 2) & 3)) << 4);
-
-    i32x4_t acc[kTM][kTN];
 #pragma unroll
-    for (int i = 0; i < kTM; ++i)
-#pragma unroll
-        for (int j = 0; j < kTN; ++j) acc[i][j] = i32x4_t{0, 0, 0, 0};
+        for (int h = 0; h < 2; ++h)
+            foff[sub][h] = kBits == 4 ? r32 * 64 + (((2 * sub + h) ^ ((r32 >> 2) & 3)) << 4) + kh * 8
+                                      : r32 * 64 + (((2 * h + kh) ^ ((r32 >> 2) & 3)) << 4);
 
-    i32x4_t af[2][kTM], bf[2][kTN];
+    i32x16_t acc[kUM][kUN][kAccs];
+#pragma unroll
+    for (int i = 0; i < kUM; ++i)
+#pragma unroll
+        for (int j = 0; j < kUN; ++j)
+#pragma unroll
+            for (int c = 0; c < kAccs; ++c)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][c][r] = 0;
+
+    i32x4_t af[2][kUM][2], bf[2][kUN][2];
     auto fetch = [&](int slot, int sub, int reg) {
-        const unsigned char* As = smem + slot * kStageBytes + wm * (BM / 2) * 64 + foff[sub];
-        const unsigned char* Bs = smem + slot * kStageBytes + BM * 64 + wn * (BN / 2) * 64 + foff[sub];
+        const unsigned char* As = smem + slot * kStageBytes + wm * (BM / 2) * 64;
+        const unsigned char* Bs = smem + slot * kStageBytes + BM * 64 + wn * (BN / 2) * 64;
 #pragma unroll
-        for (int i = 0; i < kTM; ++i) {
-            if constexpr (kBits == 4) {
-                const uint2 p = *reinterpret_cast<const uint2*>(As + i * 16 * 64);
-                af[reg][i] = i32x4_t{(int)(p.x & 0x0F0F0F0Fu), (int)((p.x >> 4) & 0x0F0F0F0Fu),
-                                     (int)(p.y & 0x0F0F0F0Fu), (int)((p.y >> 4) & 0x0F0F0F0Fu)};
-            } else {
-                af[reg][i] = *reinterpret_cast<const i32x4_t*>(As + i * 16 * 64);
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int i = 0; i < kUM; ++i) {
+                if constexpr (kBits == 4) {
+                    const uint2 p = *reinterpret_cast<const uint2*>(As + foff[sub][h] + i * 32 * 64);
+                    af[reg][i][h] = i32x4_t{(int)(p.x & 0x0F0F0F0Fu), (int)((p.x >> 4) & 0x0F0F0F0Fu),
+                                            (int)(p.y & 0x0F0F0F0Fu), (int)((p.y >> 4) & 0x0F0F0F0Fu)};
+                } else {
+                    af[reg][i][h] = *reinterpret_cast<const i32x4_t*>(As + foff[sub][h] + i * 32 * 64);
+                }
             }
-        }
 #pragma unroll
-        for (int j = 0; j < kTN; ++j) {
-            if constexpr (kBits == 4) {
-                const uint2 p = *reinterpret_cast<const uint2*>(Bs + j * 16 * 64);
-                bf[reg][j] = i32x4_t{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
-                                     (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
-            } else {
-                bf[reg][j] = *reinterpret_cast<const i32x4_t*>(Bs + j * 16 * 64);
+            for (int j = 0; j < kUN; ++j) {
+                if constexpr (kBits == 4) {
+                    const uint2 p = *reinterpret_cast<const uint2*>(Bs + foff[sub][h] + j * 32 * 64);
+                    bf[reg][j][h] = i32x4_t{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
+                                            (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
+                } else {
+                    bf[reg][j][h] = *reinterpret_cast<const i32x4_t*>(Bs + foff[sub][h] + j * 32 * 64);
+                }
             }
         }
     };
     auto multiply = [&](int reg) {
 #pragma unroll
-        for (int i = 0; i < kTM; ++i)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int j = 0; j < kTN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[reg][i], bf[reg][j], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < kUM; ++i)
+#pragma unroll
+                for (int j = 0; j < kUN; ++j)
+                    acc[i][j][h % kAccs] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[reg][i][h], bf[reg][j][h],
+                                                                                 acc[i][j][h % kAccs], 0, 0, 0);
         // issue order: the LDS reads and the widening of the next fragments go between the MFMAs
-        constexpr int kM = kTM * kTN, kR = kTM + kTN;
+        constexpr int kM = 2 * kUM * kUN, kR = 2 * (kUM + kUN);
+        constexpr int kRead = (kR + kM - 1) / kM;
 #pragma unroll
         for (int u = 0; u < kM; ++u) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (u < kR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (u * kRead < kR) __builtin_amdgcn_sched_group_barrier(0x100, kRead, 0);
             if (kBits == 4) __builtin_amdgcn_sched_group_barrier(0x002, (4 * kR + kM - 1) / kM, 0);
         }
     };
@@ -373,14 +393,17 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
         if (pass) __syncthreads();  // the previous pass has been read
         if (kPasses == 1 || wm == pass) {
             const int rbase = kPasses == 1 ? wm * (BM / 2) : 0;
+            // 32 x 32 accumulator: register r of lane (c32, hi) is row 8 (r / 4) + 4 hi + r % 4, column c32
 #pragma unroll
-            for (int i = 0; i < kTM; ++i)
+            for (int i = 0; i < kUM; ++i)
 #pragma unroll
-                for (int j = 0; j < kTN; ++j)
+                for (int j = 0; j < kUN; ++j)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        stage[(rbase + i * 16 + (lane >> 4) * 4 + r) * kSPitch + wn * (BN / 2) + j * 16 + (lane & 15)] =
-                            kBits == 4 ? acc[i][j][r] >> 4 : acc[i][j][r];  // 4-bit: the accumulator is 16 * result
+                    for (int r = 0; r < 16; ++r) {
+                        const int v = kAccs == 2 ? acc[i][j][0][r] + acc[i][j][kAccs - 1][r] : acc[i][j][0][r];
+                        stage[(rbase + i * 32 + 8 * (r / 4) + 4 * kh + (r % 4)) * kSPitch + wn * (BN / 2) + j * 32 + r32] =
+                            kBits == 4 ? v >> 4 : v;  // 4-bit: the accumulator is 16 * result
+                    }
         }
         __syncthreads();
         if (out.out_u4) {
