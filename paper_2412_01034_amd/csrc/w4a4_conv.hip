@@ -29,6 +29,7 @@
 // straight into a ring of three LDS slots, one barrier per step.
 // Zero padding costs nothing: code 0 of the unsigned activations is the value 0.
 #include "qail_internal.h"
+#include <cmath>
 
 namespace qail {
 
@@ -61,19 +62,34 @@ struct ConvOut {
     const uint32_t* res_u4;
     const float* res_f32;
     float s_out, res_scale;
+    float inv_s_out;  // 1 / s_out, correctly rounded (host division)
+    int quick;        // s_out and its reciprocal are normal numbers: the quotient may be tried as a product first
 };
 
 // One output element of the fused epilogue (Sec. 5.1: every activation tensor of the driving
 // encoder is 4-bit with one step per tensor, so the consumer's step is known here).  Each
 // line is one correctly rounded fp32 operation; contraction to fma is switched off because
 // the code is decided by these roundings and must equal the reference bit for bit.
-__device__ __forceinline__ uint32_t fused_code(int acc, float scale, float bias, float r, float s_out) {
+__device__ __forceinline__ float fused_value(int acc, float scale, float bias, float r) {
 #pragma clang fp contract(off)
     float t = (float)acc * scale;
     t = t + bias;
     t = t + r;
-    t = fmaxf(t, 0.f);
+    return fmaxf(t, 0.f);
+}
+__device__ __forceinline__ uint32_t fused_code(float t, float s_out) {
     const float q = __builtin_rintf(t / s_out);
+    return (uint32_t)fminf(q, 15.f);
+}
+// The same code without the division wherever that is provably the same: u = t * fl(1 / s) is
+// within 1.5 * 2^-23 (relative) of fl(t / s), so below 16 the two differ by less than 2^-18 and
+// round to the same integer unless u lies within 2^-17 of a half-integer (`doubt`; the caller
+// then divides).  From 15.6 upwards both round to 16 or more and the code is 15 either way.
+__device__ __forceinline__ uint32_t fused_code_quick(float t, float inv_s, bool& doubt) {
+#pragma clang fp contract(off)
+    const float u = t * inv_s;
+    const float q = __builtin_rintf(u);
+    doubt = doubt || (__builtin_fabsf(__builtin_fabsf(u - q) - 0.5f) < 0x1p-17f);
     return (uint32_t)fminf(q, 15.f);
 }
 
@@ -99,11 +115,17 @@ __device__ __forceinline__ uint32_t fused_word(const int (&acc)[8], const ConvOu
 #pragma unroll
         for (int e = 0; e < 8; ++e) r[e] = 0.f;
     }
-    uint32_t word = 0;
+    float t[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        // without a shortcut r is 0 and t + 0 == t (a -0 becomes +0; both end as code 0)
-        word |= fused_code(acc[e], sc[e], bi[e], r[e], o.s_out) << (4 * e);
+    for (int e = 0; e < 8; ++e) t[e] = fused_value(acc[e], sc[e], bi[e], r[e]);  // no shortcut: t + 0 == t
+    uint32_t word = 0;
+    bool doubt = !o.quick;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) word |= fused_code_quick(t[e], o.inv_s_out, doubt) << (4 * e);
+    if (__builtin_expect(doubt, 0)) {
+        word = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) word |= fused_code(t[e], o.s_out) << (4 * e);
     }
     return word;
 }
@@ -583,20 +605,22 @@ hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_
 
 hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
                             const float* scale, const float* bias, float* y, hipStream_t st) {
-    const ConvOut out{acc, scale, bias, y, nullptr, nullptr, nullptr, 1.f, 0.f};
+    const ConvOut out{acc, scale, bias, y, nullptr, nullptr, nullptr, 1.f, 0.f, 1.f, 0};
     return launch_conv<4>(d, a, w, out, st);
 }
 
 hipError_t launch_w8a8_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
                             const float* scale, const float* bias, float* y, hipStream_t st) {
-    const ConvOut out{acc, scale, bias, y, nullptr, nullptr, nullptr, 1.f, 0.f};
+    const ConvOut out{acc, scale, bias, y, nullptr, nullptr, nullptr, 1.f, 0.f, 1.f, 0};
     return launch_conv<8>(d, a, w, out, st);
 }
 
 hipError_t launch_w4a4_conv_u4(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const float* scale,
                                const float* bias, float s_out, const uint32_t* res_u4, float res_scale,
                                const float* res_f32, uint32_t* out_u4, hipStream_t st) {
-    const ConvOut out{nullptr, scale, bias, nullptr, out_u4, res_u4, res_f32, s_out, res_scale};
+    const float inv = 1.0f / s_out;
+    const int quick = std::isnormal(s_out) && std::isnormal(inv) && s_out > 0.f;
+    const ConvOut out{nullptr, scale, bias, nullptr, out_u4, res_u4, res_f32, s_out, res_scale, inv, quick};
     return launch_conv<4>(d, a, w, out, st);
 }
 

@@ -177,6 +177,30 @@ def test_fused_u4_ties_and_clamps(B):
     assert np.array_equal(got, O.pack_nibbles(ref))
 
 
+@pytest.mark.parametrize("s_out", [0.3, 0.0123, 1.1754944e-38, 1e-39, 3e38])
+def test_fused_u4_quotient_paths(B, s_out):
+    # The kernel may replace t / s_out by a product when that provably gives the same code and
+    # divides otherwise.  scale = s_out / 2 (exact) puts t / s_out within an ulp of a multiple of
+    # 1/2 for every element, a step that is not a power of two makes the quotient inexact, and
+    # steps at the ends of the range (smallest normal, denormal, near the largest float) take
+    # the division throughout.
+    s = synth.ConvShape("quot", 2, 5, 5, 64, 64, 3, 3, 1, 1)
+    a = synth.random_codes((s.B, s.H, s.W, s.Cin), 0, 3, 31).astype(np.uint8)
+    w = synth.random_codes((s.Cout, s.K), -1, 1, 32)
+    aw, ww = O.pack_nibbles(a), O.pack_nibbles(w)
+    acc_ref = O.w4a4_conv_acc(aw, ww, *geom(s))
+    so = np.float32(s_out)
+    scale = np.full(s.Cout, so / np.float32(2), np.float32)
+    bias = np.zeros(s.Cout, np.float32)
+    with np.errstate(over="ignore"):                          # the largest step overflows to inf: code 15
+        ref = O.fused_requant_u4(acc_ref, scale, bias, so)
+    if 1e-30 < s_out < 1e30:
+        assert len(np.unique(ref)) >= 8                       # codes spread over the range
+        assert np.any((acc_ref > 0) & (acc_ref < 31) & (acc_ref % 2 == 1))   # near-ties below the clamp
+    got = gpu_conv_u4(B, s, aw, ww, scale, bias, so)
+    assert np.array_equal(got, O.pack_nibbles(ref))
+
+
 def test_fused_output_feeds_the_next_layer(B):
     # conv1 (fused) -> conv2 (int32): the codes written by the first call are the a_u4 of the second
     import torch
