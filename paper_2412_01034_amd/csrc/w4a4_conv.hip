@@ -93,31 +93,13 @@ __device__ __forceinline__ uint32_t fused_code_quick(float t, float inv_s, bool&
     return (uint32_t)fminf(q, 15.f);
 }
 
-// 8 consecutive channels of one output pixel -> one packed word.
-__device__ __forceinline__ uint32_t fused_word(const int (&acc)[8], const ConvOut& o, size_t m, int n0, int cout) {
-    const float4 s0 = *reinterpret_cast<const float4*>(o.scale + n0), s1 = *reinterpret_cast<const float4*>(o.scale + n0 + 4);
-    const float4 b0 = *reinterpret_cast<const float4*>(o.bias + n0), b1 = *reinterpret_cast<const float4*>(o.bias + n0 + 4);
-    const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-    const float bi[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-    float r[8];
-    if (o.res_u4) {
-        const uint32_t rw = o.res_u4[m * (size_t)(cout / 8) + n0 / 8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-#pragma clang fp contract(off)
-            r[e] = o.res_scale * (float)((rw >> (4 * e)) & 0xFu);
-        }
-    } else if (o.res_f32) {
-        const float4 r0 = *reinterpret_cast<const float4*>(o.res_f32 + m * (size_t)cout + n0);
-        const float4 r1 = *reinterpret_cast<const float4*>(o.res_f32 + m * (size_t)cout + n0 + 4);
-        r[0] = r0.x; r[1] = r0.y; r[2] = r0.z; r[3] = r0.w; r[4] = r1.x; r[5] = r1.y; r[6] = r1.z; r[7] = r1.w;
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) r[e] = 0.f;
-    }
+// 8 consecutive channels of one output pixel -> one packed word; sc / bi: their scales and
+// biases, r: their shortcut values (0 without a shortcut: t + 0 == t).
+__device__ __forceinline__ uint32_t fused_pack(const int (&acc)[8], const float (&sc)[8], const float (&bi)[8],
+                                               const float (&r)[8], const ConvOut& o) {
     float t[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) t[e] = fused_value(acc[e], sc[e], bi[e], r[e]);  // no shortcut: t + 0 == t
+    for (int e = 0; e < 8; ++e) t[e] = fused_value(acc[e], sc[e], bi[e], r[e]);
     uint32_t word = 0;
     bool doubt = !o.quick;
 #pragma unroll
@@ -128,6 +110,32 @@ __device__ __forceinline__ uint32_t fused_word(const int (&acc)[8], const ConvOu
         for (int e = 0; e < 8; ++e) word |= fused_code(t[e], o.s_out) << (4 * e);
     }
     return word;
+}
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+// Shortcut values of 8 channels from a word of 4-bit codes (each times its step: one rounding).
+__device__ __forceinline__ void shortcut_from_codes(uint32_t rw, float res_scale, float (&r)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+#pragma clang fp contract(off)
+        r[e] = res_scale * (float)((rw >> (4 * e)) & 0xFu);
+    }
+}
+__device__ __forceinline__ uint32_t fused_word(const int (&acc)[8], const ConvOut& o, size_t m, int n0, int cout) {
+    float sc[8], bi[8], r[8];
+    load8(o.scale + n0, sc);
+    load8(o.bias + n0, bi);
+    if (o.res_u4) {
+        shortcut_from_codes(o.res_u4[m * (size_t)(cout / 8) + n0 / 8], o.res_scale, r);
+    } else if (o.res_f32) {
+        load8(o.res_f32 + m * (size_t)cout + n0, r);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = 0.f;
+    }
+    return fused_pack(acc, sc, bi, r, o);
 }
 
 // Global -> LDS copy by the load unit through a buffer descriptor: lane l's 16 bytes at byte
@@ -410,9 +418,39 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
     // are staged in LDS (pitch BN + 4 words: conflict-free for the writes below) and leave as
     // whole pieces of rows.
     int32_t* const stage = reinterpret_cast<int32_t*>(smem);
+    // A thread writes the same columns in every iteration of the store loops below (the block's
+    // thread count is a multiple of the pieces per row), so their scales and biases are fetched
+    // once, here, and the shortcut words of a pass before its barrier: a load inside the store
+    // loop would wait out its full latency in every iteration, behind the previous store.
+    constexpr int kWordsPerRow = BN / 8, kQuadsPerRow = BN / 4;
+    static_assert(kThreads % kWordsPerRow == 0 && kThreads % kQuadsPerRow == 0, "columns fixed per thread");
+    constexpr int kItF = (kPassRows * kWordsPerRow + kThreads - 1) / kThreads;
+    const int n0f = bn + (t % kWordsPerRow) * 8, n0q = bn + (t % kQuadsPerRow) * 4;
+    const bool vec = (gm.Cout % 4) == 0;
+    float scf[8], bif[8];
+    float4 scq = make_float4(0.f, 0.f, 0.f, 0.f), biq = scq;
+    if (out.out_u4) {
+        if (n0f < gm.Cout) {
+            load8(out.scale + n0f, scf);
+            load8(out.bias + n0f, bif);
+        }
+    } else if (out.y && vec && n0q < gm.Cout) {
+        scq = *reinterpret_cast<const float4*>(out.scale + n0q);
+        biq = *reinterpret_cast<const float4*>(out.bias + n0q);
+    }
 #pragma unroll
     for (int pass = 0; pass < kPasses; ++pass) {
         if (pass) __syncthreads();  // the previous pass has been read
+        uint32_t rwf[kItF];
+        if (out.out_u4 && out.res_u4) {
+#pragma unroll
+            for (int it = 0; it < kItF; ++it) {
+                const int idx = t + it * kThreads;
+                const int m = bm + pass * kPassRows + idx / kWordsPerRow;
+                rwf[it] = (idx < kPassRows * kWordsPerRow && m < gm.M && n0f < gm.Cout)
+                              ? out.res_u4[(size_t)m * (gm.Cout / 8) + n0f / 8] : 0u;
+            }
+        }
         if (kPasses == 1 || wm == pass) {
             const int rbase = kPasses == 1 ? wm * (BM / 2) : 0;
             // 32 x 32 accumulator: register r of lane (c32, hi) is row 8 (r / 4) + 4 hi + r % 4, column c32
@@ -430,10 +468,12 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
         __syncthreads();
         if (out.out_u4) {
             // fused output: 8 consecutive channels of a pixel -> one packed word
-            constexpr int kWordsPerRow = BN / 8;
-            for (int idx = t; idx < kPassRows * kWordsPerRow; idx += kThreads) {
+#pragma unroll
+            for (int it = 0; it < kItF; ++it) {
+                const int idx = t + it * kThreads;
+                if (idx >= kPassRows * kWordsPerRow) break;
                 const int row = idx / kWordsPerRow, wd = idx % kWordsPerRow;
-                const int m = bm + pass * kPassRows + row, n0 = bn + wd * 8;
+                const int m = bm + pass * kPassRows + row, n0 = n0f;
                 if (m >= gm.M || n0 >= gm.Cout) continue;
                 i32x4_t v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
 #pragma unroll
@@ -443,12 +483,19 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
                     v1 += *reinterpret_cast<const i32x4_t*>(&sg[row * kSPitch + wd * 8 + 4]);
                 }
                 const int av[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-                out.out_u4[(size_t)m * (gm.Cout / 8) + n0 / 8] = fused_word(av, out, (size_t)m, n0, gm.Cout);
+                float r[8];
+                if (out.res_u4) {
+                    shortcut_from_codes(rwf[it], out.res_scale, r);
+                } else if (out.res_f32) {
+                    load8(out.res_f32 + (size_t)m * gm.Cout + n0, r);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) r[e] = 0.f;
+                }
+                out.out_u4[(size_t)m * (gm.Cout / 8) + n0 / 8] = fused_pack(av, scf, bif, r, out);
             }
         } else {
             // plain outputs: 4 consecutive channels per thread, 16-byte stores when Cout allows
-            constexpr int kQuadsPerRow = BN / 4;
-            const bool vec = (gm.Cout % 4) == 0;
             for (int idx = t; idx < kPassRows * kQuadsPerRow; idx += kThreads) {
                 const int row = idx / kQuadsPerRow, qd = idx % kQuadsPerRow;
                 const int m = bm + pass * kPassRows + row, n0 = bn + qd * 4;
@@ -462,8 +509,7 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
                 if (vec) {
                     if (out.acc) *reinterpret_cast<i32x4_t*>(out.acc + o) = v;
                     if (out.y) {
-                        const float4 sc = *reinterpret_cast<const float4*>(out.scale + n0);
-                        const float4 bi = *reinterpret_cast<const float4*>(out.bias + n0);
+                        const float4 sc = scq, bi = biq;
                         *reinterpret_cast<float4*>(out.y + o) =
                             make_float4(fmaf((float)v[0], sc.x, bi.x), fmaf((float)v[1], sc.y, bi.y),
                                         fmaf((float)v[2], sc.z, bi.z), fmaf((float)v[3], sc.w, bi.w));
