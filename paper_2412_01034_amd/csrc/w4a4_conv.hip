@@ -39,7 +39,28 @@ constexpr int kStepWords = 16;  // packed words per row per K step (128 codes)
 
 struct ConvGeom {
     int B, H, W, Cin, Cout, KH, KW, stride, pad, OH, OW, M;
+    // ceil(2^32 / d) for the four divisors of the tiled kernel's set-up (OH * OW, OW, words per
+    // pixel, KW), valid when `fastdiv` is set: the host has checked that the high word of
+    // x * magic is x / d for every x the kernel divides.
+    uint32_t mg_ohow, mg_ow, mg_cw, mg_kw;
+    int fastdiv;
 };
+
+// x / d as the high word of x * ceil(2^32 / d): with e = d * magic - 2^32 (0 <= e < d) the product
+// is x / d + x e / (d 2^32), and its floor is floor(x / d) as long as x e < 2^32 (then the excess
+// stays below 1 / d).  `ok` tells whether that holds for every x up to xmax; d = 1 has no 32-bit
+// magic and is marked by 0.
+inline uint32_t div_magic(uint32_t d, uint64_t xmax, bool& ok) {
+    if (d == 0) ok = false;
+    if (d < 2) return 0;
+    const uint64_t mg = ((1ull << 32) + d - 1) / d;
+    const uint64_t e = mg * d - (1ull << 32);
+    if (e * xmax >= (1ull << 32)) ok = false;
+    return (uint32_t)mg;
+}
+__device__ __forceinline__ int div_by(int x, int d, uint32_t magic, int fast) {
+    return fast ? (magic ? (int)__umulhi((uint32_t)x, magic) : x) : x / d;
+}
 
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
 
@@ -223,9 +244,9 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
         abase[i] = 0;
         amask[i] = 0;
         if (m < gm.M) {
-            const int b = m / (gm.OH * gm.OW);
+            const int b = div_by(m, gm.OH * gm.OW, gm.mg_ohow, gm.fastdiv);
             const int rem = m - b * (gm.OH * gm.OW);
-            const int oh = rem / gm.OW, ow = rem - oh * gm.OW;
+            const int oh = div_by(rem, gm.OW, gm.mg_ow, gm.fastdiv), ow = rem - oh * gm.OW;
             const int ih0 = oh * gm.stride - gm.pad, iw0 = ow * gm.stride - gm.pad;
             abase[i] = ((b * gm.H + ih0) * gm.W + iw0) * cw * 4;
             // taps inside the image: kw in [kw_lo, kw_hi) for every kh in [kh_lo, kh_hi)
@@ -252,8 +273,8 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
             const int kw0 = (e >> 2) * kStepWords + (e & 3) * 4;   // first word of the chunk
             uint2 v = make_uint2(0u, 0xFFFFFFFFu);
             if (kw0 < kwords) {
-                const int tap = kw0 / cw, cword = kw0 - tap * cw;
-                const int kh = tap / gm.KW, kwi = tap - kh * gm.KW;
+                const int tap = div_by(kw0, cw, gm.mg_cw, gm.fastdiv), cword = kw0 - tap * cw;
+                const int kh = div_by(tap, gm.KW, gm.mg_kw, gm.fastdiv), kwi = tap - kh * gm.KW;
                 v.x = (uint32_t)(((kh * gm.W + kwi) * cw + cword) * 4);
                 v.y = (uint32_t)(kw0 * 4) | ((uint32_t)tap << 26);
             }
@@ -617,6 +638,17 @@ hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_
     gm.OH = (d.H + 2 * d.pad - d.KH) / d.stride + 1;
     gm.OW = (d.W + 2 * d.pad - d.KW) / d.stride + 1;
     gm.M = d.B * gm.OH * gm.OW;
+    {
+        // the tiled kernel divides m < M by OH OW, the remainder by OW, a word index below the
+        // filter's words by the words per pixel and a tap below KH KW by KW
+        const uint32_t cw = (uint32_t)(gm.Cin / kPerWord);
+        bool ok = gm.M > 0;
+        gm.mg_ohow = div_magic((uint32_t)(gm.OH * gm.OW), (uint64_t)gm.M, ok);
+        gm.mg_ow = div_magic((uint32_t)gm.OW, (uint64_t)gm.OH * gm.OW, ok);
+        gm.mg_cw = div_magic(cw, (uint64_t)gm.KH * gm.KW * cw, ok);
+        gm.mg_kw = div_magic((uint32_t)gm.KW, (uint64_t)gm.KH * gm.KW, ok);
+        gm.fastdiv = ok ? 1 : 0;
+    }
     const size_t cwb = (size_t)gm.Cin / kPerWord * 4;  // bytes per pixel
     const bool fits32 = (size_t)gm.B * gm.H * gm.W * cwb < 0xFFFFFFF0ull &&
                         (size_t)gm.Cout * gm.KH * gm.KW * cwb < 0xFFFFFFF0ull &&
