@@ -186,8 +186,9 @@ constexpr int kMaxSteps = 128;  // rows of the step table (K steps plus the ring
 // Tiling: a block of 4 waves (2 x 2) owns a BM x BN output tile and walks K in steps of 128
 // codes (64 B per row; K is ordered (kh, kw, c) and Cin % 32 == 0, so every 16-byte chunk lies
 // inside one filter tap).  Rows are unpadded in LDS; chunk c of row r is kept at position
-// c ^ ((r / 4) % 4), chosen through the loading lane's address, which makes the 8-byte fragment
-// reads of 16 consecutive rows conflict-free.
+// c ^ swz(r), swz(r) = ((r / 4) % 4) ^ (r & 2), chosen through the loading lane's address: the
+// 16-byte fragment reads of 8 consecutive rows then fall into 8 different 16-byte columns of
+// a 128-byte line, and those of 16 consecutive rows into 16 different ones of a 256-byte line.
 //
 // KS > 1: KS groups of 4 waves share the tile and split K between them (group g takes steps
 // g, g + KS, ...), each with its own ring; their int32 partial tiles are added in the epilogue
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
     // Loader geometry: load i of this wave fills rows (4 i + wave) * 16 + lane / 4, position
     // lane % 4, with the chunk that belongs there.
     const int lrow = lane >> 2;
-    const int chunk = (lane & 3) ^ ((lrow >> 2) & 3);  // which 16 bytes of a step this lane fetches
+    const int chunk = (lane & 3) ^ ((lrow >> 2) & 3) ^ (lrow & 2);  // which 16 bytes of a step this lane fetches
     int abase[kLA];       // byte offset of (b, ih0, iw0, 0); may be negative at the border
     uint32_t amask[kLA];  // bit tap = the tap's pixel is inside the image
 #pragma unroll
@@ -307,18 +308,17 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
     };
 
     // Fragment reads for the 32 x 32 x 32 MFMA (a wave issuing only 16 x 16 x 64 ones reaches 0.6 of
-    // the matrix rate, measured): lane (r32, kh) holds 16 consecutive codes of row r32, the
-    // half kh of the MFMA's 32.  4-bit: a K step is two 64-code halves (sub), each two MFMAs (h)
-    // deep; the lane takes 8 bytes of chunk 2 sub + h.  8-bit: a K step is two MFMAs deep; the
-    // lane takes the 16 bytes of chunk 2 h + kh.
+    // the matrix rate, measured): lane (r32, kh) supplies 16 codes of row r32 to each MFMA, as
+    // the half kh of the MFMA's 32.  Which codes those are is free as long as both operands
+    // agree, so a lane reads whole 16-byte chunks (an 8-byte read of one half of a chunk by
+    // every lane leaves half of the banks idle).  4-bit: chunk 2 sub + kh of the K step, whose
+    // first 8 bytes go to the first MFMA of the half-step `sub` and the rest to the second.
+    // 8-bit: chunk 2 h + kh for MFMA h of the step.
     const int r32 = lane & 31, kh = lane >> 5;
-    int foff[2][2];
+    const int swz = ((r32 >> 2) & 3) ^ (r32 & 2);
+    int foff[2];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-            foff[sub][h] = kBits == 4 ? r32 * 64 + (((2 * sub + h) ^ ((r32 >> 2) & 3)) << 4) + kh * 8
-                                      : r32 * 64 + (((2 * h + kh) ^ ((r32 >> 2) & 3)) << 4);
+    for (int u = 0; u < 2; ++u) foff[u] = r32 * 64 + (((2 * u + kh) ^ swz) << 4);
 
     i32x16_t acc[kUM][kUN][kAccs];
 #pragma unroll
@@ -331,30 +331,39 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
                 for (int r = 0; r < 16; ++r) acc[i][j][c][r] = 0;
 
     i32x4_t af[2][kUM][2], bf[2][kUN][2];
+    auto widen_a = [](uint32_t x, uint32_t y) {
+        return i32x4_t{(int)(x & 0x0F0F0F0Fu), (int)((x >> 4) & 0x0F0F0F0Fu), (int)(y & 0x0F0F0F0Fu),
+                       (int)((y >> 4) & 0x0F0F0F0Fu)};
+    };
+    auto widen_b = [](uint32_t x, uint32_t y) {
+        return i32x4_t{(int)((x << 4) & 0xF0F0F0F0u), (int)(x & 0xF0F0F0F0u), (int)((y << 4) & 0xF0F0F0F0u),
+                       (int)(y & 0xF0F0F0F0u)};
+    };
     auto fetch = [&](int slot, int sub, int reg) {
         const unsigned char* As = smem + slot * kStageBytes + wm * (BM / 2) * 64;
         const unsigned char* Bs = smem + slot * kStageBytes + BM * 64 + wn * (BN / 2) * 64;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        if constexpr (kBits == 4) {
 #pragma unroll
             for (int i = 0; i < kUM; ++i) {
-                if constexpr (kBits == 4) {
-                    const uint2 p = *reinterpret_cast<const uint2*>(As + foff[sub][h] + i * 32 * 64);
-                    af[reg][i][h] = i32x4_t{(int)(p.x & 0x0F0F0F0Fu), (int)((p.x >> 4) & 0x0F0F0F0Fu),
-                                            (int)(p.y & 0x0F0F0F0Fu), (int)((p.y >> 4) & 0x0F0F0F0Fu)};
-                } else {
-                    af[reg][i][h] = *reinterpret_cast<const i32x4_t*>(As + foff[sub][h] + i * 32 * 64);
-                }
+                const uint4 p = *reinterpret_cast<const uint4*>(As + foff[sub] + i * 32 * 64);
+                af[reg][i][0] = widen_a(p.x, p.y);
+                af[reg][i][1] = widen_a(p.z, p.w);
             }
 #pragma unroll
             for (int j = 0; j < kUN; ++j) {
-                if constexpr (kBits == 4) {
-                    const uint2 p = *reinterpret_cast<const uint2*>(Bs + foff[sub][h] + j * 32 * 64);
-                    bf[reg][j][h] = i32x4_t{(int)((p.x << 4) & 0xF0F0F0F0u), (int)(p.x & 0xF0F0F0F0u),
-                                            (int)((p.y << 4) & 0xF0F0F0F0u), (int)(p.y & 0xF0F0F0F0u)};
-                } else {
-                    bf[reg][j][h] = *reinterpret_cast<const i32x4_t*>(Bs + foff[sub][h] + j * 32 * 64);
-                }
+                const uint4 p = *reinterpret_cast<const uint4*>(Bs + foff[sub] + j * 32 * 64);
+                bf[reg][j][0] = widen_b(p.x, p.y);
+                bf[reg][j][1] = widen_b(p.z, p.w);
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int i = 0; i < kUM; ++i)
+                    af[reg][i][h] = *reinterpret_cast<const i32x4_t*>(As + foff[h] + i * 32 * 64);
+#pragma unroll
+                for (int j = 0; j < kUN; ++j)
+                    bf[reg][j][h] = *reinterpret_cast<const i32x4_t*>(Bs + foff[h] + j * 32 * 64);
             }
         }
     };
@@ -368,13 +377,14 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
                     acc[i][j][h % kAccs] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[reg][i][h], bf[reg][j][h],
                                                                                  acc[i][j][h % kAccs], 0, 0, 0);
         // issue order: the LDS reads and the widening of the next fragments go between the MFMAs
-        constexpr int kM = 2 * kUM * kUN, kR = 2 * (kUM + kUN);
+        constexpr int kM = 2 * kUM * kUN, kF = 2 * (kUM + kUN);   // MFMAs, operand fragments
+        constexpr int kR = kBits == 4 ? kF / 2 : kF;               // LDS reads (4-bit: one per two fragments)
         constexpr int kRead = (kR + kM - 1) / kM;
 #pragma unroll
         for (int u = 0; u < kM; ++u) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             if (u * kRead < kR) __builtin_amdgcn_sched_group_barrier(0x100, kRead, 0);
-            if (kBits == 4) __builtin_amdgcn_sched_group_barrier(0x002, (4 * kR + kM - 1) / kM, 0);
+            if (kBits == 4) __builtin_amdgcn_sched_group_barrier(0x002, (4 * kF + kM - 1) / kM, 0);
         }
     };
 
