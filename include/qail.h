@@ -17,7 +17,10 @@
  * Conventions for every call
  *   - All data pointers are DEVICE pointers into memory owned by the caller,
  *     16-byte aligned.  Descriptors and size outputs are HOST pointers.  The
- *     library allocates nothing, frees nothing and keeps no state.
+ *     library allocates nothing and frees nothing.  The only state it keeps is
+ *     what it learns about the device at a call's first use (the number of
+ *     compute units, the opt-in for large LDS blocks); those are set once,
+ *     through atomics, so calls may come from several host threads.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     A call validates its arguments, enqueues its kernels and returns; it never
  *     synchronises.  Outputs are fully overwritten.
@@ -288,8 +291,8 @@ typedef struct {
 int qail_w8a16_linear_batch(const qail_w8a16_item* items, int32_t count, int32_t M, void* stream);
 
 /* ------------------------------------------------------- training-side operators --
- * Sec. 3.2 / Algorithm 1: the quantised policy is trained through its quantisers with the
- * straight-through estimator.  Sec. 3.3 / Eq. 3: the QBC term; the appendix instantiates its
+ * Sec. 4.1 / Algorithm 1: the quantised policy is trained through its quantisers with the
+ * straight-through estimator.  Sec. 4.2 / Eq. 3: the QBC term; the appendix instantiates its
  * discrepancy as the mean L2 distance between the two policies' final logits. */
 
 /* Forward of quantisation-aware training for a 4-bit group-quantised weight: w_hat =

@@ -189,12 +189,6 @@ def w4a16_row_norms(x_bf16_bits, qweight, scales, zeros_packed, group_size):
     return np.sqrt((x * x).sum(axis=1)), np.sqrt((w_hat * w_hat).sum(axis=1))
 
 
-# ---------------------------------------------------------------------------
-# W4A4: signed 4-bit weights per output channel, unsigned 4-bit activations
-# per tensor (Sec. 5.1 "Autonomous Driving"; appendix granularity)
-# ---------------------------------------------------------------------------
-
-
 def w4a16_linear_lora(x_bf16_bits: np.ndarray, qweight: np.ndarray, scales: np.ndarray,
                       zeros_packed: np.ndarray, group_size: int, a_bf16_bits: np.ndarray,
                       b_bf16_bits: np.ndarray, scaling: float) -> np.ndarray:
@@ -210,6 +204,12 @@ def w4a16_linear_lora(x_bf16_bits: np.ndarray, qweight: np.ndarray, scales: np.n
     x = bf16_bits_to_f64(x_bf16_bits)
     t = x @ bf16_bits_to_f64(a_bf16_bits).T          # [M, r]
     return base + np.float64(scaling) * (t @ bf16_bits_to_f64(b_bf16_bits).T)
+
+
+# ---------------------------------------------------------------------------
+# W4A4: signed 4-bit weights per output channel, unsigned 4-bit activations
+# per tensor (Sec. 5.1 "Autonomous Driving"; appendix granularity)
+# ---------------------------------------------------------------------------
 
 
 def quantize_w4_sym_channel(w: np.ndarray):
@@ -282,6 +282,39 @@ def w4a4_conv_acc(a_words: np.ndarray, w_words: np.ndarray, B: int, H: int, W: i
     return acc.astype(np.int32)
 
 
+def im2col_rows_nhwc(a: np.ndarray, KH: int, KW: int, stride: int, pad: int, rows: np.ndarray) -> np.ndarray:
+    """Selected rows of im2col_nhwc(a, ...) without forming the others: row m = (b, oh, ow) with
+    m = (b * OH + oh) * OW + ow gathers a[b, oh*stride + kh - pad, ow*stride + kw - pad, :] for
+    every tap (kh, kw), zero outside the image.  Returns [len(rows), KH*KW*C]."""
+    B, H, W, C = a.shape
+    OH = (H + 2 * pad - KH) // stride + 1
+    OW = (W + 2 * pad - KW) // stride + 1
+    rows = np.asarray(rows, dtype=np.int64)
+    b, oh, ow = rows // (OH * OW), (rows // OW) % OH, rows % OW
+    out = np.zeros((rows.size, KH, KW, C), dtype=a.dtype)
+    for kh in range(KH):
+        for kw in range(KW):
+            ih = oh * stride + kh - pad
+            iw = ow * stride + kw - pad
+            ok = (ih >= 0) & (ih < H) & (iw >= 0) & (iw < W)
+            out[ok, kh, kw, :] = a[b[ok], ih[ok], iw[ok], :]
+    return out.reshape(rows.size, KH * KW * C)
+
+
+def w4a4_conv_acc_rows(a_words: np.ndarray, w_words: np.ndarray, B: int, H: int, W: int, Cin: int,
+                       Cout: int, KH: int, KW: int, stride: int, pad: int, rows: np.ndarray) -> np.ndarray:
+    """Rows `rows` of w4a4_conv_acc(...): the same sum for selected output pixels only, so that
+    outputs of a tensor too large to recompute whole can be checked one by one.  int32
+    [len(rows), Cout]."""
+    a = unpack_nibbles_u4(np.asarray(a_words).reshape(B, H, W, Cin // 8), Cin)
+    K = KH * KW * Cin
+    wq = unpack_nibbles_s4(np.asarray(w_words).reshape(Cout, K // 8), K).astype(np.int64)
+    acc = im2col_rows_nhwc(a, KH, KW, stride, pad, rows).astype(np.int64) @ wq.T
+    if acc.size and np.abs(acc).max() > 8 * 15 * K:
+        raise AssertionError("accumulator exceeds 8*15*K")
+    return acc.astype(np.int32)
+
+
 def requant(acc: np.ndarray, scale: np.ndarray, bias: np.ndarray) -> np.ndarray:
     """y[m, n] = acc[m, n] * scale[n] + bias[n] in float64, where scale[n] is
     the float32 product s_a * s_w[n] and bias a float32 per-channel shift."""
@@ -292,6 +325,31 @@ def requant(acc: np.ndarray, scale: np.ndarray, bias: np.ndarray) -> np.ndarray:
 def requant_scale(s_a, s_w: np.ndarray) -> np.ndarray:
     """scale[n] = float32(s_a * s_w[n])."""
     return (F32(s_a) * np.asarray(s_w, dtype=F32)).astype(F32)
+
+
+def requant_f32(acc: np.ndarray, scale: np.ndarray, bias: np.ndarray) -> np.ndarray:
+    """The requantised output as the float32 tensor a layer hands on (the projection shortcut
+    of a residual block): per element ONE float32 fused multiply-add, i.e. the exact value
+    acc * scale[n] + bias[n] rounded once to float32, ties to even.
+
+    float(acc) * scale is exact in float64 (24 x 24 significand bits).  Adding the bias in
+    float64 rounds to 53 bits first, and rounding that again to 24 bits goes wrong exactly when
+    the float64 sum lands on the midpoint of two neighbouring float32 values although the true
+    sum does not; the error of the float64 addition (recovered exactly by the two-sum
+    identities) then says on which side of the midpoint the true sum lies."""
+    p = acc.astype(np.float64) * np.asarray(scale, dtype=F32).astype(np.float64)[None, :]
+    b = np.broadcast_to(np.asarray(bias, dtype=F32).astype(np.float64)[None, :], p.shape)
+    s = p + b
+    bv = s - p
+    err = (p - (s - bv)) + (b - bv)               # true sum = s + err exactly
+    r = s.astype(F32)                             # nearest float32 of s, ties to even
+    r64 = r.astype(np.float64)
+    other = np.where(r64 <= s, np.nextafter(r, F32(np.inf)), np.nextafter(r, F32(-np.inf))).astype(F32)
+    o64 = other.astype(np.float64)
+    tie = (np.abs(s - r64) == np.abs(o64 - s)) & (s != r64) & np.isfinite(o64)
+    # on a tie of s the true sum is nearer to the neighbour on the side err points to
+    toward_other = tie & (np.sign(err) == np.sign(o64 - r64)) & (err != 0)
+    return np.where(toward_other, other, r).astype(F32)
 
 
 def fused_requant_u4(acc: np.ndarray, scale: np.ndarray, bias: np.ndarray, s_out,
@@ -392,6 +450,18 @@ def w8a8_conv_acc(a_words: np.ndarray, w_words: np.ndarray, B: int, H: int, W: i
     return acc.astype(np.int32)
 
 
+def w8a8_conv_acc_rows(a_words: np.ndarray, w_words: np.ndarray, B: int, H: int, W: int, Cin: int,
+                       Cout: int, KH: int, KW: int, stride: int, pad: int, rows: np.ndarray) -> np.ndarray:
+    """Rows `rows` of w8a8_conv_acc(...), for outputs checked one by one.  int32 [len(rows), Cout]."""
+    a = unpack_bytes_s8(np.asarray(a_words).reshape(B, H, W, Cin // 4), Cin)
+    K = KH * KW * Cin
+    wq = unpack_bytes_s8(np.asarray(w_words).reshape(Cout, K // 4), K).astype(np.int64)
+    acc = im2col_rows_nhwc(a, KH, KW, stride, pad, rows).astype(np.int64) @ wq.T
+    if acc.size and np.abs(acc).max() > 128 * 128 * K:
+        raise AssertionError("accumulator exceeds 128*128*K")
+    return acc.astype(np.int32)
+
+
 def quantize_w8_sym_group(w: np.ndarray, group_size: int):
     """Weight-only 8-bit: per row n and group of g consecutive k, in float32:
     s = float16 round-up of max|w| / 127, at least 2^-14 (1 for an all-zero group;
@@ -420,8 +490,8 @@ def w8a16_linear(x_bf16_bits: np.ndarray, codes: np.ndarray, scales: np.ndarray,
 
 
 # ===========================================================================
-# Training-side operators (Sec. 3.2, Algorithm 1: the quantised policy is trained
-# through its quantisers with the straight-through estimator; Sec. 3.3, Eq. 3 and the
+# Training-side operators (Sec. 4.1, Algorithm 1: the quantised policy is trained
+# through its quantisers with the straight-through estimator; Sec. 4.2, Eq. 3 and the
 # appendix's implementation details: the QBC term is the mean L2 distance between
 # the final logits of the quantised and the full-precision policy).
 # ===========================================================================

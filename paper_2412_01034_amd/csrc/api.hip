@@ -2,18 +2,22 @@
 // done on the host before the first HIP call, so that the error paths can be
 // exercised on a machine without a GPU.
 #include <algorithm>
+#include <atomic>
 
 #include "qail_internal.h"
 
 namespace qail {
 int device_cu_count() {
-    static int cus = 0;
+    // read-only after the first call; two host threads racing here store the same value
+    static std::atomic<int> cached{0};
+    int cus = cached.load(std::memory_order_relaxed);
     if (cus == 0) {
         int dev = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
             cus = prop.multiProcessorCount;
         if (cus <= 0) cus = 256;
+        cached.store(cus, std::memory_order_relaxed);
     }
     return cus;
 }
@@ -268,6 +272,7 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
 
 namespace {
 constexpr int kLoraStride = 64;  // floats per row of a down-projection in the workspace (r <= 64)
+constexpr int kLoraMaxM = 65535;  // the adapter kernels put the rows of x on the grid's y axis
 
 int check_loras(const qail_w4a16_item* items, const qail_lora* loras, int count) {
     for (int i = 0; i < count; ++i) {
@@ -287,9 +292,11 @@ size_t round256(size_t b) { return (b + 255) / 256 * 256; }
 int qail_w4a16_lora_workspace(const qail_w4a16_item* items, const qail_lora* loras, int32_t count, int32_t M,
                               size_t* bytes) {
     size_t base = 0;
+    if (!bytes) return QAIL_ERR_NULL;
     const int e = qail_w4a16_batch_workspace(items, count, M, &base);
     if (e != QAIL_OK) return e;
-    if (count > 0 && !loras) return QAIL_ERR_NULL;
+    if (!bytes || (count > 0 && !loras)) return QAIL_ERR_NULL;
+    if (M > kLoraMaxM) return QAIL_ERR_UNSUPPORTED;
     *bytes = round256(base) + round256((size_t)count * M * kLoraStride * sizeof(float));
     return QAIL_OK;
 }
@@ -299,6 +306,7 @@ int qail_w4a16_linear_lora_batch(const qail_w4a16_item* items, const qail_lora* 
     if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
     if (count == 0) return QAIL_OK;
     if (!items || !loras) return QAIL_ERR_NULL;
+    if (M > kLoraMaxM) return QAIL_ERR_UNSUPPORTED;
     for (int i = 0; i < count; ++i) {
         const int e = check_item(items[i], M);
         if (e != QAIL_OK) return e;

@@ -1,5 +1,5 @@
-// Training-side operators (Sec. 3.2, Algorithm 1: the quantised policy is trained through its
-// quantisers with the straight-through estimator; Sec. 3.3, Eq. 3: the QBC term, which the
+// Training-side operators (Sec. 4.1, Algorithm 1: the quantised policy is trained through its
+// quantisers with the straight-through estimator; Sec. 4.2, Eq. 3: the QBC term, which the
 // appendix instantiates as the mean L2 distance between the two policies' final logits).
 // All are HBM-bound elementwise / reduction kernels.  Reductions are in a fixed order (per-block
 // partial sums, then one block adds them): the results do not depend on scheduling.

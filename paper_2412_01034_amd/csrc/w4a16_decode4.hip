@@ -30,6 +30,8 @@
 // + scalar offset + a lane offset that never changes.
 #include <string.h>
 
+#include <atomic>
+
 #include "qail_internal.h"
 
 namespace qail {
@@ -366,13 +368,15 @@ size_t d4_lds_bytes(const qail_wdesc& d) {
 }
 
 hipError_t d4_launch_chunk(const qail_w4a16_item* items, int count, int M, hipStream_t st) {
-    static bool attr_done = false;  // more than 64 KB of LDS needs an opt-in, once per process
-    if (!attr_done) {
+    // more than 64 KB of LDS needs an opt-in; the call is idempotent, so two host threads that
+    // both find the flag clear may both make it
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done.load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_decode4_kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  kD4MaxChunks * kWave * (4 * 16 + 16));
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_done.store(true, std::memory_order_release);
     }
     D4Args a;
     memset(a.item_of_block, 0, sizeof(a.item_of_block));

@@ -28,6 +28,8 @@
 // for r = 0..15.  A = activations (rows m), B = weights (columns n).
 #include <algorithm>
 
+#include <atomic>
+
 #include "qail_internal.h"
 
 namespace qail {
@@ -634,12 +636,14 @@ template <int MB, int WN>
 hipError_t launch_tile(const GemmArgs* gas, int n, hipStream_t st) {
     constexpr int kBM = 32 * MB, kBN = 128 * WN;
     const size_t lds = (size_t)kStages * (kBM * 256 + 4 * WN * 2560);
-    static bool attr_set = false;
-    if (!attr_set) {
+    // more than 64 KB of LDS needs an opt-in; the call is idempotent, so two host threads that
+    // both find the flag clear may both make it
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_gemm_f16_kernel<MB, WN>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     GemmBatch gb;
     int grid = 0, max_tail = 0;
@@ -709,6 +713,9 @@ int tile_rows(int M) {
 
 bool gemm_f16_supports(const qail_wdesc& d, int M) {
     if (d.K % 64 != 0 || d.group_size % 64 != 0) return false;
+    // A scale is fetched as the aligned 4-byte word that holds it; with an odd number of scales
+    // the word of the last one would reach two bytes past the caller's buffer.
+    if (((unsigned long long)d.N * (unsigned long long)(d.K / d.group_size)) % 2 != 0) return false;
     // 32-bit byte offsets inside the kernel
     const unsigned long long lim = 0xFFFFFFFFull;
     const unsigned long long Mpad = (unsigned long long)round_up(M, kRowPad), Kpad = (unsigned long long)round_up(d.K, kBK);

@@ -24,6 +24,8 @@
 //   * As for M = 1, one launch serves a list of linears, blocks divided by bytes.
 #include <string.h>
 
+#include <atomic>
+
 #include "qail_internal.h"
 
 namespace qail {
@@ -283,12 +285,14 @@ size_t sm_item_bytes(const qail_wdesc& d) {
 }
 
 hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipStream_t st) {
-    static bool attr_done = false;  // more than 64 KB of LDS needs an opt-in, once per process
-    if (!attr_done) {
+    // more than 64 KB of LDS needs an opt-in; the call is idempotent, so two host threads that
+    // both find the flag clear may both make it
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done.load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_smallm_kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmLdsBytes);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_done.store(true, std::memory_order_release);
     }
     SmArgs a;
     int grid = device_cu_count();

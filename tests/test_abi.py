@@ -101,6 +101,11 @@ def test_argument_errors_are_reported_without_a_gpu(B):
     assert f(its, lo, 0, 1, None, 0, None) == B.QAIL_OK
     szl = ctypes.c_size_t(0)
     assert L.qail_w4a16_lora_workspace(its, lo, 1, 3, ctypes.byref(szl)) == B.QAIL_OK and szl.value == 768
+    assert L.qail_w4a16_lora_workspace(its, lo, 1, 3, None) == B.QAIL_ERR_NULL
+    # the adapter kernels index the rows of x with the grid's y axis: larger batches are refused
+    # before anything is launched, by the size query and by the call
+    assert L.qail_w4a16_lora_workspace(its, lo, 1, 65536, ctypes.byref(szl)) == B.QAIL_ERR_UNSUPPORTED
+    assert f(its, lo, 1, 65536, ok, 1 << 40, None) == B.QAIL_ERR_UNSUPPORTED
     sz = ctypes.c_size_t(99)
     assert L.qail_w4a4_workspace(ctypes.byref(c), ctypes.byref(sz)) == B.QAIL_OK
     assert L.qail_w4a16_workspace(ctypes.byref(d), 1, ctypes.byref(sz)) == B.QAIL_OK

@@ -105,9 +105,20 @@ def test_resnet34_shapes_small_batch(B, s):
     assert np.array_equal(y_only, y)
 
 
+def stratified_rows(M, stripe, seed):
+    """One output row drawn from every run of `stripe` consecutive rows, plus both ends: the
+    convolution's tiles are 64 or 128 rows high with edges on multiples of 64, so every tile of
+    every launch has rows in the sample."""
+    rng = np.random.default_rng(seed)
+    lo = np.arange(0, M, stripe)
+    return np.unique(np.r_[0, lo + rng.integers(0, np.minimum(stripe, M - lo)), M - 1])
+
+
 @pytest.mark.parametrize("s", distinct_resnet_shapes(32), ids=lambda s: s.name)
 def test_resnet34_shapes_full_batch_sampled_images(B, s):
-    # batch 32 as benchmarked; the oracle recomputes images 0, 13 and 31 (images are independent)
+    # batch 32 as benchmarked; the oracle recomputes images 0, 13 and 31 whole (images are
+    # independent) and, over the whole batch, an output row out of every 32 with all its
+    # channels, so that every tile of the launch is covered
     aw, ww, scale, bias = quantised_inputs(s, synth.seed_for(3, 1, 0))
     acc, y = gpu_conv(B, s, aw, ww, scale, bias)
     per = s.OH * s.OW
@@ -116,6 +127,10 @@ def test_resnet34_shapes_full_batch_sampled_images(B, s):
         ref = O.w4a4_conv_acc(aw[b:b + 1], ww, *one, use_blas=True)
         assert np.array_equal(acc[b * per:(b + 1) * per], ref)
         check_requant(y[b * per:(b + 1) * per], ref, scale, bias)
+    rows = stratified_rows(s.M, 32, s.M)
+    ref = O.w4a4_conv_acc_rows(aw, ww, *geom(s), rows)
+    assert np.array_equal(acc[rows], ref)
+    check_requant(y[rows], ref, scale, bias)
 
 
 # ------------------------------------------------------------------ fused 4-bit output
@@ -274,9 +289,7 @@ def test_chained_resnet34_body_bit_exact(B):
                 wd, swd, bd = layer(cd)
                 accd = O.w4a4_conv_acc(a_words, wd, *geom(cd))
                 scd = O.requant_scale(s_in, swd)
-                # one fp32 fused multiply-add per element; float64 holds the product exactly and the sum to
-                # 53 bits, so rounding it to float32 is that result (bar a double rounding of probability 2^-29)
-                res_f32 = (accd.astype(np.float64) * scd.astype(np.float64)[None, :] + bd.astype(np.float64)[None, :]).astype(np.float32)
+                res_f32 = O.requant_f32(accd, scd, bd)
             else:
                 res_codes = codes
             # ---- oracle: conv2 + shortcut + ReLU -> codes
@@ -335,4 +348,10 @@ def test_fused_u4_full_batch_sampled_images(B, batch):
             res = O.unpack_nibbles_u4(a_words[b].reshape(per, s.Cin // 8), s.Cin) if identity else None
             ref = O.fused_requant_u4(acc, scale, bias, s_out, res_codes=res, res_scale=rs if identity else None)
             assert np.array_equal(got[b * per:(b + 1) * per], O.pack_nibbles(ref)), (s.name, b)
+        # over the whole batch: an output row out of every 32 (every tile of the launch), all channels
+        rows = stratified_rows(s.M, 32, 8400 + n)
+        acc = O.w4a4_conv_acc_rows(a_words, ww, *geom(s), rows)
+        res = O.unpack_nibbles_u4(a_words.reshape(s.M, s.Cin // 8)[rows], s.Cin) if identity else None
+        ref = O.fused_requant_u4(acc, scale, bias, s_out, res_codes=res, res_scale=rs if identity else None)
+        assert np.array_equal(got[rows], O.pack_nibbles(ref)), s.name
         del out, a_dev

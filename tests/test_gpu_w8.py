@@ -125,6 +125,10 @@ def test_w8a8_resnet34_shapes_full_batch_sampled_images(B):
         for b in (0, 13, 31):
             ref = O.w8a8_conv_acc(aw[b:b + 1], ww, 1, *geom(s)[1:])
             assert np.array_equal(got[b * per:(b + 1) * per], ref), (s.name, b)
+        # over the whole batch: an output row out of every 32 (every tile of the launch), all channels
+        lo = np.arange(0, s.M, 32)
+        rows = np.unique(np.r_[0, lo + rng.integers(0, np.minimum(32, s.M - lo)), s.M - 1])
+        assert np.array_equal(got[rows], O.w8a8_conv_acc_rows(aw, ww, *geom(s), rows)), s.name
         del acc
 
 

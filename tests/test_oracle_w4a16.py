@@ -264,6 +264,49 @@ def test_linear_power_of_two_homogeneity_and_shapes():
     assert np.all(np.abs(y1) <= nx[:, None] * nw[None, :] * (1 + 1e-12))      # Cauchy-Schwarz
 
 
+def test_row_norms_equal_closed_forms_and_library_norm():
+    # The norms are the denominator of the acceptance error of every W4A16 parity test: an
+    # over-estimate would loosen the bar, so they are pinned by equalities, not by a bound.
+    N, K, g = 7, 256, 64
+    G = K // g
+    ones = synth.f32_to_bf16_bits(np.ones((3, K), np.float32))
+    # x = 1 everywhere -> ||x|| = sqrt(K); constant code c, z = 0, s = 1 -> ||w_hat|| = c sqrt(K)
+    for c in (1, 3, 15):
+        qw = O.pack_nibbles(np.full((N, K), c))
+        zw = O.pack_nibbles(np.zeros((N, G), np.uint8))
+        nx, nw = O.w4a16_row_norms(ones, qw, np.ones((N, G), np.float16), zw, g)
+        assert np.array_equal(nx, np.full(3, 16.0)) and np.array_equal(nw, np.full(N, c * 16.0))
+    # a zero-point and a scale: every dequantised weight is (5 - 2) * 0.5 = 1.5
+    qw = O.pack_nibbles(np.full((N, K), 5))
+    zw = O.pack_nibbles(np.full((N, G), 2))
+    _, nw = O.w4a16_row_norms(ones, qw, np.full((N, G), 0.5, np.float16), zw, g)
+    assert np.array_equal(nw, np.full(N, 1.5 * 16.0))
+    # 3-4-5 triangle on one row of x
+    x = np.zeros((1, K), np.float32)
+    x[0, 3], x[0, 200] = 3.0, -4.0
+    nx, _ = O.w4a16_row_norms(synth.f32_to_bf16_bits(x), qw, np.ones((N, G), np.float16), zw, g)
+    assert nx[0] == 5.0
+    # random case against numpy's norm of a matrix dequantised here, code by code, from the
+    # packed words (not through the oracle's unpack / dequantise helpers)
+    w, q, s, z = _quant(N, K, g, 61)
+    qw, zw = O.pack_w4a16(q, z)
+    xb = synth.llm_activation_bf16(4, K, 62)
+    w_hat = np.empty((N, K))
+    for n in range(N):
+        for k in range(K):
+            code = (int(qw[n, k // 8]) >> (4 * (k % 8))) & 15
+            zp = (int(zw[n, (k // g) // 8]) >> (4 * ((k // g) % 8))) & 15
+            w_hat[n, k] = (code - zp) * float(s[n, k // g])
+    nx, nw = O.w4a16_row_norms(xb, qw, s, zw, g)
+    assert np.allclose(nw, np.linalg.norm(w_hat, axis=1), rtol=1e-14, atol=0)
+    assert np.allclose(nx, np.linalg.norm(synth.bf16_bits_to_f32(xb).astype(np.float64), axis=1), rtol=1e-14, atol=0)
+    # per row, not per matrix: scaling one weight row changes only its own norm
+    s2 = s.copy()
+    s2[2] = s2[2] * np.float16(2)
+    _, nw2 = O.w4a16_row_norms(xb, qw, s2, zw, g)
+    assert np.allclose(nw2[2], 2 * nw[2], rtol=1e-14) and np.array_equal(np.delete(nw2, 2), np.delete(nw, 2))
+
+
 def test_packed_size_consistent_with_paper_memory_table():
     # Table "Performance Metrics for OpenVLA": BF16 15.2 GB -> INT4 4.0 GB.
     # The 32 x 4 backbone linears at 4 + 16/128 + 4/128 bits per weight must

@@ -101,6 +101,29 @@ def test_conv_matches_nested_loop_definition(shape):
     assert np.array_equal(_acc(shape, a, w, use_blas=True), ref)
 
 
+@pytest.mark.parametrize("shape", [
+    _tiny(),
+    _tiny(B=2, H=5, W=6, Cin=8, Cout=4, stride=2, pad=1),
+    _tiny(B=3, H=6, W=6, Cin=16, Cout=2, KH=1, KW=1, stride=2, pad=0),
+    _tiny(B=2, H=7, W=5, Cin=8, Cout=2, KH=3, KW=3, stride=2, pad=1),
+])
+def test_selected_rows_match_nested_loop_definition(shape):
+    # the row-sampling form used on tensors too large to recompute whole: every row, in a shuffled
+    # order with repeats, against the brute-force definition (not against the oracle's own full form)
+    a, w = _codes(shape, 27)
+    ref = _brute(shape, a, w)
+    rows = np.random.default_rng(5).permutation(np.r_[np.arange(shape.M), [0, shape.M - 1]])
+    got = O.w4a4_conv_acc_rows(O.pack_nibbles(a), O.pack_nibbles(w.reshape(shape.Cout, -1)),
+                               shape.B, shape.H, shape.W, shape.Cin, shape.Cout, shape.KH, shape.KW,
+                               shape.stride, shape.pad, rows)
+    assert np.array_equal(got, ref[rows])
+    cols = O.im2col_rows_nhwc(a.astype(np.int64), shape.KH, shape.KW, shape.stride, shape.pad, rows)
+    assert np.array_equal(cols, O.im2col_nhwc(a.astype(np.int64), shape.KH, shape.KW, shape.stride, shape.pad)[rows])
+    assert O.w4a4_conv_acc_rows(O.pack_nibbles(a), O.pack_nibbles(w.reshape(shape.Cout, -1)),
+                                shape.B, shape.H, shape.W, shape.Cin, shape.Cout, shape.KH, shape.KW,
+                                shape.stride, shape.pad, np.zeros(0, np.int64)).shape == (0, shape.Cout)
+
+
 def test_1x1_conv_is_plain_gemm():
     sh = _tiny(B=2, H=3, W=5, Cin=24, Cout=7, KH=1, KW=1, stride=1, pad=0)
     a, w = _codes(sh, 9)
@@ -160,6 +183,54 @@ def test_requant_closed_form():
     for i, sw in enumerate((0.3, 2.0)):
         exact = Fraction(float(np.float32(0.1))) * Fraction(float(np.float32(sw)))
         assert abs(Fraction(float(s[i])) - exact) <= abs(exact) * Fraction(1, 2 ** 24)
+
+
+def _round_to_f32(v: Fraction) -> np.float32:
+    """Nearest float32 of an exact rational, ties to even, by comparing exact distances."""
+    c = np.float32(float(v))
+    cands = [np.nextafter(c, np.float32(-np.inf)), c, np.nextafter(c, np.float32(np.inf))]
+    best = min(cands, key=lambda f: (abs(Fraction(float(f)) - v), int(np.float32(f).view(np.uint32)) & 1))
+    return np.float32(best)
+
+
+def test_requant_f32_is_one_correctly_rounded_fma():
+    # hand cases: exact results, and a sum that needs the single rounding
+    acc = np.array([[3, -4], [0, 100]], np.int32)
+    scale = np.array([0.5, 0.25], np.float32)
+    bias = np.array([1.0, -2.0], np.float32)
+    got = O.requant_f32(acc, scale, bias)
+    assert got.dtype == np.float32 and got.tolist() == [[2.5, -3.0], [1.0, 23.0]]
+    # 1 + 2^-24 + 2^-47 lies just above the midpoint of 1 and 1 + 2^-23: a multiply rounded on its
+    # own (2^-24 exactly) followed by an add would tie to even (1.0); the single rounding gives 1 + 2^-23
+    sc = np.array([np.float32(2.0 ** -24) * (np.float32(1) + np.float32(2.0 ** -23))], np.float32)
+    assert O.requant_f32(np.array([[1]], np.int32), sc, np.array([1.0], np.float32))[0, 0] == np.float32(1 + 2.0 ** -23)
+    # a float64 sum that lands on a float32 midpoint although the true sum is below it:
+    # p = (2^23 + 1)(1 - 2^-23) = 2^23 - 2^-23, bias = 2^47 + 2^24 (odd significand); the midpoint above
+    # the bias is 2^47 + 2^24 + 2^23, float64 resolves 2^-5 there, so the float64 sum is that midpoint and
+    # ties-to-even on it would round up, while the true sum rounds down to the bias
+    acc2 = np.array([[2 ** 23 + 1]], np.int32)
+    sc2 = np.array([1 - 2.0 ** -23], np.float32)
+    b2 = np.array([2.0 ** 47 + 2.0 ** 24], np.float32)
+    exact = Fraction(2 ** 23 + 1) * Fraction(float(sc2[0])) + Fraction(float(b2[0]))
+    assert exact == Fraction(2 ** 47 + 2 ** 24 + 2 ** 23) - Fraction(1, 2 ** 23)
+    naive = (acc2.astype(np.float64) * sc2.astype(np.float64) + b2.astype(np.float64)).astype(np.float32)
+    assert naive[0, 0] == np.float32(2.0 ** 47 + 2.0 ** 25)                  # the double rounding this guards against
+    assert O.requant_f32(acc2, sc2, b2)[0, 0] == b2[0] == _round_to_f32(exact)
+    # mirrored: true sum just above the midpoint below an even neighbour
+    assert O.requant_f32(-acc2, sc2, -b2)[0, 0] == -b2[0]
+    # random operands, cancelling and not, against exact rational arithmetic
+    rng = np.random.default_rng(77)
+    acc = rng.integers(-552960, 552961, size=(40, 6)).astype(np.int32)
+    scale = (rng.random(6) * 1e-3 + 1e-6).astype(np.float32)
+    bias = np.array([0.0, 0.3, -0.3, 1e-7, -250.0, 3e4], np.float32)
+    got = O.requant_f32(acc, scale, bias)
+    for m in range(40):
+        for n in range(6):
+            v = Fraction(int(acc[m, n])) * Fraction(float(scale[n])) + Fraction(float(bias[n]))
+            assert got[m, n] == _round_to_f32(v), (m, n)
+    # and it is the float64 definition rounded: never further than half a float32 step from it
+    y64 = O.requant(acc, scale, bias)
+    assert np.all(np.abs(got.astype(np.float64) - y64) <= np.abs(y64) * 2.0 ** -24 + 1e-45)
 
 
 def test_end_to_end_quantised_conv_tracks_real_conv():

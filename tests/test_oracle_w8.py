@@ -74,6 +74,10 @@ def test_w8a8_conv_brute_force_and_special_cases():
                                 t += int(a[0, ih, iw, c]) * int(w[n, kh, kw, c])
                 ref[oh * W + ow, n] = t
     assert np.array_equal(got, ref)
+    # the row-sampling form, every row in shuffled order, against the same brute force
+    rows = rng.permutation(B * H * W)
+    assert np.array_equal(O.w8a8_conv_acc_rows(O.pack_bytes(a), O.pack_bytes(w.reshape(Cout, -1)), B, H, W, Cin, Cout,
+                                               KH, KW, stride, pad, rows), ref[rows])
     # 1x1, stride 1: a plain integer matrix product
     a1 = rng.integers(-128, 128, size=(2, 3, 3, 8)).astype(np.int8)
     w1 = rng.integers(-128, 128, size=(5, 8)).astype(np.int8)
