@@ -209,6 +209,23 @@ int qail_w4a16_lora_workspace(const qail_w4a16_item* items, const qail_lora* lor
 int qail_w4a16_linear_lora_batch(const qail_w4a16_item* items, const qail_lora* loras, int32_t count,
                                  int32_t M, void* workspace, size_t workspace_bytes, void* stream);
 
+/* qail_w4a16_linear_lora_batch for callers that cannot allocate device memory (code under
+ * HIP graph capture, serving loops that must not call hipMalloc, harnesses that forbid it):
+ * the same kernels and the same results, with the workspace taken from a scratch array that is
+ * part of the library's device image (qail_static_scratch_bytes: 1 MiB, held on every GPU the
+ * library runs on until the process ends).  The call allocates nothing and frees nothing.
+ * A request whose qail_w4a16_lora_workspace figure exceeds the scratch returns
+ * QAIL_ERR_WORKSPACE before anything is launched (a decode batch of M <= 16 on up to 16
+ * linears that the streaming kernels take, e.g. the 7B shapes with groups of 128, needs
+ * 64 KiB; anything routed to the matrix-core GEMM needs megabytes and does not fit).  All calls on one GPU share that GPU's array: calls that
+ * overlap on one GPU (two streams, two host threads) race on it and must be serialised by the
+ * caller; calls that follow each other on one stream are safe, since each call writes what it
+ * reads.  The scratch address of a GPU is looked up at the first call made with that GPU
+ * current; make that first call outside graph capture. */
+int qail_static_scratch_bytes(size_t* bytes);
+int qail_w4a16_linear_lora_batch_static(const qail_w4a16_item* items, const qail_lora* loras,
+                                        int32_t count, int32_t M, void* stream);
+
 /* ------------------------------------------------------------------- W4A4 --
  * acc[(b,oh,ow)][n] = sum_{kh,kw,c} a[b][oh*stride+kh-pad][ow*stride+kw-pad][c] * w[n][kh][kw][c]
  * with zero outside the image, exact in int32; then optionally

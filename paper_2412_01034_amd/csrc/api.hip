@@ -301,10 +301,11 @@ int qail_w4a16_lora_workspace(const qail_w4a16_item* items, const qail_lora* lor
     return QAIL_OK;
 }
 
-int qail_w4a16_linear_lora_batch(const qail_w4a16_item* items, const qail_lora* loras, int32_t count, int32_t M,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
-    if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
-    if (count == 0) return QAIL_OK;
+namespace {
+
+// Validation shared by the two adapter entry points; *need_out = bytes of workspace the call uses.
+int check_lora_call(const qail_w4a16_item* items, const qail_lora* loras, int32_t count, int32_t M,
+                    size_t* base_out, size_t* need_out) {
     if (!items || !loras) return QAIL_ERR_NULL;
     if (M > kLoraMaxM) return QAIL_ERR_UNSUPPORTED;
     for (int i = 0; i < count; ++i) {
@@ -314,9 +315,15 @@ int qail_w4a16_linear_lora_batch(const qail_w4a16_item* items, const qail_lora* 
     const size_t base = batch_need(items, count, M);
     const int el = check_loras(items, loras, count);
     if (el != QAIL_OK) return el;
-    const size_t need = round256(base) + round256((size_t)count * M * kLoraStride * sizeof(float));
-    if (!workspace || workspace_bytes < need) return QAIL_ERR_WORKSPACE;
-    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QAIL_ERR_ALIGN;
+    *base_out = base;
+    *need_out = round256(base) + round256((size_t)count * M * kLoraStride * sizeof(float));
+    return QAIL_OK;
+}
+
+// The launches of the adapter path on a validated call; `workspace` holds at least the bytes
+// check_lora_call reported, 256-byte aligned.
+int run_lora_batch(const qail_w4a16_item* items, const qail_lora* loras, int32_t count, int32_t M,
+                   void* workspace, size_t base, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* t = reinterpret_cast<float*>(static_cast<char*>(workspace) + round256(base));
 
@@ -331,6 +338,63 @@ int qail_w4a16_linear_lora_batch(const qail_w4a16_item* items, const qail_lora* 
         if (launch_lora_up_add(items[i], loras[i], t + (size_t)i * M * kLoraStride, M, st) != hipSuccess)
             return QAIL_ERR_HIP;
     return QAIL_OK;
+}
+
+// Scratch of the entry point that takes no workspace: device memory that exists from the
+// moment the library is loaded, one copy per GPU, so that nothing has to be allocated for it.
+// The name is only a handle in host code; the address on the current device comes from
+// hipGetSymbolAddress and is looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> scratch_ptr[kMaxDevices];
+
+int static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return QAIL_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return QAIL_ERR_UNSUPPORTED;
+    void* p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // two host threads may both get here: they read the same address
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return QAIL_ERR_HIP;
+        scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return QAIL_OK;
+}
+
+}  // namespace
+
+int qail_w4a16_linear_lora_batch(const qail_w4a16_item* items, const qail_lora* loras, int32_t count, int32_t M,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
+    if (count == 0) return QAIL_OK;
+    size_t base = 0, need = 0;
+    const int e = check_lora_call(items, loras, count, M, &base, &need);
+    if (e != QAIL_OK) return e;
+    if (!workspace || workspace_bytes < need) return QAIL_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QAIL_ERR_ALIGN;
+    return run_lora_batch(items, loras, count, M, workspace, base, stream);
+}
+
+int qail_static_scratch_bytes(size_t* bytes) {
+    if (!bytes) return QAIL_ERR_NULL;
+    *bytes = kStaticScratchBytes;
+    return QAIL_OK;
+}
+
+int qail_w4a16_linear_lora_batch_static(const qail_w4a16_item* items, const qail_lora* loras, int32_t count,
+                                        int32_t M, void* stream) {
+    if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
+    if (count == 0) return QAIL_OK;
+    size_t base = 0, need = 0;
+    const int e = check_lora_call(items, loras, count, M, &base, &need);
+    if (e != QAIL_OK) return e;
+    if (need > kStaticScratchBytes) return QAIL_ERR_WORKSPACE;   // beyond the built-in scratch: use the call above
+    void* ws = nullptr;
+    const int es = static_scratch(&ws);
+    if (es != QAIL_OK) return es;
+    return run_lora_batch(items, loras, count, M, ws, base, stream);
 }
 
 int qail_w4a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales,
