@@ -5,8 +5,8 @@ Primary workload (the one `value` is quoted on): the four W4A16 linears of a
 Llama-2-7B decoder layer at M = 1 (fused QKV 4096->12288, out 4096->4096, fused
 gate+up 4096->22016, down 11008->4096; group 128, asymmetric uint4).  One step
 = one decoder layer's four GEMVs through qail_w4a16_linear_batch.  The steps
-rotate through `--layers` independently seeded layers (default 8, 841 MB of
-packed weights) so that neither L2 nor the 256 MB last-level cache can serve the
+rotate through `--layers` independently seeded layers (default 32: the whole
+decode stack of the full-stack configuration, 3.36 GB of packed weights) so that neither L2 nor the 256 MB last-level cache can serve the
 reads.  Throughput = algorithmic bytes (packed weights + scales + zero-points +
 x + y) per second, with everything resident in HBM before the timed region.
 
@@ -52,8 +52,12 @@ def parse():
     p.add_argument("--warmup", type=int, default=100)
     p.add_argument("--settle-ms", type=float, default=200.0,
                    help="how long a matrix-core-bound extra line repeats its work before it is timed")
-    p.add_argument("--layers", type=int, default=8, help="independently seeded layers to rotate through")
+    p.add_argument("--layers", type=int, default=32,
+                   help="independently seeded layers to rotate through (32 = the full decode stack, 3.36 GB packed)")
     p.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
+    p.add_argument("--only", type=str, default="",
+                   help="comma-separated names of the secondary workloads to run (default: all): spread, singles, "
+                        "stack, lora, prefill, conv32, conv32_fused, conv256, w8, train, cpu_extra")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run a few 256 MiB device copies (a kernel of known traffic, for scaling "
@@ -211,56 +215,64 @@ def main():
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": gemv_traffic(),
+            "traffic_source": "profiles/w4a16_gemv_decode_layer_pmc.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
+                              "not re-measured in this run; null when the kernel source has changed since)",
             "avg_launch_us": round(kern_us, 3),
         },
     }
+    # spread of single launches of the headline step: an event pair around each of 300 launches
+    # (the pair's own gap is inside each reading, so the median sits above avg_launch_us)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(300)]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(stream)
+        step(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)
+    result["us_per_step_p10_p50_p90"] = [round(us[len(us) // 10], 2), round(us[len(us) // 2], 2),
+                                         round(us[len(us) * 9 // 10], 2)]
 
     # --------------------------------------------------------------- extras
     extra = {}
-    if not args.no_extra:
-        def timed(fn, iters, warm=5, settle=False):
-            # settle: matrix-core-bound work is timed at the clock the chip sustains under it.  Coming
-            # from idle (or from memory-bound work) the first milliseconds run at a lower clock, so
-            # such a line first repeats its work for --settle-ms (0.2 s) and is then timed over half of that or more.
-            for _ in range(warm):
-                fn()
-            torch.cuda.synchronize()
-            if settle:
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(stream)
-                for _ in range(3):
-                    fn()
-                b.record(stream)
-                torch.cuda.synchronize()
-                once = max(a.elapsed_time(b) * 1e-3 / 3, 1e-6)
-                for _ in range(min(20000, int(args.settle_ms * 1e-3 / once) + 1)):
-                    fn()
-                iters = max(iters, min(20000, int(args.settle_ms * 0.5e-3 / once) + 1))
-                torch.cuda.synchronize()
+    only = [w for w in args.only.split(",") if w]
+
+    def want(name):
+        return not args.no_extra and (not only or name in only)
+
+    def timed(fn, iters, warm=5, settle=False):
+        # settle: matrix-core-bound work is timed at the clock the chip sustains under it.  Coming
+        # from idle (or from memory-bound work) the first milliseconds run at a lower clock, so
+        # such a line first repeats its work for --settle-ms (0.2 s) and is then timed over half of that or more.
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        if settle:
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record(stream)
-            for _ in range(iters):
+            for _ in range(3):
                 fn()
             b.record(stream)
             torch.cuda.synchronize()
-            return a.elapsed_time(b) * 1e-3 / iters
-
-        # the headline launch again: spread of single launches (an event pair around each of 300), and the
-        # same layer launched over and over, labelled as what it is: its 105 MB stay in the last-level cache
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(300)]
-        for i, (e0, e1) in enumerate(evs):
-            e0.record(stream)
-            step(i)
-            e1.record(stream)
+            once = max(a.elapsed_time(b) * 1e-3 / 3, 1e-6)
+            for _ in range(min(20000, int(args.settle_ms * 1e-3 / once) + 1)):
+                fn()
+            iters = max(iters, min(20000, int(args.settle_ms * 0.5e-3 / once) + 1))
+            torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(iters):
+            fn()
+        b.record(stream)
         torch.cuda.synchronize()
-        us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)
-        tcr = timed(lambda: step(0), 400)
-        extra["decode_layer_launch_spread"] = {
-            "us_p10_p50_p90": [round(us[len(us) // 10], 2), round(us[len(us) // 2], 2), round(us[len(us) * 9 // 10], 2)],
-            "note": "event pair around every launch (includes the events' own gap)",
-            "cache_resident_one_layer_us": round(tcr * 1e6, 2),
-            "cache_resident_one_layer_GBps": round(bytes_per_step / tcr / 1e9, 1)}
+        return a.elapsed_time(b) * 1e-3 / iters
 
+    if want("spread"):
+        # the headline layer launched over and over, labelled as what it is: its 105 MB stay in the last-level cache
+        tcr = timed(lambda: step(0), 400)
+        extra["decode_layer_cache_resident"] = {"us": round(tcr * 1e6, 2), "GBps": round(bytes_per_step / tcr / 1e9, 1),
+                                                "note": "one layer repeated: served by the last-level cache, not HBM"}
+
+    if want("singles"):
         # single-linear decode launches (cold weights: rotate layers)
         per = {}
         for i, (name, N, K) in enumerate(shapes):
@@ -271,11 +283,15 @@ def main():
                 B.qail_w4a16_linear_batch(singles[cnt[0] % L], 1, 1, None, sh)
                 cnt[0] += 1
             t = timed(one, 400)
-            per[name] = {"us": round(t * 1e6, 2), "GBps": round(linear_bytes(N, K, 1) / t / 1e9, 1)}
+            gbps = linear_bytes(N, K, 1) / t / 1e9
+            per[name] = {"us": round(t * 1e6, 2), "GBps": round(gbps, 1), "frac_hbm_peak": round(gbps / HBM_PEAK_GBS, 4)}
         extra["decode_single_linear"] = per
 
-        # decode stack walk: 32 layer-steps per token (the loaded layers cycled), 7 tokens
+    if want("stack"):
+        # the full decode stack: 32 layers x 4 linears per token-step, 7 token-steps per timing;
+        # with the default --layers 32 every layer has its own seeded weights (3.36 GB per token-step)
         stack = {}
+        stack_bytes_w = 32 * sum(linear_bytes(N, K, 0) for _, N, K in shapes)
         for M in (1, 4, 16, 64):
             io = dec if M == 1 else with_io(M)
             nws = B.qail_w4a16_batch_workspace(io[0][0], 4, M)   # M > 16: the matrix-core GEMM's
@@ -285,8 +301,9 @@ def main():
                 for l in range(32):
                     B.qail_w4a16_linear_batch(io[l % L][0], 4, M, wsk, sh)
             t = timed(walk, 7, warm=1)
+            gbps = 32 * sum(linear_bytes(N, K, M) for _, N, K in shapes) / t / 1e9
             stack[f"M={M}"] = {"ms_per_token_step": round(t * 1e3, 4), "tokens_per_s": round(M / t, 1),
-                               "GBps": round(32 * sum(linear_bytes(N, K, M) for _, N, K in shapes) / t / 1e9, 1)}
+                               "GBps": round(gbps, 1), "frac_hbm_peak": round(gbps / HBM_PEAK_GBS, 4)}
             if M in (1, 16):
                 # the same walk with one launch per linear: stream order then makes every linear wait for
                 # the one before it, as the data dependences of a real decoder layer would
@@ -297,20 +314,26 @@ def main():
                         for i in range(4):
                             B.qail_w4a16_linear_batch(ones[l % L][i], 1, M, wsk, sh)
                 t = timed(walk_dep, 7, warm=1)
+                gbps1 = 32 * sum(linear_bytes(N, K, M) for _, N, K in shapes) / t / 1e9
                 stack[f"M={M}, one launch per linear"] = {"ms_per_token_step": round(t * 1e3, 4),
-                                                          "tokens_per_s": round(M / t, 1)}
+                                                          "tokens_per_s": round(M / t, 1), "GBps": round(gbps1, 1),
+                                                          "frac_hbm_peak": round(gbps1 / HBM_PEAK_GBS, 4)}
                 del ones
             if M != 1:
                 del io
-        stack["note"] = f"32 layer-steps per token over {L} distinct layers cycled"
+        stack["note"] = (f"32 layer-steps per token over {L} distinct layers"
+                         + ("" if L >= 32 else " cycled") + f"; packed weights per token-step {stack_bytes_w} B; "
+                         "the bound at 8 TB/s is 2378 token-steps/s")
         extra["decode_stack"] = stack
 
+    if want("lora"):
         # the same decode layer with a rank-32 adapter beside each linear (unmerged, as the
         # fine-tuned 4-bit policy runs): down-projections in one small launch, up-projections
         # inside the streaming kernel's final store
         R = 32
+        LL = min(L, 8)
         lora_io = []
-        for l in range(L):
+        for l in range(LL):
             lents = []
             for i, (_, N, K) in enumerate(shapes):
                 ab, bb = synth.lora_factors(N, K, R, synth.seed_for(4, l * 4 + i, 5))
@@ -320,7 +343,7 @@ def main():
         cntl = [0]
 
         def lora_step():
-            l = cntl[0] % L
+            l = cntl[0] % LL
             B.qail_w4a16_linear_lora_batch(dec[l][0], lora_io[l][0], 4, 1, wsl, sh)
             cntl[0] += 1
         tl = timed(lora_step, 400)
@@ -331,7 +354,7 @@ def main():
                                           "launches_per_layer": 2}
         del lora_io, wsl
 
-        # prefill GEMM
+    if want("prefill"):
         pre = {}
         for M in (288, 1024):
             io = with_io(M)
@@ -353,22 +376,72 @@ def main():
             del io
         extra["prefill_gemm"] = pre
 
-        # W4A4 ResNet-34 body, batch 32
-        convs = synth.resnet34_convs(32)
-        rng = np.random.default_rng(synth.seed_for(3, 0, 0))
-        calls, tot_ops = [], 0
-        cache = {}
-        for li, s in enumerate(convs):
-            key = (s.H, s.Cin)
-            if key not in cache:   # one code tensor per input shape (values do not affect timing)
-                cache[key] = dev(rng.integers(0, 2 ** 32, size=s.B * s.H * s.W * s.Cin // 8,
-                                              dtype=np.uint64).astype(np.uint32))
-            ww = dev(rng.integers(0, 2 ** 32, size=s.Cout * s.K // 8, dtype=np.uint64).astype(np.uint32))
-            scale = torch.full((s.Cout,), 1e-3, dtype=torch.float32, device="cuda")
-            bias = torch.zeros(s.Cout, dtype=torch.float32, device="cuda")
-            y = torch.empty(s.M * s.Cout, dtype=torch.float32, device="cuda")
-            calls.append((s, cache[key], ww, scale, bias, y))
-            tot_ops += s.ops
+    # ---- W4A4 ResNet-34 body.  Roof of a layer: max(ops / int8 peak, algorithmic bytes / HBM peak) with the
+    # input tensor counted once (for a stride-2 1x1 only the sampled pixels), the packed weights, and 4 B
+    # (int32 / fp32 output) or 0.5 B (fused 4-bit output) per output element.
+    def conv_bytes(s, out_bytes):
+        a_pix = s.B * s.H * s.W if s.KH > 1 else s.M
+        return a_pix * s.Cin // 2 + s.Cout * s.K // 2 + int(s.M * s.Cout * out_bytes) + 8 * s.Cout
+
+    def conv_roof_us(s, out_bytes):
+        return max(s.ops / (INT8_PEAK_TOPS * 1e12), conv_bytes(s, out_bytes) / (HBM_PEAK_GBS * 1e9)) * 1e6
+
+    def mfma_bound(s, out_bytes):
+        return s.ops / (INT8_PEAK_TOPS * 1e12) >= conv_bytes(s, out_bytes) / (HBM_PEAK_GBS * 1e9)
+
+    def conv_key(s):
+        return f"{s.KH}x{s.KW}_{s.Cin}to{s.Cout}_s{s.stride}"
+
+    def conv_summary(convs_, per_shape, t_pass, out_bytes):
+        """Aggregates over all calls and over the layers whose roof is the matrix pipe, from the per-shape
+        times (a sum of single-call times: no gaps between calls) and from the back-to-back pass."""
+        tot_ops_ = sum(s.ops for s in convs_)
+        sub = [s for s in convs_ if mfma_bound(s, out_bytes)]
+        t_sum = sum(per_shape[conv_key(s)]["us"] for s in convs_) * 1e-6
+        t_sub = sum(per_shape[conv_key(s)]["us"] for s in sub) * 1e-6
+        roof = sum(conv_roof_us(s, out_bytes) for s in convs_) * 1e-6
+        return {
+            "all_calls": {"calls": len(convs_), "GOP": round(tot_ops_ / 1e9, 1),
+                          "TOPs_back_to_back": round(tot_ops_ / t_pass / 1e12, 1),
+                          "frac_int8_peak_back_to_back": round(tot_ops_ / t_pass / 1e12 / INT8_PEAK_TOPS, 4),
+                          "TOPs_sum_of_calls": round(tot_ops_ / t_sum / 1e12, 1),
+                          "roof_us": round(roof * 1e6, 1), "frac_of_roof": round(roof / t_pass, 4)},
+            "mfma_bound_subset": {"calls": len(sub), "shapes": sorted({conv_key(s) for s in sub}),
+                                  "GOP": round(sum(s.ops for s in sub) / 1e9, 1),
+                                  "us_sum_of_calls": round(t_sub * 1e6, 1),
+                                  "TOPs": round(sum(s.ops for s in sub) / max(t_sub, 1e-12) / 1e12, 1),
+                                  "frac_int8_peak": round(sum(s.ops for s in sub) / max(t_sub, 1e-12) / 1e12 / INT8_PEAK_TOPS, 4)},
+        }
+
+    conv_state = {}
+
+    def conv32_calls():
+        if "calls" not in conv_state:
+            convs = synth.resnet34_convs(32)
+            rng = np.random.default_rng(synth.seed_for(3, 0, 0))
+            calls, cache = [], {}
+            for li, s in enumerate(convs):
+                key = (s.H, s.Cin)
+                if key not in cache:   # one code tensor per input shape (values do not affect timing)
+                    cache[key] = dev(rng.integers(0, 2 ** 32, size=s.B * s.H * s.W * s.Cin // 8,
+                                                  dtype=np.uint64).astype(np.uint32))
+                ww = dev(rng.integers(0, 2 ** 32, size=s.Cout * s.K // 8, dtype=np.uint64).astype(np.uint32))
+                scale = torch.full((s.Cout,), 1e-3, dtype=torch.float32, device="cuda")
+                bias = torch.zeros(s.Cout, dtype=torch.float32, device="cuda")
+                y = torch.empty(s.M * s.Cout, dtype=torch.float32, device="cuda")
+                calls.append((s, cache[key], ww, scale, bias, y))
+            conv_state["calls"] = calls
+            conv_state["rng"] = rng
+        return conv_state["calls"]
+
+    def shape_line(s, tt, out_bytes):
+        roof = conv_roof_us(s, out_bytes)
+        return {"us": round(tt * 1e6, 2), "TOPs": round(s.ops / tt / 1e12, 1), "roof_us": round(roof, 2),
+                "roof": "mfma" if mfma_bound(s, out_bytes) else "hbm", "frac_of_roof": round(roof / (tt * 1e6), 4)}
+
+    if want("conv32"):
+        calls = conv32_calls()
+        tot_ops = sum(c[0].ops for c in calls)
 
         def body():
             for s, a, ww, scale, bias, y in calls:
@@ -377,12 +450,11 @@ def main():
         t = timed(body, 20, settle=True)
         per_shape = {}
         for s, a, ww, scale, bias, y in calls:
-            key = f"{s.KH}x{s.KW}_{s.Cin}to{s.Cout}_s{s.stride}"
-            if key in per_shape:
+            if conv_key(s) in per_shape:
                 continue
             tt = timed(lambda: B.qail_w4a4_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad,
                                                 a, ww, scale=scale, bias=bias, y_out=y, stream=sh), 50, settle=True)
-            per_shape[key] = {"us": round(tt * 1e6, 2), "TOPs": round(s.ops / tt / 1e12, 1)}
+            per_shape[conv_key(s)] = shape_line(s, tt, 4)
         # the same 35 calls captured once into a graph and replayed (the library only launches kernels)
         gs = torch.cuda.Stream()
         with torch.cuda.stream(gs):
@@ -397,10 +469,14 @@ def main():
         extra["w4a4_resnet34_b32"] = {"ms_per_pass": round(t * 1e3, 4), "TOPs": round(tot_ops / t / 1e12, 1),
                                       "frac_int8_peak": round(tot_ops / t / 1e12 / INT8_PEAK_TOPS, 4),
                                       "calls": len(calls), "ms_per_pass_graph_replay": round(tg * 1e3, 4),
-                                      "per_shape": per_shape}
+                                      "per_shape": per_shape,
+                                      "aggregate": conv_summary([c[0] for c in calls], per_shape, t, 4)}
 
+    if want("conv32_fused"):
         # the same 35 calls with the fused 4-bit output (ReLU + shortcut + quantise for the next
         # layer): every call writes 0.5 B per output instead of 4 B
+        calls = conv32_calls()
+        tot_ops = sum(c[0].ops for c in calls)
         fcalls = []
         for s, a, ww, scale, bias, y in calls:
             out = torch.empty(s.M * s.Cout // 8, dtype=torch.int32, device="cuda")
@@ -414,19 +490,34 @@ def main():
         tf_ = timed(fused_body, 20, settle=True)
         fper = {}
         for s, a, ww, scale, bias, out, res in fcalls:
-            key = f"{s.KH}x{s.KW}_{s.Cin}to{s.Cout}_s{s.stride}"
-            if key in fper:
+            if conv_key(s) in fper:
                 continue
             tt = timed(lambda: B.qail_w4a4_conv_u4(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww,
                                                    scale, bias, 0.37, out, res_u4=res, res_scale=0.11, stream=sh), 50, settle=True)
-            fper[key] = {"us": round(tt * 1e6, 2), "TOPs": round(s.ops / tt / 1e12, 1)}
+            fper[conv_key(s)] = shape_line(s, tt, 0.5)
+        gs = torch.cuda.Stream()
+        with torch.cuda.stream(gs):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=gs):
+                for s, a, ww, scale, bias, out, res in fcalls:
+                    B.qail_w4a4_conv_u4(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww, scale, bias,
+                                        0.37, out, res_u4=res, res_scale=0.11, stream=gs.cuda_stream)
+        torch.cuda.synchronize()
+        tgf = timed(graph.replay, 20, settle=True)
+        del graph
         extra["w4a4_resnet34_b32_fused_u4"] = {"ms_per_pass": round(tf_ * 1e3, 4),
                                                "TOPs": round(tot_ops / tf_ / 1e12, 1),
                                                "frac_int8_peak": round(tot_ops / tf_ / 1e12 / INT8_PEAK_TOPS, 4),
-                                               "calls": len(fcalls), "per_shape": fper}
+                                               "calls": len(fcalls), "ms_per_pass_graph_replay": round(tgf * 1e3, 4),
+                                               "per_shape": fper,
+                                               "aggregate": conv_summary([c[0] for c in fcalls], fper, tf_, 0.5)}
+        del fcalls
+
+    if want("conv256"):
         # the same body at batch 256 with the fused 4-bit output: the matrix-core-bound regime of the
-        # same kernels (batch 32 above is bound by per-call fixed cost); one code tensor per input
-        # shape, one output tensor per output shape
+        # same kernels (batch 32 above is bound by per-call fixed cost); NOT the configuration's batch.
+        # One code tensor per input shape, one output tensor per output shape.
+        rng = np.random.default_rng(synth.seed_for(3, 0, 7))
         convs256 = synth.resnet34_convs(256)
         big, ops256, cache_a, cache_o = [], 0, {}, {}
         for s2 in convs256:
@@ -447,12 +538,26 @@ def main():
                 B.qail_w4a4_conv_u4(s2.B, s2.H, s2.W, s2.Cin, s2.Cout, s2.KH, s2.KW, s2.stride, s2.pad, a2, w2, sc2, bi2,
                                     0.37, o2, stream=sh)
         t256 = timed(body256, 5, settle=True)
+        per256 = {}
+        for s2, a2, w2, sc2, bi2, o2 in big:
+            if conv_key(s2) in per256:
+                continue
+            tt = timed(lambda: B.qail_w4a4_conv_u4(s2.B, s2.H, s2.W, s2.Cin, s2.Cout, s2.KH, s2.KW, s2.stride, s2.pad,
+                                                   a2, w2, sc2, bi2, 0.37, o2, stream=sh), 10, settle=True)
+            per256[conv_key(s2)] = shape_line(s2, tt, 0.5)
         extra["w4a4_resnet34_b256_fused_u4"] = {"ms_per_pass": round(t256 * 1e3, 4),
                                                 "TOPs": round(ops256 / t256 / 1e12, 1),
                                                 "frac_int8_peak": round(ops256 / t256 / 1e12 / INT8_PEAK_TOPS, 4),
-                                                "calls": len(big)}
+                                                "calls": len(big), "per_shape": per256,
+                                                "aggregate": conv_summary([c[0] for c in big], per256, t256, 0.5),
+                                                "note": "saturating batch, not the configuration's batch of 32"}
         del big, cache_a, cache_o
+
+    if want("w8"):
         # 8-bit variants: the same 35 conv calls as W8A8, and the decode layer with 8-bit weights only
+        calls = conv32_calls()
+        tot_ops = sum(c[0].ops for c in calls)
+        rng = np.random.default_rng(synth.seed_for(3, 0, 8))
         c8 = []
         for s, a, ww, scale, bias, y in calls:
             a8 = dev(rng.integers(0, 2 ** 32, size=s.B * s.H * s.W * s.Cin // 4, dtype=np.uint64).astype(np.uint32))
@@ -497,6 +602,8 @@ def main():
                                        "us_per_layer_one_launch_per_linear": round(tl8 * 1e6, 2),
                                        "note": f"{L8} distinct layers cycled"}
         del w8ls, it8
+
+    if want("train"):
         # training-side operators (HBM-bound elementwise / reduction kernels): GB/s of bytes touched
         tr = {}
         Nq, Kq = shapes[0][1], shapes[0][2]
@@ -529,6 +636,40 @@ def main():
         tr["qbc_loss_grad_1024x32000"] = {"us": round(tt * 1e6, 1), "GBps": round(3 * lq_.numel() * 4 / tt / 1e9, 1)}
         extra["train_ops"] = tr
         del wq_, wh_, dv_, lq_, lf_, gq_
+
+    if want("cpu_extra") and not args.no_cpu:
+        # The oracle timed on this machine's host cores for the other two hot paths, in their own units, on
+        # bounded samples (the headline's cpu_baseline below stays the decode layer): one convolution
+        # shape per encoder stage (16 images each, exact integer GEMM through float64 BLAS, im2col
+        # included) and one prefill linear (out projection, M = 288: unpack + dequantise + fp64 matmul).
+        from oracle import qail_oracle as O
+        cpu = {}
+        rng = np.random.default_rng(synth.seed_for(3, 0, 9))
+        for s in synth.resnet34_convs(16):
+            if not (s.KH == 3 and s.stride == 1 and s.Cin == s.Cout) or conv_key(s) in cpu:
+                continue
+            aw = rng.integers(0, 2 ** 32, size=(s.B, s.H, s.W, s.Cin // 8), dtype=np.uint64).astype(np.uint32)
+            ww = rng.integers(0, 2 ** 32, size=(s.Cout, s.K // 8), dtype=np.uint64).astype(np.uint32)
+            c0, w0 = time.process_time(), time.perf_counter()
+            O.w4a4_conv_acc(aw, ww, s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, use_blas=True)
+            cs, ws_ = time.process_time() - c0, time.perf_counter() - w0
+            cpu[conv_key(s)] = {"TOPs": round(s.ops / ws_ / 1e12, 5), "s": round(ws_, 3), "images": s.B,
+                                "cores": max(1, int(round(cs / ws_)))}
+        name, N, K = shapes[1]
+        e = dec[0][1][1]
+        xb = synth.llm_activation_bf16(288, K, synth.seed_for(2, 1, 1), outlier_frac=0.005)
+        qw_h = e["qweight"].cpu().numpy().view(np.uint32).reshape(N, K // 8)
+        sc_h = e["scales"].cpu().numpy().view(np.float16).reshape(N, K // GROUP)
+        zr_h = e["zeros"].cpu().numpy().view(np.uint32).reshape(N, -1)
+        c0, w0 = time.process_time(), time.perf_counter()
+        O.w4a16_linear(xb, qw_h, sc_h, zr_h, GROUP)
+        cs, ws_ = time.process_time() - c0, time.perf_counter() - w0
+        cpu[f"{name}_M288"] = {"TFLOPs": round(2.0 * 288 * N * K / ws_ / 1e12, 5), "s": round(ws_, 3),
+                               "cores": max(1, int(round(cs / ws_)))}
+        cpu["note"] = f"numpy oracle on the host ({os.cpu_count()} logical CPUs), kind = oracle, not tuned"
+        extra["cpu_oracle_other_paths"] = cpu
+
+    if extra:
         result["extra"] = extra
         log("[bench] extra:", json.dumps(extra))
 
@@ -536,7 +677,7 @@ def main():
     if not args.no_cpu:
         from oracle import qail_oracle as O
         host = []
-        for l in range(L):
+        for l in range(min(L, 8)):
             for i, (_, N, K) in enumerate(shapes):
                 e = dec[l][1][i]
                 host.append((e["qweight"].cpu().numpy().view(np.uint32).reshape(N, K // 8),
@@ -546,7 +687,7 @@ def main():
         # bounded sample: whole layers until about 15 s of wall time have been spent
         done, c0, w0 = 0, time.process_time(), time.perf_counter()
         while done < 64 and time.perf_counter() - w0 < 15.0:
-            for qw, sc, zr, xb in host[(done % L) * 4:(done % L) * 4 + 4]:
+            for qw, sc, zr, xb in host[(done % min(L, 8)) * 4:(done % min(L, 8)) * 4 + 4]:
                 O.w4a16_linear(xb, qw, sc, zr, GROUP)
             done += 1
         cpu_s, wall_s = time.process_time() - c0, time.perf_counter() - w0
