@@ -304,6 +304,20 @@ def main():
             gbps = 32 * sum(linear_bytes(N, K, M) for _, N, K in shapes) / t / 1e9
             stack[f"M={M}"] = {"ms_per_token_step": round(t * 1e3, 4), "tokens_per_s": round(M / t, 1),
                                "GBps": round(gbps, 1), "frac_hbm_peak": round(gbps / HBM_PEAK_GBS, 4)}
+            if M == 1:
+                # the same walk with real dependences, as a decoder has them (each linear may read what the
+                # one before it wrote), in one launch per 32 linears: the blocks meet between two linears
+                # through counters while the next linear's first weights are already on their way
+                ents_all = [io[l % L][1][i] for l in range(32) for i in range(4)]
+                chain_items = B.make_w4a16_items(ents_all, 1)
+                wsc = torch.zeros(B.qail_w4a16_chain_workspace(chain_items, len(ents_all)), dtype=torch.uint8, device="cuda")
+                t = timed(lambda: B.qail_w4a16_linear_chain(chain_items, len(ents_all), wsc, sh), 7, warm=1)
+                torch.cuda.synchronize()
+                gbps1 = 32 * sum(linear_bytes(N, K, M) for _, N, K in shapes) / t / 1e9
+                stack["M=1, dependent linears chained in one launch per 32"] = {
+                    "ms_per_token_step": round(t * 1e3, 4), "tokens_per_s": round(M / t, 1), "GBps": round(gbps1, 1),
+                    "frac_hbm_peak": round(gbps1 / HBM_PEAK_GBS, 4), "status_word": int(wsc[:4].view(torch.int32)[0].item())}
+                del ents_all, chain_items, wsc
             if M in (1, 16):
                 # the same walk with one launch per linear: stream order then makes every linear wait for
                 # the one before it, as the data dependences of a real decoder layer would
@@ -318,6 +332,20 @@ def main():
                 stack[f"M={M}, one launch per linear"] = {"ms_per_token_step": round(t * 1e3, 4),
                                                           "tokens_per_s": round(M / t, 1), "GBps": round(gbps1, 1),
                                                           "frac_hbm_peak": round(gbps1 / HBM_PEAK_GBS, 4)}
+                if M == 1:
+                    # the same 128 launches recorded once into a graph and replayed
+                    gs = torch.cuda.Stream()
+                    with torch.cuda.stream(gs):
+                        graph = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(graph, stream=gs):
+                            for l in range(32):
+                                for i in range(4):
+                                    B.qail_w4a16_linear_batch(ones[l % L][i], 1, M, None, gs.cuda_stream)
+                    torch.cuda.synchronize()
+                    tg = timed(graph.replay, 7, warm=1)
+                    del graph
+                    stack["M=1, one launch per linear, graph replay"] = {"ms_per_token_step": round(tg * 1e3, 4),
+                                                                         "tokens_per_s": round(M / tg, 1)}
                 del ones
             if M != 1:
                 del io

@@ -187,6 +187,25 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
 int qail_w4a16_batch_workspace(const qail_w4a16_item* items, int32_t count, int32_t M,
                                size_t* bytes);
 
+/* Linears that depend on each other, M = 1, in one launch (appendix "Analysis": the decode stage
+ * walks the backbone's linears one after the other, each a bandwidth-bound stream of weights).
+ * Item i + 1 does not read its x before every element of item i's y has been written, so x of
+ * item i + 1 may be, or overlap, y of item i; apart from that the results are those of
+ * qail_w4a16_linear_batch at M = 1, bit for bit.  The whole grid is resident on the GPU and the
+ * blocks meet between two items through counters in the workspace, while the first weights of the
+ * next item are already on their way: the stream of weights does not stop between items as it
+ * does between launches.  Up to 32 items share a launch; longer lists take several.
+ *   items      HOST array; every item must be one the M = 1 streaming kernel takes
+ *              (K % 32 == 0, group_size % 32 == 0, K <= 12288) with N <= 512 * CUs, else
+ *              QAIL_ERR_UNSUPPORTED.
+ *   workspace  qail_w4a16_chain_workspace() bytes, 256-byte aligned.  Its first uint32 is a status
+ *              word, written by the call: 0 if every block saw the others arrive, 1 if some block
+ *              gave up waiting (possible only when other work keeps part of the grid off the GPU;
+ *              the outputs are then unspecified, and every kernel still ends). */
+int qail_w4a16_chain_workspace(const qail_w4a16_item* items, int32_t count, size_t* bytes);
+int qail_w4a16_linear_chain(const qail_w4a16_item* items, int32_t count, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
 /* Low-rank adapter beside a 4-bit linear (Sec. 5.1: the 4-bit policy is fine-tuned with
  * rank-32 adapters on the quantised backbone; they stay separate from the packed weights):
  *     y[m][n] = sum_k x[m][k] w_hat[n][k]  +  scaling * sum_j (sum_k x[m][k] A[j][k]) B[n][j]

@@ -35,6 +35,7 @@ EXPORTS = (
     "qail_w4a4_workspace", "qail_w4a4_gemm", "qail_w4a4_conv_u4",
     "qail_w4a16_lora_workspace", "qail_w4a16_linear_lora_batch",
     "qail_static_scratch_bytes", "qail_w4a16_linear_lora_batch_static",
+    "qail_w4a16_chain_workspace", "qail_w4a16_linear_chain",
     "qail_act_scale_s8", "qail_quantize_act_s8", "qail_w8a8_gemm", "qail_w8a16_linear",
     "qail_w8a16_linear_batch",
     "qail_fake_quant_w4", "qail_lsq_forward", "qail_lsq_backward_workspace", "qail_lsq_backward", "qail_qbc_loss",
@@ -100,6 +101,8 @@ def lib() -> ctypes.CDLL:
         L.qail_w4a16_linear_lora_batch.argtypes = [ctypes.POINTER(qail_w4a16_item), ctypes.POINTER(qail_lora), i32,
                                                    i32, vp, sz, vp]
         L.qail_static_scratch_bytes.argtypes = [psz]
+        L.qail_w4a16_chain_workspace.argtypes = [ctypes.POINTER(qail_w4a16_item), i32, psz]
+        L.qail_w4a16_linear_chain.argtypes = [ctypes.POINTER(qail_w4a16_item), i32, vp, sz, vp]
         L.qail_w4a16_linear_lora_batch_static.argtypes = [ctypes.POINTER(qail_w4a16_item), ctypes.POINTER(qail_lora),
                                                           i32, i32, vp]
         L.qail_fake_quant_w4.argtypes = [ctypes.POINTER(qail_wdesc), vp, vp, vp]
@@ -346,6 +349,18 @@ def qail_w4a16_linear_lora_batch(items, loras, count: int, M: int, workspace: to
     _check(lib().qail_w4a16_linear_lora_batch(items, loras, count, M, _ptr(workspace), wsb,
                                               _stream() if stream is None else stream),
            "qail_w4a16_linear_lora_batch")
+
+
+def qail_w4a16_chain_workspace(items, count: int) -> int:
+    b = ctypes.c_size_t()
+    _check(lib().qail_w4a16_chain_workspace(items, count, ctypes.byref(b)), "qail_w4a16_chain_workspace")
+    return b.value
+
+
+def qail_w4a16_linear_chain(items, count: int, workspace: torch.Tensor, stream: Optional[int] = None) -> None:
+    wsb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().qail_w4a16_linear_chain(items, count, _ptr(workspace), wsb, _stream() if stream is None else stream),
+           "qail_w4a16_linear_chain")
 
 
 def qail_static_scratch_bytes() -> int:

@@ -270,6 +270,33 @@ int qail_w4a16_linear_batch(const qail_w4a16_item* items, int32_t count, int32_t
     return QAIL_OK;
 }
 
+int qail_w4a16_chain_workspace(const qail_w4a16_item* items, int32_t count, size_t* bytes) {
+    if (count < 0) return QAIL_ERR_SHAPE;
+    if (!bytes || (count > 0 && !items)) return QAIL_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const int e = check_wdesc(&items[i].d);
+        if (e != QAIL_OK) return e;
+        if (items[i].d.scheme != QAIL_W4_ASYM_GROUP || !gemv_chain_supports(items[i].d)) return QAIL_ERR_UNSUPPORTED;
+    }
+    *bytes = gemv_chain_workspace(count);
+    return QAIL_OK;
+}
+
+int qail_w4a16_linear_chain(const qail_w4a16_item* items, int32_t count, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    if (count < 0) return QAIL_ERR_SHAPE;
+    if (count == 0) return QAIL_OK;
+    if (!items) return QAIL_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const int e = check_item(items[i], 1);
+        if (e != QAIL_OK) return e;
+        if (!gemv_chain_supports(items[i].d)) return QAIL_ERR_UNSUPPORTED;
+    }
+    if (!workspace || workspace_bytes < gemv_chain_workspace(count)) return QAIL_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QAIL_ERR_ALIGN;
+    return hip_status(launch_w4a16_chain(items, count, workspace, static_cast<hipStream_t>(stream)));
+}
+
 namespace {
 constexpr int kLoraStride = 64;  // floats per row of a down-projection in the workspace (r <= 64)
 constexpr int kLoraMaxM = 65535;  // the adapter kernels put the rows of x on the grid's y axis

@@ -56,6 +56,11 @@ bool gemv_supports(const qail_wdesc& d);
 hipError_t launch_w4a16_gemv(const qail_w4a16_item* items, int count, hipStream_t st);
 hipError_t launch_w4a16_gemv_lora(const qail_w4a16_item* items, const qail_lora* loras, const float* t,
                                   int t_stride, int count, hipStream_t st);
+// Linears that depend on each other (M = 1, every item taken by the streaming kernel), in one
+// launch per 32 items; `ws`: gemv_chain_workspace(count) bytes, 256-byte aligned.
+bool gemv_chain_supports(const qail_wdesc& d);
+size_t gemv_chain_workspace(int count);
+hipError_t launch_w4a16_chain(const qail_w4a16_item* items, int count, void* ws, hipStream_t st);
 bool lora_supports(const qail_wdesc& d, const qail_lora& l);
 hipError_t launch_lora_down(const qail_w4a16_item* items, const qail_lora* loras, float* t, int t_stride,
                             int count, int M, hipStream_t st);

@@ -74,6 +74,18 @@ struct GemvLoraArgs {
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
+// Linears that depend on each other in one launch (see w4a16_chain_kernel).  Every block works on
+// every item in turn; between two items all blocks meet through counters in the workspace.
+constexpr int kChainMaxItems = 32;   // items per launch (their records travel in the kernel arguments)
+constexpr int kChainFlagBase = 64;   // workspace words: [0] status, [16 + i] arrivals at item i, [64 + b] flag of block b
+constexpr int kChainMaxPolls = 1 << 16;   // a block gives up waiting after this many looks at its flag
+
+struct ChainCtx {
+    const uint32_t* flag;   // this block's flag: holds the number of items every block has finished
+    uint32_t need;          // value the flag must reach before this item's x may be read; 0: nothing to wait for
+    uint32_t* status;       // one word of the workspace: set to 1 by a block that gave up waiting
+};
+
 template <int kCtrl>
 __device__ __forceinline__ float dpp_add(float v) {
     const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xF, 0xF, true);
@@ -196,25 +208,37 @@ __device__ __forceinline__ void stage_x(const GemvItem& it, int nu, uint4* __res
 // eight such instructions, chained through the accumulator, give every lane the dot
 // product of its 32 codes with the 32 activations at the same k.  The other entries of D
 // are ignored.  The vector ALU only expands nibbles: 5 operations per 8 codes.
-template <int NU, int kPR, int kSub>
+//
+// kChain: the item's activations may have been written by the previous item of the same launch
+// (by other blocks, on other XCDs).  The order then is: a first look at the previous item's
+// counters, the first ring of weight loads (they depend on nothing), the wait, and only then
+// the loads of x, which carry the agent scope so that they see what the other blocks released.
+// Vector loads return in order, so the first look (issued before the ring) is the one poll whose
+// answer arrives while the ring is still in flight; later polls queue behind the ring.
+template <int NU, int kPR, int kSub, bool kChain>
 __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* lo, const float4* lora_t,
                                             int rbase, int nrows, int lane,
-                                            uint4* __restrict__ xlds) {
+                                            uint4* __restrict__ xlds, int wave, const ChainCtx& cc) {
     typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
     const int K = it.K, g = it.g;
     const int G = K / g, zwords = (G + 7) / 8, kw = K / 8;
 
-    // x first: it is needed first and loads return in order
     constexpr int kLaneK = kChunkK * kSub;  // k per lane and unit
     constexpr int kUnitK = kWave * kLaneK;  // k per wave-wide unit
     constexpr int kMaxRuns = (NU * (kUnitK / 8) + kGemvThreads - 1) / kGemvThreads;
     uint4 xr[kMaxRuns];
+    uint32_t seen = 0;
+    if (!kChain) {
+        // x first: it is needed first and loads return in order
 #pragma unroll
-    for (int u = 0; u < kMaxRuns; ++u) {
-        const int i = threadIdx.x + u * kGemvThreads;
-        xr[u] = (i < K / 8) ? reinterpret_cast<const uint4*>(it.x)[i] : make_uint4(0, 0, 0, 0);
+        for (int u = 0; u < kMaxRuns; ++u) {
+            const int i = threadIdx.x + u * kGemvThreads;
+            xr[u] = (i < K / 8) ? reinterpret_cast<const uint4*>(it.x)[i] : make_uint4(0, 0, 0, 0);
+        }
+    } else if (cc.need) {
+        seen = __hip_atomic_load(cc.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __builtin_amdgcn_sched_barrier(0);  // the scheduler must not move the x load behind the weights
+    __builtin_amdgcn_sched_barrier(0);  // the scheduler must not move these loads behind the weights
 
     // Per-unit constants of this lane.  Only the last unit of a row can run past K (a lane's
     // stretch lies entirely inside or outside: K is a multiple of its length); there the lane
@@ -269,6 +293,33 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
             __builtin_amdgcn_sched_barrier(0);  // program order = consumption order, see above
         }
 
+    if (kChain) {
+        if (cc.need && wave == 0) {
+            // bounded: a block that never sees the others arrive (the grid was not resident as a
+            // whole) says so in the status word and goes on, so every wave ends
+            int polls = 0;
+            while (__builtin_amdgcn_readfirstlane(seen) < cc.need) {
+                if (++polls > kChainMaxPolls) {
+                    if (lane == 0) __hip_atomic_store(cc.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
+                seen = __hip_atomic_load(cc.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        // every wave of the block is through with the previous item's staged x, and the previous
+        // item's outputs are visible at agent scope
+        __syncthreads();
+        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(it.x), 0, K * 2, 0x00020000);
+#pragma unroll
+        for (int u = 0; u < kMaxRuns; ++u) {
+            const int i = threadIdx.x + u * kGemvThreads;
+            // aux 16 = sc1: agent scope, the load is served from where the other XCDs' released stores are
+            // visible; past the end of x the descriptor returns zeros
+            const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rx, i * 16, 0, 16);
+            xr[u] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+    }
     stage_x<kMaxRuns, kSub>(it, NU, xlds, xr);
 
     // Per unit, for the lane's own stretch (written by the staging):
@@ -404,7 +455,13 @@ __device__ __forceinline__ void stream_rows(const GemvItem& it, const GemvLora* 
             }
             v = fmaf(lo->scaling, dot, v);
         }
-        it.y[row] = f32_to_bf16_rne(v);
+        if (kChain) {
+            // written through to where the other XCDs' agent-scope loads look: the next item's blocks
+            // may run anywhere on the chip
+            __hip_atomic_store(it.y + row, f32_to_bf16_rne(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            it.y[row] = f32_to_bf16_rne(v);
+        }
     }
 }
 
@@ -443,19 +500,19 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& args, const GemvLoraAr
     // about kUnits wave-wide loads (1 KB each) in flight per wave
     if (wide) {
         switch (nu) {
-            case 1: stream_rows<1, kUnits / 2, 2>(it, lo, lora_t, r0, r1, lane, lds); break;
-            case 2: stream_rows<2, kUnits / 4, 2>(it, lo, lora_t, r0, r1, lane, lds); break;
-            default: stream_rows<3, 1, 2>(it, lo, lora_t, r0, r1, lane, lds); break;
+            case 1: stream_rows<1, kUnits / 2, 2, false>(it, lo, lora_t, r0, r1, lane, lds, wave, ChainCtx{}); break;
+            case 2: stream_rows<2, kUnits / 4, 2, false>(it, lo, lora_t, r0, r1, lane, lds, wave, ChainCtx{}); break;
+            default: stream_rows<3, 1, 2, false>(it, lo, lora_t, r0, r1, lane, lds, wave, ChainCtx{}); break;
         }
         return;
     }
     switch (nu) {
-        case 1: stream_rows<1, kUnits, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
-        case 2: stream_rows<2, kUnits / 2, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
-        case 3: stream_rows<3, kUnits / 3, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
-        case 4: stream_rows<4, kUnits / 4, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
-        case 5: stream_rows<5, 1, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
-        default: stream_rows<6, 1, 1>(it, lo, lora_t, r0, r1, lane, lds); break;
+        case 1: stream_rows<1, kUnits, 1, false>(it, lo, lora_t, r0, r1, lane, lds, wave, ChainCtx{}); break;
+        case 2: stream_rows<2, kUnits / 2, 1, false>(it, lo, lora_t, r0, r1, lane, lds, wave, ChainCtx{}); break;
+        case 3: stream_rows<3, kUnits / 3, 1, false>(it, lo, lora_t, r0, r1, lane, lds, wave, ChainCtx{}); break;
+        case 4: stream_rows<4, kUnits / 4, 1, false>(it, lo, lora_t, r0, r1, lane, lds, wave, ChainCtx{}); break;
+        case 5: stream_rows<5, 1, 1, false>(it, lo, lora_t, r0, r1, lane, lds, wave, ChainCtx{}); break;
+        default: stream_rows<6, 1, 1, false>(it, lo, lora_t, r0, r1, lane, lds, wave, ChainCtx{}); break;
     }
 }
 
@@ -468,6 +525,93 @@ __global__ __launch_bounds__(kGemvThreads) void w4a16_gemv_kernel(const GemvArgs
 template <int kUnits>
 __global__ __launch_bounds__(kGemvThreads) void w4a16_gemv_lora_kernel(const GemvArgs args, const GemvLoraArgs lora) {
     gemv_body<kUnits, true>(args, lora);
+}
+
+// Linears that depend on each other, in ONE launch.  A decoder layer's linears cannot share a
+// launch as independent items: each needs what the one before it produced.  Launched one by one
+// they each pay a ramp and a tail during which HBM idles.  Here the grid is resident as a whole
+// (one or two blocks per CU), every block takes its slab of rows of item 0, then of item 1, and
+// so on, and before it reads item i + 1's activations it waits until every block has written
+// its rows of item i.  The weights do not depend on the activations, so a wave asks for its
+// first rows of item i + 1 before it waits: while the blocks meet, HBM keeps delivering.
+//
+// Meeting point, in the workspace (cleared by a small kernel in front): one arrival counter per
+// item and one flag per block.  A block whose waves' stores of item i have been acknowledged
+// adds one to the item's counter; the block that finds it was the last one writes i + 1 into
+// every block's flag.  A waiting block looks only at its own flag: 512 blocks spinning on the
+// counters themselves delay the very additions they wait for (measured: 26 us per item).
+struct ChainArgs {
+    GemvItem it[kChainMaxItems];
+    uint32_t* ws;
+    int count;
+};
+
+__global__ __launch_bounds__(256) void w4a16_chain_clear_kernel(uint32_t* ws, int words) {
+    for (int i = threadIdx.x; i < words; i += 256) ws[i] = 0u;
+}
+
+template <int kUnits>
+__global__ __launch_bounds__(kGemvThreads, 4) void w4a16_chain_kernel(const ChainArgs args) {
+    extern __shared__ uint4 lds[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int lane0 = threadIdx.x % kWave;
+    const int P = (int)gridDim.x, b = (int)blockIdx.x;
+    ChainCtx cc;
+    cc.status = args.ws;
+    cc.flag = args.ws + kChainFlagBase + b;
+    for (int i = 0; i < args.count; ++i) {
+        const GemvItem it = args.it[i];
+        cc.need = (uint32_t)i;   // items that must be complete before this one's x is read
+        // the lane index is laundered per item: what the compiler derives from it (offsets, masks,
+        // picks) would otherwise be hoisted out of this loop for all nine shapes of the stream at
+        // once and held in registers across it
+        int lane = lane0;
+        asm volatile("" : "+v"(lane));
+        const int K = it.K;
+        const bool wide = it.g % (2 * kChunkK) == 0 && K % (2 * kChunkK) == 0;
+        const int nu = wide ? (K + 2 * kWaveK - 1) / (2 * kWaveK) : (K + kWaveK - 1) / kWaveK;
+        const int s0 = b * it.rows_base + min(b, it.rows_rem);
+        const int s1 = s0 + it.rows_base + (b < it.rows_rem ? 1 : 0);
+        const int r0 = s0 + wave;
+        const int r1 = max(0, (s1 - s0 - wave + kGemvWaves - 1) / kGemvWaves);
+        if (wide) {
+            switch (nu) {
+                case 1: stream_rows<1, kUnits / 2, 2, true>(it, nullptr, nullptr, r0, r1, lane, lds, wave, cc); break;
+                case 2: stream_rows<2, kUnits / 4, 2, true>(it, nullptr, nullptr, r0, r1, lane, lds, wave, cc); break;
+                default: stream_rows<3, 1, 2, true>(it, nullptr, nullptr, r0, r1, lane, lds, wave, cc); break;
+            }
+        } else {
+            switch (nu) {
+                case 1: stream_rows<1, kUnits, 1, true>(it, nullptr, nullptr, r0, r1, lane, lds, wave, cc); break;
+                case 2: stream_rows<2, kUnits / 2, 1, true>(it, nullptr, nullptr, r0, r1, lane, lds, wave, cc); break;
+                case 3: stream_rows<3, kUnits / 3, 1, true>(it, nullptr, nullptr, r0, r1, lane, lds, wave, cc); break;
+                case 4: stream_rows<4, kUnits / 4, 1, true>(it, nullptr, nullptr, r0, r1, lane, lds, wave, cc); break;
+                case 5: stream_rows<5, 1, 1, true>(it, nullptr, nullptr, r0, r1, lane, lds, wave, cc); break;
+                default: stream_rows<6, 1, 1, true>(it, nullptr, nullptr, r0, r1, lane, lds, wave, cc); break;
+            }
+        }
+        if (i + 1 < args.count) {
+            // This wave's rows of item i went out as agent-scope stores (written through the XCD's L2),
+            // so they are visible chip-wide once they are acknowledged: the wave waits for that, the
+            // block's waves meet, and one wave reports.  (A release fence at agent scope would
+            // do, but it writes back the whole L2 each time: measured 70 us per item.)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+            __syncthreads();
+            if (wave == 0) {
+                uint32_t before = 0;
+                if (lane == 0)
+                    before = __hip_atomic_fetch_add(args.ws + 16 + i, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                before = __builtin_amdgcn_readfirstlane(before);
+                if (before == (uint32_t)(P - 1)) {
+                    // the last block to arrive: every block's outputs of item i are visible; tell them all
+                    for (int j = lane; j < P; j += kWave)
+                        __hip_atomic_store(args.ws + kChainFlagBase + j, (uint32_t)(i + 1), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+    }
 }
 
 size_t item_bytes(const qail_wdesc& d) {
@@ -566,6 +710,72 @@ hipError_t launch_w4a16_gemv(const qail_w4a16_item* items, int count, hipStream_
     for (int i0 = 0; i0 < count; i0 += kGemvMaxItems) {
         const int c = (count - i0 < kGemvMaxItems) ? count - i0 : kGemvMaxItems;
         const hipError_t e = launch_chunk(items + i0, nullptr, c, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Status word, arrival counters of up to 32 items and one flag per block of the largest grid
+// (two blocks per CU), in 4-byte words.
+static int chain_ws_words() { return kChainFlagBase + 2 * device_cu_count(); }
+size_t gemv_chain_workspace(int count) {
+    (void)count;
+    return ((size_t)chain_ws_words() * sizeof(uint32_t) + 255) / 256 * 256;
+}
+
+// Largest grid of the chain kernel that is resident as a whole on the current device with `lds`
+// bytes of dynamic LDS per block: two blocks per CU if they fit, else one; 0 if none fits.
+static int chain_grid(size_t lds) {
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&w4a16_chain_kernel<8>),
+                                                     kGemvThreads, lds) != hipSuccess)
+        return 0;
+    if (per_cu > 2) per_cu = 2;
+    return per_cu * device_cu_count();
+}
+
+bool gemv_chain_supports(const qail_wdesc& d) {
+    // every block takes a slab of every item, a wave keeps at most 64 rows' results
+    return gemv_supports(d) && (long long)d.N <= 64LL * kGemvWaves * device_cu_count();
+}
+
+hipError_t launch_w4a16_chain(const qail_w4a16_item* items, int count, void* ws, hipStream_t st) {
+    for (int i0 = 0; i0 < count; i0 += kChainMaxItems) {
+        const int c = (count - i0 < kChainMaxItems) ? count - i0 : kChainMaxItems;
+        size_t lds = 0;
+        for (int i = 0; i < c; ++i) {
+            const qail_wdesc& d = items[i0 + i].d;
+            const bool wide = d.group_size % (2 * kChunkK) == 0 && d.K % (2 * kChunkK) == 0;
+            const int nu = wide ? (d.K + 2 * kWaveK - 1) / (2 * kWaveK) : (d.K + kWaveK - 1) / kWaveK;
+            const size_t need_lds = (size_t)nu * kWave * (wide ? 9 : 5) * 16;
+            if (need_lds > lds) lds = need_lds;
+        }
+        int P = chain_grid(lds);
+        if (P <= 0) return hipErrorLaunchOutOfResources;
+        // two blocks per CU only when that leaves the shortest item a row per wave
+        int nmin = items[i0].d.N;
+        for (int i = 1; i < c; ++i) nmin = items[i0 + i].d.N < nmin ? items[i0 + i].d.N : nmin;
+        if (P > device_cu_count() && nmin < P * kGemvWaves) P = device_cu_count();
+        ChainArgs a;
+        for (int i = 0; i < c; ++i) {
+            const qail_w4a16_item& s = items[i0 + i];
+            GemvItem& t = a.it[i];
+            t.qw = s.qweight; t.sc = s.scales; t.zr = s.zeros; t.x = s.x; t.y = s.y;
+            t.N = s.d.N; t.K = s.d.K; t.g = s.d.group_size;
+            t.block_begin = 0;
+            t.rows_base = s.d.N / P;
+            t.rows_rem = s.d.N % P;
+        }
+        for (int i = c; i < kChainMaxItems; ++i) a.it[i] = a.it[c - 1];
+        a.ws = static_cast<uint32_t*>(ws);
+        a.count = c;
+        // the status word survives from chunk to chunk; counters and flags are cleared for each launch
+        hipLaunchKernelGGL(w4a16_chain_clear_kernel, dim3(1), dim3(256), 0, st, a.ws + (i0 == 0 ? 0 : 1),
+                           chain_ws_words() - (i0 == 0 ? 0 : 1));
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(w4a16_chain_kernel<8>, dim3(P), dim3(kGemvThreads), lds, st, a);
+        e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

@@ -99,6 +99,25 @@ def test_argument_errors_are_reported_without_a_gpu(B):
     assert f(its, lo, 1, 1, None, 0, None) == B.QAIL_ERR_WORKSPACE          # the down-projection needs room
     assert f(its, None, 1, 1, ok, 1 << 20, None) == B.QAIL_ERR_NULL
     assert f(its, lo, 0, 1, None, 0, None) == B.QAIL_OK
+    # dependent linears in one launch: a status word, arrival counters and a flag per block (two blocks
+    # on each of 256 CUs when no GPU can be asked); every item must be
+    # one the M = 1 stream takes
+    szc = ctypes.c_size_t(0)
+    assert L.qail_w4a16_chain_workspace(its, 1, ctypes.byref(szc)) == B.QAIL_OK and szc.value == (64 + 512) * 4
+    its40 = (B.qail_w4a16_item * 40)(*([it] * 40))
+    assert L.qail_w4a16_chain_workspace(its40, 40, ctypes.byref(szc)) == B.QAIL_OK and szc.value == (64 + 512) * 4
+    assert L.qail_w4a16_chain_workspace(its, 1, None) == B.QAIL_ERR_NULL
+    assert L.qail_w4a16_chain_workspace(None, 1, ctypes.byref(szc)) == B.QAIL_ERR_NULL
+    assert L.qail_w4a16_linear_chain(its, 0, None, 0, None) == B.QAIL_OK
+    assert L.qail_w4a16_linear_chain(its, -1, None, 0, None) == B.QAIL_ERR_SHAPE
+    assert L.qail_w4a16_linear_chain(None, 1, ok, 1 << 20, None) == B.QAIL_ERR_NULL
+    assert L.qail_w4a16_linear_chain(its, 1, None, 0, None) == B.QAIL_ERR_WORKSPACE
+    assert L.qail_w4a16_linear_chain(its, 1, ok, 100, None) == B.QAIL_ERR_WORKSPACE
+    assert L.qail_w4a16_linear_chain(its, 1, odd, 1 << 20, None) == B.QAIL_ERR_ALIGN
+    dbig = B.qail_wdesc(16, 16384, 128, B.QAIL_W4_ASYM_GROUP)            # K beyond the streaming kernel
+    itb = (B.qail_w4a16_item * 1)(B.qail_w4a16_item(dbig, ok, ok, ok, ok, ok))
+    assert L.qail_w4a16_linear_chain(itb, 1, ok, 1 << 20, None) == B.QAIL_ERR_UNSUPPORTED
+    assert L.qail_w4a16_chain_workspace(itb, 1, ctypes.byref(szc)) == B.QAIL_ERR_UNSUPPORTED
     szl = ctypes.c_size_t(0)
     assert L.qail_w4a16_lora_workspace(its, lo, 1, 3, ctypes.byref(szl)) == B.QAIL_OK and szl.value == 768
     assert L.qail_w4a16_lora_workspace(its, lo, 1, 3, None) == B.QAIL_ERR_NULL

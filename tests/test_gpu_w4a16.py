@@ -338,6 +338,122 @@ def test_full_size_prefill_linears_sampled(B, M):
     _sampled_full_size(B, M, dict(outlier_frac=0.005))
 
 
+# ------------------------------------------------------------------ dependent linears in one launch
+
+def _chain_status(ws):
+    return int(host(ws[:4], np.uint32)[0])
+
+
+def test_chain_equals_single_calls_bit_for_bit(B):
+    """Independent inputs: the chained launch must give exactly what one call per linear gives
+    (the same stream sums a row in the same order).  40 items: two launches of the chain kernel;
+    shapes with one to six wave-wide units per row, 32 and 64 k per lane, ragged slabs, items
+    with fewer rows than the grid has waves."""
+    import torch
+    shapes = [(4096, 4096, 128), (1000, 2048, 128), (37, 11008, 128), (130, 2048, 32), (64, 32, 32), (33, 8192, 64),
+              (20, 11040, 32), (18, 6176, 32), (16, 12288, 128), (2100, 1024, 256)]
+    ents, singles = [], []
+    for rep in range(4):
+        for i, (N, K, g) in enumerate(shapes):
+            w = synth.llm_weight(N, K, 3000 + 20 * rep + i, outlier_frac=0.01)
+            xb = synth.llm_activation_bf16(1, K, 3500 + 20 * rep + i)
+            qw, s, zw = oracle_pack(w, g)
+            ents.append(dict(N=N, K=K, group_size=g, qweight=dev(qw), scales=dev(s.view(np.uint16)), zeros=dev(zw),
+                             x=dev(xb), y=torch.full((N,), 0x7FC0, dtype=torch.int16, device="cuda")))
+            singles.append(gpu_linear(B, qw, s, zw, xb, g, N, K, 1))
+    items = B.make_w4a16_items(ents, 1)
+    ws = torch.full((B.qail_w4a16_chain_workspace(items, len(ents)),), 0xAB, dtype=torch.uint8, device="cuda")
+    for _ in range(2):       # a second call finds the first one's counters in the workspace
+        for e in ents:
+            e["y"].fill_(0x7FC0)
+        B.qail_w4a16_linear_chain(items, len(ents), ws)
+        torch.cuda.synchronize()
+        assert _chain_status(ws) == 0
+        for e, ref in zip(ents, singles):
+            assert np.array_equal(host(e["y"], np.uint16).reshape(ref.shape), ref), (e["N"], e["K"])
+
+
+def test_chain_feeds_each_linear_the_previous_output(B):
+    """x of item i + 1 IS y of item i (the same buffer): every block must see all of the previous
+    item's outputs, written by other blocks, before it stages them.  Checked link by link against
+    single calls fed the same way, and the first links against the oracle."""
+    import torch
+    K = N = 4096
+    links = 9
+    packs = []
+    for i in range(links):
+        w = synth.llm_weight(N, K, 3800 + i, outlier_frac=0.01)
+        packs.append(oracle_pack(w, 128))
+    x0 = synth.llm_activation_bf16(1, K, 3900)
+    bufs = [dev(x0)] + [torch.full((N,), 0x7FC0, dtype=torch.int16, device="cuda") for _ in range(links)]
+    ents = [dict(N=N, K=K, group_size=128, qweight=dev(qw), scales=dev(s.view(np.uint16)), zeros=dev(zw),
+                 x=bufs[i], y=bufs[i + 1]) for i, (qw, s, zw) in enumerate(packs)]
+    items = B.make_w4a16_items(ents, 1)
+    ws = torch.zeros(B.qail_w4a16_chain_workspace(items, links), dtype=torch.uint8, device="cuda")
+    for trial in range(3):
+        for b in bufs[1:]:
+            b.fill_(0x7FC0)
+        B.qail_w4a16_linear_chain(items, links, ws)
+        torch.cuda.synchronize()
+        assert _chain_status(ws) == 0
+        got = [host(b, np.uint16).reshape(1, -1).copy() for b in bufs]
+        for i, (qw, s, zw) in enumerate(packs):
+            # the link recomputed alone from the chain's own input to it
+            assert np.array_equal(gpu_linear(B, qw, s, zw, got[i], 128, N, K, 1), got[i + 1]), (trial, i)
+        for i in range(2):
+            qw, s, zw = packs[i]
+            ref = O.w4a16_linear(got[i], qw, s, zw, 128)
+            nx, nw = O.w4a16_row_norms(got[i], qw, s, zw, 128)
+            assert w4a16_norm_err(got[i + 1], ref, nx, nw) <= TOL
+
+
+def test_chain_full_size_decoder_layers_sampled(B):
+    """Eight decoder layers (32 linears, one launch) at full size as the benchmark chains them;
+    the GPU quantises the full matrices, the oracle re-derives a weight row out of every 16."""
+    import torch
+    rng = np.random.default_rng(78)
+    ents, keep = [], []
+    for l in range(2):
+        for i, (name, N, K) in enumerate(synth.LLAMA7B_LINEARS):
+            w = synth.llm_weight(N, K, synth.seed_for(4, l * 4 + i, 0), outlier_frac=0.01)
+            xb = synth.llm_activation_bf16(1, K, synth.seed_for(1, i, 1))
+            qb, sb, zb = B.qail_packed_sizes(N, K, 128, B.QAIL_W4_ASYM_GROUP)
+            qw = torch.zeros(qb // 4, dtype=torch.int32, device="cuda")
+            sc = torch.zeros(sb // 2, dtype=torch.int16, device="cuda")
+            zr = torch.zeros(zb // 4, dtype=torch.int32, device="cuda")
+            wd = dev(w)
+            B.qail_quantize_weights(wd, 128, B.QAIL_W4_ASYM_GROUP, qw, sc, zr)
+            torch.cuda.synchronize()
+            del wd
+            rows = _stratified(N, 16, rng)
+            ents.append(dict(N=N, K=K, group_size=128, qweight=qw, scales=sc, zeros=zr, x=dev(xb),
+                             y=torch.full((N,), 0x7FC0, dtype=torch.int16, device="cuda")))
+            keep.append((w[rows], xb, rows))
+            del w
+    # 32 items: the two layers four times over (same weights, own outputs)
+    full = []
+    for rep in range(4):
+        for e in ents:
+            f = dict(e)
+            f["y"] = torch.full((e["N"],), 0x7FC0, dtype=torch.int16, device="cuda")
+            full.append(f)
+    items = B.make_w4a16_items(full, 1)
+    ws = torch.zeros(B.qail_w4a16_chain_workspace(items, len(full)), dtype=torch.uint8, device="cuda")
+    B.qail_w4a16_linear_chain(items, len(full), ws)
+    torch.cuda.synchronize()
+    assert _chain_status(ws) == 0
+    worst = 0.0
+    for j, f in enumerate(full):
+        w_rows, xb, rows = keep[j % len(keep)]
+        q, s, z = O.quantize_w4_asym_group(w_rows, 128)
+        qw_ref, zw_ref = O.pack_w4a16(q, z)
+        y = host(f["y"], np.uint16).reshape(1, -1)[:, rows]
+        ref = O.w4a16_linear(xb, qw_ref, s, zw_ref, 128)
+        nx, nw = O.w4a16_row_norms(xb, qw_ref, s, zw_ref, 128)
+        worst = max(worst, w4a16_norm_err(y, ref, nx, nw))
+    assert worst <= TOL, worst
+
+
 # ------------------------------------------------------------------ low-rank adapters
 
 def _lora_run(B, specs, M, seed):
