@@ -622,13 +622,36 @@ def main():
                                    for N, K, q8, s8, x8, y8 in w8l], 1) for w8l in w8ls]
 
         def layer8b():
-            B.qail_w8a16_linear_batch(it8[c8l[0] % L8], 4, 1, sh)
+            B.qail_w8a16_linear_batch(it8[c8l[0] % L8], 4, 1, None, sh)
             c8l[0] += 1
         tb8 = timed(layer8b, 200)
         extra["w8a16_decode_layer"] = {"us_per_layer": round(tb8 * 1e6, 2), "GBps": round(b8 / tb8 / 1e9, 1),
                                        "bytes": b8, "launches_per_layer": 1,
                                        "us_per_layer_one_launch_per_linear": round(tl8 * 1e6, 2),
                                        "note": f"{L8} distinct layers cycled"}
+        # the same layer at M > 1: the byte-code instantiation of the matrix-core GEMM, one batched call per layer
+        w8m = {}
+        for M8 in (4, 16, 288, 1024):
+            xs8 = [dev(synth.llm_activation_bf16(M8, K, synth.seed_for(1, i, 1))) for i, (_, N, K) in enumerate(shapes)]
+            its = []
+            for w8l in w8ls:
+                its.append(B.make_w8a16_items([dict(N=N, K=K, group_size=GROUP, qweight=q8, scales=s8, x=xs8[i],
+                                                    y=torch.empty(M8 * N, dtype=torch.int16, device="cuda"))
+                                               for i, (N, K, q8, s8, x8, y8) in enumerate(w8l)], M8))
+            nws8 = B.qail_w8a16_batch_workspace(its[0], 4, M8)
+            ws8 = torch.empty(nws8, dtype=torch.uint8, device="cuda") if nws8 else None
+            c8m = [0]
+
+            def layer8m():
+                B.qail_w8a16_linear_batch(its[c8m[0] % L8], 4, M8, ws8, sh)
+                c8m[0] += 1
+            tm = timed(layer8m, 20, settle=M8 > 16)
+            tf8 = sum(2.0 * M8 * N * K for _, N, K in shapes) / tm / 1e12
+            w8m[f"M={M8}"] = {"us_per_layer": round(tm * 1e6, 1), "TFLOPs": round(tf8, 1),
+                              "frac_f16_peak": round(tf8 / BF16_PEAK_TFLOPS, 4),
+                              "GBps_weights": round((b8 - sum(2 * (N + K) for _, N, K in shapes)) / tm / 1e9, 1)}
+            del its, xs8, ws8
+        extra["w8a16_layer_matrix_cores"] = w8m
         del w8ls, it8
 
     if want("train"):

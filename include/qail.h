@@ -306,9 +306,15 @@ int qail_w8a8_gemm(const qail_conv_desc* d, const uint32_t* a_s8, const uint32_t
 
 /* y[m][n] = sum_k x[m][k] * q[n][k] * s[n][k/g], d of scheme QAIL_W8_SYM_GROUP, x and y bf16,
  * fp32 accumulation, one rounding.  M = 1 runs a bandwidth-bound streaming kernel (K % 16 == 0,
- * group_size % 16 == 0, K + K/g <= 16384), anything else a plain one-thread-per-output kernel. */
+ * group_size % 16 == 0, K + K/g <= 16384).  M > 1 runs on the fp16 matrix cores (the kernel of
+ * qail_w4a16_linear for M > 16 with byte codes: K % 64 == 0, group_size % 64 == 0, an even
+ * number of scales; (q * s) is rounded once to fp16 before the fp32 accumulation) and needs the
+ * workspace the query below reports, 256-byte aligned.  Shapes outside both go to a plain
+ * one-thread-per-output kernel.  Errors as for qail_w4a16_linear. */
+int qail_w8a16_workspace(const qail_wdesc* d, int32_t M, size_t* bytes);
 int qail_w8a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales,
-                      const uint16_t* x, uint16_t* y, int32_t M, void* stream);
+                      const uint16_t* x, uint16_t* y, int32_t M, void* workspace,
+                      size_t workspace_bytes, void* stream);
 
 /* One linear of a batch for qail_w8a16_linear_batch (device pointers, 16-byte aligned). */
 typedef struct {
@@ -321,10 +327,15 @@ typedef struct {
 
 /* `count` independent 8-bit weight-only linears with the same M, given as a HOST array
  * (Sec. 5.4 also deploys the backbone with 8-bit weights: a decode step is again four such
- * linears per layer).  Same results, bit for bit, as `count` calls of qail_w8a16_linear; at
- * M = 1 the items the streaming kernel takes share launches (up to 8 each), every item on a
- * share of the blocks.  count >= 0 (0 is a no-op); errors as for the single call. */
-int qail_w8a16_linear_batch(const qail_w8a16_item* items, int32_t count, int32_t M, void* stream);
+ * linears per layer, a prefill pass four such GEMMs).  At M = 1 the items the streaming kernel
+ * takes share launches (up to 8 each), every item on a share of the blocks, with the single
+ * calls' results bit for bit; at M > 1 up to 8 consecutive items of the matrix-core path share
+ * launches the same way (a different division of K than in a call of its own, so equal within
+ * the W4A16 tolerance rather than bit for bit).  count >= 0 (0 is a no-op); workspace as
+ * reported by the batch query; errors as for the single call. */
+int qail_w8a16_batch_workspace(const qail_w8a16_item* items, int32_t count, int32_t M, size_t* bytes);
+int qail_w8a16_linear_batch(const qail_w8a16_item* items, int32_t count, int32_t M, void* workspace,
+                            size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------- training-side operators --
  * Sec. 4.1 / Algorithm 1: the quantised policy is trained through its quantisers with the

@@ -37,7 +37,7 @@ EXPORTS = (
     "qail_static_scratch_bytes", "qail_w4a16_linear_lora_batch_static",
     "qail_w4a16_chain_workspace", "qail_w4a16_linear_chain",
     "qail_act_scale_s8", "qail_quantize_act_s8", "qail_w8a8_gemm", "qail_w8a16_linear",
-    "qail_w8a16_linear_batch",
+    "qail_w8a16_linear_batch", "qail_w8a16_workspace", "qail_w8a16_batch_workspace",
     "qail_fake_quant_w4", "qail_lsq_forward", "qail_lsq_backward_workspace", "qail_lsq_backward", "qail_qbc_loss",
 )
 
@@ -113,8 +113,10 @@ def lib() -> ctypes.CDLL:
         L.qail_act_scale_s8.argtypes = [vp, sz, vp, vp]
         L.qail_quantize_act_s8.argtypes = [vp, sz, vp, vp, vp]
         L.qail_w8a8_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
-        L.qail_w8a16_linear.argtypes = [ctypes.POINTER(qail_wdesc), vp, vp, vp, vp, i32, vp]
-        L.qail_w8a16_linear_batch.argtypes = [ctypes.POINTER(qail_w8a16_item), i32, i32, vp]
+        L.qail_w8a16_linear.argtypes = [ctypes.POINTER(qail_wdesc), vp, vp, vp, vp, i32, vp, sz, vp]
+        L.qail_w8a16_workspace.argtypes = [ctypes.POINTER(qail_wdesc), i32, psz]
+        L.qail_w8a16_batch_workspace.argtypes = [ctypes.POINTER(qail_w8a16_item), i32, i32, psz]
+        L.qail_w8a16_linear_batch.argtypes = [ctypes.POINTER(qail_w8a16_item), i32, i32, vp, sz, vp]
         L.qail_w4a4_workspace.argtypes = [ctypes.POINTER(qail_conv_desc), psz]
         L.qail_w4a4_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.qail_w4a4_conv_u4.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, ctypes.c_float, vp,
@@ -405,15 +407,24 @@ def qail_w8a8_gemm(B, H, W, Cin, Cout, KH, KW, stride, pad, a_s8: torch.Tensor, 
                                 _ptr(y_out), None, 0, _stream() if stream is None else stream), "qail_w8a8_gemm")
 
 
+def qail_w8a16_workspace(N: int, K: int, group_size: int, M: int) -> int:
+    d = qail_wdesc(N, K, group_size, QAIL_W8_SYM_GROUP)
+    b = ctypes.c_size_t()
+    _check(lib().qail_w8a16_workspace(ctypes.byref(d), M, ctypes.byref(b)), "qail_w8a16_workspace")
+    return b.value
+
+
 def qail_w8a16_linear(N: int, K: int, group_size: int, qweight: torch.Tensor, scales: torch.Tensor,
-                      x: torch.Tensor, y: torch.Tensor, M: int, stream: Optional[int] = None) -> None:
+                      x: torch.Tensor, y: torch.Tensor, M: int, workspace: Optional[torch.Tensor] = None,
+                      stream: Optional[int] = None) -> None:
     _need(qweight, N * K, "qweight")
     _need(scales, N * (K // group_size) * 2, "scales")
     _need(x, M * K * 2, "x")
     _need(y, M * N * 2, "y")
     d = qail_wdesc(N, K, group_size, QAIL_W8_SYM_GROUP)
+    wsb = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().qail_w8a16_linear(ctypes.byref(d), _ptr(qweight), _ptr(scales), _ptr(x), _ptr(y), M,
-                                   _stream() if stream is None else stream), "qail_w8a16_linear")
+                                   _ptr(workspace), wsb, _stream() if stream is None else stream), "qail_w8a16_linear")
 
 
 def make_w8a16_items(entries: Sequence[dict], M: int):
@@ -434,9 +445,17 @@ def make_w8a16_items(entries: Sequence[dict], M: int):
     return arr
 
 
-def qail_w8a16_linear_batch(items, count: int, M: int, stream: Optional[int] = None) -> None:
-    _check(lib().qail_w8a16_linear_batch(items, count, M, _stream() if stream is None else stream),
-           "qail_w8a16_linear_batch")
+def qail_w8a16_batch_workspace(items, count: int, M: int) -> int:
+    b = ctypes.c_size_t()
+    _check(lib().qail_w8a16_batch_workspace(items, count, M, ctypes.byref(b)), "qail_w8a16_batch_workspace")
+    return b.value
+
+
+def qail_w8a16_linear_batch(items, count: int, M: int, workspace: Optional[torch.Tensor] = None,
+                            stream: Optional[int] = None) -> None:
+    wsb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().qail_w8a16_linear_batch(items, count, M, _ptr(workspace), wsb,
+                                         _stream() if stream is None else stream), "qail_w8a16_linear_batch")
 
 
 def qail_fake_quant_w4(w: torch.Tensor, group_size: int, w_hat: torch.Tensor) -> None:

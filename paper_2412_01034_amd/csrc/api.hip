@@ -493,30 +493,91 @@ int qail_quantize_act_s8(const float* a, size_t n, const float* s_a, uint32_t* a
     return hip_status(launch_act_quant_s8(a, n, s_a, a_s8, static_cast<hipStream_t>(stream)));
 }
 
-int qail_w8a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales, const uint16_t* x,
-                      uint16_t* y, int32_t M, void* stream) {
+namespace {
+
+// Whether an 8-bit weight-only linear at batch M goes to the matrix-core GEMM (M > 1 on the shapes
+// it takes; M = 1 is the streaming kernel's).
+bool w8_takes_gemm(const qail_wdesc& d, int M) { return M > 1 && gemm_f16_supports(d, M); }
+
+qail_w4a16_item as_gemm_item(const qail_w8a16_item& it) {
+    qail_w4a16_item g;
+    g.d = it.d;
+    g.qweight = it.qweight;
+    g.scales = it.scales;
+    g.zeros = nullptr;
+    g.x = it.x;
+    g.y = it.y;
+    return g;
+}
+
+int check_w8_item(const qail_w8a16_item& it, int M) {
+    const int e = check_wdesc(&it.d);
+    if (e != QAIL_OK) return e;
+    if (it.d.scheme != QAIL_W8_SYM_GROUP) return QAIL_ERR_UNSUPPORTED;
+    if ((long long)M * it.d.N > 0x7FFFFFFFll * 64) return QAIL_ERR_UNSUPPORTED;
+    if (!it.qweight || !it.scales || !it.x || !it.y) return QAIL_ERR_NULL;
+    if (!aligned16(it.qweight) || !aligned16(it.scales) || !aligned16(it.x) || !aligned16(it.y)) return QAIL_ERR_ALIGN;
+    return QAIL_OK;
+}
+
+// Workspace of a batch: runs of consecutive items that go to the GEMM share launches, eight at a time.
+size_t w8_batch_need(const qail_w8a16_item* items, int count, int M) {
+    size_t need = 0;
+    int i = 0;
+    while (i < count) {
+        int j = i;
+        qail_w4a16_item run[8];
+        while (j < count && j - i < 8 && w8_takes_gemm(items[j].d, M)) {
+            run[j - i] = as_gemm_item(items[j]);
+            ++j;
+        }
+        if (j > i) {
+            need = std::max(need, gemm_f16_batch_workspace(run, j - i, M));
+            i = j;
+        } else {
+            ++i;
+        }
+    }
+    return need;
+}
+
+}  // namespace
+
+int qail_w8a16_workspace(const qail_wdesc* d, int32_t M, size_t* bytes) {
     const int e = check_wdesc(d);
     if (e != QAIL_OK) return e;
     if (d->scheme != QAIL_W8_SYM_GROUP) return QAIL_ERR_UNSUPPORTED;
     if (M < 1) return QAIL_ERR_SHAPE;
-    if ((long long)M * d->N > 0x7FFFFFFFll * 64) return QAIL_ERR_UNSUPPORTED;
-    if (!qweight || !scales || !x || !y) return QAIL_ERR_NULL;
-    if (!aligned16(qweight) || !aligned16(scales) || !aligned16(x) || !aligned16(y)) return QAIL_ERR_ALIGN;
-    return hip_status(launch_w8a16_linear(*d, qweight, scales, x, y, M, static_cast<hipStream_t>(stream)));
+    if (!bytes) return QAIL_ERR_NULL;
+    *bytes = w8_takes_gemm(*d, M) ? gemm_f16_workspace(*d, M) : 0;
+    return QAIL_OK;
 }
 
-int qail_w8a16_linear_batch(const qail_w8a16_item* items, int32_t count, int32_t M, void* stream) {
+int qail_w8a16_batch_workspace(const qail_w8a16_item* items, int32_t count, int32_t M, size_t* bytes) {
+    if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
+    if (!bytes || (count > 0 && !items)) return QAIL_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const int e = check_wdesc(&items[i].d);
+        if (e != QAIL_OK) return e;
+        if (items[i].d.scheme != QAIL_W8_SYM_GROUP) return QAIL_ERR_UNSUPPORTED;
+    }
+    *bytes = w8_batch_need(items, count, M);
+    return QAIL_OK;
+}
+
+int qail_w8a16_linear_batch(const qail_w8a16_item* items, int32_t count, int32_t M, void* workspace,
+                            size_t workspace_bytes, void* stream) {
     if (count < 0 || M < 1) return QAIL_ERR_SHAPE;
     if (count == 0) return QAIL_OK;
     if (!items) return QAIL_ERR_NULL;
     for (int i = 0; i < count; ++i) {
-        const qail_w8a16_item& it = items[i];
-        const int e = check_wdesc(&it.d);
+        const int e = check_w8_item(items[i], M);
         if (e != QAIL_OK) return e;
-        if (it.d.scheme != QAIL_W8_SYM_GROUP) return QAIL_ERR_UNSUPPORTED;
-        if ((long long)M * it.d.N > 0x7FFFFFFFll * 64) return QAIL_ERR_UNSUPPORTED;
-        if (!it.qweight || !it.scales || !it.x || !it.y) return QAIL_ERR_NULL;
-        if (!aligned16(it.qweight) || !aligned16(it.scales) || !aligned16(it.x) || !aligned16(it.y)) return QAIL_ERR_ALIGN;
+    }
+    const size_t need = w8_batch_need(items, count, M);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return QAIL_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QAIL_ERR_ALIGN;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     int i = 0;
@@ -528,11 +589,33 @@ int qail_w8a16_linear_batch(const qail_w8a16_item* items, int32_t count, int32_t
             i = j;
             continue;
         }
+        qail_w4a16_item run[8];
+        while (j < count && j - i < 8 && w8_takes_gemm(items[j].d, M)) {
+            run[j - i] = as_gemm_item(items[j]);
+            ++j;
+        }
+        if (j > i) {
+            if (launch_w4a16_gemm_f16_batch(run, j - i, M, workspace, st) != hipSuccess) return QAIL_ERR_HIP;
+            i = j;
+            continue;
+        }
         const qail_w8a16_item& it = items[i];
         if (launch_w8a16_linear(it.d, it.qweight, it.scales, it.x, it.y, M, st) != hipSuccess) return QAIL_ERR_HIP;
         ++i;
     }
     return QAIL_OK;
+}
+
+int qail_w8a16_linear(const qail_wdesc* d, const uint32_t* qweight, const uint16_t* scales, const uint16_t* x,
+                      uint16_t* y, int32_t M, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!d) return QAIL_ERR_NULL;
+    qail_w8a16_item it;
+    it.d = *d;
+    it.qweight = qweight;
+    it.scales = scales;
+    it.x = x;
+    it.y = y;
+    return qail_w8a16_linear_batch(&it, 1, M, workspace, workspace_bytes, stream);
 }
 
 int qail_fake_quant_w4(const qail_wdesc* d, const float* w, float* w_hat, void* stream) {

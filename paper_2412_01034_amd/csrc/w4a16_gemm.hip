@@ -23,6 +23,15 @@
 //     are multiplied back in fp32 at the end.  A weight is therefore rounded once to 11
 //     significant bits (the bf16 alternative keeps 8).
 //
+// kBits = 8 is the 8-bit weight-only variant (Sec. 5.4 deploys the backbone with 8-bit weights
+// too): signed bytes, one fp16 scale per group, no zero-point.  A byte q becomes fp16 without a
+// conversion: (q ^ 0x80) is q + 128 as an unsigned byte u, and 0x6400 | u is the fp16 number
+// 1024 + u, so one XOR per word, one byte permute per pair of codes, a packed add of -1152 (exact)
+// and a packed multiply by the scale give (q * s): 14 vector operations per 8 codes.  The codes
+// come out in their natural order, so x is stored in natural order for this variant.  A lane's
+// 64 k of a step are four 16-byte pieces instead of two; with that the ring only fits LDS with
+// 128-column tiles.
+//
 // MFMA operand layout (32x32x16, wave64): lane l supplies row (A) / column (B) l%32 and
 // the 8 consecutive k starting at 8*(l/32); it receives D[8*(r/4) + 4*(l/32) + r%4][l%32]
 // for r = 0..15.  A = activations (rows m), B = weights (columns n).
@@ -62,6 +71,7 @@ struct PrepItem {
 struct PrepBatch {
     PrepItem it[kGemmBatch];
     int M, Mpad;
+    int natural;   // 8-bit codes expand in their natural order, 4-bit ones as 0,4,1,5,2,6,3,7
 };
 
 __global__ __launch_bounds__(256) void gemm_prep_kernel(const PrepBatch args) {
@@ -115,8 +125,10 @@ __global__ __launch_bounds__(256) void gemm_prep_kernel(const PrepBatch args) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
                     h[j] = __builtin_bit_cast(uint16_t, (_Float16)(bf16_bits_to_f32(b[j]) * up));
-                // stored order inside the 8: 0,4,1,5,2,6,3,7
-                o = make_uint4(h[0] | (h[4] << 16), h[1] | (h[5] << 16), h[2] | (h[6] << 16), h[3] | (h[7] << 16));
+                // stored order inside the 8: 0,4,1,5,2,6,3,7 (4-bit codes) or as they are (8-bit codes)
+                o = args.natural
+                        ? make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16))
+                        : make_uint4(h[0] | (h[4] << 16), h[1] | (h[5] << 16), h[2] | (h[6] << 16), h[3] | (h[7] << 16));
             }
             dst[i] = o;
         }
@@ -152,6 +164,20 @@ __device__ __forceinline__ f16x8_t expand_word(uint32_t w, uint32_t magic, f16x2
     const f16x2_t h1 = (p1 * sixteenth + nz6) * s2;
     const f16x2_t h2 = (p2 + nz) * s2;
     const f16x2_t h3 = (p3 * sixteenth + nz6) * s2;
+    return f16x8_t{h0[0], h0[1], h1[0], h1[1], h2[0], h2[1], h3[0], h3[1]};
+}
+
+// 8 signed bytes (two words) -> 8 fp16 q * s in their natural order.
+//   flip = 0x80808080, sixfour = 0x64646464 (in vector registers), off = -1152 in both halves.
+__device__ __forceinline__ f16x8_t expand_bytes(uint32_t w0, uint32_t w1, uint32_t flip, uint32_t sixfour, f16x2_t off,
+                                                f16x2_t s2) {
+    const uint32_t u0 = w0 ^ flip, u1 = w1 ^ flip;
+    // v_perm_b32: bytes 0-3 of the selector pick from {second operand (bytes 0-3), first operand (bytes 4-7)}
+    const f16x2_t p0 = __builtin_bit_cast(f16x2_t, __builtin_amdgcn_perm(sixfour, u0, 0x04010400u));
+    const f16x2_t p1 = __builtin_bit_cast(f16x2_t, __builtin_amdgcn_perm(sixfour, u0, 0x04030402u));
+    const f16x2_t p2 = __builtin_bit_cast(f16x2_t, __builtin_amdgcn_perm(sixfour, u1, 0x04010400u));
+    const f16x2_t p3 = __builtin_bit_cast(f16x2_t, __builtin_amdgcn_perm(sixfour, u1, 0x04030402u));
+    const f16x2_t h0 = (p0 + off) * s2, h1 = (p1 + off) * s2, h2 = (p2 + off) * s2, h3 = (p3 + off) * s2;
     return f16x8_t{h0[0], h0[1], h1[0], h1[1], h2[0], h2[1], h3[0], h3[1]};
 }
 
@@ -233,12 +259,14 @@ constexpr int kStages = 3;
 // s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt untouched.
 __host__ __device__ constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
-template <int MB, int WN>
+template <int MB, int WN, int kBits>
 __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch args) {
     constexpr int kBM = 32 * MB;
     constexpr int kBN = 128 * WN;
     constexpr int kALoads = kBM / 16;             // wave-wide 1 KB loads per wave per step
-    constexpr int kStepLoads = kALoads + 4 * WN;  // all loads a lane issues per step
+    constexpr int kCodeLoads = kBits == 4 ? 2 : 4;               // 16-byte pieces of a lane's 64 codes of a step
+    constexpr int kBParts = kCodeLoads + (kBits == 4 ? 2 : 1);   // ... plus the scale word and (4-bit) the zero word
+    constexpr int kStepLoads = kALoads + kBParts * WN;           // all loads a lane issues per step
     constexpr int kBufBytes = kBM * 256;          // one x tile
     constexpr int kCPitch = kBN * 2 + 16;         // bytes per row of the output staging tile
     extern __shared__ __attribute__((aligned(16))) unsigned char As[];  // [kStages][kBM][256 B]
@@ -253,10 +281,12 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
         if (i < args.count && (int)blockIdx.x >= args.it[i].block_begin) item = i;
     const GemmArgs ga = args.it[item];
     const int bid = (int)blockIdx.x - ga.block_begin, P = ga.P;   // this block among the linear's own
-    const int G = ga.K / ga.g, zwords = (G + 7) / 8, kw = ga.K / 8;
+    const int G = ga.K / ga.g, zwords = (G + 7) / 8, kw = ga.K / (32 / kBits);
 
-    uint32_t magic = 0x64006400u;
+    uint32_t magic = kBits == 4 ? 0x64006400u : 0x64646464u;
     asm volatile("" : "+v"(magic));  // in a VGPR: v_and_or_b32 takes one scalar operand only
+    uint32_t flip = 0x80808080u;
+    asm volatile("" : "+v"(flip));
 
     const long long units = (long long)(ga.tiles - ga.whole) * ga.steps;
     const int unit0 = (int)first_unit(bid, units, P);
@@ -328,7 +358,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
     // The group of a lane's 64 k is tracked without divisions (the group size is a multiple
     // of 64, so they never straddle two groups).
     unsigned char* const Bs = As + kStages * kBufBytes;  // [kStages][4 waves][WN][2560 B]
-    constexpr int kBLane = 2560;                          // 2 x 1024 (codes) + 256 (scale) + 256 (zero)
+    constexpr int kBLane = kCodeLoads * 1024 + 512;       // codes, then 256 (scale) + 256 (zero)
     constexpr int kBStage = 4 * WN * kBLane;
     int lk = ka * kBK + 64 * kb, lgrp = lk / ga.g, lkin = lk - lgrp * ga.g;  // position of the next planned step
     int pstep = ka;
@@ -340,7 +370,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
         const uint32_t grp = v ? (uint32_t)lgrp : 0u;
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
-            pq[j] = qoff[j] + kc / 2;
+            pq[j] = qoff[j] + kc * kBits / 8;
             ps[j] = (soff[j] + grp * 2u) & ~3u;
             pz[j] = zoff[j] + (grp / 8u) * 4u;
         }
@@ -357,17 +387,16 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
         if (i < kALoads) {
             dma16(xbase, xoff0 + i * xstride + pk0b, as_lds + slot * kBufBytes + (i * 256 + wave * 64) * 16);
         } else {
-            const int j = (i - kALoads) / 4, part = (i - kALoads) % 4;
+            const int j = (i - kALoads) / kBParts, part = (i - kALoads) % kBParts;
             const uint32_t dst = as_lds + kStages * kBufBytes + slot * kBStage + (wave * WN + j) * kBLane;
-            if (part == 0) dma16(qbase, pq[j], dst);
-            if (part == 1) dma16(qbase, pq[j] + 16, dst + 1024);
-            if (part == 2) dma4(sbase, ps[j], dst + 2048);
-            if (part == 3) dma4(zbase, pz[j], dst + 2304);
+            if (part < kCodeLoads) dma16(qbase, pq[j] + 16 * part, dst + 1024 * part);
+            if (part == kCodeLoads) dma4(sbase, ps[j], dst + kCodeLoads * 1024);
+            if (part == kCodeLoads + 1) dma4(zbase, pz[j], dst + kCodeLoads * 1024 + 256);
         }
     };
 
     // operands of the step being multiplied; ck / cgrp follow the consumed steps like lk / lgrp
-    uint32_t wq[WN][8];
+    uint32_t wq[WN][4 * kCodeLoads];
     f16x2_t nz[WN], nz6[WN], s2[WN];
     int ck = ka * kBK + 64 * kb, cgrp = ck / ga.g, ckin = ck - cgrp * ga.g;
     auto take = [&](int stage) {
@@ -376,16 +405,17 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const unsigned char* src = Bs + stage * kBStage + (wave * WN + j) * kBLane;
-            const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(src + lane * 16);
-            const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(src + 1024 + lane * 16);
-            const uint32_t sword = *reinterpret_cast<const uint32_t*>(src + 2048 + lane * 4);
-            const uint32_t zword = *reinterpret_cast<const uint32_t*>(src + 2304 + lane * 4);
-            wq[j][0] = lo.x; wq[j][1] = lo.y; wq[j][2] = lo.z; wq[j][3] = lo.w;
-            wq[j][4] = hi.x; wq[j][5] = hi.y; wq[j][6] = hi.z; wq[j][7] = hi.w;
+#pragma unroll
+            for (int pc = 0; pc < kCodeLoads; ++pc) {
+                const u32x4_t v = *reinterpret_cast<const u32x4_t*>(src + pc * 1024 + lane * 16);
+                wq[j][4 * pc] = v.x; wq[j][4 * pc + 1] = v.y; wq[j][4 * pc + 2] = v.z; wq[j][4 * pc + 3] = v.w;
+            }
+            const uint32_t sword = *reinterpret_cast<const uint32_t*>(src + kCodeLoads * 1024 + lane * 4);
+            const uint32_t zword = kBits == 4 ? *reinterpret_cast<const uint32_t*>(src + kCodeLoads * 1024 + 256 + lane * 4) : 0u;
             // the scale's 2 bytes inside the aligned word that was fetched
             const uint32_t sbits = (sword >> (8u * ((soff[j] + grp * 2u) & 2u))) & 0xFFFFu;
             const float sf = (float)__builtin_bit_cast(_Float16, (uint16_t)sbits);
-            const float z = (float)((zword >> (4u * (grp & 7u))) & 0xFu);
+            const float z = kBits == 4 ? (float)((zword >> (4u * (grp & 7u))) & 0xFu) : 128.f;   // bytes: the flip's 128
             const _Float16 srel = v ? (_Float16)(sf * winv[j]) : (_Float16)0.f;
             const _Float16 a = (_Float16)(-1024.f - z), b = (_Float16)(-64.f - z);
             nz[j] = f16x2_t{a, a};
@@ -416,7 +446,12 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
         for (int i = 0; i < MB; ++i)
             af[slot][i] = *reinterpret_cast<const f16x8_t*>(As + stage * kBufBytes + i * (32 * 256) + aoff[jj]);
 #pragma unroll
-        for (int j = 0; j < WN; ++j) bf[slot][j] = expand_word(wq[j][jj], magic, nz[j], nz6[j], s2[j]);
+        for (int j = 0; j < WN; ++j) {
+            if constexpr (kBits == 4)
+                bf[slot][j] = expand_word(wq[j][jj], magic, nz[j], nz6[j], s2[j]);
+            else
+                bf[slot][j] = expand_bytes(wq[j][2 * jj], wq[j][2 * jj + 1], flip, magic, nz[j], s2[j]);
+        }
     };
     auto multiply = [&](int slot) {
 #pragma unroll
@@ -430,7 +465,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
         for (int u = 0; u < MB * WN; ++u) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
-            __builtin_amdgcn_sched_group_barrier(0x002, (13 * WN + MB * WN - 1) / (MB * WN), 0);  // VALU
+            __builtin_amdgcn_sched_group_barrier(0x002, ((kBits == 4 ? 13 : 14) * WN + MB * WN - 1) / (MB * WN), 0);  // VALU
         }
     };
 
@@ -485,7 +520,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
         // part of a tile's K: the raw sums go to this block's slot, tile-shaped [kBM][kBN],
         // through LDS so that they leave as 16-byte pieces of full lines
         constexpr int kPPitch = kBN + 4;  // floats per staged row
-        static_assert(kBM * kPPitch * 4 <= kStages * (kBufBytes + 4 * WN * 2560), "the fp32 tile fits in the ring");
+        static_assert(kBM * kPPitch * 4 <= kStages * (kBufBytes + 4 * WN * kBLane), "the fp32 tile fits in the ring");
         float* const stage = reinterpret_cast<float*>(As) + (4 * kb) * kPPitch + wave * WN * 32 + c;
 #pragma unroll
         for (int j = 0; j < WN; ++j)
@@ -632,15 +667,15 @@ int plan_tiles(GemmArgs& ga, bool split_tail, int cus) {
 }
 
 // One launch for `n` linears that use the same tile, each on its own blocks (ga[i].block_begin, P set).
-template <int MB, int WN>
+template <int MB, int WN, int kBits>
 hipError_t launch_tile(const GemmArgs* gas, int n, hipStream_t st) {
     constexpr int kBM = 32 * MB, kBN = 128 * WN;
-    const size_t lds = (size_t)kStages * (kBM * 256 + 4 * WN * 2560);
+    const size_t lds = (size_t)kStages * (kBM * 256 + 4 * WN * ((kBits == 4 ? 2 : 4) * 1024 + 512));
     // more than 64 KB of LDS needs an opt-in; the call is idempotent, so two host threads that
     // both find the flag clear may both make it
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_gemm_f16_kernel<MB, WN>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_gemm_f16_kernel<MB, WN, kBits>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set.store(true, std::memory_order_release);
@@ -660,7 +695,7 @@ hipError_t launch_tile(const GemmArgs* gas, int n, hipStream_t st) {
         }
     }
     gb.count = n;
-    hipLaunchKernelGGL((w4a16_gemm_f16_kernel<MB, WN>), dim3(grid), dim3(256), lds, st, gb);
+    hipLaunchKernelGGL((w4a16_gemm_f16_kernel<MB, WN, kBits>), dim3(grid), dim3(256), lds, st, gb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (max_tail > 0) {
@@ -673,7 +708,15 @@ hipError_t launch_tile(const GemmArgs* gas, int n, hipStream_t st) {
 // Tile width and the treatment of the last, incomplete round of tiles, for a linear that has
 // `cus` blocks to itself.
 template <int MB>
-void choose_tile(const GemmArgs& ga, int cus, bool alone, int* wn_out, bool* split_out) {
+void choose_tile(const GemmArgs& ga, int cus, bool alone, bool narrow_only, int* wn_out, bool* split_out) {
+    if (narrow_only) {
+        // 8-bit codes: the ring fits LDS only with 128-column tiles.  A round or more of them: the
+        // incomplete last round in K steps when it is short; less than a round: everything in K steps.
+        const int t1 = ((ga.M + 32 * MB - 1) / (32 * MB)) * ((ga.N + 127) / 128);
+        *wn_out = 1;
+        *split_out = t1 < cus ? true : (t1 % cus) * 5 <= cus * 2;
+        return;
+    }
     // Measured on the four linears of a 7B decoder layer at M = 288 and 1024 (256 CUs), one launch each:
     //   * a round or more of wide tiles: wide tiles, and the incomplete last round is dealt in
     //     K steps only when it is short (a fuller one is cheaper left as it is: blocks that
@@ -719,7 +762,8 @@ bool gemm_f16_supports(const qail_wdesc& d, int M) {
     // 32-bit byte offsets inside the kernel
     const unsigned long long lim = 0xFFFFFFFFull;
     const unsigned long long Mpad = (unsigned long long)round_up(M, kRowPad), Kpad = (unsigned long long)round_up(d.K, kBK);
-    return (unsigned long long)d.N * d.K / 2 <= lim && Mpad * Kpad * 2 <= lim && (unsigned long long)M * d.N * 2 <= lim;
+    const unsigned long long code_bytes = (unsigned long long)d.N * d.K / (d.scheme == QAIL_W8_SYM_GROUP ? 1 : 2);
+    return code_bytes <= lim && Mpad * Kpad * 2 <= lim && (unsigned long long)M * d.N * 2 <= lim;
 }
 
 // Workspace of one linear without the slots: x as fp16, the row scales, the weight rows' powers of two.
@@ -730,11 +774,13 @@ static size_t gemm_head_bytes(const qail_wdesc& d, int M) {
 }
 
 // Two tile-shaped fp32 slots per block of the grid for tiles whose K range is shared between blocks.
-static size_t gemm_slot_bytes(int M, bool wide) {
+static size_t gemm_slot_bytes(int M, bool wide) {   // wide: 256-column tiles (4-bit codes with N > 128)
     return 2 * (size_t)gemm_max_blocks() * (size_t)tile_rows(M) * (wide ? 256 : 128) * 4;
 }
 
-size_t gemm_f16_workspace(const qail_wdesc& d, int M) { return gemm_head_bytes(d, M) + gemm_slot_bytes(M, d.N > 128); }
+size_t gemm_f16_workspace(const qail_wdesc& d, int M) {
+    return gemm_head_bytes(d, M) + gemm_slot_bytes(M, d.N > 128 && d.scheme != QAIL_W8_SYM_GROUP);
+}
 
 size_t gemm_f16_batch_workspace(const qail_w4a16_item* items, int count, int M) {
     // linears that share a launch (kGemmBatch at a time) need their heads side by side; the
@@ -745,7 +791,7 @@ size_t gemm_f16_batch_workspace(const qail_w4a16_item* items, int count, int M) 
         bool wide = false;
         for (int i = i0; i < count && i < i0 + kGemmBatch; ++i) {
             b += gemm_head_bytes(items[i].d, M);
-            wide = wide || items[i].d.N > 128;
+            wide = wide || (items[i].d.N > 128 && items[i].d.scheme != QAIL_W8_SYM_GROUP);
         }
         b += gemm_slot_bytes(M, wide);
         if (b > need) need = b;
@@ -755,12 +801,14 @@ size_t gemm_f16_batch_workspace(const qail_w4a16_item* items, int count, int M) 
 
 template <int MB>
 static hipError_t launch_chunk(const qail_w4a16_item* items, int n, int M, void* ws, hipStream_t st) {
+    const bool bytes = items[0].d.scheme == QAIL_W8_SYM_GROUP;   // all items of a call have the same code width
     const int Mpad = round_up(M, kRowPad);
     const int cus = gemm_max_blocks();
     GemmArgs ga[kGemmBatch];
     PrepBatch pb;
     pb.M = M;
     pb.Mpad = Mpad;
+    pb.natural = bytes ? 1 : 0;
     char* at = static_cast<char*>(ws);
     int prep_blocks = 0;
     for (int i = 0; i < n; ++i) {
@@ -805,7 +853,7 @@ static hipError_t launch_chunk(const qail_w4a16_item* items, int n, int M, void*
     int all[kGemmBatch];
     for (int i = 0; i < n; ++i) all[i] = i;
     deal(all, n, std::max(cus, n));
-    for (int i = 0; i < n; ++i) choose_tile<MB>(ga[i], share[i], n == 1, &wn[i], &split[i]);
+    for (int i = 0; i < n; ++i) choose_tile<MB>(ga[i], share[i], n == 1, bytes, &wn[i], &split[i]);
     // linears with the same tile width go out together, each group on the whole chip
     for (int w = 2; w >= 1; --w) {
         int idx[kGemmBatch], m = 0;
@@ -816,7 +864,7 @@ static hipError_t launch_chunk(const qail_w4a16_item* items, int n, int M, void*
             deal(idx, m, std::max(cus, m));
             for (int j = 0; j < m; ++j) {
                 int w2;
-                choose_tile<MB>(ga[idx[j]], share[idx[j]], n == 1, &w2, &split[idx[j]]);
+                choose_tile<MB>(ga[idx[j]], share[idx[j]], n == 1, bytes, &w2, &split[idx[j]]);
             }
         }
         GemmArgs grp[kGemmBatch];
@@ -829,7 +877,8 @@ static hipError_t launch_chunk(const qail_w4a16_item* items, int n, int M, void*
             begin += P;
             grp[j] = g;
         }
-        e = w == 2 ? launch_tile<MB, 2>(grp, m, st) : launch_tile<MB, 1>(grp, m, st);
+        e = bytes ? launch_tile<MB, 1, 8>(grp, m, st)
+                  : (w == 2 ? launch_tile<MB, 2, 4>(grp, m, st) : launch_tile<MB, 1, 4>(grp, m, st));
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

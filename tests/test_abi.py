@@ -118,6 +118,24 @@ def test_argument_errors_are_reported_without_a_gpu(B):
     itb = (B.qail_w4a16_item * 1)(B.qail_w4a16_item(dbig, ok, ok, ok, ok, ok))
     assert L.qail_w4a16_linear_chain(itb, 1, ok, 1 << 20, None) == B.QAIL_ERR_UNSUPPORTED
     assert L.qail_w4a16_chain_workspace(itb, 1, ctypes.byref(szc)) == B.QAIL_ERR_UNSUPPORTED
+    # 8-bit weight-only linear: M > 1 on the matrix cores needs the workspace its query reports
+    d8 = B.qail_wdesc(256, 1024, 128, B.QAIL_W8_SYM_GROUP)
+    sz8 = ctypes.c_size_t(99)
+    assert L.qail_w8a16_workspace(ctypes.byref(d8), 1, ctypes.byref(sz8)) == B.QAIL_OK and sz8.value == 0
+    assert L.qail_w8a16_workspace(ctypes.byref(d8), 40, ctypes.byref(sz8)) == B.QAIL_OK and sz8.value > 0
+    assert L.qail_w8a16_workspace(ctypes.byref(d8), 0, ctypes.byref(sz8)) == B.QAIL_ERR_SHAPE
+    assert L.qail_w8a16_workspace(ctypes.byref(d8), 40, None) == B.QAIL_ERR_NULL
+    assert L.qail_w8a16_workspace(ctypes.byref(d), 40, ctypes.byref(sz8)) == B.QAIL_ERR_UNSUPPORTED   # a 4-bit descriptor
+    assert L.qail_w8a16_linear(ctypes.byref(d8), ok, ok, ok, ok, 40, None, 0, None) == B.QAIL_ERR_WORKSPACE
+    assert L.qail_w8a16_linear(ctypes.byref(d8), ok, ok, ok, ok, 40, odd, 1 << 30, None) == B.QAIL_ERR_ALIGN
+    assert L.qail_w8a16_linear(ctypes.byref(d8), ok, None, ok, ok, 40, ok, 1 << 30, None) == B.QAIL_ERR_NULL
+    assert L.qail_w8a16_linear(ctypes.byref(d8), ok, ok, ok, ok, 0, ok, 1 << 30, None) == B.QAIL_ERR_SHAPE
+    it8 = (B.qail_w8a16_item * 2)(B.qail_w8a16_item(d8, ok, ok, ok, ok), B.qail_w8a16_item(d8, ok, ok, ok, ok))
+    assert L.qail_w8a16_batch_workspace(it8, 2, 40, ctypes.byref(sz8)) == B.QAIL_OK and sz8.value > 0
+    assert L.qail_w8a16_batch_workspace(it8, 2, 1, ctypes.byref(sz8)) == B.QAIL_OK and sz8.value == 0
+    assert L.qail_w8a16_linear_batch(it8, 2, 40, None, 0, None) == B.QAIL_ERR_WORKSPACE
+    assert L.qail_w8a16_linear_batch(it8, 0, 40, None, 0, None) == B.QAIL_OK
+    assert L.qail_w8a16_linear_batch(None, 2, 40, ok, 1 << 30, None) == B.QAIL_ERR_NULL
     szl = ctypes.c_size_t(0)
     assert L.qail_w4a16_lora_workspace(its, lo, 1, 3, ctypes.byref(szl)) == B.QAIL_OK and szl.value == 768
     assert L.qail_w4a16_lora_workspace(its, lo, 1, 3, None) == B.QAIL_ERR_NULL

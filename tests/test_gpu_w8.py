@@ -146,7 +146,13 @@ def test_w8a8_extremes(B):
     assert got[centre, 0] == 128 * 128 * s.K and got[centre, 1] == -128 * 127 * s.K
 
 
-@pytest.mark.parametrize("M", [1, 5])
+def w8_ws(B, N, K, g, M):
+    import torch
+    n = B.qail_w8a16_workspace(N, K, g, M)
+    return torch.empty(n, dtype=torch.uint8, device="cuda") if n else None
+
+
+@pytest.mark.parametrize("M", [1, 5, 16, 40])
 @pytest.mark.parametrize("N,K,g", [(300, 4096, 128), (64, 11008, 128), (33, 256, 32), (7, 40, 8),
                                    (5, 16, 16),            # one stretch of one chunk
                                    (40, 4096, 1024),       # a group is a chunk
@@ -160,7 +166,7 @@ def test_w8a16_linear(B, M, N, K, g):
     xb = synth.llm_activation_bf16(M, K, 51 + N)
     q, s = O.quantize_w8_sym_group(w, g)
     y = torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")
-    B.qail_w8a16_linear(N, K, g, dev(O.pack_bytes(q)), dev(s.view(np.uint16)), dev(xb), y, M)
+    B.qail_w8a16_linear(N, K, g, dev(O.pack_bytes(q)), dev(s.view(np.uint16)), dev(xb), y, M, w8_ws(B, N, K, g, M))
     torch.cuda.synchronize()
     ref = O.w8a16_linear(xb, q, s, g)
     nx = np.sqrt((O.bf16_bits_to_f64(xb) ** 2).sum(axis=1))
@@ -170,12 +176,12 @@ def test_w8a16_linear(B, M, N, K, g):
     assert w4a16_norm_err(host(y, np.uint16).reshape(M, N), ref, nx, nw) <= tol
 
 
-@pytest.mark.parametrize("M", [1, 3])
-def test_w8a16_batch_equals_single_calls(B, M):
+def test_w8a16_batch_equals_single_calls(B):
     """Up to 8 linears share a launch at M = 1, each on its own run of blocks; more than 8 and
     shapes the streaming kernel does not take (K beyond its range) go out on their own.  Rows are
     summed in the same order either way: bit for bit the single calls' results."""
     import torch
+    M = 1
     shapes = [(300, 4096, 128), (64, 11008, 128), (33, 256, 32), (20, 12304, 16), (1000, 2048, 64), (5, 16, 16),
               (40, 4096, 1024), (700, 1024, 128), (18, 12288, 64), (129, 512, 16), (257, 8192, 2048)]
     ents, singles = [], []
@@ -190,6 +196,7 @@ def test_w8a16_batch_equals_single_calls(B, M):
         ents.append(e)
         singles.append(y1)
     items = B.make_w8a16_items(ents, M)
+    assert B.qail_w8a16_batch_workspace(items, len(ents), M) == 0
     B.qail_w8a16_linear_batch(items, len(ents), M)
     B.qail_w8a16_linear_batch(items, 0, M)     # a no-op
     torch.cuda.synchronize()
@@ -197,41 +204,118 @@ def test_w8a16_batch_equals_single_calls(B, M):
         assert np.array_equal(host(e["y"], np.uint16), host(y1, np.uint16))
 
 
-def test_w8a16_full_size_decode_layer_batched_sampled(B):
-    """The four Llama-2-7B linears at full size with 8-bit weights through the batched call, M = 1 (the
-    launch the benchmark times): the GPU quantises the full matrices, the oracle re-derives sampled
-    rows only (rows are independent)."""
+def _w8_norms(xb, q, s, g):
+    nx = np.sqrt((O.bf16_bits_to_f64(xb) ** 2).sum(axis=1))
+    wh = q.astype(np.float64) * np.repeat(s.astype(np.float64), g, axis=1)
+    return nx, np.sqrt((wh ** 2).sum(axis=1))
+
+
+@pytest.mark.parametrize("M", [3, 17, 130])
+def test_w8a16_batch_on_the_matrix_cores(B, M):
+    """M > 1: linears the matrix-core kernel takes share launches (each on a share of the blocks, K
+    dealt in steps), the others (odd scale counts, K not a multiple of 64) go out on their own;
+    all against the oracle."""
+    import torch
+    shapes = [(300, 4096, 128), (64, 11008, 128), (1000, 2048, 64), (96, 1024, 256), (257, 8192, 2048), (520, 192, 64),
+              (33, 256, 32), (20, 12304, 16), (301, 192, 64), (2100, 1024, 128), (40, 8256, 64)]
+    ents, keep = [], []
+    for i, (N, K, g) in enumerate(shapes):
+        w = synth.llm_weight(N, K, 640 + i, outlier_frac=0.01)
+        xb = synth.llm_activation_bf16(M, K, 740 + i, outlier_frac=0.005)
+        q, s = O.quantize_w8_sym_group(w, g)
+        ents.append(dict(N=N, K=K, group_size=g, qweight=dev(O.pack_bytes(q)), scales=dev(s.view(np.uint16)), x=dev(xb),
+                         y=torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")))
+        keep.append((xb, q, s))
+    items = B.make_w8a16_items(ents, M)
+    nws = B.qail_w8a16_batch_workspace(items, len(ents), M)
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    for _ in range(2):     # run-to-run identical
+        B.qail_w8a16_linear_batch(items, len(ents), M, ws)
+        torch.cuda.synchronize()
+        got = [host(e["y"], np.uint16).copy() for e in ents]
+        if _ == 0:
+            first = got
+    for e, (xb, q, s), y, y0 in zip(ents, keep, got, first):
+        assert np.array_equal(y, y0)
+        ref = O.w8a16_linear(xb, q, s, e["group_size"])
+        nx, nw = _w8_norms(xb, q, s, e["group_size"])
+        tol = TOL if e["K"] >= 512 else 2.0 ** -8 * 1.01
+        assert w4a16_norm_err(y.reshape(M, e["N"]), ref, nx, nw) <= tol, (e["N"], e["K"])
+
+
+def test_w8a16_closed_forms_on_the_matrix_cores(B):
+    # all codes c, s = 1, x = 1 -> y = K * c exactly (K * 127 = 130048 = 127 * 2^10 is a bf16 number);
+    # one-hot x reads single weights: q * s rounded to fp16 (exact here: 8-bit q, s a power of two)
+    import torch
+    N, K, g, M = 96, 1024, 128, 40
+    for c in (-128, -1, 1, 127):
+        q = np.full((N, K), c, np.int8)
+        s = np.ones((N, K // g), np.float16)
+        xb = synth.f32_to_bf16_bits(np.ones((M, K), np.float32))
+        y = torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")
+        B.qail_w8a16_linear(N, K, g, dev(O.pack_bytes(q)), dev(s.view(np.uint16)), dev(xb), y, M, w8_ws(B, N, K, g, M))
+        torch.cuda.synchronize()
+        assert np.all(host(y, np.uint16) == synth.f32_to_bf16_bits(np.float32([K * c]))[0]), c
+    rng = np.random.default_rng(5)
+    q = rng.integers(-128, 128, size=(N, K)).astype(np.int8)
+    s = (2.0 ** rng.integers(-6, 3, size=(N, K // g))).astype(np.float16)
+    for k in (0, 5, 63, 64, 127, 128, 1023):
+        x = np.zeros((M, K), np.float32)
+        x[:, k] = 1.0
+        x[M - 1, k] = -2.0
+        y = torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")
+        B.qail_w8a16_linear(N, K, g, dev(O.pack_bytes(q)), dev(s.view(np.uint16)), dev(synth.f32_to_bf16_bits(x)), y, M,
+                            w8_ws(B, N, K, g, M))
+        torch.cuda.synchronize()
+        exp = np.repeat((q[:, k].astype(np.float32) * s[:, k // g].astype(np.float32))[None, :], M, axis=0)
+        exp[M - 1] *= -2.0
+        assert np.array_equal(synth.bf16_bits_to_f32(host(y, np.uint16).reshape(M, N)),
+                              synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(exp))), k
+
+
+@pytest.mark.parametrize("M", [1, 4, 16, 288, 1024])
+def test_w8a16_full_size_layer_batched_sampled(B, M):
+    """The four Llama-2-7B linears at full size with 8-bit weights through the batched call (M = 1:
+    the decode launch the benchmark times; 288 and 1024: its prefill lines): the GPU quantises the
+    full matrices, the oracle re-derives a weight row out of every 16 and checks them against a
+    row of x out of every 16 (every tile of the launch has outputs in the sample)."""
     import torch
     rng = np.random.default_rng(88)
+
+    def strat(n):
+        lo = np.arange(0, n, 16)
+        return np.unique(np.r_[0, lo + rng.integers(0, np.minimum(16, n - lo)), n - 1])
+
     ents, keep = [], []
     for i, (name, N, K) in enumerate(synth.LLAMA7B_LINEARS):
         w = synth.llm_weight(N, K, synth.seed_for(1, i, 0), outlier_frac=0.01)
-        xb = synth.llm_activation_bf16(1, K, synth.seed_for(1, i, 1))
+        xb = synth.llm_activation_bf16(M, K, synth.seed_for(1, i, 1), **({} if M <= 16 else dict(outlier_frac=0.005)))
         qw = torch.zeros(N * K // 4, dtype=torch.int32, device="cuda")
         sc = torch.zeros(N * (K // 128), dtype=torch.int16, device="cuda")
         wd = dev(w)
         B.qail_quantize_weights(wd, 128, B.QAIL_W8_SYM_GROUP, qw, sc, None)
         torch.cuda.synchronize()
         del wd
-        rows = np.sort(rng.choice(N, 64, replace=False))
-        rows[0], rows[-1] = 0, N - 1
+        rows = strat(N)
         ents.append(dict(N=N, K=K, group_size=128, qweight=qw, scales=sc, x=dev(xb),
-                         y=torch.full((N,), 0x7FC0, dtype=torch.int16, device="cuda")))
+                         y=torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")))
         keep.append((w[rows], xb, rows))
         del w
-    items = B.make_w8a16_items(ents, 1)
-    B.qail_w8a16_linear_batch(items, len(ents), 1)
+    items = B.make_w8a16_items(ents, M)
+    nws = B.qail_w8a16_batch_workspace(items, len(ents), M)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+    B.qail_w8a16_linear_batch(items, len(ents), M, ws)
     torch.cuda.synchronize()
+    ms = strat(M)
     worst = 0.0
     for e, (w_rows, xb, rows) in zip(ents, keep):
         N, K = e["N"], e["K"]
         q, s = O.quantize_w8_sym_group(w_rows, 128)
         assert np.array_equal(host(e["qweight"], np.uint32).reshape(N, K // 4)[rows], O.pack_bytes(q))
         assert np.array_equal(host(e["scales"], np.uint16).reshape(N, K // 128)[rows], s.view(np.uint16))
-        y = host(e["y"], np.uint16).reshape(1, N)[:, rows]
-        ref = O.w8a16_linear(xb, q, s, 128)
-        nx = np.sqrt((O.bf16_bits_to_f64(xb) ** 2).sum(axis=1))
-        wh = q.astype(np.float64) * np.repeat(s.astype(np.float64), 128, axis=1)
-        nw = np.sqrt((wh ** 2).sum(axis=1))
+        y = host(e["y"], np.uint16).reshape(M, N)[np.ix_(ms, rows)]
+        ref = O.w8a16_linear(xb[ms], q, s, 128)
+        nx, nw = _w8_norms(xb[ms], q, s, 128)
         worst = max(worst, w4a16_norm_err(y, ref, nx, nw))
     assert worst <= TOL, worst
