@@ -721,6 +721,22 @@ def main():
         extra["cpu_oracle_other_paths"] = cpu
 
     if extra:
+        # what a decoder actually gets, beside the headline (whose four linears share one launch as
+        # independent items): each linear launched alone, and the 32-layer walk with every linear
+        # waiting for the one before it
+        beside = {}
+        if "decode_single_linear" in extra:
+            beside["single_linear_frac_hbm_peak"] = {k: v["frac_hbm_peak"] for k, v in extra["decode_single_linear"].items()}
+        if "decode_stack" in extra:
+            st_ = extra["decode_stack"]
+            beside["decode_stack_tokens_per_s_M1"] = {
+                "one call per layer (independent linears)": st_["M=1"]["tokens_per_s"],
+                "one launch per linear (dependent)": st_["M=1, one launch per linear"]["tokens_per_s"],
+                "chained in one launch per 32 linears (dependent)":
+                    st_["M=1, dependent linears chained in one launch per 32"]["tokens_per_s"],
+                "bound at 8 TB/s": 2378}
+        if beside:
+            result["beside_the_headline"] = beside
         result["extra"] = extra
         log("[bench] extra:", json.dumps(extra))
 
