@@ -32,8 +32,8 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/w4a16_gemv_decode_layer_pmc.txt), and the sha256 of the kernel source the
 # counters were taken on; reported as null once the kernel has changed.
-GEMV_TRAFFIC_BYTES = 106016859
-GEMV_TRAFFIC_SOURCE_SHA256 = "65fc87d13bdf0f422ef6caa9664d41ea77261ca4a8057a5305b4186c661c1335"
+GEMV_TRAFFIC_BYTES = 106021178
+GEMV_TRAFFIC_SOURCE_SHA256 = "46c8a68ba336220dc6951ea77e255a605ea0dc66a533767f30505c97b0f63c86"
 
 HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0     # dense bf16 MFMA, published
