@@ -48,15 +48,19 @@ int check_conv(const qail_conv_desc* d, int bits = 4) {
     if (d->B < 1 || d->H < 1 || d->W < 1 || d->Cin < per_word || d->Cin % per_word != 0 || d->Cout < 1 || d->KH < 1 ||
         d->KW < 1 || d->stride < 1 || d->pad < 0)
         return QAIL_ERR_SHAPE;
-    if (d->H + 2 * d->pad < d->KH || d->W + 2 * d->pad < d->KW) return QAIL_ERR_SHAPE;
-    const long long K = (long long)d->KH * d->KW * d->Cin;
+    // every product below in 64 bits: the fields are only known to be positive 32-bit values
+    const long long ph = (long long)d->H + 2ll * d->pad, pw = (long long)d->W + 2ll * d->pad;
+    if (ph < d->KH || pw < d->KW) return QAIL_ERR_SHAPE;
     // 4-bit: 16 * 8 * 15 * K must fit int32; 8-bit: 128 * 128 * K
-    if (K > (bits == 4 ? 1118480 : 131071)) return QAIL_ERR_UNSUPPORTED;
-    const long long OH = (d->H + 2 * d->pad - d->KH) / d->stride + 1;
-    const long long OW = (d->W + 2 * d->pad - d->KW) / d->stride + 1;
-    const long long M = (long long)d->B * OH * OW;
+    const long long kmax = bits == 4 ? 1118480 : 131071;
+    const long long taps = (long long)d->KH * d->KW;   // < 2^62
+    if (taps > kmax || taps * d->Cin > kmax) return QAIL_ERR_UNSUPPORTED;
+    const long long OH = (ph - d->KH) / d->stride + 1, OW = (pw - d->KW) / d->stride + 1;   // each < 2^33
+    if (OH * OW > 0x7FFFFFFFll) return QAIL_ERR_UNSUPPORTED;
+    const long long M = (long long)d->B * (OH * OW);   // < 2^62
     if (M > 0x7FFFFFFFll / 2 || M / 64 + 1 > 65535) return QAIL_ERR_UNSUPPORTED;
-    if ((long long)d->B * d->H * d->W > 0x7FFFFFFFll) return QAIL_ERR_UNSUPPORTED;
+    if ((long long)d->H * d->W > 0x7FFFFFFFll || (long long)d->B * ((long long)d->H * d->W) > 0x7FFFFFFFll)
+        return QAIL_ERR_UNSUPPORTED;
     return QAIL_OK;
 }
 
