@@ -76,13 +76,15 @@ static_assert(kSmWaves * 256 * 4 <= kXBytes, "the partial tiles reuse the activa
 __host__ __device__ inline void sm_plan(int M, int S, int* rows, int* pass_steps) {
     const int rmin = M == 16 ? 16 : M + 1;
     const int cap = 512 / M;
-    const int smin = min(min(kXBytes / (256 * rmin), cap), S), sodd = min(min(kXBytes / (256 * (rmin | 1)), cap), S);
+    // a pass that is not the whole of K is a multiple of eight steps, so that every pass starts at one
+    auto whole = [&](int steps) { return steps >= S ? S : (steps >= 8 ? steps & ~7 : steps); };
+    const int smin = whole(min(kXBytes / (256 * rmin), cap)), sodd = whole(min(kXBytes / (256 * (rmin | 1)), cap));
     const bool odd = (S + sodd - 1) / sodd <= (S + smin - 1) / smin;
     *rows = odd ? (rmin | 1) : rmin;
     *pass_steps = odd ? sodd : smin;
 }
 
-__global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs args) {
+__global__ __launch_bounds__(kSmThreads) void w4a16_smallm_general_kernel(const SmArgs args) {
     extern __shared__ __attribute__((aligned(16))) unsigned char sm_lds[];
     unsigned char* xl = sm_lds;
     float* xs_tab = reinterpret_cast<float*>(sm_lds + kXBytes);
@@ -279,17 +281,358 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     }
 }
 
+
+// ---- The kernel for group_size 128 (a step is a group) and an even number of groups per row.
+//
+// A block owns up to 32 consecutive tiles.  With more than 16 a wave owns one or two whole tiles
+// and walks all of K for them; with fewer, the block's 16 waves are dealt to (tile, K part) pairs,
+// K parts being whole turns of the ring (eight steps), and the parts' 16 x 16 results meet once,
+// after the stream, in LDS (added in the order of the parts: deterministic).  After the staging
+// of a pass's x there is no barrier: a wave's stream is one ring of loads over its (tile, step)
+// pairs.  The scales and zero-points
+// of eight steps are one 16-byte piece and one word of the lane's row and are fetched once per
+// turn of the ring, with the first load of the turn: fetched per step, as two more load
+// instructions that each touch 16 lines, they cost more than the codes themselves (a bare model
+// of this loop runs at 3.7 TB/s with them and at 5.0 TB/s without).  A tile's steps are padded to
+// a multiple of eight per pass, so slot p of the ring always holds a step whose group is p of
+// the turn's eight; padded steps re-read the last step and are not consumed.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+constexpr int kTilesPerWave = 2;
+
+__global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs args) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char sm_lds[];
+    unsigned char* xl = sm_lds;
+    float* xs_tab = reinterpret_cast<float*>(sm_lds + kXBytes);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int lane = threadIdx.x % kWave;
+    const int li = lane & 15, kb = lane >> 4;
+    const int M = args.M;
+
+    int idx = 0;
+    if (blockIdx.x < (unsigned)kSmMaxBlocks) idx = (args.item_of_block[blockIdx.x / 8] >> (4 * (blockIdx.x % 8))) & 15;
+    idx = __builtin_amdgcn_readfirstlane(idx);
+    const SmItem it = args.it[idx];
+    const int K = it.K, N = it.N;
+    const int G = K / kStepK, zwords = (G + 7) / 8, kw = K / 8, S = G;
+    // the block's tiles, then this wave's: whole tiles (one or two) when the block has more than
+    // 16, else one (tile, K part) pair with as many K parts as the waves and the turns of K allow
+    const int b = (int)blockIdx.x - it.block_begin;
+    const int tile0 = b * it.tiles_base + min(b, it.tiles_rem);
+    const int nt = it.tiles_base + (b < it.tiles_rem ? 1 : 0);   // at most 32 (the launcher sees to it)
+    const int turns = (S + 7) / 8;
+    const int ks = nt > kSmWaves ? 1 : max(1, min(kSmWaves / max(nt, 1), turns));   // K parts per tile; block-uniform
+    int t0, ntw, kpart = 0;
+    if (nt > kSmWaves) {
+        t0 = tile0 + (nt * wave) / kSmWaves;
+        ntw = tile0 + (nt * (wave + 1)) / kSmWaves - t0;           // 1 or 2
+    } else {
+        const int slot = wave / ks;
+        kpart = wave % ks;
+        t0 = tile0 + min(slot, max(nt - 1, 0));
+        ntw = slot < nt ? 1 : 0;
+    }
+    const int my0 = 8 * ((turns * kpart) / ks), my1 = min(S, 8 * ((turns * (kpart + 1)) / ks));   // this wave's steps
+
+    int Mp, pass_steps;
+    sm_plan(M, S, &Mp, &pass_steps);
+    const int step_bytes = 16 * Mp * 16;                       // 16 (j, kb) blocks per step
+    const int npass = (S + pass_steps - 1) / pass_steps;
+    const int xrow = min(li, M) * 16;                          // this lane's row inside a block (li <= 15)
+
+    uint32_t magic = 0x43004300u;    // bf16 pair (128, 128); in a vector register so that the
+    asm volatile("" : "+v"(magic));  // AND-OR needs only one scalar operand
+
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.qw), 0, N * kw * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(it.sc), 0, N * G * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.zr), 0, N * zwords * 4, 0x00020000);
+    // per tile of the wave: lane offsets of its row in the three tensors (rows past N: the last row)
+    uint32_t qlane[kTilesPerWave], slane[kTilesPerWave], zlane[kTilesPerWave];
+#pragma unroll
+    for (int tw = 0; tw < kTilesPerWave; ++tw) {
+        const int row = min((t0 + min(tw, max(ntw - 1, 0))) * 16 + li, N - 1);
+        qlane[tw] = (uint32_t)row * (uint32_t)(kw * 4) + 16u * kb;
+        slane[tw] = (uint32_t)row * (uint32_t)(G * 2);
+        zlane[tw] = (uint32_t)row * (uint32_t)(zwords * 4);
+    }
+
+    f32x4_t acc[kTilesPerWave];
+#pragma unroll
+    for (int tw = 0; tw < kTilesPerWave; ++tw) acc[tw] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    u32x4_t q[kRing];
+    u32x4_t msc = {0u, 0u, 0u, 0u}, nsc = msc;   // scales of the eight steps of the turn being consumed / being fetched
+    uint32_t mzw = 0, nzw = 0;                   // ... their zero-points
+
+    // Staging: 16 neighbouring threads take the 16 pieces (16 bytes each) of one (step, row) pair,
+    // pair p = step * M + row; p / M for p < 4096 is a multiplication.
+    const uint32_t inv_m = (65536u + (uint32_t)M - 1u) / (uint32_t)M;
+    const int tg = threadIdx.x >> 4, t16 = threadIdx.x & 15;
+    const int blk_off = ((t16 & 3) * 4 + (t16 >> 2)) * (Mp * 16);   // block (j, kb) of piece 4 kb + j
+    uint4 xr[8];
+    const char* xbase = reinterpret_cast<const char*>(it.x);   // M * K < 2^31 elements: 32-bit offsets
+
+    for (int pass = 0; pass < npass; ++pass) {
+        const int p0 = pass * pass_steps, p1 = min(S, p0 + pass_steps);   // p0 is a multiple of eight
+        const int k0 = max(my0, p0), k1 = min(my1, p1);                    // this wave's steps in the pass; k0 is a multiple of eight
+        const int psteps = max(0, k1 - k0), upt = (psteps + 7) & ~7;      // steps and ring slots per tile in this pass
+        const int units = ntw * upt;                                       // a multiple of eight
+        const int pairs = (p1 - p0) * M;
+        if (pass) __syncthreads();  // the previous pass's activations are no longer read
+        // ---- the pass's x is requested first, then the first weights of the pass: loads return
+        // in order, x is needed first, and the staging then hides the weights' latency
+        int tg1 = tg;                    // worked out per pass rather than kept in registers
+        asm volatile("" : "+v"(tg1));
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int pi = tg1 + 64 * u;
+            if (pi < pairs) {
+                const int sx = (int)(((uint32_t)pi * inv_m) >> 16), m = pi - sx * M;
+                xr[u] = *reinterpret_cast<const uint4*>(xbase + ((uint32_t)(m * K + (p0 + sx) * kStepK + t16 * 8) * 2u));
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // The ring walks (tile of the wave, step of the pass); both counters are wave-uniform and
+        // advance by one per load / per consumed slot.  Past the last pair the last one is repeated.
+        int itw = 0, is = 0;   // tile and step (relative to p0, may run into the padding) of the next load
+        auto issue = [&](int p) {
+            const int tw = min(itw, max(ntw - 1, 0));
+            const uint32_t step = (uint32_t)(k0 + min(is, psteps - 1));
+            q[p] = __builtin_amdgcn_raw_buffer_load_b128(rq, tw ? qlane[1] : qlane[0], step * (kStepK / 2), 0);
+            if (p == 0) {   // is is a multiple of eight here; the eight groups from p0 + is on
+                nsc = __builtin_amdgcn_raw_buffer_load_b128(rs, tw ? slane[1] : slane[0], (uint32_t)(k0 + is) * 2u, 0);
+                nzw = __builtin_amdgcn_raw_buffer_load_b32(rz, tw ? zlane[1] : zlane[0], (uint32_t)((k0 + is) >> 3) * 4u, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
+            if (itw < ntw) {
+                ++is;
+                if (is == upt) is = 0, ++itw;
+            }
+        };
+        if (units > 0) {
+#pragma unroll
+            for (int p = 0; p < kRing; ++p) issue(p);
+        }
+        // ---- stage x[:, 128 p0 .. 128 p1), its sums over each step, and the zero rows
+        int tg2 = tg;                    // the pairs are worked out again rather than kept in
+        asm volatile("" : "+v"(tg2));    // registers across the loads
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int pi = tg2 + 64 * u;
+            if (pi < pairs) {
+                const int sx = (int)(((uint32_t)pi * inv_m) >> 16), m = pi - sx * M;
+                const uint4 v = xr[u];
+                uint4 o;
+                o.x = (v.x & 0xFFFFu) | (v.z << 16);      // x0,x4
+                o.y = (v.x >> 16) | (v.z & 0xFFFF0000u);  // x1,x5
+                o.z = (v.y & 0xFFFFu) | (v.w << 16);      // x2,x6
+                o.w = (v.y >> 16) | (v.w & 0xFFFF0000u);  // x3,x7
+                *reinterpret_cast<uint4*>(xl + sx * step_bytes + blk_off + m * 16) = o;
+                // the step's sum of this row: 8 values here, then the 16 pieces in a fixed tree
+                const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+                float t = 0.f;
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    t += __builtin_bit_cast(float, w4[q4] << 16) + __builtin_bit_cast(float, w4[q4] & 0xFFFF0000u);
+                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x128, 0xF, 0xF, true));  // row_ror:8
+                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x124, 0xF, 0xF, true));  // row_ror:4
+                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x122, 0xF, 0xF, true));  // row_ror:2
+                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x121, 0xF, 0xF, true));  // row_ror:1
+                if (t16 == 0) xs_tab[sx * 16 + m] = t;
+            }
+        }
+        if (Mp != M)
+            for (int e = threadIdx.x; e < (p1 - p0) * 16; e += kSmThreads)
+                *reinterpret_cast<uint4*>(xl + (e >> 4) * step_bytes + (e & 15) * (Mp * 16) + M * 16) = make_uint4(0, 0, 0, 0);
+        __syncthreads();
+
+        // ---- this wave's (tile, step) pairs of the pass
+        if (units > 0) {
+            int ctw = 0, cs = 0;   // tile and step of the slot being consumed
+            auto consume = [&](int p) {
+                if (cs < psteps) {   // wave-uniform: not a padded slot
+                    const unsigned char* xb = xl + (k0 - p0 + cs) * step_bytes + kb * (Mp * 16) + xrow;
+                    const u32x4_t wq = q[p];
+                    f32x4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint4 a = *reinterpret_cast<const uint4*>(xb + j * 4 * (Mp * 16));
+                        const uint4 bq = make_uint4((wq[j] & 0x000F000Fu) | magic, ((wq[j] >> 4) & 0x000F000Fu) | magic,
+                                                    ((wq[j] >> 8) & 0x000F000Fu) | magic, ((wq[j] >> 12) & 0x000F000Fu) | magic);
+                        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                    __builtin_bit_cast(bf16x8_t, bq), d, 0, 0, 0);
+                    }
+                    // slot p holds the step whose group is p of the turn's eight
+                    const uint16_t sbits = (uint16_t)(msc[p >> 1] >> (16 * (p & 1)));
+                    const float s = (float)__builtin_bit_cast(_Float16, sbits);
+                    const float zc = (float)(128u + ((mzw >> (4 * p)) & 0xFu));
+                    const float4 xs = *reinterpret_cast<const float4*>(xs_tab + (k0 - p0 + cs) * 16 + 4 * kb);
+                    const float r0 = s * fmaf(-zc, xs.x, d[0]), r1 = s * fmaf(-zc, xs.y, d[1]);
+                    const float r2 = s * fmaf(-zc, xs.z, d[2]), r3 = s * fmaf(-zc, xs.w, d[3]);
+                    if (ctw == 0) {   // wave-uniform
+                        acc[0][0] += r0; acc[0][1] += r1; acc[0][2] += r2; acc[0][3] += r3;
+                    } else {
+                        acc[1][0] += r0; acc[1][1] += r1; acc[1][2] += r2; acc[1][3] += r3;
+                    }
+                }
+                ++cs;
+                if (cs == upt) cs = 0, ++ctw;
+            };
+            msc = nsc;   // the first turn's scales and zero-points
+            mzw = nzw;
+            // Refills go out four at a time: the four loads of a row then cover 256 contiguous
+            // bytes and reach DRAM together, instead of 64 isolated bytes from each of 16 rows.
+            for (int u = 0; u + kRing < units; u += kRing) {
+#pragma unroll
+                for (int h = 0; h < kRing; h += 4) {
+#pragma unroll
+                    for (int p = h; p < h + 4; ++p) consume(p);
+#pragma unroll
+                    for (int p = h; p < h + 4; ++p) issue(p);
+                }
+                msc = nsc;
+                mzw = nzw;
+            }
+#pragma unroll
+            for (int p = 0; p < kRing; ++p) consume(p);   // the last turn (units is a multiple of eight)
+        }
+    }
+
+    // ---- y[m][tile * 16 + n]: register i of lane l holds row m = 4 (l / 16) + i, column n = l % 16
+    if (ks > 1) {   // block-uniform: the K parts of a tile meet in LDS, parts in order
+        float* partial = reinterpret_cast<float*>(sm_lds);
+        __syncthreads();  // x is no longer read
+#pragma unroll
+        for (int i = 0; i < 4; ++i) partial[wave * 256 + i * kWave + lane] = acc[0][i];
+        __syncthreads();
+        for (int e = threadIdx.x; e < nt * 256; e += kSmThreads) {
+            const int tl = e >> 8, rem = e & 255;
+            const int m = rem >> 4, nn = rem & 15;   // consecutive threads -> consecutive n
+            const int o = (m & 3) * kWave + (m >> 2) * 16 + nn;
+            float sum = 0.f;
+            for (int kp = 0; kp < ks; ++kp) sum += partial[(tl * ks + kp) * 256 + o];
+            const int rown = (tile0 + tl) * 16 + nn;
+            if (m < M && rown < N) it.y[(size_t)m * N + rown] = f32_to_bf16_rne(sum);
+        }
+        return;
+    }
+#pragma unroll
+    for (int tw = 0; tw < kTilesPerWave; ++tw) {
+        const int n = (t0 + tw) * 16 + li;
+        if (tw < ntw && n < N) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int m = 4 * kb + i;
+                if (m < M) it.y[(size_t)m * N + n] = f32_to_bf16_rne(acc[tw][i]);
+            }
+        }
+    }
+}
+
 size_t sm_item_bytes(const qail_wdesc& d) {
     const size_t G = (size_t)d.K / d.group_size;
     return (size_t)d.N * (d.K / 2 + G * 2 + ((G + 7) / 8) * 4);
 }
 
+// Shapes of the kernel with one group per step: group_size 128 and an even number of groups per row
+// (the eight scales of a turn are fetched as words), tensors below 2 GB (32-bit offsets).
+bool sm_one_group_per_step(const qail_wdesc& d) {
+    return d.group_size == kStepK && (d.K / kStepK) % 2 == 0 && (unsigned long long)d.N * d.K / 2 <= 0x7FFFFFFFull;
+}
+
+// Every item of the list is of that shape: whole tiles per wave, blocks divided by bytes.
+hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int M, hipStream_t st) {
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done.load(std::memory_order_acquire)) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_smallm_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_done.store(true, std::memory_order_release);
+    }
+    SmArgs a;
+    int grid = device_cu_count();
+    if (grid < count) grid = count;
+    // a block's cost: its share of the item's bytes plus x, which every block fetches once
+    int nb[kSmMaxItems], lo[kSmMaxItems], hi[kSmMaxItems];
+    double bytes[kSmMaxItems], fixed[kSmMaxItems];
+    double t_lo = 0, t_hi = 0;
+    for (int i = 0; i < count; ++i) {
+        const int ntiles = (items[i].d.N + 15) / 16;
+        lo[i] = (ntiles + kSmWaves * kTilesPerWave - 1) / (kSmWaves * kTilesPerWave);  // a block owns at most 32 tiles
+        hi[i] = ntiles;
+        bytes[i] = (double)sm_item_bytes(items[i].d);
+        fixed[i] = 2.0 * M * items[i].d.K;
+        if (fixed[i] + bytes[i] > t_hi) t_hi = fixed[i] + bytes[i];
+    }
+    auto blocks_for = [&](double T, int* out) {
+        int used = 0;
+        for (int i = 0; i < count; ++i) {
+            int n = hi[i];
+            if (T > fixed[i]) {
+                const double need = bytes[i] / (T - fixed[i]);
+                n = need >= (double)hi[i] ? hi[i] : (int)need + 1;
+            }
+            if (n < lo[i]) n = lo[i];
+            if (n > hi[i]) n = hi[i];
+            out[i] = n;
+            used += n;
+        }
+        return used;
+    };
+    for (int iter = 0; iter < 40; ++iter) {
+        const double T = 0.5 * (t_lo + t_hi);
+        if (blocks_for(T, nb) <= grid) t_hi = T;
+        else t_lo = T;
+    }
+    int used = blocks_for(t_hi, nb);
+    while (used < grid) {   // left-over blocks go where a block's cost is highest
+        int best = -1;
+        double best_cost = 0;
+        for (int i = 0; i < count; ++i) {
+            const double c = fixed[i] + bytes[i] / nb[i];
+            if (nb[i] < hi[i] && (best < 0 || c > best_cost)) best = i, best_cost = c;
+        }
+        if (best < 0) break;
+        ++nb[best];
+        ++used;
+    }
+    if (count > 1 && used > kSmMaxBlocks) {
+        // the block-to-item table is too short: one launch per item (a lone item needs no table)
+        for (int i = 0; i < count; ++i) {
+            const hipError_t e = sm_launch_tiles_per_wave(items + i, 1, M, st);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    memset(a.item_of_block, 0, sizeof(a.item_of_block));
+    int bb = 0;
+    for (int i = 0; i < count; ++i) {
+        const qail_w4a16_item& s = items[i];
+        SmItem& t = a.it[i];
+        t.qw = s.qweight; t.sc = s.scales; t.zr = s.zeros; t.x = s.x; t.y = s.y;
+        t.N = s.d.N; t.K = s.d.K; t.g = s.d.group_size;
+        t.block_begin = bb;
+        const int ntiles = (s.d.N + 15) / 16;
+        t.tiles_base = ntiles / nb[i];
+        t.tiles_rem = ntiles % nb[i];
+        for (int b = bb; b < bb + nb[i] && b < kSmMaxBlocks; ++b) a.item_of_block[b / 8] |= (uint32_t)i << (4 * (b % 8));
+        bb += nb[i];
+    }
+    for (int i = count; i < kSmMaxItems; ++i) a.it[i] = a.it[count - 1];
+    a.M = M;
+    hipLaunchKernelGGL(w4a16_smallm_kernel, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
+    return hipGetLastError();
+}
+
 hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipStream_t st) {
+    bool one_group = true;
+    for (int i = 0; i < count; ++i) one_group = one_group && sm_one_group_per_step(items[i].d);
+    if (one_group) return sm_launch_tiles_per_wave(items, count, M, st);
     // more than 64 KB of LDS needs an opt-in; the call is idempotent, so two host threads that
     // both find the flag clear may both make it
     static std::atomic<bool> attr_done{false};
     if (!attr_done.load(std::memory_order_acquire)) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_smallm_kernel),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_smallm_general_kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmLdsBytes);
         if (e != hipSuccess) return e;
         attr_done.store(true, std::memory_order_release);
@@ -371,7 +714,7 @@ hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipSt
     }
     for (int i = count; i < kSmMaxItems; ++i) a.it[i] = a.it[count - 1];
     a.M = M;
-    hipLaunchKernelGGL(w4a16_smallm_kernel, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
+    hipLaunchKernelGGL(w4a16_smallm_general_kernel, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
     return hipGetLastError();
 }
 
