@@ -302,7 +302,6 @@ constexpr int kTilesPerWave = 2;
 __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs args) {
     extern __shared__ __attribute__((aligned(16))) unsigned char sm_lds[];
     unsigned char* xl = sm_lds;
-    float* xs_tab = reinterpret_cast<float*>(sm_lds + kXBytes);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
     const int li = lane & 15, kb = lane >> 4;
@@ -341,6 +340,7 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
 
     uint32_t magic = 0x43004300u;    // bf16 pair (128, 128); in a vector register so that the
     asm volatile("" : "+v"(magic));  // AND-OR needs only one scalar operand
+    const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);   // eight bf16 ones
 
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.qw), 0, N * kw * 4, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(it.sc), 0, N * G * 2, 0x00020000);
@@ -363,9 +363,11 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     u32x4_t msc = {0u, 0u, 0u, 0u}, nsc = msc;   // scales of the eight steps of the turn being consumed / being fetched
     uint32_t mzw = 0, nzw = 0;                   // ... their zero-points
 
-    // Staging: 16 neighbouring threads take the 16 pieces (16 bytes each) of one (step, row) pair,
-    // pair p = step * M + row; p / M for p < 4096 is a multiplication.
-    const uint32_t inv_m = (65536u + (uint32_t)M - 1u) / (uint32_t)M;
+    // Staging: 16 neighbouring threads take the 16 pieces (16 bytes each) of one (row, step) pair,
+    // pair p = row * (steps of the pass) + step: neighbouring groups of threads fetch neighbouring
+    // 256-byte stretches of one row of x.  (With the rows of one step side by side, every block of
+    // the grid asks for addresses 2 K bytes apart at the same moment, which one L2 channel serves:
+    // the fetch of x then took 5 us.)  p / steps as a multiplication, exact for p < 2^16.
     const int tg = threadIdx.x >> 4, t16 = threadIdx.x & 15;
     const int blk_off = ((t16 & 3) * 4 + (t16 >> 2)) * (Mp * 16);   // block (j, kb) of piece 4 kb + j
     uint4 xr[8];
@@ -377,18 +379,21 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
         const int psteps = max(0, k1 - k0), upt = (psteps + 7) & ~7;      // steps and ring slots per tile in this pass
         const int units = ntw * upt;                                       // a multiple of eight
         const int pairs = (p1 - p0) * M;
+        // floor(p / ps) = (p * ceil(2^32 / ps)) >> 32 for p < 2^16 (the factor is 2^32 itself for a pass of one step)
+        const uint32_t ps = (uint32_t)(p1 - p0);
+        const uint64_t inv_ps = (((uint64_t)1 << 32) + ps - 1) / ps;
         if (pass) __syncthreads();  // the previous pass's activations are no longer read
         // ---- the pass's x is requested first, then the first weights of the pass: loads return
         // in order, x is needed first, and the staging then hides the weights' latency
         int tg1 = tg;                    // worked out per pass rather than kept in registers
         asm volatile("" : "+v"(tg1));
+        // (every load is issued, a pair past the last one re-reads the last: behind a condition each
+        // load waited for the one before it, and the fetch of x took eight round trips instead of one)
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int pi = tg1 + 64 * u;
-            if (pi < pairs) {
-                const int sx = (int)(((uint32_t)pi * inv_m) >> 16), m = pi - sx * M;
-                xr[u] = *reinterpret_cast<const uint4*>(xbase + ((uint32_t)(m * K + (p0 + sx) * kStepK + t16 * 8) * 2u));
-            }
+            const int pi = min(tg1 + 64 * u, pairs - 1);
+            const int m = (int)(((uint64_t)(uint32_t)pi * inv_ps) >> 32), sx = pi - m * (int)ps;
+            xr[u] = *reinterpret_cast<const uint4*>(xbase + ((uint32_t)(m * K + (p0 + sx) * kStepK + t16 * 8) * 2u));
         }
         __builtin_amdgcn_sched_barrier(0);
 
@@ -413,14 +418,16 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
 #pragma unroll
             for (int p = 0; p < kRing; ++p) issue(p);
         }
-        // ---- stage x[:, 128 p0 .. 128 p1), its sums over each step, and the zero rows
+        // ---- stage x[:, 128 p0 .. 128 p1) and the zero rows (the sums of x over a step that the
+        // offset form needs come from the matrix cores, see below: summed here they tripled the
+        // vector work of the staging, which nothing hides)
         int tg2 = tg;                    // the pairs are worked out again rather than kept in
         asm volatile("" : "+v"(tg2));    // registers across the loads
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int pi = tg2 + 64 * u;
             if (pi < pairs) {
-                const int sx = (int)(((uint32_t)pi * inv_m) >> 16), m = pi - sx * M;
+                const int m = (int)(((uint64_t)(uint32_t)pi * inv_ps) >> 32), sx = pi - m * (int)ps;
                 const uint4 v = xr[u];
                 uint4 o;
                 o.x = (v.x & 0xFFFFu) | (v.z << 16);      // x0,x4
@@ -428,17 +435,6 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
                 o.z = (v.y & 0xFFFFu) | (v.w << 16);      // x2,x6
                 o.w = (v.y >> 16) | (v.w & 0xFFFF0000u);  // x3,x7
                 *reinterpret_cast<uint4*>(xl + sx * step_bytes + blk_off + m * 16) = o;
-                // the step's sum of this row: 8 values here, then the 16 pieces in a fixed tree
-                const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
-                float t = 0.f;
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4)
-                    t += __builtin_bit_cast(float, w4[q4] << 16) + __builtin_bit_cast(float, w4[q4] & 0xFFFF0000u);
-                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x128, 0xF, 0xF, true));  // row_ror:8
-                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x124, 0xF, 0xF, true));  // row_ror:4
-                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x122, 0xF, 0xF, true));  // row_ror:2
-                t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x121, 0xF, 0xF, true));  // row_ror:1
-                if (t16 == 0) xs_tab[sx * 16 + m] = t;
             }
         }
         if (Mp != M)
@@ -453,7 +449,10 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
                 if (cs < psteps) {   // wave-uniform: not a padded slot
                     const unsigned char* xb = xl + (k0 - p0 + cs) * step_bytes + kb * (Mp * 16) + xrow;
                     const u32x4_t wq = q[p];
-                    f32x4_t d = {0.f, 0.f, 0.f, 0.f};
+                    // d = sum_k x (q + 128); xs = sum_k x, the same products against ones: register i of
+                    // every lane then holds the sum of row 4 kb + i of x over the step, which is the row
+                    // of its d[i] (the matrix pipe has the time: it is a tenth busy)
+                    f32x4_t d = {0.f, 0.f, 0.f, 0.f}, xs = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const uint4 a = *reinterpret_cast<const uint4*>(xb + j * 4 * (Mp * 16));
@@ -461,14 +460,15 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
                                                     ((wq[j] >> 8) & 0x000F000Fu) | magic, ((wq[j] >> 12) & 0x000F000Fu) | magic);
                         d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                                     __builtin_bit_cast(bf16x8_t, bq), d, 0, 0, 0);
+                        xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                     __builtin_bit_cast(bf16x8_t, ones), xs, 0, 0, 0);
                     }
                     // slot p holds the step whose group is p of the turn's eight
                     const uint16_t sbits = (uint16_t)(msc[p >> 1] >> (16 * (p & 1)));
                     const float s = (float)__builtin_bit_cast(_Float16, sbits);
                     const float zc = (float)(128u + ((mzw >> (4 * p)) & 0xFu));
-                    const float4 xs = *reinterpret_cast<const float4*>(xs_tab + (k0 - p0 + cs) * 16 + 4 * kb);
-                    const float r0 = s * fmaf(-zc, xs.x, d[0]), r1 = s * fmaf(-zc, xs.y, d[1]);
-                    const float r2 = s * fmaf(-zc, xs.z, d[2]), r3 = s * fmaf(-zc, xs.w, d[3]);
+                    const float r0 = s * fmaf(-zc, xs[0], d[0]), r1 = s * fmaf(-zc, xs[1], d[1]);
+                    const float r2 = s * fmaf(-zc, xs[2], d[2]), r3 = s * fmaf(-zc, xs[3], d[3]);
                     if (ctw == 0) {   // wave-uniform
                         acc[0][0] += r0; acc[0][1] += r1; acc[0][2] += r2; acc[0][3] += r3;
                     } else {
