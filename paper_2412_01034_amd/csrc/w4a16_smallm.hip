@@ -16,11 +16,13 @@
 //   * The activations of the block's linear are staged once in LDS as ready-made A operands
 //     (all of K when M * K * 2 bytes fit in 128 KB, else pass by pass), so a wave can walk any
 //     stretch of K of a tile without holding x in registers and the stream has no barrier.
-//   * A block owns at most 16 tiles.  Its 16 waves are dealt to (tile, K part) pairs, with as many
-//     K parts as the 16 waves allow (16 / tiles); every wave keeps a ring of loads in
-//     flight with exact load waits (unconditional loads, program order = consumption order,
-//     nothing stored while loads fly).  The K parts' 16 x 16 partial results meet once, after the
-//     stream, in LDS and are added in a fixed order (deterministic).
+//   * Two kernels.  Group size 128 with an even number of groups per row (every shape of the
+//     7B model): w4a16_smallm_kernel, whose description stands in front of it.  Other group
+//     sizes: w4a16_smallm_general_kernel, in which a block owns at most 16 tiles, its 16 waves
+//     are dealt to (tile, K part) pairs and every step fetches its own scale and zero-point.
+//     Both keep a ring of loads in flight with exact load waits (unconditional loads, program
+//     order = consumption order, nothing stored while loads fly); K parts' 16 x 16 partial
+//     results meet once, after the stream, in LDS and are added in a fixed order.
 //   * As for M = 1, one launch serves a list of linears, blocks divided by bytes.
 #include <string.h>
 
@@ -173,13 +175,13 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_general_kernel(const 
         // in order, x is needed first, and the staging then hides the weights' latency
         int tg1 = tg;                    // worked out per pass rather than kept in registers
         asm volatile("" : "+v"(tg1));
+        // (every load is issued, a pair past the last one re-reads the last: behind a condition each
+        // load waits for the one before it)
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int pi = tg1 + 64 * u;
-            if (pi < pairs) {
-                const int sx = (int)(((uint32_t)pi * inv_m) >> 16), m = pi - sx * M;
-                xr[u] = *reinterpret_cast<const uint4*>(xbase + ((uint32_t)(m * K + (p0 + sx) * kStepK + t16 * 8) * 2u));
-            }
+            const int pi = min(tg1 + 64 * u, pairs - 1);
+            const int sx = (int)(((uint32_t)pi * inv_m) >> 16), m = pi - sx * M;
+            xr[u] = *reinterpret_cast<const uint4*>(xbase + ((uint32_t)(m * K + (p0 + sx) * kStepK + t16 * 8) * 2u));
         }
         __builtin_amdgcn_sched_barrier(0);
         const int k0 = max(my0, p0), k1 = min(my1, p1);
