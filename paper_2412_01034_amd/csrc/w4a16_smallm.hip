@@ -407,7 +407,9 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
             const uint32_t step = (uint32_t)(k0 + min(is, psteps - 1));
             q[p] = __builtin_amdgcn_raw_buffer_load_b128(rq, tw ? qlane[1] : qlane[0], step * (kStepK / 2), 0);
             if (p == 0) {   // is is a multiple of eight here; the eight groups from p0 + is on
-                nsc = __builtin_amdgcn_raw_buffer_load_b128(rs, tw ? slane[1] : slane[0], (uint32_t)(k0 + is) * 2u, 0);
+                // (the whole offset in the lane part, which is the part the hardware checks against the tensor's
+                // size: the last turn of the last row may reach past the end of the scales, and then reads zeros)
+                nsc = __builtin_amdgcn_raw_buffer_load_b128(rs, (tw ? slane[1] : slane[0]) + (uint32_t)(k0 + is) * 2u, 0, 0);
                 nzw = __builtin_amdgcn_raw_buffer_load_b32(rz, tw ? zlane[1] : zlane[0], (uint32_t)((k0 + is) >> 3) * 4u, 0);
             }
             __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
