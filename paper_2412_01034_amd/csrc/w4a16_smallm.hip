@@ -320,8 +320,11 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     const int b = (int)blockIdx.x - it.block_begin;
     const int tile0 = b * it.tiles_base + min(b, it.tiles_rem);
     const int nt = it.tiles_base + (b < it.tiles_rem ? 1 : 0);   // at most 32 (the launcher sees to it)
-    const int turns = (S + 7) / 8;
-    const int ks = nt > kSmWaves ? 1 : max(1, min(kSmWaves / max(nt, 1), turns));   // K parts per tile; block-uniform
+    int Mp, pass_steps;
+    sm_plan(M, S, &Mp, &pass_steps);
+    // K parts per tile (block-uniform): every pass over K is divided among them in whole turns, so
+    // that all waves of the block work in every pass
+    const int ks = nt > kSmWaves ? 1 : max(1, min(kSmWaves / max(nt, 1), (min(pass_steps, S) + 7) / 8));
     int t0, ntw, kpart = 0;
     if (nt > kSmWaves) {
         t0 = tile0 + (nt * wave) / kSmWaves;
@@ -332,10 +335,7 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
         t0 = tile0 + min(slot, max(nt - 1, 0));
         ntw = slot < nt ? 1 : 0;
     }
-    const int my0 = 8 * ((turns * kpart) / ks), my1 = min(S, 8 * ((turns * (kpart + 1)) / ks));   // this wave's steps
 
-    int Mp, pass_steps;
-    sm_plan(M, S, &Mp, &pass_steps);
     const int step_bytes = 16 * Mp * 16;                       // 16 (j, kb) blocks per step
     const int npass = (S + pass_steps - 1) / pass_steps;
     const int xrow = min(li, M) * 16;                          // this lane's row inside a block (li <= 15)
@@ -377,7 +377,9 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
 
     for (int pass = 0; pass < npass; ++pass) {
         const int p0 = pass * pass_steps, p1 = min(S, p0 + pass_steps);   // p0 is a multiple of eight
-        const int k0 = max(my0, p0), k1 = min(my1, p1);                    // this wave's steps in the pass; k0 is a multiple of eight
+        const int pturns = (p1 - p0 + 7) / 8;
+        const int k0 = p0 + 8 * ((pturns * kpart) / ks);                   // this wave's steps in the pass; k0 is a multiple of eight
+        const int k1 = min(p1, p0 + 8 * ((pturns * (kpart + 1)) / ks));
         const int psteps = max(0, k1 - k0), upt = (psteps + 7) & ~7;      // steps and ring slots per tile in this pass
         const int units = ntw * upt;                                       // a multiple of eight
         const int pairs = (p1 - p0) * M;
@@ -556,16 +558,26 @@ hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int
     SmArgs a;
     int grid = device_cu_count();
     if (grid < count) grid = count;
-    // a block's cost: its share of the item's bytes plus x, which every block fetches once
+    // A block's cost: its share of the item's bytes, plus x, which every block fetches once, plus, per
+    // further pass over K, the bytes it could have streamed while the pass's activations are fetched
+    // and staged (a figure measured on this GPU).  A block owns at most 32 tiles, and at most 16 (one
+    // per wave, the step count of the longest wave halved) where the grid has the blocks for that.
+    constexpr double kPassCost = 100.0 * 1024;
     int nb[kSmMaxItems], lo[kSmMaxItems], hi[kSmMaxItems];
     double bytes[kSmMaxItems], fixed[kSmMaxItems];
     double t_lo = 0, t_hi = 0;
+    int one_tile_per_wave = 0;
+    for (int i = 0; i < count; ++i) one_tile_per_wave += ((items[i].d.N + 15) / 16 + kSmWaves - 1) / kSmWaves;
+    const int most_tiles = one_tile_per_wave <= grid ? kSmWaves : kSmWaves * kTilesPerWave;
     for (int i = 0; i < count; ++i) {
         const int ntiles = (items[i].d.N + 15) / 16;
-        lo[i] = (ntiles + kSmWaves * kTilesPerWave - 1) / (kSmWaves * kTilesPerWave);  // a block owns at most 32 tiles
+        lo[i] = (ntiles + most_tiles - 1) / most_tiles;
         hi[i] = ntiles;
+        int rows, ps;
+        const int S = items[i].d.K / kStepK;
+        sm_plan(M, S, &rows, &ps);
         bytes[i] = (double)sm_item_bytes(items[i].d);
-        fixed[i] = 2.0 * M * items[i].d.K;
+        fixed[i] = 2.0 * M * items[i].d.K + kPassCost * ((S + ps - 1) / ps - 1);
         if (fixed[i] + bytes[i] > t_hi) t_hi = fixed[i] + bytes[i];
     }
     auto blocks_for = [&](double T, int* out) {
