@@ -26,6 +26,7 @@
 //   * As for M = 1, one launch serves a list of linears, blocks divided by bytes.
 #include <string.h>
 
+#include <algorithm>
 #include <atomic>
 
 #include "qail_internal.h"
@@ -57,10 +58,23 @@ struct SmItem {
 
 constexpr int kSmMaxBlocks = 4096;  // blocks of a launch that serves more than one item
 
+// What the kernel with one group per step needs to know about an item's division of labour and
+// would otherwise divide for: worked out on the host (a CU has one scalar unit for its 16 waves,
+// and a dozen integer divisions per wave held the first load back by microseconds).
+struct SmPlan {
+    uint16_t rows, pass_steps, npass, last_steps;   // rows per LDS block; steps of a pass / of the last pass
+    uint32_t inv_steps[2];   // ceil(2^32 / steps) of a full pass [0] and of the last pass [1]: p / steps = mulhi(p, inv) for p < 2^16
+    uint16_t r64[2];         // 64 % steps
+    uint8_t q64[2];          // 64 / steps
+    uint8_t ks[2];           // K parts per tile in a block of tiles_base [0] / tiles_base + 1 [1] tiles
+    uint16_t inv_ks[2];      // ceil(2^12 / ks): v / ks = (v * inv) >> 12 for v <= 256
+};
+
 struct SmArgs {
     SmItem it[kSmMaxItems];
     uint32_t item_of_block[kSmMaxBlocks / 8];  // 4 bits per block; blocks past the table work on item 0
     int M;
+    SmPlan plan[kSmMaxItems];   // read by the kernel with one group per step only
 };
 
 // LDS: [kXBytes] activations (after the stream: [16 waves][256] fp32 partials), [max steps per pass][16]
@@ -313,6 +327,7 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     if (blockIdx.x < (unsigned)kSmMaxBlocks) idx = (args.item_of_block[blockIdx.x / 8] >> (4 * (blockIdx.x % 8))) & 15;
     idx = __builtin_amdgcn_readfirstlane(idx);
     const SmItem it = args.it[idx];
+    const SmPlan pl = args.plan[idx];
     const int K = it.K, N = it.N;
     const int G = K / kStepK, zwords = (G + 7) / 8, kw = K / 8, S = G;
     // the block's tiles, then this wave's: whole tiles (one or two) when the block has more than
@@ -320,29 +335,29 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     const int b = (int)blockIdx.x - it.block_begin;
     const int tile0 = b * it.tiles_base + min(b, it.tiles_rem);
     const int nt = it.tiles_base + (b < it.tiles_rem ? 1 : 0);   // at most 32 (the launcher sees to it)
-    int Mp, pass_steps;
-    sm_plan(M, S, &Mp, &pass_steps);
+    const int Mp = pl.rows, pass_steps = pl.pass_steps, npass = pl.npass;
     // K parts per tile (block-uniform): every pass over K is divided among them in whole turns, so
     // that all waves of the block work in every pass
-    const int ks = nt > kSmWaves ? 1 : max(1, min(kSmWaves / max(nt, 1), (min(pass_steps, S) + 7) / 8));
+    const int ks = b < it.tiles_rem ? pl.ks[1] : pl.ks[0];
+    const int inv_ks = b < it.tiles_rem ? pl.inv_ks[1] : pl.inv_ks[0];
     int t0, ntw, kpart = 0;
     if (nt > kSmWaves) {
         t0 = tile0 + (nt * wave) / kSmWaves;
         ntw = tile0 + (nt * (wave + 1)) / kSmWaves - t0;           // 1 or 2
     } else {
-        const int slot = wave / ks;
-        kpart = wave % ks;
+        const int slot = (wave * inv_ks) >> 12;
+        kpart = wave - slot * ks;
         t0 = tile0 + min(slot, max(nt - 1, 0));
         ntw = slot < nt ? 1 : 0;
     }
 
     const int step_bytes = 16 * Mp * 16;                       // 16 (j, kb) blocks per step
-    const int npass = (S + pass_steps - 1) / pass_steps;
     const int xrow = min(li, M) * 16;                          // this lane's row inside a block (li <= 15)
 
     uint32_t magic = 0x43004300u;    // bf16 pair (128, 128); in a vector register so that the
     asm volatile("" : "+v"(magic));  // AND-OR needs only one scalar operand
-    const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);   // eight bf16 ones
+    uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);   // eight bf16 ones,
+    asm volatile("" : "+v"(ones.x), "+v"(ones.y), "+v"(ones.z), "+v"(ones.w));         // kept in vector registers
 
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.qw), 0, N * kw * 4, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(it.sc), 0, N * G * 2, 0x00020000);
@@ -378,41 +393,59 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     for (int pass = 0; pass < npass; ++pass) {
         const int p0 = pass * pass_steps, p1 = min(S, p0 + pass_steps);   // p0 is a multiple of eight
         const int pturns = (p1 - p0 + 7) / 8;
-        const int k0 = p0 + 8 * ((pturns * kpart) / ks);                   // this wave's steps in the pass; k0 is a multiple of eight
-        const int k1 = min(p1, p0 + 8 * ((pturns * (kpart + 1)) / ks));
+        const int k0 = p0 + 8 * ((pturns * kpart * inv_ks) >> 12);        // this wave's steps in the pass; k0 is a multiple of eight
+        const int k1 = min(p1, p0 + 8 * ((pturns * (kpart + 1) * inv_ks) >> 12));
         const int psteps = max(0, k1 - k0), upt = (psteps + 7) & ~7;      // steps and ring slots per tile in this pass
         const int units = ntw * upt;                                       // a multiple of eight
-        const int pairs = (p1 - p0) * M;
-        // floor(p / ps) = (p * ceil(2^32 / ps)) >> 32 for p < 2^16 (the factor is 2^32 itself for a pass of one step)
-        const uint32_t ps = (uint32_t)(p1 - p0);
-        const uint64_t inv_ps = (((uint64_t)1 << 32) + ps - 1) / ps;
+        // Pair p = row * ps + step of the pass; a thread's pairs are tg + 64 u.  Row and step of the
+        // first come from one multiplication by a reciprocal the host worked out, those of the next
+        // by adding 64 / ps and 64 % ps with a carry: no division and no 32-bit multiplication here.
+        const int last = pass == npass - 1 ? 1 : 0;
+        const int ps = p1 - p0;
+        const int q64 = pl.q64[last], r64 = pl.r64[last];
+        const int m0 = (int)__umulhi((uint32_t)tg, pl.inv_steps[last]);
+        const int sx0 = tg - __mul24(m0, ps);
         if (pass) __syncthreads();  // the previous pass's activations are no longer read
         // ---- the pass's x is requested first, then the first weights of the pass: loads return
         // in order, x is needed first, and the staging then hides the weights' latency
-        int tg1 = tg;                    // worked out per pass rather than kept in registers
-        asm volatile("" : "+v"(tg1));
         // (every load is issued, a pair past the last one re-reads the last: behind a condition each
         // load waited for the one before it, and the fetch of x took eight round trips instead of one)
+        {
+            int m = m0, sx = sx0;
+            asm volatile("" : "+v"(m), "+v"(sx));   // worked out again for the staging rather than kept
+            const uint32_t xlast = (uint32_t)((M - 1) * K + (p1 - 1) * kStepK + t16 * 8) * 2u;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int pi = min(tg1 + 64 * u, pairs - 1);
-            const int m = (int)(((uint64_t)(uint32_t)pi * inv_ps) >> 32), sx = pi - m * (int)ps;
-            xr[u] = *reinterpret_cast<const uint4*>(xbase + ((uint32_t)(m * K + (p0 + sx) * kStepK + t16 * 8) * 2u));
+            for (int u = 0; u < 8; ++u) {
+                const uint32_t off = m < M ? (uint32_t)(__mul24(m, K) + (p0 + sx) * kStepK + t16 * 8) * 2u : xlast;
+                xr[u] = *reinterpret_cast<const uint4*>(xbase + off);
+                m += q64;
+                sx += r64;
+                if (sx >= ps) sx -= ps, ++m;
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
 
         // The ring walks (tile of the wave, step of the pass); both counters are wave-uniform and
         // advance by one per load / per consumed slot.  Past the last pair the last one is repeated.
         int itw = 0, is = 0;   // tile and step (relative to p0, may run into the padding) of the next load
+        // a wave without steps in this pass asks for offsets past the end of every tensor (they fit 2 GB):
+        // the range check answers those with zeros and fetches nothing
+        uint32_t ql[kTilesPerWave], sl[kTilesPerWave], zl[kTilesPerWave];
+#pragma unroll
+        for (int tw = 0; tw < kTilesPerWave; ++tw) {
+            ql[tw] = units > 0 ? qlane[tw] : 0x80000000u;
+            sl[tw] = units > 0 ? slane[tw] : 0x80000000u;
+            zl[tw] = units > 0 ? zlane[tw] : 0x80000000u;
+        }
         auto issue = [&](int p) {
             const int tw = min(itw, max(ntw - 1, 0));
-            const uint32_t step = (uint32_t)(k0 + min(is, psteps - 1));
-            q[p] = __builtin_amdgcn_raw_buffer_load_b128(rq, tw ? qlane[1] : qlane[0], step * (kStepK / 2), 0);
+            const uint32_t step = (uint32_t)max(k0 + min(is, psteps - 1), 0);
+            q[p] = __builtin_amdgcn_raw_buffer_load_b128(rq, tw ? ql[1] : ql[0], step * (kStepK / 2), 0);
             if (p == 0) {   // is is a multiple of eight here; the eight groups from p0 + is on
                 // (the whole offset in the lane part, which is the part the hardware checks against the tensor's
                 // size: the last turn of the last row may reach past the end of the scales, and then reads zeros)
-                nsc = __builtin_amdgcn_raw_buffer_load_b128(rs, (tw ? slane[1] : slane[0]) + (uint32_t)(k0 + is) * 2u, 0, 0);
-                nzw = __builtin_amdgcn_raw_buffer_load_b32(rz, tw ? zlane[1] : zlane[0], (uint32_t)((k0 + is) >> 3) * 4u, 0);
+                nsc = __builtin_amdgcn_raw_buffer_load_b128(rs, (tw ? sl[1] : sl[0]) + (uint32_t)(k0 + is) * 2u, 0, 0);
+                nzw = __builtin_amdgcn_raw_buffer_load_b32(rz, tw ? zl[1] : zl[0], (uint32_t)((k0 + is) >> 3) * 4u, 0);
             }
             __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
             if (itw < ntw) {
@@ -420,28 +453,29 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
                 if (is == upt) is = 0, ++itw;
             }
         };
-        if (units > 0) {
+        // (issued by every wave, whether it has steps in this pass or not: behind a condition the
+        // compiler can no longer count the loads in flight and drains the ring before every use)
 #pragma unroll
-            for (int p = 0; p < kRing; ++p) issue(p);
-        }
+        for (int p = 0; p < kRing; ++p) issue(p);
         // ---- stage x[:, 128 p0 .. 128 p1) and the zero rows (the sums of x over a step that the
         // offset form needs come from the matrix cores, see below: summed here they tripled the
         // vector work of the staging, which nothing hides)
-        int tg2 = tg;                    // the pairs are worked out again rather than kept in
-        asm volatile("" : "+v"(tg2));    // registers across the loads
+        int m = m0, sx = sx0;
+        asm volatile("" : "+v"(m), "+v"(sx));
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int pi = tg2 + 64 * u;
-            if (pi < pairs) {
-                const int m = (int)(((uint64_t)(uint32_t)pi * inv_ps) >> 32), sx = pi - m * (int)ps;
+            if (m < M) {
                 const uint4 v = xr[u];
                 uint4 o;
                 o.x = (v.x & 0xFFFFu) | (v.z << 16);      // x0,x4
                 o.y = (v.x >> 16) | (v.z & 0xFFFF0000u);  // x1,x5
                 o.z = (v.y & 0xFFFFu) | (v.w << 16);      // x2,x6
                 o.w = (v.y >> 16) | (v.w & 0xFFFF0000u);  // x3,x7
-                *reinterpret_cast<uint4*>(xl + sx * step_bytes + blk_off + m * 16) = o;
+                *reinterpret_cast<uint4*>(xl + __mul24(sx, step_bytes) + blk_off + m * 16) = o;
             }
+            m += q64;
+            sx += r64;
+            if (sx >= ps) sx -= ps, ++m;
         }
         if (Mp != M)
             for (int e = threadIdx.x; e < (p1 - p0) * 16; e += kSmThreads)
@@ -473,12 +507,14 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
                     const uint16_t sbits = (uint16_t)(msc[p >> 1] >> (16 * (p & 1)));
                     const float s = (float)__builtin_bit_cast(_Float16, sbits);
                     const float zc = (float)(128u + ((mzw >> (4 * p)) & 0xFu));
-                    const float r0 = s * fmaf(-zc, xs[0], d[0]), r1 = s * fmaf(-zc, xs[1], d[1]);
-                    const float r2 = s * fmaf(-zc, xs[2], d[2]), r3 = s * fmaf(-zc, xs[3], d[3]);
+                    const float r0 = fmaf(-zc, xs[0], d[0]), r1 = fmaf(-zc, xs[1], d[1]);
+                    const float r2 = fmaf(-zc, xs[2], d[2]), r3 = fmaf(-zc, xs[3], d[3]);
                     if (ctw == 0) {   // wave-uniform
-                        acc[0][0] += r0; acc[0][1] += r1; acc[0][2] += r2; acc[0][3] += r3;
+                        acc[0][0] = fmaf(s, r0, acc[0][0]); acc[0][1] = fmaf(s, r1, acc[0][1]);
+                        acc[0][2] = fmaf(s, r2, acc[0][2]); acc[0][3] = fmaf(s, r3, acc[0][3]);
                     } else {
-                        acc[1][0] += r0; acc[1][1] += r1; acc[1][2] += r2; acc[1][3] += r3;
+                        acc[1][0] = fmaf(s, r0, acc[1][0]); acc[1][1] = fmaf(s, r1, acc[1][1]);
+                        acc[1][2] = fmaf(s, r2, acc[1][2]); acc[1][3] = fmaf(s, r3, acc[1][3]);
                     }
                 }
                 ++cs;
@@ -633,8 +669,27 @@ hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int
         t.tiles_rem = ntiles % nb[i];
         for (int b = bb; b < bb + nb[i] && b < kSmMaxBlocks; ++b) a.item_of_block[b / 8] |= (uint32_t)i << (4 * (b % 8));
         bb += nb[i];
+        // the divisions the kernel would otherwise do
+        SmPlan& pl = a.plan[i];
+        int rows, ps;
+        const int S = s.d.K / kStepK;
+        sm_plan(M, S, &rows, &ps);
+        if (ps > S) ps = S;
+        const int npass = (S + ps - 1) / ps, last = S - (npass - 1) * ps;
+        if (ps < 2 || last < 2) return hipErrorInvalidValue;   // cannot happen: S is even, a pass is S or a multiple of eight
+        pl.rows = (uint16_t)rows; pl.pass_steps = (uint16_t)ps; pl.npass = (uint16_t)npass; pl.last_steps = (uint16_t)last;
+        const int steps[2] = {ps, last};
+        for (int v = 0; v < 2; ++v) {
+            pl.inv_steps[v] = (uint32_t)((((uint64_t)1 << 32) + steps[v] - 1) / steps[v]);
+            pl.q64[v] = (uint8_t)(64 / steps[v]);
+            pl.r64[v] = (uint16_t)(64 % steps[v]);
+            const int nt = t.tiles_base + v;
+            const int ks = nt > kSmWaves ? 1 : std::max(1, std::min(kSmWaves / std::max(nt, 1), (ps + 7) / 8));
+            pl.ks[v] = (uint8_t)ks;
+            pl.inv_ks[v] = (uint16_t)((4096 + ks - 1) / ks);
+        }
     }
-    for (int i = count; i < kSmMaxItems; ++i) a.it[i] = a.it[count - 1];
+    for (int i = count; i < kSmMaxItems; ++i) a.it[i] = a.it[count - 1], a.plan[i] = a.plan[count - 1];
     a.M = M;
     hipLaunchKernelGGL(w4a16_smallm_kernel, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
     return hipGetLastError();
