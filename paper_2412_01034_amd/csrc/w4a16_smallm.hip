@@ -424,6 +424,12 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        // With 96 KB of x and more per pass, every wave's x is asked for before any wave's weights
+        // (block-uniform): the CU serves its loads in the order of issue, and the last wave's x,
+        // queued behind the other waves' weights, held the block's first step back (measured:
+        // 0.5-0.9 us of the layer at M = 12 and 16, nothing or a loss below).
+        if (ps * M >= 384) __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
 
         // The ring walks (tile of the wave, step of the pass); both counters are wave-uniform and
         // advance by one per load / per consumed slot.  Past the last pair the last one is repeated.
