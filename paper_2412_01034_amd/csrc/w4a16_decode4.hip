@@ -130,14 +130,16 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
 
     // x first: it is needed first and loads return in order.  Run e = 8 consecutive k of one of
     // four rows (rows past M are zeros); the 4 threads of a quad hold the 4 runs of one stretch.
+    // Run e of row j at position r is bytes 16 e .. 16 e + 15 of x ([M][K], rows back to back), so the
+    // request needs neither j nor r, and runs past row M lie past the end of the buffer and read zeros
+    // without a fetch: every load is issued, no condition and no division stands before it.
     const int row_runs = K / 8;
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(it.x), 0, M * K * 2, 0x00020000);
     uint4 xr[kD4XRuns];
 #pragma unroll
     for (int u = 0; u < kD4XRuns; ++u) {
-        const int e = threadIdx.x + u * kD4Threads;
-        const int j = e / row_runs, r = e - j * row_runs;
-        xr[u] = (j < M) ? reinterpret_cast<const uint4*>(it.x + (size_t)j * K)[r] : make_uint4(0, 0, 0, 0);
-        if ((u + 1) * kD4Threads >= 4 * row_runs) break;  // block-uniform: the rest would be past the fourth row
+        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rx, (threadIdx.x + u * kD4Threads) * 16, 0, 0);
+        xr[u] = make_uint4(v[0], v[1], v[2], v[3]);
     }
     __builtin_amdgcn_sched_barrier(0);  // the scheduler must not move the x loads behind the weights
 
@@ -161,9 +163,14 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
     const int cpg = g < kD4ChunkK ? 1 : g / kD4ChunkK;   // chunks per group
     const int lgrp = g < kD4ChunkK ? (32 * lb) / g : 0;  // lane part of the group index
     const bool tail_out = (nc - 1) * kD4ChunkK + 32 * lb >= K;
-    const int qlane = li * kw * 4 + 16 * lb, qlane_last = tail_out ? li * kw * 4 : qlane;
-    const int slane = li * G * 2 + lgrp * 2, slane_last = tail_out ? li * G * 2 : slane;
-    const int zlane = li * zwords * 4;
+    // (a wave without rows asks for offsets past the end of every tensor, all below 2 GB: the range
+    // check answers with zeros and fetches nothing.  Its loads are issued all the same: with the
+    // ring's first loads behind a condition the compiler can no longer count the loads in flight,
+    // and the staging of x below would wait for the weights as well)
+    const int past = (int)0x80000000u;
+    const int qlane = nqw == 0 ? past : li * kw * 4 + 16 * lb, qlane_last = (tail_out && nqw != 0) ? li * kw * 4 : qlane;
+    const int slane = nqw == 0 ? past : li * G * 2 + lgrp * 2, slane_last = (tail_out && nqw != 0) ? li * G * 2 : slane;
+    const int zlane = nqw == 0 ? past : li * zwords * 4;
     // the zero-point word of group (chunk part + lane part) is the chunk part's word: the lane
     // part stays below 8 and the chunk part is a multiple of gpc (8 or a divisor of 8)
     // (both counts are powers of two: host check)
@@ -192,13 +199,11 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
             qd += last ? 1 : 0;
         }
     };
-    if (total > 0) {
 #pragma unroll
-        for (int p = 0; p < kD4Ring; ++p) {
-            issue(p, iq, ic);
-            advance(iq, ic);
-            __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
-        }
+    for (int p = 0; p < kD4Ring; ++p) {
+        issue(p, iq, ic);
+        advance(iq, ic);
+        __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
     }
 
     // ---- stage x (whole block; one barrier)
@@ -207,7 +212,9 @@ __global__ __launch_bounds__(kD4Threads) void w4a16_decode4_kernel(const D4Args 
         for (int u = 0; u < kD4XRuns; ++u) {
             if (u * kD4Threads >= 4 * row_runs) break;  // block-uniform
             const int e = threadIdx.x + u * kD4Threads;
-            const int j = e / row_runs, r = e - j * row_runs;
+            // e / row_runs, at most 4 here (the rows past the fourth are skipped below)
+            const int j = (e >= row_runs) + (e >= 2 * row_runs) + (e >= 3 * row_runs) + (e >= 4 * row_runs);
+            const int r = e - __mul24(j, row_runs);
             const uint32_t w[4] = {xr[u].x, xr[u].y, xr[u].z, xr[u].w};
             float f[8];
             float amax = 0.f;
