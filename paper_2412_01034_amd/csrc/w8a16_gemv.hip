@@ -92,12 +92,15 @@ __global__ __launch_bounds__(kW8Threads) void w8a16_stream_kernel(const W8Batch 
 
     // x first: it is needed first and loads return in order.  Run r = 8 consecutive k; two
     // neighbouring threads hold the two runs of one stretch.
+    // (Through a buffer descriptor of K elements: runs past K read zeros without a fetch, so every
+    // load is issued and no condition stands before it.)
     const int row_runs = K / 8;
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.x), 0, K * 2, 0x00020000);
     uint4 xr[kW8XRuns];
 #pragma unroll
     for (int u = 0; u < kW8XRuns; ++u) {
-        const int r = threadIdx.x + u * kW8Threads;
-        xr[u] = (r < row_runs) ? reinterpret_cast<const uint4*>(a.x)[r] : make_uint4(0, 0, 0, 0);
+        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rx, (threadIdx.x + u * kW8Threads) * 16, 0, 0);
+        xr[u] = make_uint4(v[0], v[1], v[2], v[3]);
     }
     __builtin_amdgcn_sched_barrier(0);  // the scheduler must not move the x loads behind the weights
 
@@ -121,8 +124,13 @@ __global__ __launch_bounds__(kW8Threads) void w8a16_stream_kernel(const W8Batch 
     const int cpg_shift = __builtin_ctz(cpg), gpc_shift = __builtin_ctz(gpc);
     const int lgrp = g < kW8ChunkK ? (16 * lane) / g : 0;  // lane part of the group index
     const bool tail_out = (nc - 1) * kW8ChunkK + 16 * lane >= K;
-    const int qlane = lane * 16, qlane_last = tail_out ? 0 : qlane;
-    const int slane = lgrp * 2, slane_last = tail_out ? 0 : slane;
+    // (a wave without rows asks for offsets past the end of both tensors, which are below 2 GB: the
+    // range check answers with zeros and fetches nothing.  Its loads are issued all the same: with
+    // the ring's first loads behind a condition the compiler can no longer count the loads in
+    // flight, and the staging of x below would wait for the weights as well)
+    const int past = (int)0x80000000u;
+    const int qlane = nrw == 0 ? past : lane * 16, qlane_last = (tail_out && nrw != 0) ? 0 : qlane;
+    const int slane = nrw == 0 ? past : lgrp * 2, slane_last = (tail_out && nrw != 0) ? 0 : slane;
 
     uint4 q[kW8Ring];
     uint32_t sh[kW8Ring];  // fp16 bits as loaded (zero-extended): a conversion at the load would wait there
@@ -143,13 +151,11 @@ __global__ __launch_bounds__(kW8Threads) void w8a16_stream_kernel(const W8Batch 
         }
     };
     int ir = 0, ic = 0;
-    if (total > 0) {
 #pragma unroll
-        for (int p = 0; p < kW8Ring; ++p) {
-            issue(p, ir, ic);
-            advance(ir, ic);
-            __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
-        }
+    for (int p = 0; p < kW8Ring; ++p) {
+        issue(p, ir, ic);
+        advance(ir, ic);
+        __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
     }
 
     // ---- stage x (whole block; one barrier)
