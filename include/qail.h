@@ -306,7 +306,10 @@ int qail_w8a8_gemm(const qail_conv_desc* d, const uint32_t* a_s8, const uint32_t
 
 /* y[m][n] = sum_k x[m][k] * q[n][k] * s[n][k/g], d of scheme QAIL_W8_SYM_GROUP, x and y bf16,
  * fp32 accumulation, one rounding.  M = 1 runs a bandwidth-bound streaming kernel (K % 16 == 0,
- * group_size % 16 == 0, K + K/g <= 16384).  M > 1 runs on the fp16 matrix cores (the kernel of
+ * group_size % 16 == 0, K + K/g <= 16384).  2 <= M <= 16 at group_size 128 with an even number
+ * of groups per row (N * K below 2 GB) runs the small-batch streaming kernel of
+ * qail_w4a16_linear with byte weights (x and q exact in the products, fp32 accumulation, no
+ * workspace).  Other M > 1 runs on the fp16 matrix cores (the kernel of
  * qail_w4a16_linear for M > 16 with byte codes: K % 64 == 0, group_size % 64 == 0, an even
  * number of scales; (q * s) is rounded once to fp16 before the fp32 accumulation) and needs the
  * workspace the query below reports, 256-byte aligned.  Shapes outside both go to a plain

@@ -500,8 +500,8 @@ int qail_quantize_act_s8(const float* a, size_t n, const float* s_a, uint32_t* a
 namespace {
 
 // Whether an 8-bit weight-only linear at batch M goes to the matrix-core GEMM (M > 1 on the shapes
-// it takes; M = 1 is the streaming kernel's).
-bool w8_takes_gemm(const qail_wdesc& d, int M) { return M > 1 && gemm_f16_supports(d, M); }
+// it takes; M = 1 is the streaming kernel's, 2 <= M <= 16 at group size 128 the small-batch kernel's).
+bool w8_takes_gemm(const qail_wdesc& d, int M) { return M > 1 && !smallm_w8_supports(d, M) && gemm_f16_supports(d, M); }
 
 qail_w4a16_item as_gemm_item(const qail_w8a16_item& it) {
     qail_w4a16_item g;
@@ -594,6 +594,15 @@ int qail_w8a16_linear_batch(const qail_w8a16_item* items, int32_t count, int32_t
             continue;
         }
         qail_w4a16_item run[8];
+        while (j < count && j - i < 8 && smallm_w8_supports(items[j].d, M)) {
+            run[j - i] = as_gemm_item(items[j]);
+            ++j;
+        }
+        if (j > i) {
+            if (launch_w8a16_smallm(run, j - i, M, st) != hipSuccess) return QAIL_ERR_HIP;
+            i = j;
+            continue;
+        }
         while (j < count && j - i < 8 && w8_takes_gemm(items[j].d, M)) {
             run[j - i] = as_gemm_item(items[j]);
             ++j;

@@ -70,6 +70,9 @@ bool decode4_supports(const qail_wdesc& d, int M);
 hipError_t launch_w4a16_decode4(const qail_w4a16_item* items, int count, int M, hipStream_t st);
 bool smallm_supports(const qail_wdesc& d, int M);
 hipError_t launch_w4a16_smallm(const qail_w4a16_item* items, int count, int M, hipStream_t st);
+// 8-bit weights at 2 <= M <= 16 on the same kernel (group size 128); items in the W4A16 record, zeros unused
+bool smallm_w8_supports(const qail_wdesc& d, int M);
+hipError_t launch_w8a16_smallm(const qail_w4a16_item* items, int count, int M, hipStream_t st);
 // Compute units of the current device (256 when none can be asked); the launchers size their grids by it.
 int device_cu_count();
 

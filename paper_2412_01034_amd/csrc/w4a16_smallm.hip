@@ -17,7 +17,7 @@
 //     (all of K when M * K * 2 bytes fit in 128 KB, else pass by pass), so a wave can walk any
 //     stretch of K of a tile without holding x in registers and the stream has no barrier.
 //   * Two kernels.  Group size 128 with an even number of groups per row (every shape of the
-//     7B model): w4a16_smallm_kernel, whose description stands in front of it.  Other group
+//     7B model): smallm_stream_kernel, whose description stands in front of it.  Other group
 //     sizes: w4a16_smallm_general_kernel, in which a block owns at most 16 tiles, its 16 waves
 //     are dealt to (tile, K part) pairs and every step fetches its own scale and zero-point.
 //     Both keep a ring of loads in flight with exact load waits (unconditional loads, program
@@ -315,7 +315,15 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_general_kernel(const 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 constexpr int kTilesPerWave = 2;
 
-__global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs args) {
+// kB8: the weights are signed bytes (symmetric, no zero-points) instead of unsigned nibbles.  A
+// wave-wide load is then 16 rows x 64 k, two steps make a group, and a byte b = q + 128 (one XOR per
+// word) is taken as two nibbles, q = 16 hi + lo - 128: the word goes through the same nibble
+// expansion, its low nibbles into one MFMA chain and its high nibbles into another against the
+// same x, and sum_k x q = 16 d_hi + d_lo - (16 * 128 + 128 + 128) sum_k x.  x stays bf16: nothing
+// is rounded before the fp32 accumulation.
+template <bool kB8>
+__global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs args) {
+    constexpr int kWS = kB8 ? 2 : 1;   // wave-wide loads ("steps" of the ring) per 128 k of x
     extern __shared__ __attribute__((aligned(16))) unsigned char sm_lds[];
     unsigned char* xl = sm_lds;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -329,7 +337,8 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     const SmItem it = args.it[idx];
     const SmPlan pl = args.plan[idx];
     const int K = it.K, N = it.N;
-    const int G = K / kStepK, zwords = (G + 7) / 8, kw = K / 8, S = G;
+    const int G = K / kStepK, zwords = (G + 7) / 8, S = G;
+    const int rowbytes = kB8 ? K : K / 2;
     // the block's tiles, then this wave's: whole tiles (one or two) when the block has more than
     // 16, else one (tile, K part) pair with as many K parts as the waves and the turns of K allow
     const int b = (int)blockIdx.x - it.block_begin;
@@ -359,15 +368,15 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);   // eight bf16 ones,
     asm volatile("" : "+v"(ones.x), "+v"(ones.y), "+v"(ones.z), "+v"(ones.w));         // kept in vector registers
 
-    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.qw), 0, N * kw * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.qw), 0, N * rowbytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(it.sc), 0, N * G * 2, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.zr), 0, N * zwords * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(it.zr), 0, kB8 ? 0 : N * zwords * 4, 0x00020000);
     // per tile of the wave: lane offsets of its row in the three tensors (rows past N: the last row)
     uint32_t qlane[kTilesPerWave], slane[kTilesPerWave], zlane[kTilesPerWave];
 #pragma unroll
     for (int tw = 0; tw < kTilesPerWave; ++tw) {
         const int row = min((t0 + min(tw, max(ntw - 1, 0))) * 16 + li, N - 1);
-        qlane[tw] = (uint32_t)row * (uint32_t)(kw * 4) + 16u * kb;
+        qlane[tw] = (uint32_t)row * (uint32_t)rowbytes + 16u * kb;
         slane[tw] = (uint32_t)row * (uint32_t)(G * 2);
         zlane[tw] = (uint32_t)row * (uint32_t)(zwords * 4);
     }
@@ -386,15 +395,18 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
     // the grid asks for addresses 2 K bytes apart at the same moment, which one L2 channel serves:
     // the fetch of x then took 5 us.)  p / steps as a multiplication, exact for p < 2^16.
     const int tg = threadIdx.x >> 4, t16 = threadIdx.x & 15;
-    const int blk_off = ((t16 & 3) * 4 + (t16 >> 2)) * (Mp * 16);   // block (j, kb) of piece 4 kb + j
+    // piece t16 of a (row, 128 k) pair is k = 8 t16 .. 8 t16 + 7: for nibbles block (j, kb) of piece 4 kb + j,
+    // for bytes block (half, j, kb) of piece 8 half + 2 kb + j (a lane's 16 bytes are 16 k: two MFMAs' worth)
+    const int blk_off = (kB8 ? (t16 >> 3) * 8 + (t16 & 1) * 4 + ((t16 & 7) >> 1) : (t16 & 3) * 4 + (t16 >> 2)) * (Mp * 16);
     uint4 xr[8];
     const char* xbase = reinterpret_cast<const char*>(it.x);   // M * K < 2^31 elements: 32-bit offsets
 
     for (int pass = 0; pass < npass; ++pass) {
         const int p0 = pass * pass_steps, p1 = min(S, p0 + pass_steps);   // p0 is a multiple of eight
-        const int pturns = (p1 - p0 + 7) / 8;
-        const int k0 = p0 + 8 * ((pturns * kpart * inv_ks) >> 12);        // this wave's steps in the pass; k0 is a multiple of eight
-        const int k1 = min(p1, p0 + 8 * ((pturns * (kpart + 1) * inv_ks) >> 12));
+        const int pw0 = p0 * kWS, pw1 = p1 * kWS;                          // the pass in steps of the ring
+        const int pturns = (pw1 - pw0 + 7) / 8;
+        const int k0 = pw0 + 8 * ((pturns * kpart * inv_ks) >> 12);       // this wave's steps in the pass; k0 is a multiple of eight
+        const int k1 = min(pw1, pw0 + 8 * ((pturns * (kpart + 1) * inv_ks) >> 12));
         const int psteps = max(0, k1 - k0), upt = (psteps + 7) & ~7;      // steps and ring slots per tile in this pass
         const int units = ntw * upt;                                       // a multiple of eight
         // Pair p = row * ps + step of the pass; a thread's pairs are tg + 64 u.  Row and step of the
@@ -450,8 +462,15 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
             if (p == 0) {   // is is a multiple of eight here; the eight groups from p0 + is on
                 // (the whole offset in the lane part, which is the part the hardware checks against the tensor's
                 // size: the last turn of the last row may reach past the end of the scales, and then reads zeros)
-                nsc = __builtin_amdgcn_raw_buffer_load_b128(rs, (tw ? sl[1] : sl[0]) + (uint32_t)(k0 + is) * 2u, 0, 0);
-                nzw = __builtin_amdgcn_raw_buffer_load_b32(rz, tw ? zl[1] : zl[0], (uint32_t)((k0 + is) >> 3) * 4u, 0);
+                if constexpr (kB8) {   // four groups a turn
+                    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+                    const u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(rs, (tw ? sl[1] : sl[0]) + (uint32_t)(k0 + is), 0, 0);
+                    nsc[0] = t[0];
+                    nsc[1] = t[1];
+                } else {
+                    nsc = __builtin_amdgcn_raw_buffer_load_b128(rs, (tw ? sl[1] : sl[0]) + (uint32_t)(k0 + is) * 2u, 0, 0);
+                    nzw = __builtin_amdgcn_raw_buffer_load_b32(rz, tw ? zl[1] : zl[0], (uint32_t)((k0 + is) >> 3) * 4u, 0);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);  // program order = consumption order
             if (itw < ntw) {
@@ -473,10 +492,17 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
             if (m < M) {
                 const uint4 v = xr[u];
                 uint4 o;
-                o.x = (v.x & 0xFFFFu) | (v.z << 16);      // x0,x4
-                o.y = (v.x >> 16) | (v.z & 0xFFFF0000u);  // x1,x5
-                o.z = (v.y & 0xFFFFu) | (v.w << 16);      // x2,x6
-                o.w = (v.y >> 16) | (v.w & 0xFFFF0000u);  // x3,x7
+                if constexpr (kB8) {   // the order in which the expansion lays out the bytes of two words
+                    o.x = (v.x & 0xFFFFu) | (v.y << 16);      // x0,x2
+                    o.y = (v.x >> 16) | (v.y & 0xFFFF0000u);  // x1,x3
+                    o.z = (v.z & 0xFFFFu) | (v.w << 16);      // x4,x6
+                    o.w = (v.z >> 16) | (v.w & 0xFFFF0000u);  // x5,x7
+                } else {               // ... the nibbles of one word
+                    o.x = (v.x & 0xFFFFu) | (v.z << 16);      // x0,x4
+                    o.y = (v.x >> 16) | (v.z & 0xFFFF0000u);  // x1,x5
+                    o.z = (v.y & 0xFFFFu) | (v.w << 16);      // x2,x6
+                    o.w = (v.y >> 16) | (v.w & 0xFFFF0000u);  // x3,x7
+                }
                 *reinterpret_cast<uint4*>(xl + __mul24(sx, step_bytes) + blk_off + m * 16) = o;
             }
             m += q64;
@@ -491,7 +517,49 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
         // ---- this wave's (tile, step) pairs of the pass
         if (units > 0) {
             int ctw = 0, cs = 0;   // tile and step of the slot being consumed
-            auto consume = [&](int p) {
+            // bytes: slots p and p + 1 are the two halves of one group (p even; a wave's steps in a pass are an
+            // even number, so both are padding or neither is)
+            auto consume_bytes = [&](int p) {
+                if (cs < psteps) {   // wave-uniform
+                    const unsigned char* xb = xl + ((k0 - pw0 + cs) >> 1) * step_bytes + kb * (Mp * 16) + xrow;
+                    f32x4_t dl = {0.f, 0.f, 0.f, 0.f}, dh = dl, xs = dl;
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf) {
+                        const u32x4_t wq = q[p + hf] ^ 0x80808080u;   // b = q + 128
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const uint4 a = *reinterpret_cast<const uint4*>(xb + (hf * 8 + j * 4) * (Mp * 16));
+                            const uint32_t w0 = wq[2 * j], w1 = wq[2 * j + 1];
+                            const uint4 lo = make_uint4((w0 & 0x000F000Fu) | magic, ((w0 >> 8) & 0x000F000Fu) | magic,
+                                                        (w1 & 0x000F000Fu) | magic, ((w1 >> 8) & 0x000F000Fu) | magic);
+                            const uint4 hi = make_uint4(((w0 >> 4) & 0x000F000Fu) | magic, ((w0 >> 12) & 0x000F000Fu) | magic,
+                                                        ((w1 >> 4) & 0x000F000Fu) | magic, ((w1 >> 12) & 0x000F000Fu) | magic);
+                            dl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                         __builtin_bit_cast(bf16x8_t, lo), dl, 0, 0, 0);
+                            dh = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                         __builtin_bit_cast(bf16x8_t, hi), dh, 0, 0, 0);
+                            xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                         __builtin_bit_cast(bf16x8_t, ones), xs, 0, 0, 0);
+                        }
+                    }
+                    const int g4 = p >> 1;   // the group among the turn's four
+                    const uint16_t sbits = (uint16_t)(msc[g4 >> 1] >> (16 * (g4 & 1)));
+                    const float s = (float)__builtin_bit_cast(_Float16, sbits);
+                    // sum_k x q = 16 dh + dl - (16 * 128 + 128 + 128) sum_k x
+                    const float r0 = fmaf(-2304.f, xs[0], fmaf(16.f, dh[0], dl[0])), r1 = fmaf(-2304.f, xs[1], fmaf(16.f, dh[1], dl[1]));
+                    const float r2 = fmaf(-2304.f, xs[2], fmaf(16.f, dh[2], dl[2])), r3 = fmaf(-2304.f, xs[3], fmaf(16.f, dh[3], dl[3]));
+                    if (ctw == 0) {   // wave-uniform
+                        acc[0][0] = fmaf(s, r0, acc[0][0]); acc[0][1] = fmaf(s, r1, acc[0][1]);
+                        acc[0][2] = fmaf(s, r2, acc[0][2]); acc[0][3] = fmaf(s, r3, acc[0][3]);
+                    } else {
+                        acc[1][0] = fmaf(s, r0, acc[1][0]); acc[1][1] = fmaf(s, r1, acc[1][1]);
+                        acc[1][2] = fmaf(s, r2, acc[1][2]); acc[1][3] = fmaf(s, r3, acc[1][3]);
+                    }
+                }
+                cs += 2;
+                if (cs == upt) cs = 0, ++ctw;
+            };
+            auto consume_nibbles = [&](int p) {
                 if (cs < psteps) {   // wave-uniform: not a padded slot
                     const unsigned char* xb = xl + (k0 - p0 + cs) * step_bytes + kb * (Mp * 16) + xrow;
                     const u32x4_t wq = q[p];
@@ -525,6 +593,13 @@ __global__ __launch_bounds__(kSmThreads) void w4a16_smallm_kernel(const SmArgs a
                 }
                 ++cs;
                 if (cs == upt) cs = 0, ++ctw;
+            };
+            auto consume = [&](int p) {   // slot p; the bytes' two-slot groups are consumed at their second slot
+                if constexpr (kB8) {
+                    if (p & 1) consume_bytes(p - 1);
+                } else {
+                    consume_nibbles(p);
+                }
             };
             msc = nsc;   // the first turn's scales and zero-points
             mzw = nzw;
@@ -589,13 +664,17 @@ bool sm_one_group_per_step(const qail_wdesc& d) {
 }
 
 // Every item of the list is of that shape: whole tiles per wave, blocks divided by bytes.
-hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int M, hipStream_t st) {
-    static std::atomic<bool> attr_done{false};
-    if (!attr_done.load(std::memory_order_acquire)) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_smallm_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmLdsBytes);
+// b8: the items' weights are signed bytes (zeros unused) instead of nibbles.
+hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int M, hipStream_t st, bool b8) {
+    // more than 64 KB of LDS needs an opt-in; the call is idempotent, so two host threads that
+    // both find the flag clear may both make it
+    static std::atomic<bool> attr_done[2];
+    if (!attr_done[b8].load(std::memory_order_acquire)) {
+        const void* f = b8 ? reinterpret_cast<const void*>(&smallm_stream_kernel<true>)
+                           : reinterpret_cast<const void*>(&smallm_stream_kernel<false>);
+        const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmLdsBytes);
         if (e != hipSuccess) return e;
-        attr_done.store(true, std::memory_order_release);
+        attr_done[b8].store(true, std::memory_order_release);
     }
     SmArgs a;
     int grid = device_cu_count();
@@ -618,7 +697,7 @@ hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int
         int rows, ps;
         const int S = items[i].d.K / kStepK;
         sm_plan(M, S, &rows, &ps);
-        bytes[i] = (double)sm_item_bytes(items[i].d);
+        bytes[i] = (double)sm_item_bytes(items[i].d) * (b8 ? 2 : 1);   // (twice the codes; no zero-points, which are a percent)
         fixed[i] = 2.0 * M * items[i].d.K + kPassCost * ((S + ps - 1) / ps - 1);
         if (fixed[i] + bytes[i] > t_hi) t_hi = fixed[i] + bytes[i];
     }
@@ -657,7 +736,7 @@ hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int
     if (count > 1 && used > kSmMaxBlocks) {
         // the block-to-item table is too short: one launch per item (a lone item needs no table)
         for (int i = 0; i < count; ++i) {
-            const hipError_t e = sm_launch_tiles_per_wave(items + i, 1, M, st);
+            const hipError_t e = sm_launch_tiles_per_wave(items + i, 1, M, st, b8);
             if (e != hipSuccess) return e;
         }
         return hipSuccess;
@@ -690,21 +769,23 @@ hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int
             pl.q64[v] = (uint8_t)(64 / steps[v]);
             pl.r64[v] = (uint16_t)(64 % steps[v]);
             const int nt = t.tiles_base + v;
-            const int ks = nt > kSmWaves ? 1 : std::max(1, std::min(kSmWaves / std::max(nt, 1), (ps + 7) / 8));
+            // K parts of a tile: as many as the waves allow, at most the turns of the ring in a full pass
+            const int ks = nt > kSmWaves ? 1 : std::max(1, std::min(kSmWaves / std::max(nt, 1), (ps * (b8 ? 2 : 1) + 7) / 8));
             pl.ks[v] = (uint8_t)ks;
             pl.inv_ks[v] = (uint16_t)((4096 + ks - 1) / ks);
         }
     }
     for (int i = count; i < kSmMaxItems; ++i) a.it[i] = a.it[count - 1], a.plan[i] = a.plan[count - 1];
     a.M = M;
-    hipLaunchKernelGGL(w4a16_smallm_kernel, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
+    if (b8) hipLaunchKernelGGL(smallm_stream_kernel<true>, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
+    else hipLaunchKernelGGL(smallm_stream_kernel<false>, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
     return hipGetLastError();
 }
 
 hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipStream_t st) {
     bool one_group = true;
     for (int i = 0; i < count; ++i) one_group = one_group && sm_one_group_per_step(items[i].d);
-    if (one_group) return sm_launch_tiles_per_wave(items, count, M, st);
+    if (one_group) return sm_launch_tiles_per_wave(items, count, M, st, false);
     // more than 64 KB of LDS needs an opt-in; the call is idempotent, so two host threads that
     // both find the flag clear may both make it
     static std::atomic<bool> attr_done{false};
@@ -801,6 +882,23 @@ bool smallm_supports(const qail_wdesc& d, int M) {
     const int spg = d.group_size / kStepK;
     return M >= 2 && M <= 16 && d.K % kStepK == 0 && d.group_size % kStepK == 0 && (spg & (spg - 1)) == 0 &&
            (unsigned long long)d.N * d.K / 2 <= 0xFFFFFFFFull;   // 32-bit byte offsets in the kernel
+}
+
+// 8-bit weights (signed bytes, one fp16 scale per group, no zero-points) on the kernel with one group
+// per 128 k: group size 128, an even number of groups per row, N * K below 2 GB.
+bool smallm_w8_supports(const qail_wdesc& d, int M) {
+    return M >= 2 && M <= 16 && d.group_size == kStepK && d.K % kStepK == 0 && (d.K / kStepK) % 2 == 0 &&
+           (unsigned long long)d.N * d.K <= 0x7FFFFFFFull;
+}
+
+// items: the 8-bit linears in the W4A16 item record (zeros unused)
+hipError_t launch_w8a16_smallm(const qail_w4a16_item* items, int count, int M, hipStream_t st) {
+    for (int i0 = 0; i0 < count; i0 += kSmMaxItems) {
+        const int c = (count - i0 < kSmMaxItems) ? count - i0 : kSmMaxItems;
+        const hipError_t e = sm_launch_tiles_per_wave(items + i0, c, M, st, true);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_w4a16_smallm(const qail_w4a16_item* items, int count, int M, hipStream_t st) {

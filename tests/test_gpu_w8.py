@@ -274,6 +274,86 @@ def test_w8a16_closed_forms_on_the_matrix_cores(B):
                               synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(exp))), k
 
 
+@pytest.mark.parametrize("M", [2, 3, 4, 7, 8, 13, 16])
+def test_w8a16_small_batch_kernel(B, M):
+    """2 <= M <= 16 at group size 128 with an even number of groups: the small-batch streaming kernel with
+    byte weights (a byte as two nibbles against the same x).  Shapes with one tile, a ragged last
+    tile, more than 32 tiles per block's worth, K in one, two and three passes of the staging, K
+    parts of a tile (few rows, long K); shapes it does not take (odd group count, other group
+    sizes) ride along on the other paths.  Against the oracle and run to run identical; single
+    calls of the first shapes against the oracle as well (the division of K among a tile's waves
+    depends on the blocks an item gets, so they need not equal the batched call bit for bit)."""
+    import torch
+    shapes = [(16, 256, 128), (7, 256, 128), (300, 4096, 128), (64, 11008, 128), (2100, 1024, 128), (4100, 2048, 128),
+              (33, 8192, 128), (8200, 512, 128), (40, 12288, 128), (300, 384, 128), (96, 1024, 256), (33, 256, 32)]
+    ents, keep = [], []
+    for i, (N, K, g) in enumerate(shapes):
+        w = synth.llm_weight(N, K, 1640 + i, outlier_frac=0.01)
+        xb = synth.llm_activation_bf16(M, K, 1740 + i, outlier_frac=0.005)
+        q, s = O.quantize_w8_sym_group(w, g)
+        ents.append(dict(N=N, K=K, group_size=g, qweight=dev(O.pack_bytes(q)), scales=dev(s.view(np.uint16)), x=dev(xb),
+                         y=torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")))
+        keep.append((xb, q, s))
+    items = B.make_w8a16_items(ents, M)
+    nws = B.qail_w8a16_batch_workspace(items, len(ents), M)
+    ws = torch.empty(max(nws, 256), dtype=torch.uint8, device="cuda")
+    for rep in range(2):
+        for e in ents:
+            e["y"].fill_(0x7FC0)
+        B.qail_w8a16_linear_batch(items, len(ents), M, ws)
+        torch.cuda.synchronize()
+        got = [host(e["y"], np.uint16).copy() for e in ents]
+        if rep == 0:
+            first = got
+    for e, (xb, q, s), y, y0 in zip(ents, keep, got, first):
+        assert np.array_equal(y, y0), (e["N"], e["K"])
+        ref = O.w8a16_linear(xb, q, s, e["group_size"])
+        nx, nw = _w8_norms(xb, q, s, e["group_size"])
+        tol = TOL if e["K"] >= 512 else 2.0 ** -8 * 1.01
+        assert w4a16_norm_err(y.reshape(M, e["N"]), ref, nx, nw) <= tol, (e["N"], e["K"])
+    # single calls of the shapes the kernel takes: the same sums in a different division, within the tolerance
+    for e, (xb, q, s) in list(zip(ents, keep))[:4]:
+        y1 = torch.full((M * e["N"],), 0x7FC0, dtype=torch.int16, device="cuda")
+        B.qail_w8a16_linear(e["N"], e["K"], e["group_size"], e["qweight"], e["scales"], e["x"], y1, M,
+                            w8_ws(B, e["N"], e["K"], e["group_size"], M))
+        torch.cuda.synchronize()
+        ref = O.w8a16_linear(xb, q, s, e["group_size"])
+        nx, nw = _w8_norms(xb, q, s, e["group_size"])
+        tol = TOL if e["K"] >= 512 else 2.0 ** -8 * 1.01
+        assert w4a16_norm_err(host(y1, np.uint16).reshape(M, e["N"]), ref, nx, nw) <= tol, (e["N"], e["K"])
+
+
+def test_w8a16_small_batch_kernel_closed_forms(B):
+    """All codes c, s = 1, x = 1 -> y = K * c exactly (every partial sum is an integer below 2^24, K * c a
+    bf16 number for these c); one-hot x reads single weights, q * s exactly (nothing is rounded
+    before the accumulation), at the first and last k of a load, a group, a turn of the ring, a pass."""
+    import torch
+    N, K, g, M = 96, 2048, 128, 5
+    for c in (-128, -1, 1, 127):
+        q = np.full((N, K), c, np.int8)
+        s = np.ones((N, K // g), np.float16)
+        xb = synth.f32_to_bf16_bits(np.ones((M, K), np.float32))
+        y = torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")
+        B.qail_w8a16_linear(N, K, g, dev(O.pack_bytes(q)), dev(s.view(np.uint16)), dev(xb), y, M, w8_ws(B, N, K, g, M))
+        torch.cuda.synchronize()
+        assert np.all(host(y, np.uint16) == synth.f32_to_bf16_bits(np.float32([K * c]))[0]), c
+    rng = np.random.default_rng(6)
+    q = rng.integers(-128, 128, size=(N, K)).astype(np.int8)
+    s = (2.0 ** rng.integers(-6, 3, size=(N, K // g))).astype(np.float16)
+    for k in (0, 1, 7, 8, 15, 16, 63, 64, 127, 128, 511, 512, 1023, 1024, 2047):
+        x = np.zeros((M, K), np.float32)
+        x[:, k] = 1.0
+        x[M - 1, k] = -2.0
+        y = torch.full((M * N,), 0x7FC0, dtype=torch.int16, device="cuda")
+        B.qail_w8a16_linear(N, K, g, dev(O.pack_bytes(q)), dev(s.view(np.uint16)), dev(synth.f32_to_bf16_bits(x)), y, M,
+                            w8_ws(B, N, K, g, M))
+        torch.cuda.synchronize()
+        exp = np.repeat((q[:, k].astype(np.float32) * s[:, k // g].astype(np.float32))[None, :], M, axis=0)
+        exp[M - 1] *= -2.0
+        assert np.array_equal(synth.bf16_bits_to_f32(host(y, np.uint16).reshape(M, N)),
+                              synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(exp))), k
+
+
 @pytest.mark.parametrize("M", [1, 4, 16, 288, 1024])
 def test_w8a16_full_size_layer_batched_sampled(B, M):
     """The four Llama-2-7B linears at full size with 8-bit weights through the batched call (M = 1:
