@@ -545,13 +545,22 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
     float wm[WN];
 #pragma unroll
     for (int j = 0; j < WN; ++j) wm[j] = ga.wmul[min(bn + (wave * WN + j) * 32 + c, ga.N - 1)];
+    // the row factors of the lane's 16 MB rows, four neighbouring rows per load, all requested before
+    // the first is used (fetched where they are used, each load waited for the one before it: 4 MB
+    // round trips per tile)
+    f32x4_t rsv[MB][4];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd)
+            rsv[i][qd] = *reinterpret_cast<const f32x4_t*>(ga.rscale + bm + i * 32 + 8 * qd + 4 * kb);
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
             // registers r and r + 1 are two neighbouring rows of the lane's column
             const int row = i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
-            const float rs0 = ga.rscale[bm + row], rs1 = ga.rscale[bm + row + 1];
+            const float rs0 = rsv[i][r / 4][r % 4], rs1 = rsv[i][r / 4][r % 4 + 1];
 #pragma unroll
             for (int j = 0; j < WN; ++j) {
                 const int col = (wave * WN + j) * 32 + c;
