@@ -292,9 +292,9 @@ def main():
         # with the default --layers 32 every layer has its own seeded weights (3.36 GB per token-step)
         stack = {}
         stack_bytes_w = 32 * sum(linear_bytes(N, K, 0) for _, N, K in shapes)
-        for M in (1, 4, 16, 64):
+        for M in (1, 4, 16, 32, 64):
             io = dec if M == 1 else with_io(M)
-            nws = B.qail_w4a16_batch_workspace(io[0][0], 4, M)   # M > 16: the matrix-core GEMM's
+            nws = B.qail_w4a16_batch_workspace(io[0][0], 4, M)   # M > 32: the matrix-core GEMM's
             wsk = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
 
             def walk():

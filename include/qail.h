@@ -139,7 +139,8 @@ int qail_quantize_act_u4(const float* a, size_t n, const float* s_a, uint32_t* a
  * the memory-bound stage, prefill the compute-heavy one). */
 
 /* Bytes of device scratch the call below needs for this (d, M).  0 for the streaming
- * kernels (M <= 16 on shapes they take); for the matrix-core GEMM it holds an fp16 copy
+ * kernels (M <= 16 on shapes they take, M <= 32 at group_size 128 with an even number of
+ * groups per row); for the matrix-core GEMM it holds an fp16 copy
  * of x (rows padded to a multiple of 128, K to a multiple of 128), one float per padded
  * row and per output column, and two tile-shaped fp32 slots per block of the grid (one
  * block per compute unit) for output tiles whose K range is shared between blocks (tens
@@ -151,7 +152,8 @@ int qail_w4a16_workspace(const qail_wdesc* d, int32_t M, size_t* bytes);
 /* d must be ASYM_GROUP.  x: bf16 [M][K]; y: bf16 [M][N].  Products are accumulated
  * in fp32 and rounded once to bf16 (nearest even).  M = 1 (decode) is served by a
  * bandwidth-bound streaming kernel, 2 <= M <= 4 by the same stream with four rows of x,
- * up to M = 16 by a weight-streaming MFMA kernel,
+ * up to M = 16 (M = 32 at group_size 128 with an even number of groups per row) by a
+ * weight-streaming MFMA kernel (x and codes exact in the products),
  * larger M (prefill) by an fp16 MFMA kernel that expands the codes in registers
  * ((q - z) * s rounded once to fp16, x rescaled per row by a power of two).
  * workspace may be NULL when the query returns 0; otherwise a missing or short one
@@ -306,7 +308,7 @@ int qail_w8a8_gemm(const qail_conv_desc* d, const uint32_t* a_s8, const uint32_t
 
 /* y[m][n] = sum_k x[m][k] * q[n][k] * s[n][k/g], d of scheme QAIL_W8_SYM_GROUP, x and y bf16,
  * fp32 accumulation, one rounding.  M = 1 runs a bandwidth-bound streaming kernel (K % 16 == 0,
- * group_size % 16 == 0, K + K/g <= 16384).  2 <= M <= 16 at group_size 128 with an even number
+ * group_size % 16 == 0, K + K/g <= 16384).  2 <= M <= 32 at group_size 128 with an even number
  * of groups per row (N * K below 2 GB) runs the small-batch streaming kernel of
  * qail_w4a16_linear with byte weights (x and q exact in the products, fp32 accumulation, no
  * workspace).  Other M > 1 runs on the fp16 matrix cores (the kernel of

@@ -81,7 +81,7 @@ struct SmArgs {
 // fp32 step sums.
 constexpr int kMaxPassSteps = kXBytes / (16 * 3 * 16) + 6;  // M >= 2 (3 rows per block): steps per pass, rounded up
 constexpr size_t kSmLdsBytes = (size_t)kXBytes + (size_t)kMaxPassSteps * 16 * 4;
-static_assert(kSmWaves * 256 * 4 <= kXBytes, "the partial tiles reuse the activations' space");
+static_assert(kSmWaves * 2 * 256 * 4 <= kXBytes, "the partial tiles (two row blocks) reuse the activations' space");
 
 // Rows per LDS block and 128-k steps per pass over K for a batch of M rows and S steps in all.
 // Rows beyond M read a row of zeros appended to every block (M = 16 needs none).  A block holds
@@ -90,7 +90,7 @@ static_assert(kSmWaves * 256 * 4 <= kXBytes, "the partial tiles reuse the activa
 // banks -- unless that costs a pass more over K.  A pass is at most 512 (row, step) pairs, so
 // that its x travels through 8 registers per thread.
 __host__ __device__ inline void sm_plan(int M, int S, int* rows, int* pass_steps) {
-    const int rmin = M == 16 ? 16 : M + 1;
+    const int rmin = M % 16 == 0 ? M : M + 1;
     const int cap = 512 / M;
     // a pass that is not the whole of K is a multiple of eight steps, so that every pass starts at one
     auto whole = [&](int steps) { return steps >= S ? S : (steps >= 8 ? steps & ~7 : steps); };
@@ -321,9 +321,12 @@ constexpr int kTilesPerWave = 2;
 // expansion, its low nibbles into one MFMA chain and its high nibbles into another against the
 // same x, and sum_k x q = 16 d_hi + d_lo - (16 * 128 + 128 + 128) sum_k x.  x stays bf16: nothing
 // is rounded before the fp32 accumulation.
-template <bool kB8>
+// kRB: blocks of 16 rows of x (M <= 16 kRB).  With two, every expanded operand feeds two MFMAs (rows
+// 0-15 and 16-31 of x) and a wave owns one tile (the launcher gives a block at most 16).
+template <bool kB8, int kRB>
 __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs args) {
     constexpr int kWS = kB8 ? 2 : 1;   // wave-wide loads ("steps" of the ring) per 128 k of x
+    constexpr int kTPW = kRB == 1 ? kTilesPerWave : 1;   // tiles a wave can own
     extern __shared__ __attribute__((aligned(16))) unsigned char sm_lds[];
     unsigned char* xl = sm_lds;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -361,7 +364,9 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
     }
 
     const int step_bytes = 16 * Mp * 16;                       // 16 (j, kb) blocks per step
-    const int xrow = min(li, M) * 16;                          // this lane's row inside a block (li <= 15)
+    int xrow[kRB];                                             // this lane's rows inside a block (past M: the row of zeros)
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) xrow[rb] = min(16 * rb + li, M) * 16;
 
     uint32_t magic = 0x43004300u;    // bf16 pair (128, 128); in a vector register so that the
     asm volatile("" : "+v"(magic));  // AND-OR needs only one scalar operand
@@ -381,9 +386,21 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
         zlane[tw] = (uint32_t)row * (uint32_t)(zwords * 4);
     }
 
-    f32x4_t acc[kTilesPerWave];
+    f32x4_t acc[kTPW][kRB];
 #pragma unroll
-    for (int tw = 0; tw < kTilesPerWave; ++tw) acc[tw] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int tw = 0; tw < kTPW; ++tw)
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) acc[tw][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    // acc[tile of the wave][row block] += s * r
+    auto add_scaled = [&](int ctw, int rb, float s, const f32x4_t& r) {
+        if (kTPW == 1 || ctw == 0) {   // wave-uniform
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[0][rb][i] = fmaf(s, r[i], acc[0][rb][i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[kTPW - 1][rb][i] = fmaf(s, r[i], acc[kTPW - 1][rb][i]);
+        }
+    };
 
     u32x4_t q[kRing];
     u32x4_t msc = {0u, 0u, 0u, 0u}, nsc = msc;   // scales of the eight steps of the turn being consumed / being fetched
@@ -521,39 +538,42 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
             // even number, so both are padding or neither is)
             auto consume_bytes = [&](int p) {
                 if (cs < psteps) {   // wave-uniform
-                    const unsigned char* xb = xl + ((k0 - pw0 + cs) >> 1) * step_bytes + kb * (Mp * 16) + xrow;
-                    f32x4_t dl = {0.f, 0.f, 0.f, 0.f}, dh = dl, xs = dl;
+                    const unsigned char* xb = xl + ((k0 - pw0 + cs) >> 1) * step_bytes + kb * (Mp * 16);
+                    f32x4_t dl[kRB], dh[kRB], xs[kRB];
+#pragma unroll
+                    for (int rb = 0; rb < kRB; ++rb) dl[rb] = dh[rb] = xs[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf) {
                         const u32x4_t wq = q[p + hf] ^ 0x80808080u;   // b = q + 128
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
-                            const uint4 a = *reinterpret_cast<const uint4*>(xb + (hf * 8 + j * 4) * (Mp * 16));
                             const uint32_t w0 = wq[2 * j], w1 = wq[2 * j + 1];
                             const uint4 lo = make_uint4((w0 & 0x000F000Fu) | magic, ((w0 >> 8) & 0x000F000Fu) | magic,
                                                         (w1 & 0x000F000Fu) | magic, ((w1 >> 8) & 0x000F000Fu) | magic);
                             const uint4 hi = make_uint4(((w0 >> 4) & 0x000F000Fu) | magic, ((w0 >> 12) & 0x000F000Fu) | magic,
                                                         ((w1 >> 4) & 0x000F000Fu) | magic, ((w1 >> 12) & 0x000F000Fu) | magic);
-                            dl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                                         __builtin_bit_cast(bf16x8_t, lo), dl, 0, 0, 0);
-                            dh = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                                         __builtin_bit_cast(bf16x8_t, hi), dh, 0, 0, 0);
-                            xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                                         __builtin_bit_cast(bf16x8_t, ones), xs, 0, 0, 0);
+#pragma unroll
+                            for (int rb = 0; rb < kRB; ++rb) {
+                                const uint4 a = *reinterpret_cast<const uint4*>(xb + (hf * 8 + j * 4) * (Mp * 16) + xrow[rb]);
+                                dl[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                                 __builtin_bit_cast(bf16x8_t, lo), dl[rb], 0, 0, 0);
+                                dh[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                                 __builtin_bit_cast(bf16x8_t, hi), dh[rb], 0, 0, 0);
+                                xs[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                                 __builtin_bit_cast(bf16x8_t, ones), xs[rb], 0, 0, 0);
+                            }
                         }
                     }
                     const int g4 = p >> 1;   // the group among the turn's four
                     const uint16_t sbits = (uint16_t)(msc[g4 >> 1] >> (16 * (g4 & 1)));
                     const float s = (float)__builtin_bit_cast(_Float16, sbits);
                     // sum_k x q = 16 dh + dl - (16 * 128 + 128 + 128) sum_k x
-                    const float r0 = fmaf(-2304.f, xs[0], fmaf(16.f, dh[0], dl[0])), r1 = fmaf(-2304.f, xs[1], fmaf(16.f, dh[1], dl[1]));
-                    const float r2 = fmaf(-2304.f, xs[2], fmaf(16.f, dh[2], dl[2])), r3 = fmaf(-2304.f, xs[3], fmaf(16.f, dh[3], dl[3]));
-                    if (ctw == 0) {   // wave-uniform
-                        acc[0][0] = fmaf(s, r0, acc[0][0]); acc[0][1] = fmaf(s, r1, acc[0][1]);
-                        acc[0][2] = fmaf(s, r2, acc[0][2]); acc[0][3] = fmaf(s, r3, acc[0][3]);
-                    } else {
-                        acc[1][0] = fmaf(s, r0, acc[1][0]); acc[1][1] = fmaf(s, r1, acc[1][1]);
-                        acc[1][2] = fmaf(s, r2, acc[1][2]); acc[1][3] = fmaf(s, r3, acc[1][3]);
+#pragma unroll
+                    for (int rb = 0; rb < kRB; ++rb) {
+                        f32x4_t r;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) r[i] = fmaf(-2304.f, xs[rb][i], fmaf(16.f, dh[rb][i], dl[rb][i]));
+                        add_scaled(ctw, rb, s, r);
                     }
                 }
                 cs += 2;
@@ -561,34 +581,37 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
             };
             auto consume_nibbles = [&](int p) {
                 if (cs < psteps) {   // wave-uniform: not a padded slot
-                    const unsigned char* xb = xl + (k0 - p0 + cs) * step_bytes + kb * (Mp * 16) + xrow;
+                    const unsigned char* xb = xl + (k0 - p0 + cs) * step_bytes + kb * (Mp * 16);
                     const u32x4_t wq = q[p];
                     // d = sum_k x (q + 128); xs = sum_k x, the same products against ones: register i of
                     // every lane then holds the sum of row 4 kb + i of x over the step, which is the row
                     // of its d[i] (the matrix pipe has the time: it is a tenth busy)
-                    f32x4_t d = {0.f, 0.f, 0.f, 0.f}, xs = {0.f, 0.f, 0.f, 0.f};
+                    f32x4_t d[kRB], xs[kRB];
+#pragma unroll
+                    for (int rb = 0; rb < kRB; ++rb) d[rb] = xs[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const uint4 a = *reinterpret_cast<const uint4*>(xb + j * 4 * (Mp * 16));
                         const uint4 bq = make_uint4((wq[j] & 0x000F000Fu) | magic, ((wq[j] >> 4) & 0x000F000Fu) | magic,
                                                     ((wq[j] >> 8) & 0x000F000Fu) | magic, ((wq[j] >> 12) & 0x000F000Fu) | magic);
-                        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                                    __builtin_bit_cast(bf16x8_t, bq), d, 0, 0, 0);
-                        xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                                     __builtin_bit_cast(bf16x8_t, ones), xs, 0, 0, 0);
+#pragma unroll
+                        for (int rb = 0; rb < kRB; ++rb) {
+                            const uint4 a = *reinterpret_cast<const uint4*>(xb + j * 4 * (Mp * 16) + xrow[rb]);
+                            d[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                            __builtin_bit_cast(bf16x8_t, bq), d[rb], 0, 0, 0);
+                            xs[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                             __builtin_bit_cast(bf16x8_t, ones), xs[rb], 0, 0, 0);
+                        }
                     }
                     // slot p holds the step whose group is p of the turn's eight
                     const uint16_t sbits = (uint16_t)(msc[p >> 1] >> (16 * (p & 1)));
                     const float s = (float)__builtin_bit_cast(_Float16, sbits);
                     const float zc = (float)(128u + ((mzw >> (4 * p)) & 0xFu));
-                    const float r0 = fmaf(-zc, xs[0], d[0]), r1 = fmaf(-zc, xs[1], d[1]);
-                    const float r2 = fmaf(-zc, xs[2], d[2]), r3 = fmaf(-zc, xs[3], d[3]);
-                    if (ctw == 0) {   // wave-uniform
-                        acc[0][0] = fmaf(s, r0, acc[0][0]); acc[0][1] = fmaf(s, r1, acc[0][1]);
-                        acc[0][2] = fmaf(s, r2, acc[0][2]); acc[0][3] = fmaf(s, r3, acc[0][3]);
-                    } else {
-                        acc[1][0] = fmaf(s, r0, acc[1][0]); acc[1][1] = fmaf(s, r1, acc[1][1]);
-                        acc[1][2] = fmaf(s, r2, acc[1][2]); acc[1][3] = fmaf(s, r3, acc[1][3]);
+#pragma unroll
+                    for (int rb = 0; rb < kRB; ++rb) {
+                        f32x4_t r;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) r[i] = fmaf(-zc, xs[rb][i], d[rb][i]);
+                        add_scaled(ctw, rb, s, r);
                     }
                 }
                 ++cs;
@@ -626,28 +649,32 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
         float* partial = reinterpret_cast<float*>(sm_lds);
         __syncthreads();  // x is no longer read
 #pragma unroll
-        for (int i = 0; i < 4; ++i) partial[wave * 256 + i * kWave + lane] = acc[0][i];
+        for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) partial[(wave * kRB + rb) * 256 + i * kWave + lane] = acc[0][rb][i];
         __syncthreads();
-        for (int e = threadIdx.x; e < nt * 256; e += kSmThreads) {
-            const int tl = e >> 8, rem = e & 255;
-            const int m = rem >> 4, nn = rem & 15;   // consecutive threads -> consecutive n
-            const int o = (m & 3) * kWave + (m >> 2) * 16 + nn;
+        for (int e = threadIdx.x; e < nt * kRB * 256; e += kSmThreads) {
+            const int tl = e / (kRB * 256), rb = (e >> 8) % kRB, rem = e & 255;
+            const int mm = rem >> 4, nn = rem & 15;   // consecutive threads -> consecutive n
+            const int o = (mm & 3) * kWave + (mm >> 2) * 16 + nn;
             float sum = 0.f;
-            for (int kp = 0; kp < ks; ++kp) sum += partial[(tl * ks + kp) * 256 + o];
-            const int rown = (tile0 + tl) * 16 + nn;
+            for (int kp = 0; kp < ks; ++kp) sum += partial[((tl * ks + kp) * kRB + rb) * 256 + o];
+            const int rown = (tile0 + tl) * 16 + nn, m = 16 * rb + mm;
             if (m < M && rown < N) it.y[(size_t)m * N + rown] = f32_to_bf16_rne(sum);
         }
         return;
     }
 #pragma unroll
-    for (int tw = 0; tw < kTilesPerWave; ++tw) {
+    for (int tw = 0; tw < kTPW; ++tw) {
         const int n = (t0 + tw) * 16 + li;
         if (tw < ntw && n < N) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int m = 4 * kb + i;
-                if (m < M) it.y[(size_t)m * N + n] = f32_to_bf16_rne(acc[tw][i]);
-            }
+            for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int m = 16 * rb + 4 * kb + i;
+                    if (m < M) it.y[(size_t)m * N + n] = f32_to_bf16_rne(acc[tw][rb][i]);
+                }
         }
     }
 }
@@ -668,13 +695,17 @@ bool sm_one_group_per_step(const qail_wdesc& d) {
 hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int M, hipStream_t st, bool b8) {
     // more than 64 KB of LDS needs an opt-in; the call is idempotent, so two host threads that
     // both find the flag clear may both make it
-    static std::atomic<bool> attr_done[2];
-    if (!attr_done[b8].load(std::memory_order_acquire)) {
-        const void* f = b8 ? reinterpret_cast<const void*>(&smallm_stream_kernel<true>)
-                           : reinterpret_cast<const void*>(&smallm_stream_kernel<false>);
-        const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmLdsBytes);
+    const bool two = M > 16;   // two blocks of 16 rows of x
+    const void* const kernels[4] = {reinterpret_cast<const void*>(&smallm_stream_kernel<false, 1>),
+                                    reinterpret_cast<const void*>(&smallm_stream_kernel<true, 1>),
+                                    reinterpret_cast<const void*>(&smallm_stream_kernel<false, 2>),
+                                    reinterpret_cast<const void*>(&smallm_stream_kernel<true, 2>)};
+    const int which = (two ? 2 : 0) + (b8 ? 1 : 0);
+    static std::atomic<bool> attr_done[4];
+    if (!attr_done[which].load(std::memory_order_acquire)) {
+        const hipError_t e = hipFuncSetAttribute(kernels[which], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmLdsBytes);
         if (e != hipSuccess) return e;
-        attr_done[b8].store(true, std::memory_order_release);
+        attr_done[which].store(true, std::memory_order_release);
     }
     SmArgs a;
     int grid = device_cu_count();
@@ -689,7 +720,8 @@ hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int
     double t_lo = 0, t_hi = 0;
     int one_tile_per_wave = 0;
     for (int i = 0; i < count; ++i) one_tile_per_wave += ((items[i].d.N + 15) / 16 + kSmWaves - 1) / kSmWaves;
-    const int most_tiles = one_tile_per_wave <= grid ? kSmWaves : kSmWaves * kTilesPerWave;
+    // (with two row blocks a wave owns one tile: more blocks than CUs then, if it takes that)
+    const int most_tiles = (two || one_tile_per_wave <= grid) ? kSmWaves : kSmWaves * kTilesPerWave;
     for (int i = 0; i < count; ++i) {
         const int ntiles = (items[i].d.N + 15) / 16;
         lo[i] = (ntiles + most_tiles - 1) / most_tiles;
@@ -777,8 +809,12 @@ hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int
     }
     for (int i = count; i < kSmMaxItems; ++i) a.it[i] = a.it[count - 1], a.plan[i] = a.plan[count - 1];
     a.M = M;
-    if (b8) hipLaunchKernelGGL(smallm_stream_kernel<true>, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
-    else hipLaunchKernelGGL(smallm_stream_kernel<false>, dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a);
+    switch (which) {
+        case 0: hipLaunchKernelGGL((smallm_stream_kernel<false, 1>), dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a); break;
+        case 1: hipLaunchKernelGGL((smallm_stream_kernel<true, 1>), dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a); break;
+        case 2: hipLaunchKernelGGL((smallm_stream_kernel<false, 2>), dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a); break;
+        default: hipLaunchKernelGGL((smallm_stream_kernel<true, 2>), dim3(bb), dim3(kSmThreads), kSmLdsBytes, st, a); break;
+    }
     return hipGetLastError();
 }
 
@@ -880,14 +916,15 @@ hipError_t sm_launch_chunk(const qail_w4a16_item* items, int count, int M, hipSt
 
 bool smallm_supports(const qail_wdesc& d, int M) {
     const int spg = d.group_size / kStepK;
-    return M >= 2 && M <= 16 && d.K % kStepK == 0 && d.group_size % kStepK == 0 && (spg & (spg - 1)) == 0 &&
+    if (M > 16) return M <= 32 && d.K % kStepK == 0 && sm_one_group_per_step(d);   // two row blocks: that kernel only
+    return M >= 2 && d.K % kStepK == 0 && d.group_size % kStepK == 0 && (spg & (spg - 1)) == 0 &&
            (unsigned long long)d.N * d.K / 2 <= 0xFFFFFFFFull;   // 32-bit byte offsets in the kernel
 }
 
 // 8-bit weights (signed bytes, one fp16 scale per group, no zero-points) on the kernel with one group
 // per 128 k: group size 128, an even number of groups per row, N * K below 2 GB.
 bool smallm_w8_supports(const qail_wdesc& d, int M) {
-    return M >= 2 && M <= 16 && d.group_size == kStepK && d.K % kStepK == 0 && (d.K / kStepK) % 2 == 0 &&
+    return M >= 2 && M <= 32 && d.group_size == kStepK && d.K % kStepK == 0 && (d.K / kStepK) % 2 == 0 &&
            (unsigned long long)d.N * d.K <= 0x7FFFFFFFull;
 }
 

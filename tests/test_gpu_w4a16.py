@@ -80,7 +80,7 @@ def test_gemv_shapes(B, N, K, g):
     check(B, N, K, g, 1, 7 * N + K, w_kw=dict(outlier_frac=0.01), tol=TOL if K >= 512 else TOL_TINY_K)
 
 
-@pytest.mark.parametrize("M", [2, 4, 16, 100, 288])
+@pytest.mark.parametrize("M", [2, 4, 16, 17, 24, 32, 100, 288])   # 17..32: the small-batch stream with two blocks of 16 rows of x
 @pytest.mark.parametrize("N,K,g", [(200, 1024, 128), (384, 4096, 128), (72, 11008, 128), (16, 64, 64), (9, 48, 16),
                                    (1000, 4096, 128),     # ragged last 16-row tile
                                    (37, 6144, 128),       # odd N, largest K of the small-batch stream
@@ -152,13 +152,13 @@ def test_four_row_stream_shapes(B, M, N, K, g):
           tol=TOL if K >= 512 else TOL_TINY_K)
 
 
-@pytest.mark.parametrize("M", [3, 7, 15])
+@pytest.mark.parametrize("M", [3, 7, 15, 19, 31])
 def test_small_batch_odd_row_counts(B, M):
     check(B, 333, 4096, 128, M, 900 + M, w_kw=dict(outlier_frac=0.01), x_kw=dict(outlier_frac=0.005))
     check(B, 64, 1536, 128, M, 950 + M)
 
 
-@pytest.mark.parametrize("M", [1, 4, 16, 130])
+@pytest.mark.parametrize("M", [1, 4, 16, 21, 32, 130])
 def test_closed_forms_bit_exact(B, M):
     N, K, g = 96, 1024, 128
     G = K // g
@@ -182,7 +182,7 @@ def test_closed_forms_bit_exact(B, M):
         exp = np.repeat(w_hat[None, :, k], M, axis=0)
         exp[M - 1] *= -2.0
         got = synth.bf16_bits_to_f32(y)
-        if M <= 16:
+        if M <= 32:
             # compared as values: an exact zero may come out as +0 or -0
             assert np.array_equal(got, synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(exp.astype(np.float32))))
         else:
@@ -319,14 +319,14 @@ def _sampled_full_size(B, M, x_kw, batched=True):
     assert worst <= TOL, worst
 
 
-@pytest.mark.parametrize("M", [1, 4, 5, 16])
+@pytest.mark.parametrize("M", [1, 4, 5, 16, 32])
 def test_full_size_decode_linears_sampled(B, M):
     # M = 1: the benchmark's headline launch; 4, 16: its decode-stack lines (four-row stream, small-batch
     # kernel with 10-11 tiles per block and, at M = 16, three passes over the down projection's K)
     _sampled_full_size(B, M, {})
 
 
-@pytest.mark.parametrize("M", [3, 6, 16])
+@pytest.mark.parametrize("M", [3, 6, 16, 27])
 def test_full_size_decode_linears_one_call_each(B, M):
     # alone, a linear gets the whole grid: 1 to 6 tiles per block in the small-batch kernel, hence
     # 16, 5, 3 and 2 K parts per tile

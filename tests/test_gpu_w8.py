@@ -274,9 +274,9 @@ def test_w8a16_closed_forms_on_the_matrix_cores(B):
                               synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(exp))), k
 
 
-@pytest.mark.parametrize("M", [2, 3, 4, 7, 8, 13, 16])
+@pytest.mark.parametrize("M", [2, 3, 4, 7, 8, 13, 16, 17, 25, 32])
 def test_w8a16_small_batch_kernel(B, M):
-    """2 <= M <= 16 at group size 128 with an even number of groups: the small-batch streaming kernel with
+    """2 <= M <= 32 (two blocks of 16 rows of x above 16) at group size 128 with an even number of groups: the small-batch streaming kernel with
     byte weights (a byte as two nibbles against the same x).  Shapes with one tile, a ragged last
     tile, more than 32 tiles per block's worth, K in one, two and three passes of the staging, K
     parts of a tile (few rows, long K); shapes it does not take (odd group count, other group
@@ -323,12 +323,13 @@ def test_w8a16_small_batch_kernel(B, M):
         assert w4a16_norm_err(host(y1, np.uint16).reshape(M, e["N"]), ref, nx, nw) <= tol, (e["N"], e["K"])
 
 
-def test_w8a16_small_batch_kernel_closed_forms(B):
+@pytest.mark.parametrize("M", [5, 29])
+def test_w8a16_small_batch_kernel_closed_forms(B, M):
     """All codes c, s = 1, x = 1 -> y = K * c exactly (every partial sum is an integer below 2^24, K * c a
     bf16 number for these c); one-hot x reads single weights, q * s exactly (nothing is rounded
     before the accumulation), at the first and last k of a load, a group, a turn of the ring, a pass."""
     import torch
-    N, K, g, M = 96, 2048, 128, 5
+    N, K, g = 96, 2048, 128
     for c in (-128, -1, 1, 127):
         q = np.full((N, K), c, np.int8)
         s = np.ones((N, K // g), np.float16)
