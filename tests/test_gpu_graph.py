@@ -34,10 +34,12 @@ def _run_linear(B, t):
 
 def test_replays_match_eager(B):
     import torch
-    # one case per W4A16 kernel: M = 1 stream, four-row stream, small batch, matrix-core GEMM with
-    # tiles shared between blocks (K = 8192: 64 steps), and a convolution
+    # one case per W4A16 kernel: M = 1 stream, four-row stream, small batch (one and two blocks of 16 rows of
+    # x, the latter with K in several passes; the kernel for other group sizes), matrix-core GEMM with tiles
+    # shared between blocks (K = 8192: 64 steps), and a convolution
     lin = [_linear_case(B, 256, 4096, 128, 1, 11), _linear_case(B, 64, 11008, 128, 4, 12),
-           _linear_case(B, 80, 4096, 128, 16, 13), _linear_case(B, 300, 8192, 128, 100, 14)]
+           _linear_case(B, 80, 4096, 128, 16, 13), _linear_case(B, 300, 8192, 128, 100, 14),
+           _linear_case(B, 100, 11008, 128, 27, 15), _linear_case(B, 72, 2048, 256, 9, 16)]
     s = synth.ConvShape("graph", B=2, H=14, W=14, Cin=64, Cout=64, KH=3, KW=3, stride=1, pad=1)
     rng = np.random.default_rng(5)
     a = dev(rng.integers(0, 2 ** 32, size=s.B * s.H * s.W * s.Cin // 8, dtype=np.uint64).astype(np.uint32))
@@ -56,23 +58,36 @@ def test_replays_match_eager(B):
         w8.append(dict(N=N, K=K, group_size=g, qweight=dev(O.pack_bytes(q)), scales=dev(s8.view(np.uint16)),
                        x=dev(synth.llm_activation_bf16(1, K, 41 + i)), y=torch.zeros(N, dtype=torch.int16, device="cuda")))
     w8items = B.make_w8a16_items(w8, 1)
+    # 8-bit weights at M = 6 and 20: the small-batch stream with byte weights; the second shape rides on the matrix cores
+    w8m = {}
+    for M8 in (6, 20):
+        ents8 = []
+        for i, (N, K, g) in enumerate([(200, 4096, 128), (64, 1024, 64)]):
+            q, s8 = O.quantize_w8_sym_group(synth.llm_weight(N, K, 51 + i), g)
+            ents8.append(dict(N=N, K=K, group_size=g, qweight=dev(O.pack_bytes(q)), scales=dev(s8.view(np.uint16)),
+                              x=dev(synth.llm_activation_bf16(M8, K, 61 + i + M8)),
+                              y=torch.zeros(M8 * N, dtype=torch.int16, device="cuda")))
+        it8 = B.make_w8a16_items(ents8, M8)
+        w8m[M8] = (ents8, it8, ws_for(B, B.qail_w8a16_batch_workspace(it8, 2, M8)))
 
     def step():
         for t in lin:
             _run_linear(B, t)
         B.qail_w4a16_linear_batch(bitems, 3, 40, bws)
         B.qail_w8a16_linear_batch(w8items, 2, 1)
+        for M8, (_, it8, ws8) in w8m.items():
+            B.qail_w8a16_linear_batch(it8, 2, M8, ws8)
         B.qail_w4a4_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww, acc_out=acc)
 
     def snapshot():
         torch.cuda.synchronize()
         return ([host(t["y"], np.uint16).copy() for t in lin + bat] + [host(e["y"], np.uint16).copy() for e in w8] +
-                [host(acc, np.int32).copy()])
+                [host(e["y"], np.uint16).copy() for ents8, _, _ in w8m.values() for e in ents8] + [host(acc, np.int32).copy()])
 
     def clear():
         for t in lin + bat:
             t["y"].fill_(0x7FC0)
-        for e in w8:
+        for e in w8 + [e for ents8, _, _ in w8m.values() for e in ents8]:
             e["y"].fill_(0x7FC0)
         acc.fill_(-1)
 
