@@ -24,29 +24,49 @@ struct DownArgs {
     int M;
 };
 
-// One block per (j, m, item): the 256 threads split K, 8 elements per step.
-__global__ __launch_bounds__(256) void lora_down_kernel(const DownArgs args) {
-    __shared__ float red[4];
+// One block per (j, m, item): its 1024 threads split K, 8 elements a piece.  A thread's first two
+// pieces (all of K up to 16384) are requested before either is used: one round trip to memory
+// instead of one per piece, which is what this kernel's time consists of.
+constexpr int kDownThreads = 1024;
+__device__ __forceinline__ float dot8(const uint4& xv, const uint4& av, float acc) {
+    const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w}, aw[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        acc = fmaf(__builtin_bit_cast(float, xw[e] << 16), __builtin_bit_cast(float, aw[e] << 16), acc);
+        acc = fmaf(__builtin_bit_cast(float, xw[e] & 0xFFFF0000u), __builtin_bit_cast(float, aw[e] & 0xFFFF0000u), acc);
+    }
+    return acc;
+}
+__global__ __launch_bounds__(kDownThreads) void lora_down_kernel(const DownArgs args) {
+    __shared__ float red[kDownThreads / kWave];
     const DownItem& it = args.it[blockIdx.z];
     const int j = blockIdx.x, m = blockIdx.y;
     if (j >= it.r) return;  // block-uniform (items of a launch may differ in rank)
     const uint4* xr = reinterpret_cast<const uint4*>(it.x + (size_t)m * it.K);
     const uint4* ar = reinterpret_cast<const uint4*>(it.A + (size_t)j * it.K);
-    float acc = 0.f;
-    for (int i = threadIdx.x; i < it.K / 8; i += 256) {
-        const uint4 xv = xr[i], av = ar[i];
-        const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w}, aw[4] = {av.x, av.y, av.z, av.w};
+    const int n8 = it.K / 8;
+    uint4 xv[2], av[2];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            acc = fmaf(__builtin_bit_cast(float, xw[e] << 16), __builtin_bit_cast(float, aw[e] << 16), acc);
-            acc = fmaf(__builtin_bit_cast(float, xw[e] & 0xFFFF0000u), __builtin_bit_cast(float, aw[e] & 0xFFFF0000u), acc);
-        }
+    for (int u = 0; u < 2; ++u) {   // every load is issued; a piece past the end re-reads piece 0 and is not used
+        const int i = (int)threadIdx.x + u * kDownThreads;
+        xv[u] = xr[i < n8 ? i : 0];
+        av[u] = ar[i < n8 ? i : 0];
     }
+    float acc = 0.f;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        if ((int)threadIdx.x + u * kDownThreads < n8) acc = dot8(xv[u], av[u], acc);
+    for (int i = (int)threadIdx.x + 2 * kDownThreads; i < n8; i += kDownThreads) acc = dot8(xr[i], ar[i], acc);
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o);
     if (threadIdx.x % kWave == 0) red[threadIdx.x / kWave] = acc;
     __syncthreads();
-    if (threadIdx.x == 0) it.t[(size_t)m * it.r + j] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (threadIdx.x == 0) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDownThreads / kWave; ++w) sum += red[w];   // in the order of the waves: deterministic
+        it.t[(size_t)m * it.r + j] = sum;
+    }
 }
 
 // y[m][n] = bf16(float(y[m][n]) + scaling * sum_j t[m][j] B[n][j]); a block covers 256 columns n
@@ -110,7 +130,7 @@ hipError_t launch_lora_down(const qail_w4a16_item* items, const qail_lora* loras
         }
         for (int i = c; i < kMaxLoraItems; ++i) a.it[i] = a.it[c - 1];
         a.M = M;
-        hipLaunchKernelGGL(lora_down_kernel, dim3(rmax, M, c), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(lora_down_kernel, dim3(rmax, M, c), dim3(kDownThreads), 0, st, a);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
