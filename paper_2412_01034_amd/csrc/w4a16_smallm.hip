@@ -329,6 +329,7 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
     constexpr int kTPW = kRB == 1 ? kTilesPerWave : 1;   // tiles a wave can own
     extern __shared__ __attribute__((aligned(16))) unsigned char sm_lds[];
     unsigned char* xl = sm_lds;
+    float* xs_tab = reinterpret_cast<float*>(sm_lds + kXBytes);   // [steps of a pass][row blocks][16] sums of x
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
     const int li = lane & 15, kb = lane >> 4;
@@ -530,6 +531,24 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
             for (int e = threadIdx.x; e < (p1 - p0) * 16; e += kSmThreads)
                 *reinterpret_cast<uint4*>(xl + (e >> 4) * step_bytes + (e & 15) * (Mp * 16) + M * 16) = make_uint4(0, 0, 0, 0);
         __syncthreads();
+        // ---- sum_k x over every 128 k of the pass, per row: the offset form needs it with every step, every
+        // wave would otherwise compute it again (a second MFMA chain against ones cost 3 us of the layer at
+        // M = 16).  The waves share the steps out; with ones as B every lane's register i is the sum of row
+        // 4 kb + i, so the four lanes with li = 0 hold a step's 16 sums.
+        for (int sx = wave; sx < ps; sx += kSmWaves) {
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) {
+                f32x4_t t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {   // the step's 16 blocks are 4 j + kb in either layout
+                    const uint4 a = *reinterpret_cast<const uint4*>(xl + sx * step_bytes + (4 * j + kb) * (Mp * 16) + xrow[rb]);
+                    t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                __builtin_bit_cast(bf16x8_t, ones), t, 0, 0, 0);
+                }
+                if (li == 0) *reinterpret_cast<f32x4_t*>(xs_tab + ((sx * kRB + rb) * 16 + 4 * kb)) = t;
+            }
+        }
+        __syncthreads();
 
         // ---- this wave's (tile, step) pairs of the pass
         if (units > 0) {
@@ -541,7 +560,10 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
                     const unsigned char* xb = xl + ((k0 - pw0 + cs) >> 1) * step_bytes + kb * (Mp * 16);
                     f32x4_t dl[kRB], dh[kRB], xs[kRB];
 #pragma unroll
-                    for (int rb = 0; rb < kRB; ++rb) dl[rb] = dh[rb] = xs[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    for (int rb = 0; rb < kRB; ++rb) {
+                        dl[rb] = dh[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        xs[rb] = *reinterpret_cast<const f32x4_t*>(xs_tab + ((((k0 - pw0 + cs) >> 1) * kRB + rb) * 16 + 4 * kb));
+                    }
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf) {
                         const u32x4_t wq = q[p + hf] ^ 0x80808080u;   // b = q + 128
@@ -559,8 +581,6 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
                                                                                  __builtin_bit_cast(bf16x8_t, lo), dl[rb], 0, 0, 0);
                                 dh[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                                                  __builtin_bit_cast(bf16x8_t, hi), dh[rb], 0, 0, 0);
-                                xs[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                                                 __builtin_bit_cast(bf16x8_t, ones), xs[rb], 0, 0, 0);
                             }
                         }
                     }
@@ -583,12 +603,13 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
                 if (cs < psteps) {   // wave-uniform: not a padded slot
                     const unsigned char* xb = xl + (k0 - p0 + cs) * step_bytes + kb * (Mp * 16);
                     const u32x4_t wq = q[p];
-                    // d = sum_k x (q + 128); xs = sum_k x, the same products against ones: register i of
-                    // every lane then holds the sum of row 4 kb + i of x over the step, which is the row
-                    // of its d[i] (the matrix pipe has the time: it is a tenth busy)
+                    // d = sum_k x (q + 128); xs = sum_k x of the rows of d's registers, from the pass's table
                     f32x4_t d[kRB], xs[kRB];
 #pragma unroll
-                    for (int rb = 0; rb < kRB; ++rb) d[rb] = xs[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    for (int rb = 0; rb < kRB; ++rb) {
+                        d[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        xs[rb] = *reinterpret_cast<const f32x4_t*>(xs_tab + (((k0 - p0 + cs) * kRB + rb) * 16 + 4 * kb));
+                    }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const uint4 bq = make_uint4((wq[j] & 0x000F000Fu) | magic, ((wq[j] >> 4) & 0x000F000Fu) | magic,
@@ -598,8 +619,6 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
                             const uint4 a = *reinterpret_cast<const uint4*>(xb + j * 4 * (Mp * 16) + xrow[rb]);
                             d[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                                             __builtin_bit_cast(bf16x8_t, bq), d[rb], 0, 0, 0);
-                            xs[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                                             __builtin_bit_cast(bf16x8_t, ones), xs[rb], 0, 0, 0);
                         }
                     }
                     // slot p holds the step whose group is p of the turn's eight
