@@ -67,7 +67,8 @@ struct SmPlan {
     uint16_t r64[2];         // 64 % steps
     uint8_t q64[2];          // 64 / steps
     uint8_t ks[2];           // K parts per tile in a block of tiles_base [0] / tiles_base + 1 [1] tiles
-    uint16_t inv_ks[2];      // ceil(2^12 / ks): v / ks = (v * inv) >> 12 for v <= 256
+    uint8_t gshift[2];       // K parts are whole chunks of 8 >> gshift steps of the ring (8, 4 or 2)
+    uint32_t inv_ks[2];      // ceil(2^16 / ks): v / ks = (v * inv) >> 16 for v <= 4096
 };
 
 struct SmArgs {
@@ -352,13 +353,14 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
     // K parts per tile (block-uniform): every pass over K is divided among them in whole turns, so
     // that all waves of the block work in every pass
     const int ks = b < it.tiles_rem ? pl.ks[1] : pl.ks[0];
-    const int inv_ks = b < it.tiles_rem ? pl.inv_ks[1] : pl.inv_ks[0];
+    const int inv_ks = (int)(b < it.tiles_rem ? pl.inv_ks[1] : pl.inv_ks[0]);
+    const int gsh = b < it.tiles_rem ? pl.gshift[1] : pl.gshift[0], gran = 8 >> gsh;
     int t0, ntw, kpart = 0;
     if (nt > kSmWaves) {
         t0 = tile0 + (nt * wave) / kSmWaves;
         ntw = tile0 + (nt * (wave + 1)) / kSmWaves - t0;           // 1 or 2
     } else {
-        const int slot = (wave * inv_ks) >> 12;
+        const int slot = (wave * inv_ks) >> 16;
         kpart = wave - slot * ks;
         t0 = tile0 + min(slot, max(nt - 1, 0));
         ntw = slot < nt ? 1 : 0;
@@ -422,9 +424,13 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
     for (int pass = 0; pass < npass; ++pass) {
         const int p0 = pass * pass_steps, p1 = min(S, p0 + pass_steps);   // p0 is a multiple of eight
         const int pw0 = p0 * kWS, pw1 = p1 * kWS;                          // the pass in steps of the ring
-        const int pturns = (pw1 - pw0 + 7) / 8;
-        const int k0 = pw0 + 8 * ((pturns * kpart * inv_ks) >> 12);       // this wave's steps in the pass; k0 is a multiple of eight
-        const int k1 = min(pw1, pw0 + 8 * ((pturns * (kpart + 1) * inv_ks) >> 12));
+        // the pass in chunks of `gran` steps (a turn of the ring, or, where a block has too few tiles to keep its
+        // waves busy with whole turns, half or a quarter of one: then a K part is a single chunk, so that its
+        // steps never straddle a word of zero-points or the 16 bytes of scales fetched for them)
+        const int pchunks = (pw1 - pw0 + gran - 1) >> (3 - gsh);
+        const int k0 = pw0 + gran * ((pchunks * kpart * inv_ks) >> 16);   // this wave's steps in the pass; k0 is a multiple of gran
+        const int k1 = min(pw1, pw0 + gran * ((pchunks * (kpart + 1) * inv_ks) >> 16));
+        const int z8 = 4 * (k0 & 7);                                       // where the chunk's zero-points start in their word
         const int psteps = max(0, k1 - k0), upt = (psteps + 7) & ~7;      // steps and ring slots per tile in this pass
         const int units = ntw * upt;                                       // a multiple of eight
         // Pair p = row * ps + step of the pass; a thread's pairs are tg + 64 u.  Row and step of the
@@ -476,7 +482,9 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
         auto issue = [&](int p) {
             const int tw = min(itw, max(ntw - 1, 0));
             const uint32_t step = (uint32_t)max(k0 + min(is, psteps - 1), 0);
-            q[p] = __builtin_amdgcn_raw_buffer_load_b128(rq, tw ? ql[1] : ql[0], step * (kStepK / 2), 0);
+            // (a padded slot and a slot past the end of the wave's stream ask past the end of the tensor: no fetch)
+            const bool real = itw < ntw && is < psteps;
+            q[p] = __builtin_amdgcn_raw_buffer_load_b128(rq, real ? (tw ? ql[1] : ql[0]) : 0x80000000u, step * (kStepK / 2), 0);
             if (p == 0) {   // is is a multiple of eight here; the eight groups from p0 + is on
                 // (the whole offset in the lane part, which is the part the hardware checks against the tensor's
                 // size: the last turn of the last row may reach past the end of the scales, and then reads zeros)
@@ -624,7 +632,7 @@ __global__ __launch_bounds__(kSmThreads) void smallm_stream_kernel(const SmArgs 
                     // slot p holds the step whose group is p of the turn's eight
                     const uint16_t sbits = (uint16_t)(msc[p >> 1] >> (16 * (p & 1)));
                     const float s = (float)__builtin_bit_cast(_Float16, sbits);
-                    const float zc = (float)(128u + ((mzw >> (4 * p)) & 0xFu));
+                    const float zc = (float)(128u + ((mzw >> (4 * p + z8)) & 0xFu));
 #pragma unroll
                     for (int rb = 0; rb < kRB; ++rb) {
                         f32x4_t r;
@@ -820,10 +828,17 @@ hipError_t sm_launch_tiles_per_wave(const qail_w4a16_item* items, int count, int
             pl.q64[v] = (uint8_t)(64 / steps[v]);
             pl.r64[v] = (uint16_t)(64 % steps[v]);
             const int nt = t.tiles_base + v;
-            // K parts of a tile: as many as the waves allow, at most the turns of the ring in a full pass
-            const int ks = nt > kSmWaves ? 1 : std::max(1, std::min(kSmWaves / std::max(nt, 1), (ps * (b8 ? 2 : 1) + 7) / 8));
+            // K parts of a tile: as many as the waves allow, in whole turns of the ring; where a full pass has
+            // fewer turns than that, in single chunks of 2 or 4 steps if the pass then has no more chunks than
+            // the waves allow (the finest such division)
+            const int psw = ps * (b8 ? 2 : 1), want = nt > kSmWaves ? 1 : kSmWaves / std::max(nt, 1);
+            int ks = std::max(1, std::min(want, (psw + 7) / 8)), gshift = 0;
+            if (ks < want)
+                for (int g = b8 ? 1 : 2; g >= 1; --g)   // (a chunk's scales start at a whole word: two groups, i.e. 4 steps of bytes)
+                    if (((psw + (8 >> g) - 1) >> (3 - g)) <= want) { gshift = g; ks = (psw + (8 >> g) - 1) >> (3 - g); break; }
             pl.ks[v] = (uint8_t)ks;
-            pl.inv_ks[v] = (uint16_t)((4096 + ks - 1) / ks);
+            pl.gshift[v] = (uint8_t)gshift;
+            pl.inv_ks[v] = (uint32_t)((65536 + ks - 1) / ks);
         }
     }
     for (int i = count; i < kSmMaxItems; ++i) a.it[i] = a.it[count - 1], a.plan[i] = a.plan[count - 1];
