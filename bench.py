@@ -533,10 +533,38 @@ def main():
         torch.cuda.synchronize()
         tgf = timed(graph.replay, 20, settle=True)
         del graph
+        # the same body with the two convolutions that open each down-sampling block (3x3 stride 2 and the
+        # 1x1 projection: same input, no dependence) in one qail_w4a4_conv_batch launch: 32 launches
+        plan, i = [], 0
+        while i < len(fcalls):
+            s = fcalls[i][0]
+            nxt = fcalls[i + 1][0] if i + 1 < len(fcalls) else None
+            if nxt is not None and s.KH == 3 and s.stride == 2 and nxt.KH == 1 and nxt.stride == 2 and nxt.Cin == s.Cin:
+                ents = []
+                for s_, a_, ww_, scale_, bias_, out_, res_ in fcalls[i:i + 2]:
+                    ents.append(dict(B=s_.B, H=s_.H, W=s_.W, Cin=s_.Cin, Cout=s_.Cout, KH=s_.KH, KW=s_.KW, stride=s_.stride,
+                                     pad=s_.pad, a_u4=a_, w_s4=ww_, scale=scale_, bias=bias_, out_u4=out_, s_out=0.37))
+                plan.append(("pair", B.make_conv_items(ents)))
+                i += 2
+            else:
+                plan.append(("one", fcalls[i]))
+                i += 1
+
+        def paired_body():
+            for kind, v in plan:
+                if kind == "pair":
+                    B.qail_w4a4_conv_batch(v, 2, stream=sh)
+                else:
+                    s, a, ww, scale, bias, out, res = v
+                    B.qail_w4a4_conv_u4(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww, scale, bias,
+                                        0.37, out, res_u4=res, res_scale=0.11, stream=sh)
+        tp_ = timed(paired_body, 20, settle=True)
         extra["w4a4_resnet34_b32_fused_u4"] = {"ms_per_pass": round(tf_ * 1e3, 4),
                                                "TOPs": round(tot_ops / tf_ / 1e12, 1),
                                                "frac_int8_peak": round(tot_ops / tf_ / 1e12 / INT8_PEAK_TOPS, 4),
                                                "calls": len(fcalls), "ms_per_pass_graph_replay": round(tgf * 1e3, 4),
+                                               "ms_per_pass_paired_launches": round(tp_ * 1e3, 4),
+                                               "launches_paired": len(plan),
                                                "per_shape": fper,
                                                "aggregate": conv_summary([c[0] for c in fcalls], fper, tf_, 0.5)}
         del fcalls

@@ -288,6 +288,32 @@ int qail_w4a4_conv_u4(const qail_conv_desc* d, const uint32_t* a_u4, const uint3
                       const uint32_t* res_u4, float res_scale, const float* res_f32,
                       uint32_t* out_u4, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Several independent W4A4 convolutions in as few launches as possible (one, when every
+ * item is a shape the tiled kernel runs and count <= 4).  Sec. 5.1 / appendix: the driving
+ * encoder is a ResNet, whose down-sampling blocks start with two convolutions that read the same
+ * input, the 3x3 stride-2 one and the 1x1 projection of the shortcut; at a small batch a launch
+ * costs more than either of them.
+ * An item is the argument list of qail_w4a4_gemm (out_u4 == NULL: acc_out and / or y_out) or
+ * of qail_w4a4_conv_u4 (out_u4 != NULL: acc_out and y_out must be NULL); every rule of those
+ * two calls holds per item, and each item's results equal the single call's bit for bit.
+ * Items must be independent: no item may read a buffer another item writes, and no two may
+ * write the same one.  1 <= count <= 64.  Errors are reported before anything is launched. */
+typedef struct {
+    qail_conv_desc d;
+    const uint32_t* a_u4;    /* device */
+    const uint32_t* w_s4;    /* device */
+    const float* scale;      /* device, fp32 [Cout]; required with y_out or out_u4 */
+    const float* bias;       /* device, fp32 [Cout]; required with y_out or out_u4 */
+    int32_t* acc_out;        /* device, int32 [M][Cout] or NULL */
+    float* y_out;            /* device, fp32 [M][Cout] or NULL */
+    uint32_t* out_u4;        /* device, [M][Cout/8] words or NULL */
+    float s_out;             /* fused output only */
+    float res_scale;         /* fused output with res_u4 only */
+    const uint32_t* res_u4;  /* device or NULL */
+    const float* res_f32;    /* device or NULL */
+} qail_conv_item;
+int qail_w4a4_conv_batch(const qail_conv_item* items, int32_t count, void* stream);
+
 /* ------------------------------------------------------------------ 8-bit --
  * Sec. 5.4 deploys the driving encoder also as W8A8 and the backbone also with 8-bit
  * weights only.  Weights: qail_quantize_weights / qail_packed_sizes with the W8 schemes

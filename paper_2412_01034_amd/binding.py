@@ -32,7 +32,7 @@ EXPORTS = (
     "qail_version", "qail_status_string", "qail_packed_sizes", "qail_quantize_weights",
     "qail_unpack_weights", "qail_act_scale_u4", "qail_quantize_act_u4", "qail_w4a16_workspace",
     "qail_w4a16_linear", "qail_w4a16_linear_batch", "qail_w4a16_batch_workspace",
-    "qail_w4a4_workspace", "qail_w4a4_gemm", "qail_w4a4_conv_u4",
+    "qail_w4a4_workspace", "qail_w4a4_gemm", "qail_w4a4_conv_u4", "qail_w4a4_conv_batch",
     "qail_w4a16_lora_workspace", "qail_w4a16_linear_lora_batch",
     "qail_static_scratch_bytes", "qail_w4a16_linear_lora_batch_static",
     "qail_w4a16_chain_workspace", "qail_w4a16_linear_chain",
@@ -59,6 +59,13 @@ class qail_wdesc(ctypes.Structure):
 
 class qail_conv_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "H", "W", "Cin", "Cout", "KH", "KW", "stride", "pad")]
+
+
+class qail_conv_item(ctypes.Structure):
+    _fields_ = [("d", qail_conv_desc), ("a_u4", ctypes.c_void_p), ("w_s4", ctypes.c_void_p),
+                ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("acc_out", ctypes.c_void_p),
+                ("y_out", ctypes.c_void_p), ("out_u4", ctypes.c_void_p), ("s_out", ctypes.c_float),
+                ("res_scale", ctypes.c_float), ("res_u4", ctypes.c_void_p), ("res_f32", ctypes.c_void_p)]
 
 
 class qail_w4a16_item(ctypes.Structure):
@@ -119,6 +126,7 @@ def lib() -> ctypes.CDLL:
         L.qail_w8a16_linear_batch.argtypes = [ctypes.POINTER(qail_w8a16_item), i32, i32, vp, sz, vp]
         L.qail_w4a4_workspace.argtypes = [ctypes.POINTER(qail_conv_desc), psz]
         L.qail_w4a4_gemm.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.qail_w4a4_conv_batch.argtypes = [ctypes.POINTER(qail_conv_item), i32, vp]
         L.qail_w4a4_conv_u4.argtypes = [ctypes.POINTER(qail_conv_desc), vp, vp, vp, vp, ctypes.c_float, vp,
                                         ctypes.c_float, vp, vp, vp, sz, vp]
         for name in EXPORTS:
@@ -326,6 +334,31 @@ def qail_w4a4_conv_u4(B, H, W, Cin, Cout, KH, KW, stride, pad, a_u4: torch.Tenso
                                    float(s_out), _ptr(res_u4), float(res_scale), _ptr(res_f32), _ptr(out_u4),
                                    _ptr(workspace), wsb, _stream() if stream is None else stream),
            "qail_w4a4_conv_u4")
+
+
+def make_conv_items(entries: Sequence[dict]):
+    """entries: dicts with the conv fields B, H, W, Cin, Cout, KH, KW, stride, pad, the device tensors a_u4,
+    w_s4 and, as the item needs them, scale, bias, acc_out, y_out, out_u4, res_u4, res_f32, and the host
+    values s_out, res_scale.  The tensors must be kept alive by the caller."""
+    arr = (qail_conv_item * max(1, len(entries)))()
+    for i, e in enumerate(entries):
+        B, H, W, Cin, Cout, KH, KW, stride, pad = (int(e[k]) for k in ("B", "H", "W", "Cin", "Cout", "KH", "KW", "stride", "pad"))
+        M = B * ((H + 2 * pad - KH) // stride + 1) * ((W + 2 * pad - KW) // stride + 1)
+        _need(e["a_u4"], B * H * W * Cin // 2, "a_u4")
+        _need(e["w_s4"], Cout * KH * KW * Cin // 2, "w_s4")
+        for name, nbytes in (("scale", Cout * 4), ("bias", Cout * 4), ("acc_out", M * Cout * 4), ("y_out", M * Cout * 4),
+                             ("out_u4", M * Cout // 2), ("res_u4", M * Cout // 2), ("res_f32", M * Cout * 4)):
+            if e.get(name) is not None:
+                _need(e[name], nbytes, name)
+        arr[i] = qail_conv_item(qail_conv_desc(B, H, W, Cin, Cout, KH, KW, stride, pad), _ptr(e["a_u4"]), _ptr(e["w_s4"]),
+                                _ptr(e.get("scale")), _ptr(e.get("bias")), _ptr(e.get("acc_out")), _ptr(e.get("y_out")),
+                                _ptr(e.get("out_u4")), float(e.get("s_out", 0.0)), float(e.get("res_scale", 0.0)),
+                                _ptr(e.get("res_u4")), _ptr(e.get("res_f32")))
+    return arr
+
+
+def qail_w4a4_conv_batch(items, count: int, stream: Optional[int] = None) -> None:
+    _check(lib().qail_w4a4_conv_batch(items, count, _stream() if stream is None else stream), "qail_w4a4_conv_batch")
 
 
 def make_loras(entries: Sequence[dict]):

@@ -64,6 +64,37 @@ int check_conv(const qail_conv_desc* d, int bits = 4) {
     return QAIL_OK;
 }
 
+// The argument rules of qail_w4a4_conv_u4.
+int check_conv_u4(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t* w_s4, const float* scale,
+                         const float* bias, float s_out, const uint32_t* res_u4, float res_scale,
+                         const float* res_f32, const uint32_t* out_u4) {
+    const int e = check_conv(d);
+    if (e != QAIL_OK) return e;
+    if (d->Cout % 8 != 0) return QAIL_ERR_SHAPE;           // codes are packed 8 per word along Cout
+    if (!(s_out > 0.f) || !(s_out <= 3.0e38f)) return QAIL_ERR_SHAPE;
+    if (res_u4 && res_f32) return QAIL_ERR_SHAPE;          // at most one shortcut
+    if (res_u4 && !(res_scale >= 0.f && res_scale <= 3.0e38f)) return QAIL_ERR_SHAPE;
+    if (!a_u4 || !w_s4 || !scale || !bias || !out_u4) return QAIL_ERR_NULL;
+    if (!aligned16(a_u4) || !aligned16(w_s4) || !aligned16(scale) || !aligned16(bias) || !aligned16(out_u4) ||
+        (res_u4 && !aligned16(res_u4)) || (res_f32 && !aligned16(res_f32)))
+        return QAIL_ERR_ALIGN;
+    return QAIL_OK;
+}
+
+// The argument rules of qail_w4a4_gemm.
+int check_conv_plain(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t* w_s4, const int32_t* acc_out,
+                            const float* scale, const float* bias, const float* y_out) {
+    const int e = check_conv(d);
+    if (e != QAIL_OK) return e;
+    if (!a_u4 || !w_s4) return QAIL_ERR_NULL;
+    if (!acc_out && !y_out) return QAIL_ERR_NULL;
+    if (y_out && (!scale || !bias)) return QAIL_ERR_NULL;
+    if (!aligned16(a_u4) || !aligned16(w_s4) || (acc_out && !aligned16(acc_out)) ||
+        (y_out && !aligned16(y_out)) || (scale && !aligned16(scale)) || (bias && !aligned16(bias)))
+        return QAIL_ERR_ALIGN;
+    return QAIL_OK;
+}
+
 int check_item(const qail_w4a16_item& it, int M) {
     int e = check_wdesc(&it.d);
     if (e != QAIL_OK) return e;
@@ -455,14 +486,8 @@ int qail_w4a4_gemm(const qail_conv_desc* d, const uint32_t* a_u4, const uint32_t
                    size_t workspace_bytes, void* stream) {
     (void)workspace;
     (void)workspace_bytes;
-    const int e = check_conv(d);
+    const int e = check_conv_plain(d, a_u4, w_s4, acc_out, scale, bias, y_out);
     if (e != QAIL_OK) return e;
-    if (!a_u4 || !w_s4) return QAIL_ERR_NULL;
-    if (!acc_out && !y_out) return QAIL_ERR_NULL;
-    if (y_out && (!scale || !bias)) return QAIL_ERR_NULL;
-    if (!aligned16(a_u4) || !aligned16(w_s4) || (acc_out && !aligned16(acc_out)) ||
-        (y_out && !aligned16(y_out)) || (scale && !aligned16(scale)) || (bias && !aligned16(bias)))
-        return QAIL_ERR_ALIGN;
     return hip_status(launch_w4a4_conv(*d, a_u4, w_s4, acc_out, scale, bias, y_out,
                                        static_cast<hipStream_t>(stream)));
 }
@@ -686,18 +711,29 @@ int qail_w4a4_conv_u4(const qail_conv_desc* d, const uint32_t* a_u4, const uint3
                       void* stream) {
     (void)workspace;
     (void)workspace_bytes;
-    const int e = check_conv(d);
+    const int e = check_conv_u4(d, a_u4, w_s4, scale, bias, s_out, res_u4, res_scale, res_f32, out_u4);
     if (e != QAIL_OK) return e;
-    if (d->Cout % 8 != 0) return QAIL_ERR_SHAPE;           // codes are packed 8 per word along Cout
-    if (!(s_out > 0.f) || !(s_out <= 3.0e38f)) return QAIL_ERR_SHAPE;
-    if (res_u4 && res_f32) return QAIL_ERR_SHAPE;          // at most one shortcut
-    if (res_u4 && !(res_scale >= 0.f && res_scale <= 3.0e38f)) return QAIL_ERR_SHAPE;
-    if (!a_u4 || !w_s4 || !scale || !bias || !out_u4) return QAIL_ERR_NULL;
-    if (!aligned16(a_u4) || !aligned16(w_s4) || !aligned16(scale) || !aligned16(bias) || !aligned16(out_u4) ||
-        (res_u4 && !aligned16(res_u4)) || (res_f32 && !aligned16(res_f32)))
-        return QAIL_ERR_ALIGN;
     return hip_status(launch_w4a4_conv_u4(*d, a_u4, w_s4, scale, bias, s_out, res_u4, res_scale, res_f32, out_u4,
                                           static_cast<hipStream_t>(stream)));
+}
+
+int qail_w4a4_conv_batch(const qail_conv_item* items, int32_t count, void* stream) {
+    if (!items) return QAIL_ERR_NULL;
+    if (count < 1 || count > 64) return QAIL_ERR_SHAPE;
+    for (int i = 0; i < count; ++i) {
+        const qail_conv_item& it = items[i];
+        int e;
+        if (it.out_u4) {
+            if (it.acc_out || it.y_out) return QAIL_ERR_SHAPE;   // one kind of output per item
+            e = check_conv_u4(&it.d, it.a_u4, it.w_s4, it.scale, it.bias, it.s_out, it.res_u4, it.res_scale,
+                              it.res_f32, it.out_u4);
+        } else {
+            if (it.res_u4 || it.res_f32) return QAIL_ERR_SHAPE;  // a shortcut belongs to the fused output
+            e = check_conv_plain(&it.d, it.a_u4, it.w_s4, it.acc_out, it.scale, it.bias, it.y_out);
+        }
+        if (e != QAIL_OK) return e;
+    }
+    return hip_status(launch_w4a4_conv_batch(items, count, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

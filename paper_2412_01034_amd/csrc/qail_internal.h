@@ -113,6 +113,7 @@ hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const ui
                             const float* scale, const float* bias, float* y, hipStream_t st);
 hipError_t launch_w8a8_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
                             const float* scale, const float* bias, float* y, hipStream_t st);
+hipError_t launch_w4a4_conv_batch(const qail_conv_item* items, int count, hipStream_t st);
 hipError_t launch_w4a4_conv_u4(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const float* scale,
                                const float* bias, float s_out, const uint32_t* res_u4, float res_scale,
                                const float* res_f32, uint32_t* out_u4, hipStream_t st);

@@ -29,6 +29,7 @@
 // straight into a ring of three LDS slots, one barrier per step.
 // Zero padding costs nothing: code 0 of the unsigned activations is the value 0.
 #include "qail_internal.h"
+#include <algorithm>
 #include <cmath>
 
 namespace qail {
@@ -85,6 +86,21 @@ struct ConvOut {
     float s_out, res_scale;
     float inv_s_out;  // 1 / s_out, correctly rounded (host division)
     int quick;        // s_out and its reciprocal are normal numbers: the quotient may be tried as a product first
+};
+
+// Up to kConvBatch independent convolutions share a launch: item i is the grid's plane z = i
+// (its arguments are then at an offset known when the wave starts: no load depends on another);
+// the x and y axes are as large as the largest item needs, the blocks outside an item's own tile
+// grid leave at once.
+constexpr int kConvBatch = 4;
+struct ConvItem {
+    ConvGeom gm;
+    const uint32_t* a;
+    const uint32_t* w;
+    ConvOut out;
+};
+struct ConvBatch {
+    ConvItem it[kConvBatch];
 };
 
 // One output element of the fused epilogue (Sec. 5.1: every activation tensor of the driving
@@ -197,9 +213,12 @@ constexpr int kMaxSteps = 128;  // rows of the step table (K steps plus the ring
 //
 // kBits = 8 is the W8A8 variant of the same kernel (Sec. 5.4): bytes are MFMA operands as they
 // are, a K step is 64 codes and one MFMA deep, nothing is widened and nothing shifted back.
+//
+// The tile at rows bm.., columns bn.. of one convolution; the two kernels below call it.
 template <int BM, int BN, int KS, int kBits>
-__global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 : 4))) void w4a4_conv_kernel(
-    const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, const ConvOut out) {
+__device__ __forceinline__ void w4a4_conv_tile(const ConvGeom& gm, const uint32_t* __restrict__ a,
+                                               const uint32_t* __restrict__ w, const ConvOut& out, const int bm,
+                                               const int bn) {
     constexpr int kLA = BM / 64;   // wave-wide loads per wave and step for the activation tile
     constexpr int kLB = BN / 64;   // ... for the weight tile
     constexpr int kL = kLA + kLB;
@@ -222,7 +241,6 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
     const int grp = wave_all / 4, wave = wave_all % 4;   // K group, wave inside the group
     unsigned char* const smem = smem_all + grp * kGroupBytes;
     const int wm = wave / 2, wn = wave % 2;
-    const int bm = blockIdx.y * BM, bn = blockIdx.x * BN;
     const int cw = gm.Cin / (32 / kBits);      // words per pixel
     const int kwords = gm.KH * gm.KW * cw;     // words per filter
     const int gsteps = (kwords + kStepWords - 1) / kStepWords;   // K steps of the whole problem
@@ -556,6 +574,23 @@ __global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 :
     }
 }
 
+// One convolution per launch: grid (column tiles, row tiles).
+template <int BM, int BN, int KS, int kBits>
+__global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 : 4))) void w4a4_conv_kernel(
+    const ConvGeom gm, const uint32_t* __restrict__ a, const uint32_t* __restrict__ w, const ConvOut out) {
+    w4a4_conv_tile<BM, BN, KS, kBits>(gm, a, w, out, blockIdx.y * BM, blockIdx.x * BN);
+}
+
+// Several per launch: item i is the grid's plane z = i.
+template <int BM, int BN, int KS, int kBits>
+__global__ __launch_bounds__(256 * KS, (KS > 1 ? 1 : (BM * BN >= 128 * 128 ? 2 : 4))) void w4a4_conv_batch_kernel(
+    const ConvBatch args) {
+    const ConvItem& it = args.it[blockIdx.z];
+    const ConvGeom gm = it.gm;
+    if ((int)blockIdx.x * BN >= gm.Cout || (int)blockIdx.y * BM >= gm.M) return;   // the grid fits the largest item
+    w4a4_conv_tile<BM, BN, KS, kBits>(gm, it.a, it.w, it.out, blockIdx.y * BM, blockIdx.x * BN);
+}
+
 // Any Cin that fills whole words: one thread per output.  Slow; for shapes whose Cin is not a
 // multiple of 32, more than 32 filter taps, or tensors of 4 GB and more.
 template <int kBits>
@@ -629,20 +664,41 @@ __global__ __launch_bounds__(256) void w4a4_generic_u4_kernel(
     out.out_u4[o] = fused_word(acc, out, (size_t)m, n0, gm.Cout);
 }
 
+// One convolution made ready for a launch.
+struct ConvJob {
+    ConvGeom gm;
+    const uint32_t* a;
+    const uint32_t* w;
+    ConvOut out;
+    bool tiled;   // the tiled kernel can run it
+    int ksteps;   // K steps of the tiled kernel
+};
+
+// One launch of the tiled kernel for n jobs (n <= kConvBatch) that share a tile configuration.
 template <int kBits, int BM, int BN, int KS = 1>
-void launch_tiled(const ConvGeom& gm, const uint32_t* a, const uint32_t* w, const ConvOut& out, hipStream_t st) {
-    dim3 grid((gm.Cout + BN - 1) / BN, (gm.M + BM - 1) / BM);
-    hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN, KS, kBits>), grid, dim3(256 * KS), 0, st, gm, a, w, out);
+void launch_tiled(const ConvJob* jobs, int n, hipStream_t st) {
+    ConvBatch cb;
+    int ny = 0, nx = 0;
+    for (int i = 0; i < kConvBatch; ++i) {
+        const ConvJob& j = jobs[i < n ? i : 0];
+        cb.it[i] = ConvItem{j.gm, j.a, j.w, j.out};
+        if (i < n) {
+            ny = std::max(ny, (j.gm.M + BM - 1) / BM);
+            nx = std::max(nx, (j.gm.Cout + BN - 1) / BN);
+        }
+    }
+    if (kBits == 4 && n > 1)
+        hipLaunchKernelGGL((w4a4_conv_batch_kernel<BM, BN, KS, 4>), dim3(nx, ny, n), dim3(256 * KS), 0, st, cb);
+    else
+        hipLaunchKernelGGL((w4a4_conv_kernel<BM, BN, KS, kBits>), dim3(nx, ny, 1), dim3(256 * KS), 0, st, jobs[0].gm,
+                           jobs[0].a, jobs[0].w, jobs[0].out);
 }
 
-}  // namespace
-
-namespace {
 template <int kBits>
-hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const ConvOut& out,
-                       hipStream_t st) {
+ConvJob make_job(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const ConvOut& out) {
     constexpr int kPerWord = 32 / kBits;
-    ConvGeom gm;
+    ConvJob job;
+    ConvGeom& gm = job.gm;
     gm.B = d.B; gm.H = d.H; gm.W = d.W; gm.Cin = d.Cin; gm.Cout = d.Cout;
     gm.KH = d.KH; gm.KW = d.KW; gm.stride = d.stride; gm.pad = d.pad;
     gm.OH = (d.H + 2 * d.pad - d.KH) / d.stride + 1;
@@ -663,35 +719,107 @@ hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_
     const bool fits32 = (size_t)gm.B * gm.H * gm.W * cwb < 0xFFFFFFF0ull &&
                         (size_t)gm.Cout * gm.KH * gm.KW * cwb < 0xFFFFFFF0ull &&
                         (size_t)gm.M * gm.Cout * 4 < 0xFFFFFFF0ull;
-    const int ksteps = (gm.KH * gm.KW * (gm.Cin / kPerWord) + kStepWords - 1) / kStepWords;
+    job.ksteps = (gm.KH * gm.KW * (gm.Cin / kPerWord) + kStepWords - 1) / kStepWords;
     // a 16-byte chunk (32 or 16 codes) must lie inside one filter tap
-    if (d.Cin % (4 * kPerWord) == 0 && d.KH * d.KW <= 32 && fits32 && ksteps + 4 * (kStages + 1) <= kMaxSteps) {
-        // the largest tile that still gives every CU about two blocks
-        const long long want = 2LL * device_cu_count();
-        auto blocks = [&](int bm, int bn) {
-            return (long long)((gm.M + bm - 1) / bm) * ((gm.Cout + bn - 1) / bn);
-        };
-        const bool wide = gm.Cout > 64;
-        // (the 128 x 128 tile already from one and a half blocks per CU: at batch 256 it takes the
-        // 512 -> 512 layers from 45.7 to 37.6 us against the 128 x 64 tile)
-        if (wide && 4 * blocks(128, 128) >= 3 * want) launch_tiled<kBits, 128, 128>(gm, a, w, out, st);
-        else if (blocks(128, 64) >= want) launch_tiled<kBits, 128, 64>(gm, a, w, out, st);
-        else if (wide && blocks(64, 128) >= want / 2) launch_tiled<kBits, 64, 128>(gm, a, w, out, st);
-        else if (blocks(64, 64) <= device_cu_count() && ksteps >= 16) launch_tiled<kBits, 64, 64, 4>(gm, a, w, out, st);
-        else if (blocks(64, 64) <= 2 * device_cu_count() && ksteps >= 8) launch_tiled<kBits, 64, 64, 2>(gm, a, w, out, st);
-        else launch_tiled<kBits, 64, 64>(gm, a, w, out, st);
-    } else if (out.out_u4) {
-        const size_t words = (size_t)gm.M * (d.Cout / 8);
-        hipLaunchKernelGGL(w4a4_generic_u4_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, gm,
-                           a, w, out);
+    job.tiled = d.Cin % (4 * kPerWord) == 0 && d.KH * d.KW <= 32 && fits32 && job.ksteps + 4 * (kStages + 1) <= kMaxSteps;
+    job.a = a;
+    job.w = w;
+    job.out = out;
+    return job;
+}
+
+// Launches n jobs the tiled kernel can run (n <= kConvBatch) as one grid.  The tile is chosen for
+// the job with the longest K (the one that decides how long the launch takes); whether K is split
+// between groups of waves depends on how many blocks all jobs together put on a CU.
+template <int kBits>
+void launch_tiled_jobs(const ConvJob* jobs, int n, hipStream_t st) {
+    int lead = 0;
+    for (int i = 1; i < n; ++i)
+        if ((long long)jobs[i].ksteps * jobs[i].gm.M > (long long)jobs[lead].ksteps * jobs[lead].gm.M) lead = i;
+    const ConvGeom& gm = jobs[lead].gm;
+    const int ksteps = jobs[lead].ksteps;
+    // the largest tile that still gives every CU about two blocks
+    const long long want = 2LL * device_cu_count();
+    auto blocks = [&](int bm, int bn) {
+        return (long long)((gm.M + bm - 1) / bm) * ((gm.Cout + bn - 1) / bn);
+    };
+    long long all64 = 0;
+    for (int i = 0; i < n; ++i)
+        all64 += (long long)((jobs[i].gm.M + 63) / 64) * ((jobs[i].gm.Cout + 63) / 64);
+    const bool wide = gm.Cout > 64;
+    // (the 128 x 128 tile already from one and a half blocks per CU: at batch 256 it takes the
+    // 512 -> 512 layers from 45.7 to 37.6 us against the 128 x 64 tile)
+    if (wide && 4 * blocks(128, 128) >= 3 * want) launch_tiled<kBits, 128, 128>(jobs, n, st);
+    else if (blocks(128, 64) >= want) launch_tiled<kBits, 128, 64>(jobs, n, st);
+    else if (wide && blocks(64, 128) >= want / 2) launch_tiled<kBits, 64, 128>(jobs, n, st);
+    else if (all64 <= device_cu_count() && ksteps >= 16) launch_tiled<kBits, 64, 64, 4>(jobs, n, st);
+    else if (all64 <= 2 * device_cu_count() && ksteps >= 8) launch_tiled<kBits, 64, 64, 2>(jobs, n, st);
+    else launch_tiled<kBits, 64, 64>(jobs, n, st);
+}
+
+template <int kBits>
+hipError_t launch_job(const ConvJob& job, hipStream_t st) {
+    if (job.tiled) {
+        launch_tiled_jobs<kBits>(&job, 1, st);
+    } else if (job.out.out_u4) {
+        const size_t words = (size_t)job.gm.M * (job.gm.Cout / 8);
+        hipLaunchKernelGGL(w4a4_generic_u4_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, job.gm,
+                           job.a, job.w, job.out);
     } else {
-        const size_t outs = (size_t)gm.M * d.Cout;
-        hipLaunchKernelGGL(w4a4_generic_kernel<kBits>, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st, gm,
-                           a, w, out);
+        const size_t outs = (size_t)job.gm.M * job.gm.Cout;
+        hipLaunchKernelGGL(w4a4_generic_kernel<kBits>, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st, job.gm,
+                           job.a, job.w, job.out);
     }
     return hipGetLastError();
 }
+
+template <int kBits>
+hipError_t launch_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const ConvOut& out,
+                       hipStream_t st) {
+    return launch_job<kBits>(make_job<kBits>(d, a, w, out), st);
+}
+
+ConvOut fused_out(const float* scale, const float* bias, float s_out, const uint32_t* res_u4, float res_scale,
+                  const float* res_f32, uint32_t* out_u4) {
+    const float inv = 1.0f / s_out;
+    const int quick = std::isnormal(s_out) && std::isnormal(inv) && s_out > 0.f;
+    return ConvOut{nullptr, scale, bias, nullptr, out_u4, res_u4, res_f32, s_out, res_scale, inv, quick};
+}
 }  // namespace
+
+// Independent W4A4 convolutions (plain or fused output each) in few launches: consecutive ones the
+// tiled kernel can run share a launch, kConvBatch at a time, as long as their tile grids are of
+// similar size (every plane of the launch's grid is as large as the largest); the others go one by one.
+hipError_t launch_w4a4_conv_batch(const qail_conv_item* items, int count, hipStream_t st) {
+    ConvJob tiled[kConvBatch];
+    int n = 0;
+    long long lo = 0, hi = 0;   // smallest and largest tile grid (in 64 x 64 tiles) of the pending launch
+    auto flush = [&]() -> hipError_t {
+        if (n > 0) launch_tiled_jobs<4>(tiled, n, st);
+        n = 0;
+        return hipGetLastError();
+    };
+    for (int i = 0; i < count; ++i) {
+        const qail_conv_item& it = items[i];
+        const ConvOut out = it.out_u4 ? fused_out(it.scale, it.bias, it.s_out, it.res_u4, it.res_scale, it.res_f32, it.out_u4)
+                                      : ConvOut{it.acc_out, it.scale, it.bias, it.y_out, nullptr, nullptr, nullptr, 1.f, 0.f, 1.f, 0};
+        const ConvJob job = make_job<4>(it.d, it.a_u4, it.w_s4, out);
+        if (!job.tiled) {
+            const hipError_t e = launch_job<4>(job, st);
+            if (e != hipSuccess) return e;
+            continue;
+        }
+        const long long t = (long long)((job.gm.M + 63) / 64) * ((job.gm.Cout + 63) / 64);
+        if (n == kConvBatch || (n > 0 && (2 * std::min(lo, t) < std::max(hi, t)))) {
+            const hipError_t e = flush();
+            if (e != hipSuccess) return e;
+        }
+        lo = n ? std::min(lo, t) : t;
+        hi = n ? std::max(hi, t) : t;
+        tiled[n++] = job;
+    }
+    return flush();
+}
 
 hipError_t launch_w4a4_conv(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, int32_t* acc,
                             const float* scale, const float* bias, float* y, hipStream_t st) {
@@ -708,10 +836,7 @@ hipError_t launch_w8a8_conv(const qail_conv_desc& d, const uint32_t* a, const ui
 hipError_t launch_w4a4_conv_u4(const qail_conv_desc& d, const uint32_t* a, const uint32_t* w, const float* scale,
                                const float* bias, float s_out, const uint32_t* res_u4, float res_scale,
                                const float* res_f32, uint32_t* out_u4, hipStream_t st) {
-    const float inv = 1.0f / s_out;
-    const int quick = std::isnormal(s_out) && std::isnormal(inv) && s_out > 0.f;
-    const ConvOut out{nullptr, scale, bias, nullptr, out_u4, res_u4, res_f32, s_out, res_scale, inv, quick};
-    return launch_conv<4>(d, a, w, out, st);
+    return launch_conv<4>(d, a, w, fused_out(scale, bias, s_out, res_u4, res_scale, res_f32, out_u4), st);
 }
 
 }  // namespace qail

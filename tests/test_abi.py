@@ -82,6 +82,28 @@ def test_argument_errors_are_reported_without_a_gpu(B):
     assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, ok, 0.1, ok, ok, None, 0, None) == B.QAIL_ERR_SHAPE    # two shortcuts
     assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, ok, -1.0, None, ok, None, 0, None) == B.QAIL_ERR_SHAPE
     assert f(ctypes.byref(c8), ok, ok, ok, ok, 0.5, odd, 0.1, None, ok, None, 0, None) == B.QAIL_ERR_ALIGN
+    # several convolutions per launch: each item obeys the rules of the single call of its kind
+    f = L.qail_w4a4_conv_batch
+
+    def conv_item(desc, **kw):
+        it = B.qail_conv_item()
+        it.d = desc
+        for k in ("a_u4", "w_s4", "scale", "bias", "acc_out", "y_out", "out_u4", "res_u4", "res_f32"):
+            setattr(it, k, kw.get(k))
+        it.s_out = kw.get("s_out", 0.0)
+        it.res_scale = kw.get("res_scale", 0.0)
+        return (B.qail_conv_item * 1)(it)
+    assert f(None, 1, None) == B.QAIL_ERR_NULL
+    good = conv_item(c8, a_u4=ok, w_s4=ok, scale=ok, bias=ok, out_u4=ok, s_out=0.5)
+    assert f(good, 0, None) == B.QAIL_ERR_SHAPE and f(good, 65, None) == B.QAIL_ERR_SHAPE
+    assert f(conv_item(c8, a_u4=ok, w_s4=ok), 1, None) == B.QAIL_ERR_NULL                      # no output at all
+    assert f(conv_item(c8, a_u4=ok, w_s4=ok, y_out=ok), 1, None) == B.QAIL_ERR_NULL            # y without scale
+    assert f(conv_item(c8, a_u4=ok, w_s4=ok, scale=ok, bias=ok, out_u4=ok, acc_out=ok, s_out=0.5), 1, None) == B.QAIL_ERR_SHAPE
+    assert f(conv_item(c8, a_u4=ok, w_s4=ok, acc_out=ok, res_u4=ok), 1, None) == B.QAIL_ERR_SHAPE   # shortcut without fused output
+    assert f(conv_item(c8, a_u4=ok, w_s4=ok, scale=ok, bias=ok, out_u4=ok, s_out=0.0), 1, None) == B.QAIL_ERR_SHAPE
+    assert f(conv_item(c, a_u4=ok, w_s4=ok, scale=ok, bias=ok, out_u4=ok, s_out=0.5), 1, None) == B.QAIL_ERR_SHAPE   # Cout = 4
+    assert f(conv_item(c8, a_u4=ok, w_s4=odd, acc_out=ok), 1, None) == B.QAIL_ERR_ALIGN
+    assert f(conv_item(bad, a_u4=ok, w_s4=ok, acc_out=ok), 1, None) == B.QAIL_ERR_SHAPE
     # low-rank adapters: rank must be a multiple of 8 in [8, 64], factors present and aligned
     it = B.qail_w4a16_item(d, ok, ok, ok, ok, ok)
     its = (B.qail_w4a16_item * 1)(it)

@@ -19,6 +19,10 @@ def geom(s):
     return (s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad)
 
 
+def conv_fields(s):
+    return dict(B=s.B, H=s.H, W=s.W, Cin=s.Cin, Cout=s.Cout, KH=s.KH, KW=s.KW, stride=s.stride, pad=s.pad)
+
+
 def gpu_conv(B, s, a_words, w_words, scale=None, bias=None, want_acc=True):
     import torch
     acc = torch.full((s.M * s.Cout,), 0x55555555, dtype=torch.int32, device="cuda") if want_acc else None
@@ -238,13 +242,16 @@ def test_fused_output_feeds_the_next_layer(B):
     assert np.array_equal(host(acc2, np.int32).reshape(s2.M, s2.Cout), ref2)
 
 
-def test_chained_resnet34_body_bit_exact(B):
+@pytest.mark.parametrize("paired", [False, True])
+def test_chained_resnet34_body_bit_exact(B, paired):
     """The whole ResNet-34 body (16 residual blocks, 32 3x3 convolutions and the 3 projection
     shortcuts) chained on the 4-bit path at a small image: every convolution but the projections
     writes the next layer's packed codes, identity shortcuts come in as the block input's codes,
     projection shortcuts as fp32.  Every step of every tensor is fixed by the oracle's own chain
     (the largest pre-quantisation value / 15), so the GPU chain must reproduce the oracle's codes
-    bit for bit down to the last layer."""
+    bit for bit down to the last layer.  `paired`: the two convolutions that open a down-sampling
+    block (3x3 stride 2 with fused output, 1x1 projection with fp32 output; both read the block
+    input) go out as one qail_w4a4_conv_batch launch instead of two calls."""
     import torch
     Bn, H = 2, 16
     stages = [(64, 3), (128, 4), (256, 6), (512, 3)]
@@ -301,11 +308,21 @@ def test_chained_resnet34_body_bit_exact(B):
                                      res_scale=np.float32(s_in) if res_codes is not None else None, res_f32=res_f32)
             # ---- GPU: the same three or two calls
             g_mid = torch.zeros(c1.M * C // 8, dtype=torch.int32, device="cuda")
-            B.qail_w4a4_conv_u4(*geom(c1), g_codes, dev(w1), dev(sc1), dev(b1), float(s_mid), g_mid)
             g_out = torch.zeros(c2.M * C // 8, dtype=torch.int32, device="cuda")
-            if stride == 2:
+            if stride == 2 and paired:
                 g_res = torch.zeros(cd.M * C, dtype=torch.float32, device="cuda")
-                B.qail_w4a4_gemm(*geom(cd), g_codes, dev(wd), scale=dev(scd), bias=dev(bd), y_out=g_res)
+                keep = [dev(w1), dev(sc1), dev(b1), dev(wd), dev(scd), dev(bd)]
+                items = B.make_conv_items([
+                    dict(conv_fields(c1), a_u4=g_codes, w_s4=keep[0], scale=keep[1], bias=keep[2], out_u4=g_mid,
+                         s_out=float(s_mid)),
+                    dict(conv_fields(cd), a_u4=g_codes, w_s4=keep[3], scale=keep[4], bias=keep[5], y_out=g_res)])
+                B.qail_w4a4_conv_batch(items, 2)
+            else:
+                B.qail_w4a4_conv_u4(*geom(c1), g_codes, dev(w1), dev(sc1), dev(b1), float(s_mid), g_mid)
+            if stride == 2:
+                if not paired:
+                    g_res = torch.zeros(cd.M * C, dtype=torch.float32, device="cuda")
+                    B.qail_w4a4_gemm(*geom(cd), g_codes, dev(wd), scale=dev(scd), bias=dev(bd), y_out=g_res)
                 B.qail_w4a4_conv_u4(*geom(c2), g_mid, dev(w2), dev(sc2), dev(b2), float(s_out), g_out, res_f32=g_res)
             else:
                 B.qail_w4a4_conv_u4(*geom(c2), g_mid, dev(w2), dev(sc2), dev(b2), float(s_out), g_out,
@@ -316,6 +333,55 @@ def test_chained_resnet34_body_bit_exact(B):
             assert out.max() == 15 and mid.max() == 15       # the steps use the full code range
             codes, s_in, g_codes, Cin, H = out, s_out, g_out, C, Ho
     assert H == 2 and Cin == 512 and codes.any()
+
+
+BATCHES = [
+    # the two convolutions that open a down-sampling block (same input, same M and Cout)
+    [("u4", synth.ConvShape("p1", 2, 14, 14, 128, 256, 3, 3, 2, 1)), ("y", synth.ConvShape("p1d", 2, 14, 14, 128, 256, 1, 1, 2, 0))],
+    # different widths (the grid is as wide as the widest), different M, a ragged last tile, all three outputs
+    [("y", synth.ConvShape("q0", 1, 9, 9, 64, 200, 3, 3, 1, 1)), ("acc", synth.ConvShape("q1", 3, 6, 6, 128, 64, 1, 1, 2, 0)),
+     ("u4", synth.ConvShape("q2", 2, 12, 12, 192, 40, 3, 3, 1, 1)), ("res", synth.ConvShape("q3", 1, 8, 8, 64, 64, 3, 3, 1, 1))],
+    # more items than one launch takes, one of them a shape only the one-thread-per-output kernel runs
+    [("acc", synth.ConvShape("r0", 1, 6, 6, 64, 32, 3, 3, 1, 1)), ("y", synth.ConvShape("r1", 2, 5, 5, 8, 6, 3, 3, 1, 1)),
+     ("u4", synth.ConvShape("r2", 1, 6, 6, 64, 64, 3, 3, 2, 1)), ("acc", synth.ConvShape("r3", 1, 4, 4, 256, 512, 3, 3, 1, 1)),
+     ("y", synth.ConvShape("r4", 1, 7, 7, 512, 24, 1, 1, 1, 0)), ("u4", synth.ConvShape("r5", 2, 4, 4, 64, 8, 1, 1, 1, 0))],
+]
+
+
+@pytest.mark.parametrize("case", range(len(BATCHES)))
+def test_conv_batch_equals_single_calls(B, case):
+    """qail_w4a4_conv_batch: every item's result equals the single call's bit for bit (and the oracle's
+    accumulators), whatever shares the launch with it."""
+    import torch
+    entries, singles, keep = [], [], []
+    for i, (kind, s) in enumerate(BATCHES[case]):
+        aw, ww, scale, bias = quantised_inputs(s, 1300 + 10 * case + i)
+        t = dict(a=dev(aw), w=dev(ww), scale=dev(scale), bias=dev(bias))
+        keep.append(t)
+        e = dict(conv_fields(s), a_u4=t["a"], w_s4=t["w"])
+        if kind == "acc":
+            outs = [torch.full((s.M * s.Cout,), 0x55555555, dtype=torch.int32, device="cuda") for _ in range(2)]
+            e.update(acc_out=outs[0])
+            B.qail_w4a4_gemm(*geom(s), t["a"], t["w"], acc_out=outs[1])
+        elif kind == "y":
+            outs = [torch.full((s.M * s.Cout,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(2)]
+            e.update(scale=t["scale"], bias=t["bias"], y_out=outs[0])
+            B.qail_w4a4_gemm(*geom(s), t["a"], t["w"], scale=t["scale"], bias=t["bias"], y_out=outs[1])
+        else:
+            outs = [torch.full((s.M * s.Cout // 8,), 0x55555555, dtype=torch.int32, device="cuda") for _ in range(2)]
+            res = t["a"] if kind == "res" else None   # identity shortcut: Cin == Cout, stride 1
+            e.update(scale=t["scale"], bias=t["bias"], out_u4=outs[0], s_out=0.21, res_u4=res, res_scale=0.07)
+            B.qail_w4a4_conv_u4(*geom(s), t["a"], t["w"], t["scale"], t["bias"], 0.21, outs[1], res_u4=res, res_scale=0.07)
+        entries.append(e)
+        singles.append((kind, s, outs, aw, ww))
+    items = B.make_conv_items(entries)
+    B.qail_w4a4_conv_batch(items, len(entries))
+    torch.cuda.synchronize()
+    for kind, s, outs, aw, ww in singles:
+        got, ref = host(outs[0], np.uint32), host(outs[1], np.uint32)
+        assert np.array_equal(got, ref), (kind, s.name)
+        if kind == "acc":
+            assert np.array_equal(got.view(np.int32).reshape(s.M, s.Cout), O.w4a4_conv_acc(aw, ww, *geom(s))), s.name
 
 
 @pytest.mark.parametrize("batch", [32, 256])
