@@ -45,6 +45,14 @@ def test_replays_match_eager(B):
     a = dev(rng.integers(0, 2 ** 32, size=s.B * s.H * s.W * s.Cin // 8, dtype=np.uint64).astype(np.uint32))
     ww = dev(rng.integers(0, 2 ** 32, size=s.Cout * s.K // 8, dtype=np.uint64).astype(np.uint32))
     acc = torch.zeros(s.M * s.Cout, dtype=torch.int32, device="cuda")
+    # two convolutions on the same input in one launch: a fused 4-bit output and an int32 output
+    acc2 = torch.zeros(s.M * s.Cout, dtype=torch.int32, device="cuda")
+    u4 = torch.zeros(s.M * s.Cout // 8, dtype=torch.int32, device="cuda")
+    cscale = torch.full((s.Cout,), 2e-3, dtype=torch.float32, device="cuda")
+    cbias = torch.zeros(s.Cout, dtype=torch.float32, device="cuda")
+    cf = dict(B=s.B, H=s.H, W=s.W, Cin=s.Cin, Cout=s.Cout, KH=s.KH, KW=s.KW, stride=s.stride, pad=s.pad)
+    citems = B.make_conv_items([dict(cf, a_u4=a, w_s4=ww, scale=cscale, bias=cbias, out_u4=u4, s_out=0.3),
+                                dict(cf, a_u4=a, w_s4=ww, acc_out=acc2)])
 
     # three linears of the matrix-core path in one batched call (they share launches), and an 8-bit batch
     bat = [_linear_case(B, 300, 4096, 128, 40, 21), _linear_case(B, 96, 11008, 128, 40, 22),
@@ -78,11 +86,12 @@ def test_replays_match_eager(B):
         for M8, (_, it8, ws8) in w8m.items():
             B.qail_w8a16_linear_batch(it8, 2, M8, ws8)
         B.qail_w4a4_gemm(s.B, s.H, s.W, s.Cin, s.Cout, s.KH, s.KW, s.stride, s.pad, a, ww, acc_out=acc)
+        B.qail_w4a4_conv_batch(citems, 2)
 
     def snapshot():
         torch.cuda.synchronize()
         return ([host(t["y"], np.uint16).copy() for t in lin + bat] + [host(e["y"], np.uint16).copy() for e in w8] +
-                [host(e["y"], np.uint16).copy() for ents8, _, _ in w8m.values() for e in ents8] + [host(acc, np.int32).copy()])
+                [host(e["y"], np.uint16).copy() for ents8, _, _ in w8m.values() for e in ents8] + [host(acc, np.int32).copy(), host(acc2, np.int32).copy(), host(u4, np.int32).copy()])
 
     def clear():
         for t in lin + bat:
@@ -90,6 +99,8 @@ def test_replays_match_eager(B):
         for e in w8 + [e for ents8, _, _ in w8m.values() for e in ents8]:
             e["y"].fill_(0x7FC0)
         acc.fill_(-1)
+        acc2.fill_(-1)
+        u4.fill_(-1)
 
     gs = torch.cuda.Stream()
     with torch.cuda.stream(gs):
