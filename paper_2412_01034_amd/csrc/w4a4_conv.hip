@@ -114,20 +114,30 @@ __device__ __forceinline__ float fused_value(int acc, float scale, float bias, f
     t = t + r;
     return fmaxf(t, 0.f);
 }
-__device__ __forceinline__ uint32_t fused_code(float t, float s_out) {
-    const float q = __builtin_rintf(t / s_out);
-    return (uint32_t)fminf(q, 15.f);
+__device__ __forceinline__ float fused_code(float t, float s_out) {
+    return fminf(__builtin_rintf(t / s_out), 15.f);
 }
 // The same code without the division wherever that is provably the same: u = t * fl(1 / s) is
 // within 1.5 * 2^-23 (relative) of fl(t / s), so below 16 the two differ by less than 2^-18 and
-// round to the same integer unless u lies within 2^-17 of a half-integer (`doubt`; the caller
-// then divides).  From 15.6 upwards both round to 16 or more and the code is 15 either way.
-__device__ __forceinline__ uint32_t fused_code_quick(float t, float inv_s, bool& doubt) {
+// round to the same integer unless u lies within 2^-17 of a half-integer, i.e. |u - rint(u)|
+// (an exact difference) exceeds 1/2 - 2^-17; `worst` keeps the largest such distance of a word and
+// the caller divides when it is that large.  From 15.6 upwards both round to 16 or more and the
+// code is 15 either way.  (The ReLU stays in front of the quotient: behind it, one median-of-three
+// would do for both clamps, but negative values would then reach the tie test, and with round
+// steps, where ties are exact and common, nearly every wave would divide.)
+__device__ __forceinline__ float fused_code_quick(float t, float inv_s, float& worst) {
 #pragma clang fp contract(off)
     const float u = t * inv_s;
     const float q = __builtin_rintf(u);
-    doubt = doubt || (__builtin_fabsf(__builtin_fabsf(u - q) - 0.5f) < 0x1p-17f);
-    return (uint32_t)fminf(q, 15.f);
+    worst = fmaxf(worst, __builtin_fabsf(u - q));
+    return fminf(q, 15.f);
+}
+// Eight codes (small non-negative integers held as floats) -> one packed word, code e in nibble e.
+__device__ __forceinline__ uint32_t pack_codes(const float (&q)[8]) {
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) word |= (uint32_t)q[e] << (4 * e);
+    return word;
 }
 
 // 8 consecutive channels of one output pixel -> one packed word; sc / bi: their scales and
@@ -137,16 +147,15 @@ __device__ __forceinline__ uint32_t fused_pack(const int (&acc)[8], const float 
     float t[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) t[e] = fused_value(acc[e], sc[e], bi[e], r[e]);
-    uint32_t word = 0;
-    bool doubt = !o.quick;
+    float q[8];
+    float worst = o.quick ? 0.f : 1.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) word |= fused_code_quick(t[e], o.inv_s_out, doubt) << (4 * e);
-    if (__builtin_expect(doubt, 0)) {
-        word = 0;
+    for (int e = 0; e < 8; ++e) q[e] = fused_code_quick(t[e], o.inv_s_out, worst);
+    if (__builtin_expect(!(worst <= 0.5f - 0x1p-17f), 0)) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) word |= fused_code(t[e], o.s_out) << (4 * e);
+        for (int e = 0; e < 8; ++e) q[e] = fused_code(t[e], o.s_out);
     }
-    return word;
+    return pack_codes(q);
 }
 __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
     const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
