@@ -731,7 +731,7 @@ void choose_tile(const GemmArgs& ga, int cus, bool alone, bool narrow_only, int*
     //     K steps only when it is short (a fuller one is cheaper left as it is: blocks that
     //     share tiles pay for slots and a second kernel, and a chip that is not full clocks higher);
     //   * between half a round and a round of wide tiles: wide tiles, whole;
-    //   * less: narrow tiles (twice as many), dealt in K steps when K is long.
+    //   * less: narrow tiles (twice as many), dealt in K steps when K is long or the tiles are few.
     // A linear that shares the launch with others has only its share of the blocks, which it must
     // keep busy to the end because the others cannot use them: less than a round of wide tiles is
     // dealt in K steps, and as narrow tiles when M is a single tile high (measured 3-6 % faster than
@@ -749,7 +749,10 @@ void choose_tile(const GemmArgs& ga, int cus, bool alone, bool narrow_only, int*
         split = true;
     } else if (t2 * 2 <= cus) {
         wn = 1;
-        split = ga.Kpad / kBK >= 64;
+        // in K steps when K is long, or when whole narrow tiles would leave half of the CUs idle
+        // (measured on single linears at M = 48 .. 288: the out projection 27 -> 19 us at M = 64,
+        // 37 -> 25 us at M = 128; with more tiles than that the shared tiles cost more than they give)
+        split = ga.Kpad / kBK >= 64 || (t2 * 4 <= cus && ga.Kpad / kBK >= 16);
     }
     *wn_out = wn;
     *split_out = split;
