@@ -259,8 +259,21 @@ constexpr int kStages = 3;
 // s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt untouched.
 __host__ __device__ constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
-template <int MB, int WN, int kBits>
-__global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch args) {
+//
+// LW > 0: LW more waves per block that only load.  The first LW - LW / 2 of them share the x tile loads
+// of a step, the other LW / 2 the weight loads (for all four column groups, with the addresses the
+// owning lanes would use); each waits for the step that is due and meets the four MFMA waves at the
+// step's barrier.  The MFMA waves then issue no memory instruction in the K loop: with one wave per
+// SIMD every load instruction otherwise sits in the same instruction stream as the MFMAs it delays.
+// A second wave on a SIMD halves the registers a wave may have (256), which the 128 x 256 tile just
+// fits.  Measured on a decoder layer's four linears with nibble weights: three loading waves (two for
+// x, one for the weights) are 4-9 % faster than none at every M from 33 to 2048; two are as good on
+// 96-row tiles and much slower on 128-row ones (32 x loads per step from one wave), four are slower
+// than three (a loading wave on every SIMD).
+template <int MB, int WN, int kBits, int LW>
+__global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const GemmBatch args) {
+    static_assert(LW == 0 || LW == 2 || LW == 3 || LW == 4, "no loader waves, or LW - LW / 2 for x and LW / 2 for the weights");
+    constexpr int kThreads = 256 + 64 * LW;
     constexpr int kBM = 32 * MB;
     constexpr int kBN = 128 * WN;
     constexpr int kALoads = kBM / 16;             // wave-wide 1 KB loads per wave per step
@@ -275,6 +288,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
     const int lane = t % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(t / kWave);
     const int c = lane & 31, kb = lane >> 5;
+    const bool loader = LW > 0 && wave >= 4;   // wave-uniform
     int item = 0;
 #pragma unroll
     for (int i = 1; i < kGemmBatch; ++i)
@@ -319,9 +333,10 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
     // below 4 GB (checked by the host), so addresses are a uniform base plus a 32-bit offset.
     uint32_t qoff[WN], soff[WN], zoff[WN];
     float winv[WN];
+    const int cwave = LW > 0 ? (wave & 3) : wave;   // (a loader's own values of these are not used)
 #pragma unroll
     for (int j = 0; j < WN; ++j) {
-        const int n = min(bn + (wave * WN + j) * 32 + c, ga.N - 1);
+        const int n = min(bn + (cwave * WN + j) * 32 + c, ga.N - 1);
         qoff[j] = (uint32_t)n * (uint32_t)kw * 4u;
         soff[j] = (uint32_t)n * (uint32_t)G * 2u;
         zoff[j] = (uint32_t)n * (uint32_t)zwords * 4u;
@@ -347,9 +362,8 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
     uint32_t pk0b = 0;                    // x: byte offset of the step inside a row
     uint32_t pq[WN], ps[WN], pz[WN];      // weights: byte offsets of codes, scale word, zero word
     // fragment read offsets of this lane for the 8 sub-steps (row c of a 32-row block)
-    int aoff[8];
-#pragma unroll
-    for (int jj = 0; jj < 8; ++jj) aoff[jj] = c * 256 + (((8 * kb + jj) ^ (c & 15)) << 4);
+    // (sub-step jj < 8 only touches the low three bits of the chunk index, so it folds in by an XOR)
+    const int aoff0 = c * 256 + (((8 * kb) ^ (c & 15)) << 4);
 
     // Weight loader: the lane's 64 k of a step (two 16-byte pieces per column block) plus the
     // 4-byte words holding its group's scale and zero-point, again through the load unit into
@@ -385,10 +399,10 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
     };
     auto issue = [&](int i, int slot) {
         if (i < kALoads) {
-            dma16(xbase, xoff0 + i * xstride + pk0b, as_lds + slot * kBufBytes + (i * 256 + wave * 64) * 16);
+            dma16(xbase, xoff0 + i * xstride + pk0b, as_lds + slot * kBufBytes + (i * 256 + cwave * 64) * 16);
         } else {
             const int j = (i - kALoads) / kBParts, part = (i - kALoads) % kBParts;
-            const uint32_t dst = as_lds + kStages * kBufBytes + slot * kBStage + (wave * WN + j) * kBLane;
+            const uint32_t dst = as_lds + kStages * kBufBytes + slot * kBStage + (cwave * WN + j) * kBLane;
             if (part < kCodeLoads) dma16(qbase, pq[j] + 16 * part, dst + 1024 * part);
             if (part == kCodeLoads) dma4(sbase, ps[j], dst + kCodeLoads * 1024);
             if (part == kCodeLoads + 1) dma4(zbase, pz[j], dst + kCodeLoads * 1024 + 256);
@@ -404,7 +418,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
         const uint32_t grp = v ? (uint32_t)cgrp : 0u;
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
-            const unsigned char* src = Bs + stage * kBStage + (wave * WN + j) * kBLane;
+            const unsigned char* src = Bs + stage * kBStage + (cwave * WN + j) * kBLane;
 #pragma unroll
             for (int pc = 0; pc < kCodeLoads; ++pc) {
                 const u32x4_t v = *reinterpret_cast<const u32x4_t*>(src + pc * 1024 + lane * 16);
@@ -444,7 +458,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
     auto fetch = [&](int stage, int jj, int slot) {
 #pragma unroll
         for (int i = 0; i < MB; ++i)
-            af[slot][i] = *reinterpret_cast<const f16x8_t*>(As + stage * kBufBytes + i * (32 * 256) + aoff[jj]);
+            af[slot][i] = *reinterpret_cast<const f16x8_t*>(As + stage * kBufBytes + i * (32 * 256) + (aoff0 ^ (jj << 4)));
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             if constexpr (kBits == 4)
@@ -469,15 +483,97 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
         }
     };
 
+    if (loader) {
+        // ---- the loading waves: one barrier after the first step has landed, then one per step, as
+        // the MFMA waves have them.  The first LW / 2 of them share the x tile: load q fills rows
+        // 4 q + lane / 16 (chunk lane % 16 of the row at its swizzled position) and wave i takes the
+        // loads q = i mod LW / 2.  The others share the 4 WN column blocks the same way: codes, scale
+        // words and zero words, each lane with the offsets of the lane that will read them.
+        constexpr int kXW = LW > 0 ? (LW + 1) / 2 : 1;   // waves sharing the x tile (LW = 0: this branch is never taken)
+        constexpr int kWW = LW > 1 ? LW / 2 : 1;         // waves sharing the weights
+        constexpr int kXLoads = kBM / 4 / kXW;           // per x wave and step
+        constexpr int kWBlocks = 4 * WN / kWW;           // column blocks per weight wave
+        constexpr int kWLoads = kWBlocks * kBParts;      // per weight wave and step
+        static_assert(kBM / 4 % kXW == 0 && 4 % kXW == 0 && 4 * WN % kWW == 0, "loads divide evenly");
+        static_assert(2 * kXLoads <= 64 && 2 * kWLoads <= 64, "two steps in flight fit the load counter (a 64th load only waits for the oldest)");
+        const bool xwave = wave < 4 + kXW;
+        const int share = xwave ? wave - 4 : wave - 4 - kXW;   // which of the waves of its kind
+        const int lr = lane >> 4, lp = lane & 15;
+        const uint32_t pitchb = (uint32_t)ga.Kpad * 2u;
+        const uint32_t xrow0 = (uint32_t)(bm + 4 * share + lr) * pitchb;
+        uint32_t xsw[4 / kXW];                           // swizzled chunk of load qq (period 4 rows x 4 loads)
+#pragma unroll
+        for (int qm = 0; qm < 4 / kXW; ++qm) xsw[qm] = (uint32_t)((lp ^ ((4 * (kXW * qm + share) + lr) & 15)) * 16);
+        uint32_t qo[kWBlocks], so[kWBlocks], zo[kWBlocks];
+#pragma unroll
+        for (int mm = 0; mm < kWBlocks; ++mm) {
+            const int n = min(bn + (kWW * mm + share) * 32 + c, ga.N - 1);
+            qo[mm] = (uint32_t)n * (uint32_t)kw * 4u;
+            so[mm] = (uint32_t)n * (uint32_t)G * 2u;
+            zo[mm] = (uint32_t)n * (uint32_t)zwords * 4u;
+        }
+        int lk = ka * kBK + 64 * kb, lgrp = lk / ga.g, lkin = lk - lgrp * ga.g;
+        int pstep = ka;
+        auto load_step = [&](int slot) {
+            const uint32_t slot_x = as_lds + (uint32_t)slot * kBufBytes + (uint32_t)share * 1024u;
+            const uint32_t slot_w = as_lds + kStages * kBufBytes + (uint32_t)slot * kBStage + (uint32_t)share * kBLane;
+            if (xwave) {
+                const uint32_t k0b = (uint32_t)(min(pstep, ga.steps - 1) * kBK) * 2u;
+#pragma unroll
+                for (int qq = 0; qq < kXLoads; ++qq)
+                    dma16(xbase, xrow0 + (uint32_t)(qq * kXW) * 4u * pitchb + xsw[qq % (4 / kXW)] + k0b,
+                          slot_x + qq * kXW * 1024);
+            } else {
+                const bool v = lk < ga.K;
+                const uint32_t kc = v ? (uint32_t)lk : 0u;
+                const uint32_t grp = v ? (uint32_t)lgrp : 0u;
+#pragma unroll
+                for (int mm = 0; mm < kWBlocks; ++mm) {
+                    const uint32_t dst = slot_w + mm * kWW * kBLane;
+#pragma unroll
+                    for (int part = 0; part < kCodeLoads; ++part)
+                        dma16(qbase, qo[mm] + kc * kBits / 8 + 16 * part, dst + 1024 * part);
+                    dma4(sbase, (so[mm] + grp * 2u) & ~3u, dst + kCodeLoads * 1024);
+                    if (kBits == 4) dma4(zbase, zo[mm] + (grp / 8u) * 4u, dst + kCodeLoads * 1024 + 256);
+                }
+            }
+            ++pstep;
+            lk += kBK;
+            lkin += kBK;
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int over = lkin >= ga.g;
+                lkin -= over * ga.g;
+                lgrp += over;
+            }
+        };
+        load_step(0);
+        load_step(1);
+        // in flight: steps 0 and 1; step 0 has to be complete
+        if (xwave) __builtin_amdgcn_s_waitcnt(waitcnt_vm(kXLoads));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_vm(kWLoads));
+        __syncthreads();
+        int fill = 2;
+        for (int s = 0; s < steps; ++s) {
+            // slot `fill` held step s - 1 and is free since the previous barrier
+            load_step(fill);
+            fill = fill == 2 ? 0 : fill + 1;
+            if (xwave) __builtin_amdgcn_s_waitcnt(waitcnt_vm(kXLoads));
+            else __builtin_amdgcn_s_waitcnt(waitcnt_vm(kWLoads));
+            __syncthreads();
+        }
+    } else {
     // steps 0 and 1 are loaded up front; from then on step s + 2 is loaded during step s
+    if constexpr (LW == 0) {
 #pragma unroll
-    for (int p = 0; p < kStages - 1; ++p) {
-        plan();
+        for (int p = 0; p < kStages - 1; ++p) {
+            plan();
 #pragma unroll
-        for (int i = 0; i < kStepLoads; ++i) issue(i, p);
-        __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < kStepLoads; ++i) issue(i, p);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(kStepLoads));
     }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kStepLoads));
     __syncthreads();
     take(0);
     fetch(0, 0, 0);
@@ -488,23 +584,25 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
             if (s0 + u >= steps) break;
             const int cur = u, nxt = (u + 1) % kStages, fill = (u + 2) % kStages;
             // slot `fill` held step s - 1 and is free since the previous barrier
-            plan();
+            if constexpr (LW == 0) plan();
 #pragma unroll
             for (int jj = 0; jj < 7; ++jj) {
                 __builtin_amdgcn_sched_barrier(0);
                 fetch(cur, jj + 1, (jj + 1) & 1);
                 multiply(jj & 1);
                 __builtin_amdgcn_sched_barrier(0);
+                if constexpr (LW == 0) {
 #pragma unroll
-                for (int i = 0; i < kStepLoads; ++i)
-                    if (i * 7 / kStepLoads == jj) issue(i, fill);
+                    for (int i = 0; i < kStepLoads; ++i)
+                        if (i * 7 / kStepLoads == jj) issue(i, fill);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
             // In flight: step s+1 (issued during step s-1) and step s+2 (just issued).  Step
             // s+1 has to be complete; the wait also covers this wave's LDS reads (lgkmcnt 0),
             // so after the barrier slot `cur` is dead for everyone once sub-step 7 is done
             // (its operands are already in registers).
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(kStepLoads));
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(LW == 0 ? kStepLoads : 0));
             __syncthreads();
             take(nxt);
             __builtin_amdgcn_sched_barrier(0);
@@ -512,6 +610,7 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
             multiply(1);
         }
     }
+    }  // MFMA waves
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // nothing may still be writing LDS
     __syncthreads();
@@ -521,16 +620,18 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
         // through LDS so that they leave as 16-byte pieces of full lines
         constexpr int kPPitch = kBN + 4;  // floats per staged row
         static_assert(kBM * kPPitch * 4 <= kStages * (kBufBytes + 4 * WN * kBLane), "the fp32 tile fits in the ring");
-        float* const stage = reinterpret_cast<float*>(As) + (4 * kb) * kPPitch + wave * WN * 32 + c;
+        float* const stage = reinterpret_cast<float*>(As) + (4 * kb) * kPPitch + cwave * WN * 32 + c;
+        if (!loader) {
 #pragma unroll
-        for (int j = 0; j < WN; ++j)
+            for (int j = 0; j < WN; ++j)
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
+                for (int i = 0; i < MB; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    stage[(i * 32 + 8 * (r / 4) + (r % 4)) * kPPitch + j * 32] = acc[i][j][r];
+                    for (int r = 0; r < 16; ++r)
+                        stage[(i * 32 + 8 * (r / 4) + (r % 4)) * kPPitch + j * 32] = acc[i][j][r];
+        }
         __syncthreads();
-        for (int idx = t; idx < kBM * (kBN / 4); idx += 256) {
+        for (int idx = t; idx < kBM * (kBN / 4); idx += kThreads) {
             const int row = idx / (kBN / 4), c4 = idx % (kBN / 4);
             *reinterpret_cast<f32x4_t*>(pslot + row * kBN + c4 * 4) =
                 *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(As) + row * kPPitch + c4 * 4);
@@ -542,9 +643,10 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
     }
     // y = acc * 2^-p(m) * 2^E(n), rounded once to bf16, staged in LDS so that rows leave as
     // 16-byte pieces of full lines.
+    if (!loader) {
     float wm[WN];
 #pragma unroll
-    for (int j = 0; j < WN; ++j) wm[j] = ga.wmul[min(bn + (wave * WN + j) * 32 + c, ga.N - 1)];
+    for (int j = 0; j < WN; ++j) wm[j] = ga.wmul[min(bn + (cwave * WN + j) * 32 + c, ga.N - 1)];
     // the row factors of the lane's 16 MB rows, four neighbouring rows per load, all requested before
     // the first is used (fetched where they are used, each load waited for the one before it: 4 MB
     // round trips per tile)
@@ -563,16 +665,17 @@ __global__ __launch_bounds__(256) void w4a16_gemm_f16_kernel(const GemmBatch arg
             const float rs0 = rsv[i][r / 4][r % 4], rs1 = rsv[i][r / 4][r % 4 + 1];
 #pragma unroll
             for (int j = 0; j < WN; ++j) {
-                const int col = (wave * WN + j) * 32 + c;
+                const int col = (cwave * WN + j) * 32 + c;
                 const uint32_t h = f32x2_to_bf16x2_rne(acc[i][j][r] * rs0 * wm[j], acc[i][j][r + 1] * rs1 * wm[j]);
                 *reinterpret_cast<uint16_t*>(As + row * kCPitch + col * 2) = (uint16_t)h;
                 *reinterpret_cast<uint16_t*>(As + (row + 1) * kCPitch + col * 2) = (uint16_t)(h >> 16);
             }
         }
+    }
     __syncthreads();
     constexpr int kChunks = kBN / 8;  // 16-byte pieces per row
     const bool vec_ok = (ga.N % 8) == 0;
-    for (int idx = t; idx < kBM * kChunks; idx += 256) {
+    for (int idx = t; idx < kBM * kChunks; idx += kThreads) {
         const int row = idx / kChunks, ch = idx % kChunks;
         const int m = bm + row, n = bn + ch * 8;
         if (m >= ga.M || n >= ga.N) continue;
@@ -676,7 +779,9 @@ int plan_tiles(GemmArgs& ga, bool split_tail, int cus) {
 }
 
 // One launch for `n` linears that use the same tile, each on its own blocks (ga[i].block_begin, P set).
-template <int MB, int WN, int kBits>
+// Loading waves per block (see the kernel), by code width.
+constexpr int kLoaderWaves4 = 3, kLoaderWaves8 = 0;
+template <int MB, int WN, int kBits, int LW = (kBits == 4 ? kLoaderWaves4 : kLoaderWaves8)>
 hipError_t launch_tile(const GemmArgs* gas, int n, hipStream_t st) {
     constexpr int kBM = 32 * MB, kBN = 128 * WN;
     const size_t lds = (size_t)kStages * (kBM * 256 + 4 * WN * ((kBits == 4 ? 2 : 4) * 1024 + 512));
@@ -684,7 +789,7 @@ hipError_t launch_tile(const GemmArgs* gas, int n, hipStream_t st) {
     // both find the flag clear may both make it
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_gemm_f16_kernel<MB, WN, kBits>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_gemm_f16_kernel<MB, WN, kBits, LW>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set.store(true, std::memory_order_release);
@@ -704,7 +809,7 @@ hipError_t launch_tile(const GemmArgs* gas, int n, hipStream_t st) {
         }
     }
     gb.count = n;
-    hipLaunchKernelGGL((w4a16_gemm_f16_kernel<MB, WN, kBits>), dim3(grid), dim3(256), lds, st, gb);
+    hipLaunchKernelGGL((w4a16_gemm_f16_kernel<MB, WN, kBits, LW>), dim3(grid), dim3(256 + 64 * LW), lds, st, gb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (max_tail > 0) {
