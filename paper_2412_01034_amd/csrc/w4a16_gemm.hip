@@ -409,13 +409,15 @@ __global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const Gem
         }
     };
 
-    // operands of the step being multiplied; ck / cgrp follow the consumed steps like lk / lgrp
+    // operands of the step being multiplied; ck / cgrp follow the consumed steps like lk / lgrp.
+    // A step's codes, scale word and zero word are read back from the per-lane FIFO (take_read) and
+    // turned into the expansion's constants (take_convert) in two parts, so that the reads can be in
+    // flight, and the conversions issue, under the MFMAs of the previous step's last sub-step.
     uint32_t wq[WN][4 * kCodeLoads];
+    uint32_t tsw[WN], tzw[WN];
     f16x2_t nz[WN], nz6[WN], s2[WN];
     int ck = ka * kBK + 64 * kb, cgrp = ck / ga.g, ckin = ck - cgrp * ga.g;
-    auto take = [&](int stage) {
-        const bool v = ck < ga.K;
-        const uint32_t grp = v ? (uint32_t)cgrp : 0u;
+    auto take_read = [&](int stage) {
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const unsigned char* src = Bs + stage * kBStage + (cwave * WN + j) * kBLane;
@@ -424,13 +426,24 @@ __global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const Gem
                 const u32x4_t v = *reinterpret_cast<const u32x4_t*>(src + pc * 1024 + lane * 16);
                 wq[j][4 * pc] = v.x; wq[j][4 * pc + 1] = v.y; wq[j][4 * pc + 2] = v.z; wq[j][4 * pc + 3] = v.w;
             }
-            const uint32_t sword = *reinterpret_cast<const uint32_t*>(src + kCodeLoads * 1024 + lane * 4);
-            const uint32_t zword = kBits == 4 ? *reinterpret_cast<const uint32_t*>(src + kCodeLoads * 1024 + 256 + lane * 4) : 0u;
+            tsw[j] = *reinterpret_cast<const uint32_t*>(src + kCodeLoads * 1024 + lane * 4);
+            tzw[j] = kBits == 4 ? *reinterpret_cast<const uint32_t*>(src + kCodeLoads * 1024 + 256 + lane * 4) : 0u;
+        }
+    };
+    auto take_convert = [&]() {
+        const bool v = ck < ga.K;
+        const uint32_t grp = v ? (uint32_t)cgrp : 0u;
+        // past the end of K the scale becomes 0 by a factor, in a register: as a conditional value the
+        // compiler turns it into a masked section, which nothing can be scheduled across
+        float live = v ? 1.f : 0.f;
+        asm volatile("" : "+v"(live));
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
             // the scale's 2 bytes inside the aligned word that was fetched
-            const uint32_t sbits = (sword >> (8u * ((soff[j] + grp * 2u) & 2u))) & 0xFFFFu;
+            const uint32_t sbits = (tsw[j] >> (8u * ((soff[j] + grp * 2u) & 2u))) & 0xFFFFu;
             const float sf = (float)__builtin_bit_cast(_Float16, (uint16_t)sbits);
-            const float z = kBits == 4 ? (float)((zword >> (4u * (grp & 7u))) & 0xFu) : 128.f;   // bytes: the flip's 128
-            const _Float16 srel = v ? (_Float16)(sf * winv[j]) : (_Float16)0.f;
+            const float z = kBits == 4 ? (float)((tzw[j] >> (4u * (grp & 7u))) & 0xFu) : 128.f;   // bytes: the flip's 128
+            const _Float16 srel = (_Float16)(sf * (winv[j] * live));
             const _Float16 a = (_Float16)(-1024.f - z), b = (_Float16)(-64.f - z);
             nz[j] = f16x2_t{a, a};
             nz6[j] = f16x2_t{b, b};
@@ -575,7 +588,8 @@ __global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const Gem
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(kStepLoads));
     }
     __syncthreads();
-    take(0);
+    take_read(0);
+    take_convert();
     fetch(0, 0, 0);
 
     for (int s0 = 0; s0 < steps; s0 += kStages) {
@@ -604,10 +618,29 @@ __global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const Gem
             // (its operands are already in registers).
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(LW == 0 ? kStepLoads : 0));
             __syncthreads();
-            take(nxt);
             __builtin_amdgcn_sched_barrier(0);
+            // Sub-step 7 of this step (operands already in registers) with the next step's set-up under
+            // it: all LDS reads first (FIFO and A fragments), a few MFMAs while they are in flight, then
+            // the conversions and the first expansion shared out among the remaining MFMAs.
+            take_read(nxt);
+            take_convert();
             fetch(nxt, 0, 0);
-            multiply(1);
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[1][i], bf[1][j], acc[i][j], 0, 0, 0);
+            constexpr int kLead = MB * WN < 4 ? 1 : 3;                     // MFMAs issued before any conversion
+            constexpr int kSetupValu = (kBits == 4 ? 13 + 16 : 14 + 12) * WN + 8;
+            __builtin_amdgcn_sched_group_barrier(0x100, WN * (kCodeLoads + 2) + MB, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, kLead, 0);
+            if constexpr (MB * WN > kLead) {
+#pragma unroll
+                for (int u = 0; u < MB * WN - kLead; ++u) {
+                    __builtin_amdgcn_sched_group_barrier(0x002, (kSetupValu + MB * WN - kLead - 1) / (MB * WN - kLead), 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+            }
         }
     }
     }  // MFMA waves
