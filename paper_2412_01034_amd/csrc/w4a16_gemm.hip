@@ -94,8 +94,26 @@ __global__ __launch_bounds__(256) void gemm_prep_kernel(const PrepBatch args) {
             return;
         }
         const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)m * K);
+        // the row is read once: a thread keeps its pieces (up to kKeep of them: rows up to 2048 kKeep long) in
+        // registers between the search for the largest magnitude and the rewrite; longer rows are read again
+        constexpr int kKeep = 6;
+        uint4 keep[kKeep];
         uint32_t mx = 0;  // largest magnitude bit pattern (order-preserving for bf16 magnitudes)
-        for (int i = t; i < K / 8; i += 256) {
+#pragma unroll
+        for (int r = 0; r < kKeep; ++r) {
+            const int i = t + 256 * r;
+            keep[r] = i < K / 8 ? src[i] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < kKeep; ++r) {
+            const uint32_t w[4] = {keep[r].x, keep[r].y, keep[r].z, keep[r].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                mx = max(mx, w[j] & 0x7FFFu);
+                mx = max(mx, (w[j] >> 16) & 0x7FFFu);
+            }
+        }
+        for (int i = t + 256 * kKeep; i < K / 8; i += 256) {
             const uint4 v = src[i];
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -115,23 +133,26 @@ __global__ __launch_bounds__(256) void gemm_prep_kernel(const PrepBatch args) {
         p = p > 126 ? 126 : (p < -126 ? -126 : p);
         const float up = __builtin_bit_cast(float, (uint32_t)(127 + p) << 23);
         if (t == 0) rscale[m] = __builtin_bit_cast(float, (uint32_t)(127 - p) << 23);
-        for (int i = t; i < Kpad / 8; i += 256) {
-            uint4 o = make_uint4(0, 0, 0, 0);
-            if (i < K / 8) {
-                const uint4 v = src[i];
-                const uint16_t b[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
-                                       (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
-                uint32_t h[8];
+        auto rewrite = [&](const uint4 v) {
+            const uint16_t b[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
+                                   (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
+            uint32_t h[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    h[j] = __builtin_bit_cast(uint16_t, (_Float16)(bf16_bits_to_f32(b[j]) * up));
-                // stored order inside the 8: 0,4,1,5,2,6,3,7 (4-bit codes) or as they are (8-bit codes)
-                o = args.natural
-                        ? make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16))
-                        : make_uint4(h[0] | (h[4] << 16), h[1] | (h[5] << 16), h[2] | (h[6] << 16), h[3] | (h[7] << 16));
-            }
-            dst[i] = o;
+            for (int j = 0; j < 8; ++j)
+                h[j] = __builtin_bit_cast(uint16_t, (_Float16)(bf16_bits_to_f32(b[j]) * up));
+            // stored order inside the 8: 0,4,1,5,2,6,3,7 (4-bit codes) or as they are (8-bit codes)
+            return args.natural
+                       ? make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16))
+                       : make_uint4(h[0] | (h[4] << 16), h[1] | (h[5] << 16), h[2] | (h[6] << 16), h[3] | (h[7] << 16));
+        };
+#pragma unroll
+        for (int r = 0; r < kKeep; ++r) {
+            const int i = t + 256 * r;
+            // (a kept piece past the end of the row is zero, and so is its rewrite: the padding up to Kpad)
+            if (i < Kpad / 8) dst[i] = rewrite(keep[r]);
         }
+        for (int i = t + 256 * kKeep; i < Kpad / 8; i += 256)
+            dst[i] = i < K / 8 ? rewrite(src[i]) : make_uint4(0, 0, 0, 0);
         return;
     }
     // 8 lanes per weight row, 32 rows per block
