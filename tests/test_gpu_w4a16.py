@@ -333,7 +333,7 @@ def test_full_size_decode_linears_one_call_each(B, M):
     _sampled_full_size(B, M, {}, batched=False)
 
 
-@pytest.mark.parametrize("M", [64, 288, 1024])      # 64: the benchmark's largest decode batch, on the matrix cores
+@pytest.mark.parametrize("M", [64, 288, 768, 1024])      # 64: the benchmark's largest decode batch, on the matrix cores; 768: six 128-row tiles per column in whole rounds
 def test_full_size_prefill_linears_sampled(B, M):
     _sampled_full_size(B, M, dict(outlier_frac=0.005))
 
