@@ -348,7 +348,19 @@ __global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const Gem
     }
     const bool whole = steps == ga.steps;
     float* const pslot = ga.partial + (size_t)(2 * bid + (first_shared ? 0 : 1)) * (kBM * kBN);
-    const int bm = (tile % ga.Tm) * kBM, bn = (tile / ga.Tm) * kBN;
+    int tm = tile % ga.Tm, tn = tile / ga.Tm;
+    // Whole tiles of a linear that is eight row tiles high: workgroups go to the eight XCDs (each with an
+    // L2 of its own) in turn, so in launch order the eight row tiles that share a weight tile would sit on
+    // eight XCDs and every L2 would fetch every weight column.  A round's P tiles (P / 8 columns) are
+    // dealt instead so that an XCD works on two row tiles (their x fits its L2) and on every other column:
+    // a weight tile is then fetched by four L2s, not eight.
+    if (ga.Tm == 8 && (P & 15) == 0 && (ga.block_begin & 7) == 0 && tile < ga.whole) {
+        const int round = tile / P, idx = tile - round * P;
+        const int xcd = idx & 7, j = idx >> 3;
+        tm = 2 * (xcd & 3) + (j & 1);
+        tn = round * (P >> 3) + 2 * (j >> 1) + (xcd >> 2);
+    }
+    const int bm = tm * kBM, bn = tn * kBN;
 
     // Byte offsets of this lane's weight rows (WN 32-column blocks).  All tensors here are
     // below 4 GB (checked by the host), so addresses are a uniform base plus a 32-bit offset.

@@ -338,6 +338,11 @@ def test_full_size_prefill_linears_sampled(B, M):
     _sampled_full_size(B, M, dict(outlier_frac=0.005))
 
 
+@pytest.mark.parametrize("M", [288, 1024])      # 1024: eight row tiles, whole tiles dealt to the XCDs two row tiles each
+def test_full_size_prefill_linears_one_call_each(B, M):
+    _sampled_full_size(B, M, dict(outlier_frac=0.005), batched=False)
+
+
 # ------------------------------------------------------------------ dependent linears in one launch
 
 def _chain_status(ws):
