@@ -326,7 +326,26 @@ __global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const Gem
     const long long units = (long long)(ga.tiles - ga.whole) * ga.steps;
     const int unit0 = (int)first_unit(bid, units, P);
     const int unit1 = (int)first_unit(bid + 1, units, P);
-    int wtile = bid, unit = unit0;
+    // Whole tiles are numbered with m running fastest, so consecutive tiles share their weight columns.
+    // Where the x of all row tiles fits an L2 beside the weights passing through (2.5 MB), the blocks of
+    // an XCD take consecutive tiles: workgroup b of the launch runs on XCD b mod 8, so this block's rank
+    // among its linear's blocks is counted XCD by XCD.  A weight tile is then fetched by one or two L2s
+    // instead of one per row tile.  Measured on a decoder layer's four linears as one launch: 2 % faster
+    // with three row tiles (M = 272, 288), 3-5 % slower with two (M = 160 .. 256), which stay as they
+    // were.  (Taller linears: see the dealing of eight row tiles below.)
+    int vbid = bid;
+    const bool x_fits_l2 = ga.Tm >= 3 && (long long)ga.Tm * kBM * ga.Kpad * 2 <= 2560 * 1024;
+    if (x_fits_l2) {
+        const int q = ga.block_begin & 7, mine = (q + bid) & 7;
+        int before = 0;
+        for (int x = 0; x < 8; ++x) {
+            const int first = (x - q) & 7;   // the first of the linear's blocks on XCD x
+            const int count = first < P ? (P - first + 7) >> 3 : 0;
+            if (x < mine) before += count;
+        }
+        vbid = before + ((bid - ((mine - q) & 7)) >> 3);
+    }
+    int wtile = vbid, unit = unit0;
     for (;;) {
     // ---- one segment: K steps [ka, ka + steps) of one tile
     int tile, ka, steps;
@@ -354,7 +373,7 @@ __global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const Gem
     // eight XCDs and every L2 would fetch every weight column.  A round's P tiles (P / 8 columns) are
     // dealt instead so that an XCD works on two row tiles (their x fits its L2) and on every other column:
     // a weight tile is then fetched by four L2s, not eight.
-    if (ga.Tm == 8 && (P & 15) == 0 && (ga.block_begin & 7) == 0 && tile < ga.whole) {
+    if (ga.Tm == 8 && !x_fits_l2 && (P & 15) == 0 && (ga.block_begin & 7) == 0 && tile < ga.whole) {
         const int round = tile / P, idx = tile - round * P;
         const int xcd = idx & 7, j = idx >> 3;
         tm = 2 * (xcd & 3) + (j & 1);
