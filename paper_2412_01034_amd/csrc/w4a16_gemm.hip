@@ -335,7 +335,18 @@ __global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const Gem
     // were.  (Taller linears: see the dealing of eight row tiles below.)
     int vbid = bid;
     const bool x_fits_l2 = ga.Tm >= 3 && (long long)ga.Tm * kBM * ga.Kpad * 2 <= 2560 * 1024;
-    if (x_fits_l2) {
+    // Taller linears with an even number of row tiles, where the x of two row tiles fits: the same
+    // ranks, and the whole tiles are walked pair of row tiles by pair of row tiles (inside a pair column
+    // by column), so that an XCD's consecutive tiles are two row tiles of a few columns.
+    // Only where a round of the linear's blocks stays inside a pair (a share of a launch: all XCDs then
+    // share the pair's x at the same time and each has weight columns of its own; a linear on the whole
+    // grid has several pairs at once and is 7-15 % slower this way, see the dealing of eight row tiles).
+    const int whole_cols = ga.whole / ga.Tm;
+    // Measured on a decoder layer's four linears as one launch: 0.4 / 1.1 / 1.4 % faster with 4 / 8 / 16 row
+    // tiles, 1.1 % slower with 6, which keeps the launch order.
+    const bool pair_order = !x_fits_l2 && ga.Tm >= 4 && (ga.Tm & 3) == 0 && 2ll * kBM * ga.Kpad * 2 <= 2560 * 1024 &&
+                            P <= 2 * whole_cols;
+    if (x_fits_l2 || pair_order) {
         const int q = ga.block_begin & 7, mine = (q + bid) & 7;
         int before = 0;
         for (int x = 0; x < 8; ++x) {
@@ -368,12 +379,19 @@ __global__ __launch_bounds__(256 + 64 * LW) void w4a16_gemm_f16_kernel(const Gem
     const bool whole = steps == ga.steps;
     float* const pslot = ga.partial + (size_t)(2 * bid + (first_shared ? 0 : 1)) * (kBM * kBN);
     int tm = tile % ga.Tm, tn = tile / ga.Tm;
-    // Whole tiles of a linear that is eight row tiles high: workgroups go to the eight XCDs (each with an
-    // L2 of its own) in turn, so in launch order the eight row tiles that share a weight tile would sit on
-    // eight XCDs and every L2 would fetch every weight column.  A round's P tiles (P / 8 columns) are
-    // dealt instead so that an XCD works on two row tiles (their x fits its L2) and on every other column:
-    // a weight tile is then fetched by four L2s, not eight.
-    if (ga.Tm == 8 && !x_fits_l2 && (P & 15) == 0 && (ga.block_begin & 7) == 0 && tile < ga.whole) {
+    if (pair_order && tile < ga.whole) {
+        // (a last, partial column among the whole tiles keeps its order)
+        if (tile < whole_cols * ga.Tm) {
+            const int pair = tile / (2 * whole_cols), rem = tile - pair * 2 * whole_cols;
+            tm = 2 * pair + (rem & 1);
+            tn = rem >> 1;
+        }
+    } else if (ga.Tm == 8 && !x_fits_l2 && (P & 15) == 0 && (ga.block_begin & 7) == 0 && tile < ga.whole) {
+        // Whole tiles of a linear that is eight row tiles high and has the grid to itself: in launch order
+        // the eight row tiles that share a weight tile would sit on eight XCDs and every L2 would fetch
+        // every weight column.  A round's P tiles (P / 8 columns) are dealt instead so that an XCD works on
+        // two row tiles (their x fits its L2) and on every other column: a weight tile is then fetched by
+        // four L2s, not eight.
         const int round = tile / P, idx = tile - round * P;
         const int xcd = idx & 7, j = idx >> 3;
         tm = 2 * (xcd & 3) + (j & 1);
