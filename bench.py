@@ -32,7 +32,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/w4a16_gemv_decode_layer_pmc.txt), and the sha256 of the kernel source the
 # counters were taken on; reported as null once the kernel has changed.
-GEMV_TRAFFIC_BYTES = 106019443
+GEMV_TRAFFIC_BYTES = 106030306
 GEMV_TRAFFIC_SOURCE_SHA256 = "46c8a68ba336220dc6951ea77e255a605ea0dc66a533767f30505c97b0f63c86"
 
 HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
